@@ -1,0 +1,10 @@
+"""TEST INFRASTRUCTURE: the CPU oracle (fp64 sequential scan in C, utilities in numpy).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this package.  It never
+imports the HIP package, and the HIP package never imports it.
+"""
+from .ssd import (Scales, ref_prefill, ref_decode_step, build_oracle, x_scale_table)
+from .snc import quantize, sort_and_cluster, group_scales
+
+__all__ = ["Scales", "ref_prefill", "ref_decode_step", "build_oracle", "x_scale_table",
+           "quantize", "sort_and_cluster", "group_scales"]

@@ -1,0 +1,171 @@
+"""Seeded synthetic inputs with the shapes and value structure of the paper's workloads.
+
+The paper calibrates on real activations of trained Mamba2 checkpoints, which are not
+available; these draws stand in for them.  What is reproduced is the structure the paper
+reports for the SSM input x (per-channel magnitudes that persist over time, a few
+large-magnitude outlier channels; Section 4.1 "Sort-and-cluster") and for B and C (only a
+few state groups carry large values; Section 4.1 "Per-state-group quantization").
+
+Everything here is a random draw or an index gather.  The quantizer (Eq. 1), the
+clustering and the scan are NOT here: callers apply their own.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+import numpy as np
+
+
+@dataclass(frozen=True)
+class LayerShape:
+    name: str
+    batch: int
+    seqlen: int
+    nheads: int
+    headdim: int
+    d_state: int
+    ngroups: int
+    chunk: int
+    m: int                     # head clusters per state group
+    n: int                     # channel clusters per head cluster
+    outlier_channels: int = 0  # fixed count of channels whose std is multiplied by 20
+    outlier_frac: float = 0.0  # fraction of channels multiplied by 20 and drawn Student-t(3)
+    decode_steps: int = 0
+
+    def with_(self, **kw) -> "LayerShape":
+        return replace(self, **kw)
+
+
+CONFIGS = {
+    "tiny": LayerShape("tiny", 1, 256, 8, 64, 16, 1, 64, 1, 4, outlier_channels=2),
+    "m2_130m": LayerShape("m2_130m", 1, 2048, 24, 64, 128, 1, 256, 4, 4),
+    "m2_2p7b": LayerShape("m2_2p7b", 8, 2048, 80, 64, 128, 1, 256, 4, 4, outlier_frac=0.01),
+    "m2_8b_b1": LayerShape("m2_8b_b1", 1, 4096, 128, 64, 128, 8, 256, 4, 4),
+    "m2_8b_b4": LayerShape("m2_8b_b4", 4, 4096, 128, 64, 128, 8, 256, 4, 4),
+    "m2_8b_decode": LayerShape("m2_8b_decode", 256, 1, 128, 64, 128, 8, 256, 4, 4,
+                               decode_steps=32),
+}
+
+_BASE_SEED = 228790
+
+
+def _rng(seed: int, stream: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[(_BASE_SEED + seed) & 0xFFFFFFFFFFFFFFFF,
+                                                     stream]))
+
+
+def _softplus(v: np.ndarray) -> np.ndarray:
+    return np.logaddexp(0.0, v)
+
+
+def _channel_profile(s: LayerShape, seed: int):
+    """Per-channel std sigma[h,p] and the mask of heavy-tailed channels (stream 0)."""
+    g = _rng(seed, 0)
+    sigma = np.exp(g.standard_normal((s.nheads, s.headdim)))
+    heavy = np.zeros((s.nheads, s.headdim), dtype=bool)
+    flat = s.nheads * s.headdim
+    if s.outlier_channels:
+        idx = g.choice(flat, size=s.outlier_channels, replace=False)
+        sigma.reshape(-1)[idx] *= 20.0
+    if s.outlier_frac > 0.0:
+        k = max(1, int(round(flat * s.outlier_frac)))
+        idx = g.choice(flat, size=k, replace=False)
+        sigma.reshape(-1)[idx] *= 20.0
+        heavy.reshape(-1)[idx] = True
+    return sigma, heavy
+
+
+def _group_profile(s: LayerShape, seed: int, which: int):
+    """Per-state gain for B (which=0) or C (which=1): gain[g]*tau[g,n], largest gain = 1."""
+    g = _rng(seed, 1 + which)
+    gain = np.exp(g.standard_normal(s.ngroups))
+    gain = gain / gain.max()
+    tau = np.exp(0.5 * g.standard_normal((s.ngroups, s.d_state)))
+    return gain[:, None] * tau
+
+
+def _draw_x(g: np.random.Generator, tokens_shape, sigma, heavy) -> np.ndarray:
+    shape = tuple(tokens_shape) + sigma.shape
+    x = g.standard_normal(shape, dtype=np.float32)
+    if heavy.any():
+        hh, pp = np.nonzero(heavy)
+        t3 = g.standard_t(3.0, size=tuple(tokens_shape) + (hh.size,)).astype(np.float32)
+        x[..., hh, pp] = t3
+    x *= sigma.astype(np.float32)
+    return x
+
+
+def draw_calibration(s: LayerShape, seed: int = 0, tokens: int = 8192):
+    """Per-channel |x| maxima [H,P] and per-state |B|,|C| maxima [G,N] over a separate draw
+    that plays the role of the paper's calibration set (Appendix C, "Quantization setup")."""
+    sigma, heavy = _channel_profile(s, seed)
+    g = _rng(seed, 5)
+    xmax = np.zeros(sigma.shape, dtype=np.float32)
+    step = 1024
+    for t0 in range(0, tokens, step):
+        nt = min(step, tokens - t0)
+        xmax = np.maximum(xmax, np.abs(_draw_x(g, (nt,), sigma, heavy)).max(axis=0))
+    out = [xmax]
+    for which in (0, 1):
+        prof = _group_profile(s, seed, which).astype(np.float32)
+        v = g.standard_normal((tokens,) + prof.shape, dtype=np.float32) * prof
+        out.append(np.abs(v).max(axis=0))
+    return tuple(out)
+
+
+def draw_layer(s: LayerShape, seed: int = 0) -> dict:
+    """Raw floating-point inputs of one prefill, in the model's ORIGINAL head/channel order.
+
+    Returns x [b,L,H,P], B, C [b,L,G,N], dt [b,L,H] (softplus already applied), A [H] (<0),
+    D [H], all float32.
+    """
+    sigma, heavy = _channel_profile(s, seed)
+    g = _rng(seed, 10)
+    x = _draw_x(g, (s.batch, s.seqlen), sigma, heavy)
+    bc = []
+    for which in (0, 1):
+        prof = _group_profile(s, seed, which).astype(np.float32)
+        bc.append(g.standard_normal((s.batch, s.seqlen) + prof.shape, dtype=np.float32) * prof)
+    dt = _softplus(g.standard_normal((s.batch, s.seqlen, s.nheads)) - 3.0).astype(np.float32)
+    gp = _rng(seed, 11)
+    A = (-np.exp(gp.uniform(0.0, np.log(16.0), s.nheads))).astype(np.float32)
+    D = gp.standard_normal(s.nheads).astype(np.float32)
+    return {"x": x, "B": bc[0], "C": bc[1], "dt": dt, "A": A, "D": D}
+
+
+def draw_decode_step(s: LayerShape, seed: int, step: int) -> dict:
+    """Raw inputs of decode step `step`: x [b,H,P], B, C [b,G,N], dt [b,H] (A, D as in draw_layer)."""
+    sigma, heavy = _channel_profile(s, seed)
+    g = _rng(seed, 100 + step)
+    x = _draw_x(g, (s.batch,), sigma, heavy)
+    bc = []
+    for which in (0, 1):
+        prof = _group_profile(s, seed, which).astype(np.float32)
+        bc.append(g.standard_normal((s.batch,) + prof.shape, dtype=np.float32) * prof)
+    dt = _softplus(g.standard_normal((s.batch, s.nheads)) - 3.0).astype(np.float32)
+    return {"x": x, "B": bc[0], "C": bc[1], "dt": dt}
+
+
+def draw_state(s: LayerShape, seed: int = 0, batch: int | None = None) -> np.ndarray:
+    """Persistent SSM state [b,H,P,N] float32, N(0, std 0.1)."""
+    g = _rng(seed, 20)
+    b = s.batch if batch is None else batch
+    st = g.standard_normal((b, s.nheads, s.headdim, s.d_state), dtype=np.float32)
+    st *= np.float32(0.1)
+    return st
+
+
+def apply_reorder(raw: dict, head_perm: np.ndarray, chan_perm: np.ndarray) -> dict:
+    """Gather x, dt, A, D into the sorted/clustered order (new index -> old index).
+
+    head_perm [H]; chan_perm [H,P], row i holds the channel order of NEW head i.  This is what
+    the offline weight reordering (Section 4.2) makes the projections produce directly.
+    """
+    out = dict(raw)
+    x = raw["x"][..., head_perm, :]
+    idx = np.broadcast_to(chan_perm.reshape((1,) * (x.ndim - 2) + chan_perm.shape), x.shape)
+    out["x"] = np.take_along_axis(x, idx, axis=-1)
+    out["dt"] = raw["dt"][..., head_perm]
+    for k in ("A", "D"):
+        if k in raw:
+            out[k] = raw[k][head_perm]
+    return out
