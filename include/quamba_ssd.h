@@ -1,0 +1,162 @@
+/*
+ * quamba_ssd — the 8-bit Mamba2 selective scan (SSD) of Quamba2 (arXiv 2503.22879) for AMD MI355X (gfx950).
+ *
+ * C ABI, plain pointers and sizes.  The library computes, for every batch entry b and head h (state group
+ * g = h / (nheads / ngroups)), the selective SSM of the paper's Eq. 2 with the discretisation of Section 3.2
+ * (A-dot_t = exp(dt_t A_h), B-dot_t = dt_t B_t):
+ *
+ *      h_t = exp(dt_t A_h) h_{t-1} + dt_t B_t x_t^T ,      y_t = C_t . h_t + D_h x_t
+ *
+ * on quantized operands (Eq. 1, symmetric 8-bit, static scales):
+ *      x = s_x(h,p) * xq   — sort-and-cluster scales of Section 4.1: inside each state group the heads are split into
+ *                            m head clusters, and inside each head cluster the (sorted) channel positions are split
+ *                            into n ranges; one scale per (group, head cluster, channel range);
+ *      B = s_B[g] * Bq, C = s_C[g] * Cq — one scale per state group (Section 4.1, per-state-group quantization).
+ * All tensors are in the SORTED/CLUSTERED head and channel order that the offline weight reordering of
+ * Section 4.2 makes the projections produce; quamba_reorder_params() computes that order and the scale tables.
+ *
+ * Conventions for every entry point
+ *   - returns QUAMBA_OK (0) or a negative quamba_status; never throws, never allocates device memory;
+ *   - prefill/decode only ENQUEUE work on the caller's stream (a hipStream_t passed as void*, NULL = default stream)
+ *     and never synchronise; the caller owns every buffer and keeps it alive until the stream has drained;
+ *   - all tensors are dense row-major in the stated shape; pointers named "device" must be device-accessible,
+ *     pointers named "host" must be host memory; the two structs are host structs (their members may be device
+ *     pointers as stated);
+ *   - arguments are validated before anything is enqueued, so validation errors can be observed without a GPU.
+ *     Cluster boundary tables live on the device and are trusted (not read back).
+ */
+#ifndef QUAMBA_SSD_H_
+#define QUAMBA_SSD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum quamba_status {
+    QUAMBA_OK = 0,
+    QUAMBA_ENULL = -1,      /* a required pointer is NULL                                   */
+    QUAMBA_ESHAPE = -2,     /* a dimension is non-positive, inconsistent or unsupported      */
+    QUAMBA_EWORKSPACE = -3, /* workspace_bytes smaller than quamba_ssd_prefill_workspace_size */
+    QUAMBA_EHIP = -4,       /* the HIP runtime refused the launch (no device, bad stream ...) */
+    QUAMBA_EINVAL = -5      /* an argument value is invalid (unknown flag, bad permutation ...) */
+} quamba_status;
+
+/* flags of quamba_ssd_shape_t */
+#define QUAMBA_FLAG_GENERIC_KERNEL 0x1u /* prefill: use the shape-agnostic sequential kernel even where the
+                                           chunked MFMA kernel applies (a cross-check, not a fast path)      */
+#define QUAMBA_FLAG_PRECISE_STATE 0x2u  /* prefill: compute chunk states with a two-term (hi+lo) fp16 split so
+                                           that final_state meets 1e-4 of its max; implied when final_state
+                                           is requested, settable to get the same arithmetic without it       */
+
+typedef struct quamba_ssd_shape_t {
+    int32_t batch;           /* sequences                                                             */
+    int32_t seqlen;          /* tokens per sequence (ignored by decode)                               */
+    int32_t nheads;          /* H, multiple of ngroups                                                */
+    int32_t headdim;         /* P, channels per head                                                  */
+    int32_t d_state;         /* N, states per group                                                   */
+    int32_t ngroups;         /* G, state groups sharing B and C                                       */
+    int32_t chunk;           /* Q, SSD chunk length for prefill (ignored by decode)                   */
+    int32_t n_head_clusters; /* m, head clusters per state group                                      */
+    int32_t n_chan_clusters; /* n, channel ranges per head cluster                                    */
+    uint32_t flags;          /* QUAMBA_FLAG_*                                                         */
+} quamba_ssd_shape_t;
+
+/* Sort-and-cluster result in the reordered index space (Section 4.1).  For prefill/decode every member is a
+ * DEVICE pointer; quamba_reorder_params() fills HOST arrays of the same sizes. */
+typedef struct quamba_ssd_scales_t {
+    const float *x_scales;           /* [ngroups*m*n]  scale of (group, head cluster, channel range)              */
+    const int32_t *head_cluster_end; /* [ngroups*m]    exclusive end head index of each head cluster, counted
+                                                       inside its group (0..H/G], non-decreasing, last == H/G      */
+    const int32_t *chan_cluster_end; /* [ngroups*m*n]  exclusive end channel position (0..P], non-decreasing,
+                                                       last of each head cluster == P                              */
+    const float *B_scales;           /* [ngroups] */
+    const float *C_scales;           /* [ngroups] */
+} quamba_ssd_scales_t;
+
+/*
+ * Bytes of device workspace quamba_ssd_prefill needs for this shape (may be 0).  Returns 0 for an invalid shape;
+ * quamba_ssd_prefill reports the error.
+ */
+size_t quamba_ssd_prefill_workspace_size(const quamba_ssd_shape_t *shape);
+
+/*
+ * Chunked prefill of the 8-bit SSD (Eq. 2 over a whole sequence; the chunked matmul form is the SSD algorithm the
+ * paper's Section 3.2 "Mamba2" refers to, applied to the quantized operands of Section 4.1).
+ *   x  device int8  [batch, seqlen, nheads, headdim]     B, C  device int8 [batch, seqlen, ngroups, d_state]
+ *   dt device fp32  [batch, seqlen, nheads]  final step size (softplus and bias already applied), >= 0
+ *   A  device fp32  [nheads], <= 0           D  device fp32 [nheads] or NULL (no skip term)
+ *   init_state  device fp32 [batch, nheads, headdim, d_state] or NULL (zero state)
+ *   y           device fp16 [batch, seqlen, nheads, headdim]   (written, round-to-nearest-even)
+ *   final_state device fp32 [batch, nheads, headdim, d_state] or NULL (not returned); may alias init_state
+ *   workspace   device, workspace_bytes >= quamba_ssd_prefill_workspace_size(shape); may be NULL when that is 0
+ * Any seqlen >= 1 is accepted; a last partial chunk is processed as if padded with dt = 0, x = 0 steps (identity
+ * steps of Eq. 2) whose outputs are not written.  Errors: ENULL, ESHAPE (nheads % ngroups, non-positive sizes,
+ * headdim*d_state too large for the generic kernel), EWORKSPACE, EHIP.
+ */
+int quamba_ssd_prefill(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales, const int8_t *x,
+                       const int8_t *B, const int8_t *C, const float *dt, const float *A, const float *D,
+                       const float *init_state, uint16_t *y, float *final_state, void *workspace,
+                       size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Single-token decode: one application of Eq. 2 on a persistent state, the step the paper identifies as the
+ * generation bottleneck at large batch (Appendix E, "The cached state sizes").
+ *   x device int8 [batch, nheads, headdim]    B, C device int8 [batch, ngroups, d_state]
+ *   dt device fp32 [batch, nheads]            A, D as in prefill (D may be NULL)
+ *   state device fp32 [batch, nheads, headdim, d_state], read and overwritten IN PLACE (the only in/out buffer)
+ *   y device fp16 [batch, nheads, headdim]
+ * seqlen and chunk of the shape are ignored.  Errors: ENULL, ESHAPE, EHIP.
+ */
+int quamba_ssd_decode_step(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales, const int8_t *x,
+                           const int8_t *B, const int8_t *C, const float *dt, const float *A, const float *D,
+                           float *state, uint16_t *y, void *hip_stream);
+
+/*
+ * Offline sort-and-cluster (Section 4.1) and the index tables for cluster-aware weight reordering (Section 4.2).
+ * HOST function, all pointers host memory.
+ *   x_calib_absmax [nheads*headdim]  calibrated per-channel max|x| in the model's original order
+ *   B_calib_absmax, C_calib_absmax [ngroups*d_state] calibrated per-state max|B|, max|C|
+ * Outputs:
+ *   head_perm [nheads]          new head index -> old head index (heads never leave their state group)
+ *   chan_perm [nheads*headdim]  row i (NEW head i): sorted channel position -> old channel of that head
+ *   x_scales, head_cluster_end, chan_cluster_end, B_scales, C_scales: as in quamba_ssd_scales_t
+ * Steps: sort each head's channels by calibrated max (ascending); per state group, k-means (Lloyd, deterministic
+ * start, <= 50 rounds) of the heads on their sorted-max vectors into m clusters, clusters ordered by magnitude;
+ * per head cluster, exact 1-D k-means of the max-profile over sorted positions into n contiguous ranges; every
+ * scale = (max of its cell) / 127 (Eq. 1, N = 8), 1.0 for an empty or all-zero cell.  `seed` is reserved (the
+ * default procedure draws no random numbers).  Errors: ENULL, ESHAPE, EINVAL (negative or non-finite maxima).
+ */
+int quamba_reorder_params(int32_t nheads, int32_t headdim, int32_t ngroups, int32_t m, int32_t n, uint64_t seed,
+                          int32_t d_state, const float *x_calib_absmax, const float *B_calib_absmax,
+                          const float *C_calib_absmax, int32_t *head_perm, int32_t *chan_perm, float *x_scales,
+                          int32_t *head_cluster_end, int32_t *chan_cluster_end, float *B_scales, float *C_scales);
+
+/*
+ * Apply a permutation to the rows of any host matrix: dst row i = src row new_to_old[i] (Section 4.2: in-projection
+ * output columns as rows of W^T, conv channels, norm weights, out-projection input rows, A, D, dt_bias).
+ * dst and src must not overlap.  Errors: ENULL, ESHAPE, EINVAL (index out of range).
+ */
+int quamba_gather_rows(void *dst, const void *src, const int32_t *new_to_old, int64_t rows, int64_t row_bytes);
+
+/*
+ * Eq. 1 on the host, with the static scales above (fp32 division, round half to even, clamp to [-128,127]).
+ *   quamba_quantize_x:      x [tokens, nheads, headdim] fp32, already in reordered order -> xq int8, same shape;
+ *                           scales is a struct of HOST pointers.
+ *   quamba_quantize_groups: v [tokens, ngroups, d_state] fp32 -> int8 with group_scales [ngroups] (B or C).
+ * Errors: ENULL, ESHAPE.
+ */
+int quamba_quantize_x(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *host_scales, int64_t tokens,
+                      const float *x, int8_t *xq);
+int quamba_quantize_groups(int64_t tokens, int32_t ngroups, int32_t d_state, const float *group_scales,
+                           const float *v, int8_t *vq);
+
+/* Static description of a quamba_status value. */
+const char *quamba_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUAMBA_SSD_H_ */

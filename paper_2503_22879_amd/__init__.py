@@ -1,0 +1,15 @@
+"""MI355X-native 8-bit Mamba2 selective scan (the SSD hot path of Quamba2, arXiv 2503.22879).
+
+A thin ctypes binding over libquamba_ssd.so (C ABI in include/quamba_ssd.h).  Every step of the path runs in the
+library's HIP kernels; this package only marshals arguments.  There is no CPU fallback: calls raise if the
+library has not been built.
+"""
+from .binding import (QuambaError, Shape, HostScales, DeviceScales, load_library, library_path,
+                      quamba_ssd_prefill, quamba_ssd_prefill_workspace_size, quamba_ssd_decode_step,
+                      quamba_reorder_params, quamba_gather_rows, quamba_quantize_x, quamba_quantize_groups,
+                      quamba_strerror, FLAG_GENERIC_KERNEL, FLAG_PRECISE_STATE, EXPORTED_SYMBOLS)
+
+__all__ = ["QuambaError", "Shape", "HostScales", "DeviceScales", "load_library", "library_path",
+           "quamba_ssd_prefill", "quamba_ssd_prefill_workspace_size", "quamba_ssd_decode_step",
+           "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x", "quamba_quantize_groups",
+           "quamba_strerror", "FLAG_GENERIC_KERNEL", "FLAG_PRECISE_STATE", "EXPORTED_SYMBOLS"]

@@ -1,0 +1,237 @@
+"""ctypes binding of include/quamba_ssd.h: same names, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libquamba_ssd.so")
+_lib = None
+
+FLAG_GENERIC_KERNEL = 0x1
+FLAG_PRECISE_STATE = 0x2
+
+EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "quamba_ssd_decode_step",
+                    "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x",
+                    "quamba_quantize_groups", "quamba_strerror")
+
+
+class QuambaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {quamba_strerror(status)} (status {status})")
+
+
+class Shape(C.Structure):
+    """quamba_ssd_shape_t"""
+    _fields_ = [("batch", C.c_int32), ("seqlen", C.c_int32), ("nheads", C.c_int32), ("headdim", C.c_int32),
+                ("d_state", C.c_int32), ("ngroups", C.c_int32), ("chunk", C.c_int32),
+                ("n_head_clusters", C.c_int32), ("n_chan_clusters", C.c_int32), ("flags", C.c_uint32)]
+
+
+class _ScalesStruct(C.Structure):
+    """quamba_ssd_scales_t"""
+    _fields_ = [("x_scales", C.c_void_p), ("head_cluster_end", C.c_void_p), ("chan_cluster_end", C.c_void_p),
+                ("B_scales", C.c_void_p), ("C_scales", C.c_void_p)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libquamba_ssd.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2503_22879_amd.build` "
+                "(or __graft_entry__.build()); this package has no CPU fallback")
+        lib = C.CDLL(_LIB_PATH)
+        lib.quamba_ssd_prefill_workspace_size.restype = C.c_size_t
+        lib.quamba_ssd_prefill_workspace_size.argtypes = [C.POINTER(Shape)]
+        lib.quamba_ssd_prefill.restype = C.c_int
+        lib.quamba_ssd_prefill.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 10 + \
+            [C.c_size_t, C.c_void_p]
+        lib.quamba_ssd_decode_step.restype = C.c_int
+        lib.quamba_ssd_decode_step.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 9
+        lib.quamba_reorder_params.restype = C.c_int
+        lib.quamba_reorder_params.argtypes = [C.c_int32] * 5 + [C.c_uint64, C.c_int32] + [C.c_void_p] * 10
+        lib.quamba_gather_rows.restype = C.c_int
+        lib.quamba_gather_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64]
+        lib.quamba_quantize_x.restype = C.c_int
+        lib.quamba_quantize_x.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct), C.c_int64, C.c_void_p,
+                                          C.c_void_p]
+        lib.quamba_quantize_groups.restype = C.c_int
+        lib.quamba_quantize_groups.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.quamba_strerror.restype = C.c_char_p
+        lib.quamba_strerror.argtypes = [C.c_int]
+        _lib = lib
+    return _lib
+
+
+def quamba_strerror(status: int) -> str:
+    return load_library().quamba_strerror(int(status)).decode()
+
+
+@dataclass
+class HostScales:
+    """Sort-and-cluster result on the host (numpy arrays), as quamba_reorder_params fills it."""
+    x_scales: np.ndarray
+    head_cluster_end: np.ndarray
+    chan_cluster_end: np.ndarray
+    B_scales: np.ndarray
+    C_scales: np.ndarray
+
+    def struct(self) -> _ScalesStruct:
+        return _ScalesStruct(*(a.ctypes.data for a in (self.x_scales, self.head_cluster_end,
+                                                       self.chan_cluster_end, self.B_scales, self.C_scales)))
+
+
+class DeviceScales:
+    """The same five tables as device tensors (kept alive by this object)."""
+
+    def __init__(self, host: HostScales, device="cuda"):
+        import torch
+        self.tensors = [torch.from_numpy(np.ascontiguousarray(a)).to(device) for a in
+                        (host.x_scales.astype(np.float32), host.head_cluster_end.astype(np.int32),
+                         host.chan_cluster_end.astype(np.int32), host.B_scales.astype(np.float32),
+                         host.C_scales.astype(np.float32))]
+
+    def struct(self) -> _ScalesStruct:
+        return _ScalesStruct(*(t.data_ptr() for t in self.tensors))
+
+
+def _dp(t, dtype=None, shape=None, name="tensor"):
+    """Device pointer of a torch tensor (None -> NULL), with the checks a C caller would have to make itself."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return getattr(stream, "cuda_stream", stream)
+
+
+def quamba_ssd_prefill_workspace_size(shape: Shape) -> int:
+    return int(load_library().quamba_ssd_prefill_workspace_size(C.byref(shape)))
+
+
+def quamba_ssd_prefill(shape: Shape, scales, x, B, Cm, dt, A, D, init_state, y, final_state=None,
+                       workspace=None, stream=None) -> None:
+    """Enqueue the chunked prefill on `stream` (default: torch's current stream).  Tensors are torch device tensors."""
+    import torch
+    s = shape
+    sc = scales.struct()
+    ws_ptr = _dp(workspace, name="workspace")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st_shape = (s.batch, s.nheads, s.headdim, s.d_state)
+    rc = load_library().quamba_ssd_prefill(
+        C.byref(s), C.byref(sc),
+        _dp(x, torch.int8, (s.batch, s.seqlen, s.nheads, s.headdim), "x"),
+        _dp(B, torch.int8, (s.batch, s.seqlen, s.ngroups, s.d_state), "B"),
+        _dp(Cm, torch.int8, (s.batch, s.seqlen, s.ngroups, s.d_state), "C"),
+        _dp(dt, torch.float32, (s.batch, s.seqlen, s.nheads), "dt"),
+        _dp(A, torch.float32, (s.nheads,), "A"), _dp(D, torch.float32, (s.nheads,), "D"),
+        _dp(init_state, torch.float32, st_shape, "init_state"),
+        _dp(y, torch.float16, (s.batch, s.seqlen, s.nheads, s.headdim), "y"),
+        _dp(final_state, torch.float32, st_shape, "final_state"),
+        ws_ptr, ws_bytes, _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_ssd_prefill")
+
+
+def quamba_ssd_decode_step(shape: Shape, scales, x, B, Cm, dt, A, D, state, y, stream=None) -> None:
+    """Enqueue one decode step; `state` is updated in place."""
+    import torch
+    s = shape
+    sc = scales.struct()
+    rc = load_library().quamba_ssd_decode_step(
+        C.byref(s), C.byref(sc),
+        _dp(x, torch.int8, (s.batch, s.nheads, s.headdim), "x"),
+        _dp(B, torch.int8, (s.batch, s.ngroups, s.d_state), "B"),
+        _dp(Cm, torch.int8, (s.batch, s.ngroups, s.d_state), "C"),
+        _dp(dt, torch.float32, (s.batch, s.nheads), "dt"),
+        _dp(A, torch.float32, (s.nheads,), "A"), _dp(D, torch.float32, (s.nheads,), "D"),
+        _dp(state, torch.float32, (s.batch, s.nheads, s.headdim, s.d_state), "state"),
+        _dp(y, torch.float16, (s.batch, s.nheads, s.headdim), "y"), _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_ssd_decode_step")
+
+
+def quamba_reorder_params(nheads, headdim, ngroups, m, n, d_state, x_calib_absmax, B_calib_absmax,
+                          C_calib_absmax, seed=0):
+    """Offline sort-and-cluster on the host.  Returns (head_perm [H], chan_perm [H,P], HostScales)."""
+    xm = np.ascontiguousarray(x_calib_absmax, np.float32).reshape(-1)
+    bm = np.ascontiguousarray(B_calib_absmax, np.float32).reshape(-1)
+    cm = np.ascontiguousarray(C_calib_absmax, np.float32).reshape(-1)
+    if xm.size != nheads * headdim or bm.size != ngroups * d_state or cm.size != ngroups * d_state:
+        raise ValueError("calibration arrays do not match the shape")
+    head_perm = np.empty(nheads, np.int32)
+    chan_perm = np.empty((nheads, headdim), np.int32)
+    hs = HostScales(np.empty(ngroups * m * n, np.float32), np.empty(ngroups * m, np.int32),
+                    np.empty(ngroups * m * n, np.int32), np.empty(ngroups, np.float32),
+                    np.empty(ngroups, np.float32))
+    rc = load_library().quamba_reorder_params(
+        nheads, headdim, ngroups, m, n, seed, d_state, xm.ctypes.data, bm.ctypes.data, cm.ctypes.data,
+        head_perm.ctypes.data, chan_perm.ctypes.data, hs.x_scales.ctypes.data, hs.head_cluster_end.ctypes.data,
+        hs.chan_cluster_end.ctypes.data, hs.B_scales.ctypes.data, hs.C_scales.ctypes.data)
+    if rc != 0:
+        raise QuambaError(rc, "quamba_reorder_params")
+    return head_perm, chan_perm, hs
+
+
+def quamba_gather_rows(src: np.ndarray, new_to_old: np.ndarray) -> np.ndarray:
+    """dst[i] = src[new_to_old[i]] along axis 0 (host)."""
+    src = np.ascontiguousarray(src)
+    idx = np.ascontiguousarray(new_to_old, np.int32)
+    if idx.shape != (src.shape[0],):
+        raise ValueError("need one index per row")
+    dst = np.empty_like(src)
+    row_bytes = src.nbytes // max(1, src.shape[0])
+    rc = load_library().quamba_gather_rows(dst.ctypes.data, src.ctypes.data, idx.ctypes.data, src.shape[0],
+                                           row_bytes)
+    if rc != 0:
+        raise QuambaError(rc, "quamba_gather_rows")
+    return dst
+
+
+def quamba_quantize_x(shape: Shape, host_scales: HostScales, x: np.ndarray) -> np.ndarray:
+    """Eq. 1 with the m x n cluster scales; x [..., H, P] float32 in reordered order -> int8."""
+    x = np.ascontiguousarray(x, np.float32)
+    if x.shape[-2:] != (shape.nheads, shape.headdim):
+        raise ValueError("x must end in [nheads, headdim]")
+    tokens = x.size // (shape.nheads * shape.headdim)
+    out = np.empty(x.shape, np.int8)
+    sc = host_scales.struct()
+    rc = load_library().quamba_quantize_x(C.byref(shape), C.byref(sc), tokens, x.ctypes.data, out.ctypes.data)
+    if rc != 0:
+        raise QuambaError(rc, "quamba_quantize_x")
+    return out
+
+
+def quamba_quantize_groups(v: np.ndarray, group_scales: np.ndarray) -> np.ndarray:
+    """Eq. 1 with one scale per state group; v [..., G, N] float32 -> int8."""
+    v = np.ascontiguousarray(v, np.float32)
+    gs = np.ascontiguousarray(group_scales, np.float32)
+    G, N = v.shape[-2], v.shape[-1]
+    if gs.shape != (G,):
+        raise ValueError("need one scale per group")
+    out = np.empty(v.shape, np.int8)
+    rc = load_library().quamba_quantize_groups(v.size // (G * N), G, N, gs.ctypes.data, v.ctypes.data,
+                                               out.ctypes.data)
+    if rc != 0:
+        raise QuambaError(rc, "quamba_quantize_groups")
+    return out

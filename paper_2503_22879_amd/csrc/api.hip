@@ -1,0 +1,110 @@
+// The C-ABI layer: argument validation (before anything is enqueued) and kernel dispatch.
+#include "quamba_internal.h"
+
+namespace {
+
+constexpr size_t kMaxLdsBytes = 160 * 1024;  // LDS of one gfx950 compute unit
+
+int check_shape(const quamba_ssd_shape_t *s, bool prefill)
+{
+    if (s->batch <= 0 || s->nheads <= 0 || s->headdim <= 0 || s->d_state <= 0 || s->ngroups <= 0 ||
+        s->n_head_clusters <= 0 || s->n_chan_clusters <= 0)
+        return QUAMBA_ESHAPE;
+    if (s->nheads % s->ngroups) return QUAMBA_ESHAPE;
+    if (s->flags & ~(QUAMBA_FLAG_GENERIC_KERNEL | QUAMBA_FLAG_PRECISE_STATE)) return QUAMBA_EINVAL;
+    if ((int64_t)s->batch * s->nheads > 0x7fffffffLL) return QUAMBA_ESHAPE;
+    if (prefill) {
+        if (s->seqlen <= 0 || s->chunk <= 0) return QUAMBA_ESHAPE;
+    } else if (s->headdim > 16384) {
+        return QUAMBA_ESHAPE;
+    }
+    return QUAMBA_OK;
+}
+
+int check_scales(const quamba_ssd_scales_t *sc)
+{
+    if (!sc || !sc->x_scales || !sc->head_cluster_end || !sc->chan_cluster_end || !sc->B_scales || !sc->C_scales)
+        return QUAMBA_ENULL;
+    return QUAMBA_OK;
+}
+
+quamba::SsdArgs pack(const quamba_ssd_shape_t *s, const quamba_ssd_scales_t *sc, const int8_t *x, const int8_t *B,
+                     const int8_t *C, const float *dt, const float *A, const float *D, const float *init,
+                     float *state, uint16_t *y)
+{
+    quamba::SsdArgs a;
+    a.s = *s;
+    a.x_scales = sc->x_scales;
+    a.head_cluster_end = sc->head_cluster_end;
+    a.chan_cluster_end = sc->chan_cluster_end;
+    a.B_scales = sc->B_scales;
+    a.C_scales = sc->C_scales;
+    a.x = x; a.B = B; a.C = C; a.dt = dt; a.A = A; a.D = D;
+    a.init_state = init;
+    a.state = state;
+    a.y = y;
+    return a;
+}
+
+bool use_mfma(const quamba_ssd_shape_t *s)
+{
+    return !(s->flags & QUAMBA_FLAG_GENERIC_KERNEL) && quamba::prefill_mfma_supports(*s);
+}
+
+}  // namespace
+
+extern "C" size_t quamba_ssd_prefill_workspace_size(const quamba_ssd_shape_t *shape)
+{
+    if (!shape || check_shape(shape, true) != QUAMBA_OK) return 0;
+    return 0;  // both prefill kernels keep every intermediate on chip
+}
+
+extern "C" int quamba_ssd_prefill(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                  const int8_t *x, const int8_t *B, const int8_t *C, const float *dt, const float *A,
+                                  const float *D, const float *init_state, uint16_t *y, float *final_state,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!shape) return QUAMBA_ENULL;
+    int rc = check_scales(scales);
+    if (rc != QUAMBA_OK) return rc;
+    if (!x || !B || !C || !dt || !A || !y) return QUAMBA_ENULL;
+    rc = check_shape(shape, true);
+    if (rc != QUAMBA_OK) return rc;
+    const size_t need = quamba_ssd_prefill_workspace_size(shape);
+    if (workspace_bytes < need || (need && !workspace)) return QUAMBA_EWORKSPACE;
+    if (!use_mfma(shape) && quamba::prefill_generic_lds_bytes(*shape) > kMaxLdsBytes) return QUAMBA_ESHAPE;
+
+    const quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, A, D, init_state, final_state, y);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = use_mfma(shape) ? quamba::launch_prefill_mfma(a, stream)
+                                         : quamba::launch_prefill_generic(a, stream);
+    return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
+extern "C" int quamba_ssd_decode_step(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                      const int8_t *x, const int8_t *B, const int8_t *C, const float *dt,
+                                      const float *A, const float *D, float *state, uint16_t *y, void *hip_stream)
+{
+    if (!shape) return QUAMBA_ENULL;
+    int rc = check_scales(scales);
+    if (rc != QUAMBA_OK) return rc;
+    if (!x || !B || !C || !dt || !A || !state || !y) return QUAMBA_ENULL;
+    rc = check_shape(shape, false);
+    if (rc != QUAMBA_OK) return rc;
+    const quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, A, D, nullptr, state, y);
+    const hipError_t e = quamba::launch_decode(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
+extern "C" const char *quamba_strerror(int status)
+{
+    switch (status) {
+        case QUAMBA_OK: return "ok";
+        case QUAMBA_ENULL: return "a required pointer is NULL";
+        case QUAMBA_ESHAPE: return "a dimension is non-positive, inconsistent or unsupported";
+        case QUAMBA_EWORKSPACE: return "workspace too small";
+        case QUAMBA_EHIP: return "the HIP runtime refused the launch";
+        case QUAMBA_EINVAL: return "invalid argument value";
+        default: return "unknown status";
+    }
+}

@@ -1,0 +1,48 @@
+"""Shared by the tests: build a quantized problem from a seeded workload with the ORACLE's offline utilities
+(numpy sort-and-cluster + Eq. 1), so that no oracle input ever comes from the HIP library."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+import workloads as W
+
+
+def make_problem(s: W.LayerShape, seed: int = 0, calib_tokens: int = 1024, with_D: bool = True):
+    """Returns (Scales, dict of int8/fp32 numpy arrays in reordered order)."""
+    xmax, bmax, cmax = W.draw_calibration(s, seed, tokens=calib_tokens)
+    r = oracle.sort_and_cluster(xmax, s.ngroups, s.m, s.n)
+    sc = oracle.Scales(s.m, s.n, r["x_scales"], r["head_cluster_end"], r["chan_cluster_end"],
+                       oracle.group_scales(bmax), oracle.group_scales(cmax))
+    raw = W.apply_reorder(W.draw_layer(s, seed), r["head_perm"], r["chan_perm"])
+    tab = oracle.x_scale_table(sc, s.nheads, s.headdim, s.ngroups)
+    prob = {
+        "x": oracle.quantize(raw["x"], tab),
+        "B": oracle.quantize(raw["B"], sc.B_scales[:, None]),
+        "C": oracle.quantize(raw["C"], sc.C_scales[:, None]),
+        "dt": raw["dt"], "A": raw["A"], "D": raw["D"] if with_D else None,
+    }
+    return sc, prob, r
+
+
+def make_decode_inputs(s: W.LayerShape, sc, r, seed: int, step: int, batch=None):
+    raw = W.draw_decode_step(s if batch is None else s.with_(batch=batch), seed, step)
+    raw = W.apply_reorder(raw, r["head_perm"], r["chan_perm"])
+    tab = oracle.x_scale_table(sc, s.nheads, s.headdim, s.ngroups)
+    return {"x": oracle.quantize(raw["x"], tab), "B": oracle.quantize(raw["B"], sc.B_scales[:, None]),
+            "C": oracle.quantize(raw["C"], sc.C_scales[:, None]), "dt": raw["dt"]}
+
+
+def to_shape(q, s: W.LayerShape, flags: int = 0, **over):
+    d = dict(batch=s.batch, seqlen=s.seqlen, nheads=s.nheads, headdim=s.headdim, d_state=s.d_state,
+             ngroups=s.ngroups, chunk=s.chunk, n_head_clusters=s.m, n_chan_clusters=s.n, flags=flags)
+    d.update(over)
+    return q.Shape(**d)
+
+
+def host_scales(q, sc):
+    return q.HostScales(np.ascontiguousarray(sc.x_scales, np.float32),
+                        np.ascontiguousarray(sc.head_cluster_end, np.int32),
+                        np.ascontiguousarray(sc.chan_cluster_end, np.int32),
+                        np.ascontiguousarray(sc.B_scales, np.float32),
+                        np.ascontiguousarray(sc.C_scales, np.float32))

@@ -1,0 +1,95 @@
+"""The C-ABI library loads, exports every function the header declares, and validates arguments before touching
+the device (so these run without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2503_22879_amd as q
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "quamba_ssd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(quamba_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = q.load_library()
+    names = _declared()
+    assert set(names) == set(q.EXPORTED_SYMBOLS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_strerror():
+    assert q.quamba_strerror(0) == "ok"
+    assert "NULL" in q.quamba_strerror(-1) and "unknown" in q.quamba_strerror(-99)
+
+
+def _shape(**kw):
+    d = dict(batch=1, seqlen=8, nheads=4, headdim=8, d_state=8, ngroups=2, chunk=4, n_head_clusters=1,
+             n_chan_clusters=1, flags=0)
+    d.update(kw)
+    return q.Shape(**d)
+
+
+def _call_prefill(shape, scales_ok=True, null_arg=None, ws_bytes=0):
+    lib = q.load_library()
+    dummy = C.create_string_buffer(64)
+    p = C.addressof(dummy)
+    from paper_2503_22879_amd.binding import _ScalesStruct
+    sc = _ScalesStruct(p, p, p, p, p) if scales_ok else _ScalesStruct(p, None, p, p, p)
+    args = [p] * 10          # x B C dt A D init y final workspace
+    if null_arg is not None:
+        args[null_arg] = None
+    return lib.quamba_ssd_prefill(C.byref(shape), C.byref(sc), *args, ws_bytes, None)
+
+
+def _call_decode(shape, null_arg=None):
+    lib = q.load_library()
+    dummy = C.create_string_buffer(64)
+    p = C.addressof(dummy)
+    from paper_2503_22879_amd.binding import _ScalesStruct
+    sc = _ScalesStruct(p, p, p, p, p)
+    args = [p] * 8           # x B C dt A D state y
+    if null_arg is not None:
+        args[null_arg] = None
+    return lib.quamba_ssd_decode_step(C.byref(shape), C.byref(sc), *args, None)
+
+
+@pytest.mark.parametrize("kw", [dict(batch=0), dict(seqlen=0), dict(nheads=5), dict(headdim=-1), dict(d_state=0),
+                                dict(ngroups=0), dict(chunk=0), dict(n_head_clusters=0), dict(n_chan_clusters=0),
+                                dict(headdim=512, d_state=512, flags=1)])
+def test_prefill_rejects_bad_shapes_without_a_device(kw):
+    assert _call_prefill(_shape(**kw)) == -2
+
+
+def test_prefill_rejects_nulls_and_flags():
+    for i in (0, 1, 2, 3, 4, 7):           # x B C dt A y are required
+        assert _call_prefill(_shape(), null_arg=i) == -1
+    assert _call_prefill(_shape(), scales_ok=False) == -1
+    assert _call_prefill(_shape(flags=0x80)) == -5
+    lib = q.load_library()
+    assert lib.quamba_ssd_prefill(None, None, *([None] * 10), 0, None) == -1
+    assert q.quamba_ssd_prefill_workspace_size(_shape()) == 0
+    assert q.quamba_ssd_prefill_workspace_size(_shape(nheads=5)) == 0
+
+
+def test_decode_rejects_bad_arguments_without_a_device():
+    assert _call_decode(_shape(nheads=5)) == -2
+    assert _call_decode(_shape(batch=0)) == -2
+    for i in (0, 1, 2, 3, 4, 6, 7):        # everything but D is required
+        assert _call_decode(_shape(), null_arg=i) == -1
+    assert _call_decode(_shape(seqlen=0, chunk=0), null_arg=0) == -1   # seqlen/chunk are ignored by decode
+
+
+def test_binding_fails_loudly_without_library(monkeypatch):
+    import paper_2503_22879_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libquamba_ssd.so")
+    with pytest.raises(FileNotFoundError):
+        b.load_library()

@@ -1,0 +1,193 @@
+"""GPU parity of quamba_ssd_prefill against the fp64 oracle (through the C ABI)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from helpers import make_problem, to_shape, host_scales
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 2e-3      # max|y_gpu - y_ref| <= Y_TOL * max|y_ref|   (fp16 y, fp32 accumulation)
+H_TOL = 1e-4      # max|h_gpu - h_ref| <= H_TOL * max|h_ref|   (final fp32 state)
+
+
+def run_prefill(q, s, sc, prob, flags=0, init_state=None, want_state=True, chunk=None):
+    import torch
+    dsc = q.DeviceScales(host_scales(q, sc))
+    shape = to_shape(q, s, flags=flags, **({} if chunk is None else {"chunk": chunk}))
+    t = {k: (torch.from_numpy(v).cuda() if v is not None else None) for k, v in prob.items()}
+    y = torch.full((s.batch, s.seqlen, s.nheads, s.headdim), float("nan"), dtype=torch.float16, device="cuda")
+    fin = torch.full((s.batch, s.nheads, s.headdim, s.d_state), float("nan"), device="cuda") if want_state else None
+    init = torch.from_numpy(init_state.astype(np.float32)).cuda() if init_state is not None else None
+    ws_bytes = q.quamba_ssd_prefill_workspace_size(shape)
+    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device="cuda")
+    q.quamba_ssd_prefill(shape, dsc, t["x"], t["B"], t["C"], t["dt"], t["A"], t["D"], init, y, fin, ws)
+    torch.cuda.synchronize()
+    return y.cpu().numpy().astype(np.float64), (fin.cpu().numpy().astype(np.float64) if want_state else None)
+
+
+def check(yg, hg, yref, href, what=""):
+    assert np.isfinite(yg).all(), f"{what}: non-finite y"
+    ey = np.abs(yg - yref).max() / np.abs(yref).max()
+    assert np.abs(yref).max() < 6e4, "workload overflows fp16"
+    msg = f"{what}: y err {ey:.3e}"
+    eh = None
+    if hg is not None:
+        assert np.isfinite(hg).all(), f"{what}: non-finite state"
+        eh = np.abs(hg - href).max() / np.abs(href).max()
+        msg += f", state err {eh:.3e}"
+    print(msg)
+    assert ey <= Y_TOL, msg
+    if eh is not None:
+        assert eh <= H_TOL, msg
+    return ey, eh
+
+
+GENERIC = 0x1
+
+
+@pytest.mark.parametrize("flags", [0, GENERIC])
+def test_tiny_config(gpu_lib, flags):
+    """configs[0]: batch 1, seqlen 256, 8 heads x 64, d_state 16, chunk 64, 1x4 clusters, 2 outlier channels."""
+    s = W.CONFIGS["tiny"]
+    sc, prob, _ = make_problem(s, 0)
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"])
+    yg, hg = run_prefill(gpu_lib, s, sc, prob, flags)
+    check(yg, hg, yref, href, f"tiny flags={flags}")
+
+
+@pytest.mark.parametrize("flags", [0, GENERIC])
+@pytest.mark.parametrize("with_D", [True, False])
+def test_130m_shape(gpu_lib, flags, with_D):
+    """configs[1]: Mamba2-130M-shaped layer, seqlen 2048, 24 heads, d_state 128, chunk 256, 4x4 clusters."""
+    s = W.CONFIGS["m2_130m"]
+    sc, prob, _ = make_problem(s, 1, with_D=with_D)
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"])
+    yg, hg = run_prefill(gpu_lib, s, sc, prob, flags)
+    check(yg, hg, yref, href, f"130m flags={flags} D={with_D}")
+
+
+@pytest.mark.parametrize("flags", [0, GENERIC])
+@pytest.mark.parametrize("L", [1, 5, 63, 257, 300, 777])
+def test_ragged_lengths_and_init_state(gpu_lib, flags, L):
+    """Sequence lengths that are not multiples of the chunk (several tiles + a ragged tail), with an initial state."""
+    s = W.CONFIGS["m2_8b_b1"].with_(batch=2, seqlen=L, nheads=16, ngroups=2)
+    sc, prob, _ = make_problem(s, 2, calib_tokens=256)
+    h0 = W.draw_state(s, 2).astype(np.float64)
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"],
+                                       init_state=h0.astype(np.float32).astype(np.float64))
+    yg, hg = run_prefill(gpu_lib, s, sc, prob, flags, init_state=h0)
+    check(yg, hg, yref, href, f"L={L} flags={flags}")
+
+
+@pytest.mark.parametrize("P,N,H,G,Q", [(64, 64, 4, 2, 128), (32, 128, 4, 1, 64), (64, 32, 6, 3, 256), (48, 24, 4, 2, 32),
+                                       (16, 8, 2, 1, 16)])
+def test_other_shapes(gpu_lib, P, N, H, G, Q):
+    s = W.LayerShape("t", 2, 200, H, P, N, G, Q, 2, 3)
+    sc, prob, _ = make_problem(s, 3, calib_tokens=256)
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"])
+    yg, hg = run_prefill(gpu_lib, s, sc, prob)
+    check(yg, hg, yref, href, f"P{P} N{N} H{H} G{G} Q{Q}")
+
+
+def test_exact_integer_case(gpu_lib):
+    """A = 0, dt = 1, all scales 1, small integers: y is an exact integer (< 2048, exact in fp16) and so is the state."""
+    rng = np.random.default_rng(8)
+    s = W.LayerShape("int", 1, 512, 16, 64, 128, 2, 256, 1, 1)
+    prob = {"x": rng.integers(-1, 2, (1, 512, 16, 64), dtype=np.int8),
+            "B": (rng.random((1, 512, 2, 128)) < 0.02).astype(np.int8) * rng.choice([-1, 1], (1, 512, 2, 128)).astype(np.int8),
+            "C": (rng.random((1, 512, 2, 128)) < 0.02).astype(np.int8) * rng.choice([-1, 1], (1, 512, 2, 128)).astype(np.int8),
+            "dt": np.ones((1, 512, 16), np.float32), "A": np.zeros(16, np.float32),
+            "D": rng.integers(-2, 3, 16).astype(np.float32)}
+    sc = oracle.Scales.ones(2, 8, 64)
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"])
+    assert np.abs(yref).max() < 2048 and np.abs(yref).max() > 4
+    for flags in (0, GENERIC):
+        yg, hg = run_prefill(gpu_lib, s, sc, prob, flags)
+        assert np.array_equal(yg, yref) and np.array_equal(hg, href), f"flags={flags}"
+
+
+def test_dt_zero_and_permutation_invariance(gpu_lib):
+    s = W.CONFIGS["m2_130m"].with_(seqlen=512)
+    sc, prob, _ = make_problem(s, 5, calib_tokens=256)
+    p0 = dict(prob); p0["dt"] = np.zeros_like(prob["dt"])
+    yg, hg = run_prefill(gpu_lib, s, sc, p0)
+    tab = oracle.x_scale_table(sc, s.nheads, s.headdim, s.ngroups).astype(np.float64)
+    want = (prob["D"].astype(np.float64)[None, None, :, None] * tab * prob["x"]).astype(np.float16).astype(np.float64)
+    assert np.array_equal(yg, want) and not hg.any()
+    # swap two heads of the same head cluster and reverse the channels of one channel range: y moves with them
+    he = sc.head_cluster_end.reshape(s.ngroups, s.m)[0]
+    lo = 0
+    pair = None
+    for e in he:
+        if e - lo >= 2:
+            pair = (lo, lo + 1); break
+        lo = e
+    assert pair is not None
+    hp = np.arange(s.nheads); hp[list(pair)] = hp[list(pair)][::-1]
+    i_cl = int(np.searchsorted(he, pair[0], side="right"))
+    c_end = sc.chan_cluster_end.reshape(s.ngroups, s.m, s.n)[0, i_cl]
+    cp = np.arange(s.headdim); cp[:c_end[0]] = cp[:c_end[0]][::-1]
+    p2 = dict(prob)
+    p2["x"] = np.ascontiguousarray(prob["x"][:, :, hp][..., cp]); p2["dt"] = np.ascontiguousarray(prob["dt"][:, :, hp])
+    p2["A"] = prob["A"][hp].copy(); p2["D"] = prob["D"][hp].copy()
+    y1, h1 = run_prefill(gpu_lib, s, sc, prob)
+    y2, h2 = run_prefill(gpu_lib, s, sc, p2)
+    assert np.array_equal(y2, y1[:, :, hp][..., cp]) and np.array_equal(h2, h1[:, hp][:, :, cp])
+
+
+def test_prefill_then_decode_matches_longer_prefill(gpu_lib):
+    """The final state is the resumable object: prefill(L) + k decode steps == prefill(L + k)."""
+    import torch
+    q = gpu_lib
+    s = W.CONFIGS["m2_8b_b1"].with_(seqlen=512 + 4, nheads=32, ngroups=2)
+    sc, prob, _ = make_problem(s, 6, calib_tokens=256)
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"])
+    k = 4
+    head = {n: (v[:, :-k].copy() if n in ("x", "B", "C", "dt") else v) for n, v in prob.items()}
+    yg, hg = run_prefill(q, s.with_(seqlen=512), sc, head)
+    dsc = q.DeviceScales(host_scales(q, sc))
+    st = torch.from_numpy(hg.astype(np.float32)).cuda()
+    A = torch.from_numpy(prob["A"]).cuda(); D = torch.from_numpy(prob["D"]).cuda()
+    y1 = torch.empty((1, s.nheads, s.headdim), dtype=torch.float16, device="cuda")
+    scale = np.abs(yref).max()
+    assert np.abs(yg - yref[:, :-k]).max() <= Y_TOL * scale
+    for i in range(512, 512 + k):
+        t = {n: torch.from_numpy(np.ascontiguousarray(prob[n][:, i])).cuda() for n in ("x", "B", "C", "dt")}
+        q.quamba_ssd_decode_step(to_shape(q, s), dsc, t["x"], t["B"], t["C"], t["dt"], A, D, st, y1)
+        assert np.abs(y1.cpu().numpy().astype(np.float64) - yref[:, i]).max() <= Y_TOL * scale
+    assert np.abs(st.cpu().numpy().astype(np.float64) - href).max() <= H_TOL * np.abs(href).max()
+
+
+def test_2p7b_shape_sampled(gpu_lib):
+    """configs[2] at full size (batch 8, 80 heads, heavy-tailed outlier channels, final states returned): the oracle
+    runs all heads of sequence 0 and one head of every other sequence; (b,h) pairs are independent."""
+    s = W.CONFIGS["m2_2p7b"]
+    sc, prob, _ = make_problem(s, 2)
+    pairs = [(0, h) for h in range(s.nheads)] + [(b, (11 * b) % s.nheads) for b in range(1, s.batch)]
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"], pairs=pairs)
+    yg, hg = run_prefill(gpu_lib, s, sc, prob)
+    ygs = np.stack([yg[b, :, h] for b, h in pairs]); hgs = np.stack([hg[b, h] for b, h in pairs])
+    assert np.isfinite(yg).all() and np.isfinite(hg).all()
+    check(ygs, hgs, yref, href, "2.7B-shaped sampled")
+
+
+@pytest.mark.parametrize("batch", [1, 4])
+def test_8b_shape_sampled(gpu_lib, batch):
+    """configs[3] at full size, in the launch configuration bench.py times; the oracle runs 40 sampled (b,h) pairs
+    (at least one per state group and per sequence)."""
+    s = W.CONFIGS["m2_8b_b4"].with_(batch=batch)
+    sc, prob, _ = make_problem(s, 3)
+    rng = np.random.default_rng(batch)
+    pairs = sorted({(int(b), int(h)) for b, h in zip(rng.integers(0, batch, 24), rng.integers(0, s.nheads, 24))}
+                   | {(b % batch, 16 * g + (5 * g + b) % 16) for g in range(8) for b in range(2)})
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"], pairs=pairs)
+    yg, hg = run_prefill(gpu_lib, s, sc, prob)
+    assert np.isfinite(yg).all() and np.isfinite(hg).all()
+    ygs = np.stack([yg[b, :, h] for b, h in pairs]); hgs = np.stack([hg[b, h] for b, h in pairs])
+    check(ygs, hgs, yref, href, f"8B-shaped b={batch} sampled")
+    # without the final state the same y must come out (the state output only switches precision of the state path)
+    yg2, _ = run_prefill(gpu_lib, s, sc, prob, want_state=False)
+    ygs2 = np.stack([yg2[b, :, h] for b, h in pairs])
+    check(ygs2, None, yref, None, f"8B-shaped b={batch} sampled, no state")
