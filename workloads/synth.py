@@ -163,9 +163,9 @@ def apply_reorder(raw: dict, head_perm: np.ndarray, chan_perm: np.ndarray) -> di
     out = dict(raw)
     x = raw["x"][..., head_perm, :]
     idx = np.broadcast_to(chan_perm.reshape((1,) * (x.ndim - 2) + chan_perm.shape), x.shape)
-    out["x"] = np.take_along_axis(x, idx, axis=-1)
-    out["dt"] = raw["dt"][..., head_perm]
+    out["x"] = np.ascontiguousarray(np.take_along_axis(x, idx, axis=-1))
+    out["dt"] = np.ascontiguousarray(raw["dt"][..., head_perm])
     for k in ("A", "D"):
         if k in raw:
-            out[k] = raw[k][head_perm]
+            out[k] = np.ascontiguousarray(raw[k][head_perm])
     return out
