@@ -46,9 +46,14 @@ quamba::SsdArgs pack(const quamba_ssd_shape_t *s, const quamba_ssd_scales_t *sc,
     return a;
 }
 
-bool use_mfma(const quamba_ssd_shape_t *s)
+bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
+
+// The chunked MFMA kernel moves 16-byte vectors; tensors a caller sliced to an odd offset take the generic kernel.
+bool use_mfma(const quamba_ssd_shape_t *s, const void *x, const void *B, const void *C, const void *y,
+              const void *init, const void *fin)
 {
-    return !(s->flags & QUAMBA_FLAG_GENERIC_KERNEL) && quamba::prefill_mfma_supports(*s);
+    return !(s->flags & QUAMBA_FLAG_GENERIC_KERNEL) && quamba::prefill_mfma_supports(*s) && aligned16(x) &&
+           aligned16(B) && aligned16(C) && aligned16(y) && aligned16(init) && aligned16(fin);
 }
 
 }  // namespace
@@ -72,12 +77,12 @@ extern "C" int quamba_ssd_prefill(const quamba_ssd_shape_t *shape, const quamba_
     if (rc != QUAMBA_OK) return rc;
     const size_t need = quamba_ssd_prefill_workspace_size(shape);
     if (workspace_bytes < need || (need && !workspace)) return QUAMBA_EWORKSPACE;
-    if (!use_mfma(shape) && quamba::prefill_generic_lds_bytes(*shape) > kMaxLdsBytes) return QUAMBA_ESHAPE;
+    const bool mfma = use_mfma(shape, x, B, C, y, init_state, final_state);
+    if (!mfma && quamba::prefill_generic_lds_bytes(*shape) > kMaxLdsBytes) return QUAMBA_ESHAPE;
 
     const quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, A, D, init_state, final_state, y);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const hipError_t e = use_mfma(shape) ? quamba::launch_prefill_mfma(a, stream)
-                                         : quamba::launch_prefill_generic(a, stream);
+    const hipError_t e = mfma ? quamba::launch_prefill_mfma(a, stream) : quamba::launch_prefill_generic(a, stream);
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }
 
