@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the 8-bit SSD hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload m2_8b_b4] [--no-cpu]
+
+A "step" is one pass of the hot path over one batch of synthetic input: one chunked prefill of the
+Mamba2-8B-shaped layer (batch 4 x 4096 tokens, 128 heads x 64, d_state 128, 8 state groups, chunk 256).  The
+decode state update (batch 256, 1 GiB fp32 state) is timed in the same run, K steps as well, and reported in the
+"decode" object.  Inputs are seeded synthetic tensors, resident in HBM before the timed regions; the offline
+sort-and-cluster and the quantizer run through the library's own host entry points.  The fp64 CPU oracle is
+timed on a bounded sample of the same workload for the "cpu_baseline" object (and doubles as a parity spot check).
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as W  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16/bf16
+MFMA_I8_PEAK_TOPS = 5000.0     # dense int8
+
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel of known
+# size); see profiles/.  None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def prefill_algorithmic(s: W.LayerShape):
+    """Algorithmic work per token per layer: causal lower triangle only, nothing for padding or recomputation."""
+    H, P, N, G, Q = s.nheads, s.headdim, s.d_state, s.ngroups, s.chunk
+    f16_macs = H * ((Q + 1) / 2 * P + 2 * N * P)
+    i8_macs = G * (Q + 1) / 2 * N
+    nbytes = H * P + 2 * G * N + 4 * H + 2 * H * P
+    return f16_macs, i8_macs, nbytes
+
+
+def decode_bytes(s: W.LayerShape) -> float:
+    b, H, P, N, G = s.batch, s.nheads, s.headdim, s.d_state, s.ngroups
+    return float(2 * 4 * b * H * P * N + b * H * P + 2 * b * G * N + 4 * b * H + 2 * b * H * P)
+
+
+def build_problem(q, s: W.LayerShape, seed: int):
+    """Quantized inputs in sorted/clustered order, made with the library's own offline entry points."""
+    xmax, bmax, cmax = W.draw_calibration(s, seed, tokens=2048)
+    head_perm, chan_perm, hs = q.quamba_reorder_params(s.nheads, s.headdim, s.ngroups, s.m, s.n, s.d_state,
+                                                       xmax, bmax, cmax)
+    shape = q.Shape(batch=s.batch, seqlen=s.seqlen, nheads=s.nheads, headdim=s.headdim, d_state=s.d_state,
+                    ngroups=s.ngroups, chunk=s.chunk, n_head_clusters=s.m, n_chan_clusters=s.n, flags=0)
+    return shape, hs, head_perm, chan_perm
+
+
+def quantize_layer(q, shape, hs, raw):
+    return {"x": q.quamba_quantize_x(shape, hs, raw["x"]),
+            "B": q.quamba_quantize_groups(raw["B"], hs.B_scales),
+            "C": q.quamba_quantize_groups(raw["C"], hs.C_scales),
+            "dt": np.ascontiguousarray(raw["dt"], np.float32)}
+
+
+def time_region(torch, fn, steps, warmup):
+    """Mean ms per call over `steps` calls on torch's current stream (the stream the kernels are launched on),
+    bracketed by device synchronisation; HIP events give the device-side duration."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        fn()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return ev0.elapsed_time(ev1) / steps, wall_ms / steps
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="m2_8b_b4", choices=["m2_8b_b4", "m2_8b_b1", "m2_2p7b", "m2_130m"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode leg")
+    ap.add_argument("--precise-state", action="store_true", help="also return the final fp32 state (two-term state path)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by sequence or by "
+              "state group with no exchange, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2503_22879_amd as q
+    q.load_library()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    seed = 3
+
+    # ------------------------------------------------------------------ prefill
+    s = W.CONFIGS[args.workload]
+    shape, hs, head_perm, chan_perm = build_problem(q, s, seed)
+    raw = W.apply_reorder(W.draw_layer(s, seed), head_perm, chan_perm)
+    prob = quantize_layer(q, shape, hs, raw)
+    A_np, D_np = raw["A"], raw["D"]
+    del raw
+    dsc = q.DeviceScales(hs, dev)
+    t = {k: torch.from_numpy(v).to(dev) for k, v in prob.items()}
+    A = torch.from_numpy(A_np).to(dev)
+    D = torch.from_numpy(D_np).to(dev)
+    y = torch.empty((s.batch, s.seqlen, s.nheads, s.headdim), dtype=torch.float16, device=dev)
+    fin = torch.empty((s.batch, s.nheads, s.headdim, s.d_state), device=dev) if args.precise_state else None
+    ws = torch.empty(max(1, q.quamba_ssd_prefill_workspace_size(shape)), dtype=torch.uint8, device=dev)
+
+    def prefill():
+        q.quamba_ssd_prefill(shape, dsc, t["x"], t["B"], t["C"], t["dt"], A, D, None, y, fin, ws)
+
+    ms, wall_ms = time_region(torch, prefill, args.steps, args.warmup)
+    tokens = s.batch * s.seqlen
+    f16_macs, i8_macs, bytes_tok = prefill_algorithmic(s)
+    flops_equiv = tokens * (2 * f16_macs + 2 * i8_macs * (MFMA_F16_PEAK_TFLOPS / MFMA_I8_PEAK_TOPS))
+    tflops = flops_equiv / (ms * 1e-3) / 1e12
+    gbs = tokens * bytes_tok / (ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
+
+    out = {
+        "metric": "int8 SSD prefill tokens/s/layer", "value": tokens / (ms * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "wall_ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8 x/B/C, fp16 MFMA, fp32 acc",
+        "data": "synthetic",
+        "config": {"workload": f"{s.name}: Mamba2-8B-shaped SSD layer prefill" if "8b" in s.name else s.name,
+                   "batch": s.batch, "seqlen": s.seqlen, "nheads": s.nheads, "headdim": s.headdim,
+                   "d_state": s.d_state, "ngroups": s.ngroups, "chunk": s.chunk, "clusters": f"{s.m}x{s.n} per group",
+                   "final_state": bool(args.precise_state)},
+        "roofline": {"kernel": "prefill_mfma_kernel", "bound": "mfma", "achieved": tflops,
+                     "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_F16_PEAK_TFLOPS,
+                     "traffic": traffic,
+                     "note": "algorithmic causal MACs; int8 MACs weighted by fp16/int8 peak ratio"},
+        "roofline_hbm": {"kernel": "prefill_mfma_kernel", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": traffic},
+    }
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample
+    if not args.no_cpu:
+        import oracle
+        sc = oracle.Scales(s.m, s.n, hs.x_scales, hs.head_cluster_end, hs.chan_cluster_end, hs.B_scales, hs.C_scales)
+        nseq = min(2, s.batch)
+        pairs = [(b, h) for b in range(nseq) for h in range(s.nheads)]
+        t0 = time.perf_counter()
+        yref, _, threads = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], A_np, D_np,
+                                              pairs=pairs, want_state=False)
+        cpu_s = time.perf_counter() - t0
+        yg = y[:nseq].float().cpu().numpy().transpose(0, 2, 1, 3).reshape(len(pairs), s.seqlen, s.headdim)
+        err = float(np.abs(yg - yref).max() / np.abs(yref).max())
+        out["cpu_baseline"] = {"value": nseq * s.seqlen / cpu_s, "unit": "tokens/s", "cores": int(threads),
+                               "kind": "oracle", "seconds": cpu_s,
+                               "sample": f"sequences 0..{nseq - 1} of the prefill workload, all {s.nheads} heads "
+                                         f"({nseq * s.seqlen} tokens), fp64 sequential scan"}
+        out["parity_spot_check"] = {"max_abs_err_over_max_abs_ref": err, "bar": 2e-3, "pairs": len(pairs)}
+        del yref, yg
+
+    # ------------------------------------------------------------------ decode
+    if not args.no_decode:
+        del t, y, prob
+        torch.cuda.empty_cache()
+        sd = W.CONFIGS["m2_8b_decode"]
+        dshape, dhs, dhp, dcp = build_problem(q, sd, seed)
+        ddsc = q.DeviceScales(dhs, dev)
+        rawp = W.apply_reorder({k: v for k, v in W.draw_layer(sd.with_(batch=1, seqlen=1), seed).items()
+                                if k in ("A", "D", "x", "dt")}, dhp, dcp)
+        dA = torch.from_numpy(rawp["A"]).to(dev)
+        dD = torch.from_numpy(rawp["D"]).to(dev)
+        nsets = sd.decode_steps
+        steps_in = []
+        for k in range(nsets):
+            r = W.apply_reorder(W.draw_decode_step(sd, seed, k), dhp, dcp)
+            qd = quantize_layer(q, dshape, dhs, r)
+            steps_in.append({n: torch.from_numpy(v).to(dev) for n, v in qd.items()})
+        state = torch.from_numpy(W.draw_state(sd, seed)).to(dev)
+        yd = torch.empty((sd.batch, sd.nheads, sd.headdim), dtype=torch.float16, device=dev)
+        counter = [0]
+
+        def decode():
+            i = steps_in[counter[0] % nsets]
+            counter[0] += 1
+            q.quamba_ssd_decode_step(dshape, ddsc, i["x"], i["B"], i["C"], i["dt"], dA, dD, state, yd)
+
+        dsteps = max(args.steps, sd.decode_steps)
+        dms, dwall = time_region(torch, decode, dsteps, max(args.warmup, 4))
+        dgbs = decode_bytes(sd) / (dms * 1e-3) / 1e9
+        out["decode"] = {
+            "metric": "decode state update us/step", "value": dms * 1e3, "unit": "us/step", "steps": dsteps,
+            "higher_is_better": False, "wall_us_per_step": dwall * 1e3,
+            "config": {"workload": "m2_8b_decode: batch 256, 128 heads x 64, d_state 128, fp32 state 1 GiB in place"},
+            "roofline": {"kernel": "decode_vec_kernel", "bound": "hbm", "achieved": dgbs, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": dgbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get("m2_8b_decode")},
+            "finite": bool(torch.isfinite(state).all().item()),
+        }
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
