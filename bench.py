@@ -154,7 +154,7 @@ def main() -> int:
     if not args.no_cpu:
         import oracle
         sc = oracle.Scales(s.m, s.n, hs.x_scales, hs.head_cluster_end, hs.chan_cluster_end, hs.B_scales, hs.C_scales)
-        nseq = min(2, s.batch)
+        nseq = s.batch
         pairs = [(b, h) for b in range(nseq) for h in range(s.nheads)]
         t0 = time.perf_counter()
         yref, _, threads = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], A_np, D_np,

@@ -9,8 +9,10 @@
 //   x'[s,p]    = xq[s,p] * exp(m_sb - cum_s) * dt_s                      fp16, staged once per chunk in LDS
 //   off-diagonal block pair (sb < tb):  Y^T[p,t] += x'^T[p,s] * (G^T[s,t] * exp(cum_t - m_sb))      fp16 MFMA
 //   diagonal block (sb = tb):           Y^T[p,t] += xq^T[p,s] * (G^T[s,t] * exp(cum_t - cum_s) dt_s [s <= t])
-//   carried state:                      Y^T[p,t] += exp(cum_t) * sum_n H[p,n] Cq[t,n]               fp16 MFMA
-//   state, block by block:              H <- exp(m_sb - m_{sb-1}) H + sum_{s in sb} x'[s,:]^T Bq[s,:] fp16 MFMA
+//   carried state:                      Y^T[p,t] += sum_n H[p,n] (exp(cum_t) Cq[t,n])               fp16 MFMA
+//   state:   H <- exp(cum_last) H + sum_sb sum_{s in sb} x'[s,:]^T (exp(cum_last - m_sb) Bq[s,:])   fp16 MFMA
+//            (when the final state is returned: H <- exp(m_sb - m_{sb-1}) H + x'^T Bq block by block in fp32,
+//             with x' split into two fp16 terms, so that the state meets 1e-4 of its maximum)
 //   y[t,p]     = s_x(h,p) * (s_B s_C * Y[t,p] + D_h xq[t,p])             fp32 epilogue, fp16 store
 //
 // which is Eq. 2 with A-dot = exp(dt A), B-dot = dt B (Section 3.2) regrouped; the quantization scales of
@@ -41,6 +43,7 @@ constexpr int kBtStride = 264;  // bytes per row of Bq^T [n][token]
 constexpr int kXsStride = 264;  // halves per row of x'^T [p][token]
 constexpr int kHsStride = 136;  // halves per row of H [p][n]
 constexpr int kYsStride = 72;   // halves per row of the per-wave y staging tile [t][p]
+constexpr int kBqStride = 144;  // bytes per row of Bq [token][n] (operand of the G^T product)
 constexpr float kNarrow = 1.0f / 128.0f;  // applied to G and H before narrowing to fp16; undone in the epilogue
 
 // LDS map (bytes)
@@ -53,12 +56,13 @@ constexpr int kOffBt = kOffXq + kP * kXqStride;             // int8 [128][264]
 constexpr int kOffHs = kOffBt + kN * kBtStride;             // fp16 [64][136]
 constexpr int kOffYs = kOffHs + 2 * kP * kHsStride;         // fp16 [4][32][72]
 constexpr int kOffXs = kOffYs + 2 * 4 * kBlk * kYsStride;   // fp16 [64][264]
-constexpr int kOffXl = kOffXs + 2 * kP * kXsStride;         // fp16 [64][264]  (two-term state path only)
-constexpr int kLdsFast = kOffXl;
-constexpr int kLdsPrecise = kOffXl + 2 * kP * kXsStride;
+constexpr int kOffVar = kOffXs + 2 * kP * kXsStride;        // fast path: Bq row-major int8 [256][144];
+                                                            // two-term state path: low halves of x', fp16 [64][264]
+constexpr int kLdsFast = kOffVar + kQ * kBqStride;
+constexpr int kLdsPrecise = kOffVar + 2 * kP * kXsStride;
 static_assert(kOffXq % 16 == 0 && kOffBt % 16 == 0 && kOffHs % 16 == 0 && kOffYs % 16 == 0 && kOffXs % 16 == 0 &&
-                  kOffXl % 16 == 0, "LDS arrays must be 16-byte aligned");
-static_assert(kLdsPrecise <= 160 * 1024, "exceeds the LDS of a gfx950 compute unit");
+                  kOffVar % 16 == 0, "LDS arrays must be 16-byte aligned");
+static_assert(kLdsPrecise <= 160 * 1024 && kLdsFast <= 160 * 1024, "exceeds the LDS of a gfx950 compute unit");
 
 // Storage position of token s of the chunk inside an LDS row: bits 2 and 3 swapped (see file comment).
 __device__ __forceinline__ int tok_pos(int s) { return (s & ~12) | ((s & 4) << 1) | ((s & 8) >> 1); }
@@ -111,12 +115,14 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
     unsigned char *s_bt = smem + kOffBt;
     _Float16 *s_hs = reinterpret_cast<_Float16 *>(smem + kOffHs);
     _Float16 *s_xs = reinterpret_cast<_Float16 *>(smem + kOffXs);
-    _Float16 *s_xl = reinterpret_cast<_Float16 *>(smem + kOffXl);
+    _Float16 *s_xl = reinterpret_cast<_Float16 *>(smem + kOffVar);  // PRECISE only
+    unsigned char *s_bq = smem + kOffVar;                           // !PRECISE only
 
     const int L = a.s.seqlen, H = a.s.nheads, G = a.s.ngroups;
     const int bh = blockIdx.x;
     const int b = bh / H, h = bh - b * H, g = h / (H / G);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps block indices in scalar registers
     const int l32 = lane & 31, hb = lane >> 5;
     _Float16 *s_ys = reinterpret_cast<_Float16 *>(smem + kOffYs) + wave * kBlk * kYsStride;
 
@@ -151,34 +157,60 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
     }
 
     const int nchunks = (L + kQ - 1) / kQ;
+
+    // Registers that carry one chunk's global loads from the point of issue (during the previous chunk's
+    // compute phase) to the staging phase: x codes (1 item: 4 tokens x 16 channels), B codes (2 items: 4 tokens x
+    // 16 states), dt of token tid, and the C rows of this wave's two 32-token output blocks.
+    u32x4 xr[4], br[2][4];
+    i32x4 cA[4], cB[4];
+    float dtv;
+    auto load_c_rows = [&](int c, int tb, i32x4(&ct)[4]) {
+        const int nv = min(kQ, L - c * kQ);
+        const int tl = tb * kBlk + l32;
+        const int8_t *crow = a.C + (((size_t)b * L + c * kQ + min(tl, nv - 1)) * G + g) * kN + hb * 64;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const i32x4 v = *reinterpret_cast<const i32x4 *>(crow + 16 * kk);
+            ct[kk] = tl < nv ? v : (i32x4){0, 0, 0, 0};
+        }
+    };
+    auto issue_loads = [&](int c) {
+        const int t0 = c * kQ;
+        const int nv = min(kQ, L - t0);
+        const size_t tokbase = (size_t)b * L + t0;
+        {
+            const int s4 = tid >> 2, p16 = tid & 3;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int s = 4 * s4 + k;  // rows past the end are read from the last valid row and zeroed
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(a.x + ((tokbase + min(s, nv - 1)) * H + h) * kP + 16 * p16);
+                xr[k] = s < nv ? v : (u32x4){0u, 0u, 0u, 0u};
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int item = tid + kThreads * i, s4 = item >> 3, n16 = item & 7;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int s = 4 * s4 + k;
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(a.B + ((tokbase + min(s, nv - 1)) * G + g) * kN + 16 * n16);
+                br[i][k] = s < nv ? v : (u32x4){0u, 0u, 0u, 0u};
+            }
+        }
+        {
+            const float v = a.dt[(tokbase + min(tid, nv - 1)) * H + h];
+            dtv = tid < nv ? v : 0.0f;
+        }
+    };
+    issue_loads(0);
+    load_c_rows(0, wave, cA);
+
     for (int c = 0; c < nchunks; ++c) {
         const int t0 = c * kQ;
         const int nv = min(kQ, L - t0);  // valid tokens of this chunk
         const size_t tokbase = (size_t)b * L + t0;
 
-        // ---- global loads of the chunk's x and B codes (consumed after the scan) ----
-        uint32_t xr[4][4], br[8][4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int item = tid + kThreads * i, p4 = item & 15, s4 = item >> 4;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int s = 4 * s4 + k;
-                xr[i][k] = s < nv ? *reinterpret_cast<const uint32_t *>(a.x + ((tokbase + s) * H + h) * kP + 4 * p4) : 0u;
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int item = tid + kThreads * i, n4 = item & 31, s4 = item >> 5;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int s = 4 * s4 + k;
-                br[i][k] = s < nv ? *reinterpret_cast<const uint32_t *>(a.B + ((tokbase + s) * G + g) * kN + 4 * n4) : 0u;
-            }
-        }
-
-        // ---- dt and the inclusive prefix sum of dt*A over the chunk ----
-        const float dtv = tid < nv ? a.dt[(tokbase + tid) * H + h] : 0.0f;
+        // ---- inclusive prefix sum of dt*A over the chunk ----
         float scan = dtv * Ah;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -206,10 +238,9 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
         }
         __syncthreads();
 
-        // ---- x^T (codes and scaled fp16) and B^T (codes) into LDS, token positions permuted ----
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int item = tid + kThreads * i, p4 = item & 15, s4 = item >> 4;
+        // ---- x^T (codes and scaled fp16) and B^T (codes) into LDS, token positions permuted; B row-major ----
+        {
+            const int s4 = tid >> 2, p16 = tid & 3;
             const int s0 = 4 * s4, q = tok_pos(s0);
             const float m = s_cum[(s0 & ~31) + 31];
             float colf[4], c128[4];
@@ -218,53 +249,95 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                 colf[k] = __expf(m - s_cum[s0 + k]) * s_dt[s0 + k];
                 c128[k] = -128.0f * colf[k];
             }
-            uint32_t col[4];
-            transpose4x4(xr[i], col);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int p = 4 * p4 + j;
-                *reinterpret_cast<uint32_t *>(s_xq + p * kXqStride + q) = col[j];
-                const uint32_t u = col[j] ^ 0x80808080u;
-                float v[4];
+            for (int c4 = 0; c4 < 4; ++c4) {
+                const uint32_t rows[4] = {xr[0][c4], xr[1][c4], xr[2][c4], xr[3][c4]};
+                uint32_t col[4];
+                transpose4x4(rows, col);
 #pragma unroll
-                for (int k = 0; k < 4; ++k) v[k] = fmaf((float)((u >> (8 * k)) & 0xffu), colf[k], c128[k]);
-                f16x4 hi;
+                for (int j = 0; j < 4; ++j) {
+                    const int p = 16 * p16 + 4 * c4 + j;
+                    *reinterpret_cast<uint32_t *>(s_xq + p * kXqStride + q) = col[j];
+                    const uint32_t u = col[j] ^ 0x80808080u;
+                    float v[4];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) hi[k] = (_Float16)v[k];
-                *reinterpret_cast<f16x4 *>(s_xs + p * kXsStride + q) = hi;
-                if (PRECISE) {
-                    f16x4 lo;
+                    for (int k = 0; k < 4; ++k) v[k] = fmaf((float)((u >> (8 * k)) & 0xffu), colf[k], c128[k]);
+                    f16x4 hi;
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) lo[k] = (_Float16)(v[k] - (float)hi[k]);
-                    *reinterpret_cast<f16x4 *>(s_xl + p * kXsStride + q) = lo;
+                    for (int k = 0; k < 4; ++k) hi[k] = (_Float16)v[k];
+                    *reinterpret_cast<f16x4 *>(s_xs + p * kXsStride + q) = hi;
+                    if (PRECISE) {
+                        f16x4 lo;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) lo[k] = (_Float16)(v[k] - (float)hi[k]);
+                        *reinterpret_cast<f16x4 *>(s_xl + p * kXsStride + q) = lo;
+                    }
                 }
             }
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int item = tid + kThreads * i, n4 = item & 31, s4 = item >> 5;
+        for (int i = 0; i < 2; ++i) {
+            const int item = tid + kThreads * i, s4 = item >> 3, n16 = item & 7;
             const int q = tok_pos(4 * s4);
-            uint32_t col[4];
-            transpose4x4(br[i], col);
+            if (!PRECISE) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) *reinterpret_cast<uint32_t *>(s_bt + (4 * n4 + j) * kBtStride + q) = col[j];
+                for (int k = 0; k < 4; ++k)
+                    *reinterpret_cast<u32x4 *>(s_bq + (4 * s4 + k) * kBqStride + 16 * n16) = br[i][k];
+            }
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) {
+                const uint32_t rows[4] = {br[i][0][c4], br[i][1][c4], br[i][2][c4], br[i][3][c4]};
+                uint32_t col[4];
+                transpose4x4(rows, col);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<uint32_t *>(s_bt + (16 * n16 + 4 * c4 + j) * kBtStride + q) = col[j];
+            }
         }
         __syncthreads();
+
+        // the next chunk's global loads fly while this chunk is computed
+        if (c + 1 < nchunks) issue_loads(c + 1);
+        load_c_rows(c, kNBlk - 1 - wave, cB);
 
         // ---- outputs: each wave owns the 32-token blocks tb = wave and 7 - wave (equal causal work) ----
         for (int which = 0; which < 2; ++which) {
             const int tb = which ? (kNBlk - 1 - wave) : wave;
-            if (tb * kBlk >= nv) continue;
+            if (tb * kBlk >= nv) continue;  // only in the last chunk: nothing is prefetched after it
             const int tl = tb * kBlk + l32;  // this lane's token inside the chunk
-            const bool t_ok = tl < nv;
             i32x4 ct[4];
-            {
-                const int8_t *crow = a.C + ((tokbase + tl) * G + g) * kN + hb * 64;
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    ct[kk] = t_ok ? *reinterpret_cast<const i32x4 *>(crow + 16 * kk) : (i32x4){0, 0, 0, 0};
-            }
+            for (int kk = 0; kk < 4; ++kk) ct[kk] = which ? cB[kk] : cA[kk];
+            if (which == 0 && c + 1 < nchunks) load_c_rows(c + 1, wave, cA);  // consumed in the next chunk
             const float cum_t = s_cum[tl];
+
+            // B rows of block sb as the A operand of G^T (from LDS, or from global on the two-term state path)
+            auto load_bq = [&](int sb, i32x4(&bq)[4]) {
+                if (!PRECISE) {
+                    const unsigned char *row = s_bq + (sb * kBlk + l32) * kBqStride + hb * 64;
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) bq[kk] = *reinterpret_cast<const i32x4 *>(row + 16 * kk);
+                } else {
+                    const int sl = sb * kBlk + l32;
+                    const int8_t *brow = a.B + ((tokbase + min(sl, nv - 1)) * G + g) * kN + hb * 64;
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) {
+                        const i32x4 v = *reinterpret_cast<const i32x4 *>(brow + 16 * kk);
+                        bq[kk] = sl < nv ? v : (i32x4){0, 0, 0, 0};
+                    }
+                }
+            };
+            auto gemm_g = [&](const i32x4(&bq)[4]) {
+                i32x16 gi;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) gi[r] = 0;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) gi = __builtin_amdgcn_mfma_i32_32x32x32_i8(bq[kk], ct[kk], gi, 0, 0, 0);
+                return gi;
+            };
+            i32x4 bq[4];
+            load_bq(0, bq);
+            i32x16 gi = gemm_g(bq);
 
             // carried-state term: Y^T[p,t] = exp(cum_t) * sum_n H[p,n] Cq[t,n]
             f32x16 acc[2];
@@ -272,71 +345,61 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
             for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[pt][r] = 0.0f;
+            const _Float16 e_t = (_Float16)__expf(cum_t);  // per lane (token t); folded into the C operand
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                const f16x8 cf = i8x8_to_f16((uint32_t)ct[kk >> 1][2 * (kk & 1)], (uint32_t)ct[kk >> 1][2 * (kk & 1) + 1]);
+                const f16x8 cf =
+                    i8x8_to_f16((uint32_t)ct[kk >> 1][2 * (kk & 1)], (uint32_t)ct[kk >> 1][2 * (kk & 1) + 1]) * e_t;
 #pragma unroll
                 for (int pt = 0; pt < 2; ++pt) {
                     const f16x8 hf = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32) * kHsStride + hb * 64 + 8 * kk);
                     acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf, cf, acc[pt], 0, 0, 0);
                 }
             }
-            {
-                const float e = __expf(cum_t);
-#pragma unroll
-                for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[pt][r] *= e;
-            }
 
-            // intra-chunk term, block pairs (sb <= tb)
-            for (int sb = 0; sb <= tb; ++sb) {
-                const int sl = sb * kBlk + l32;
-                i32x4 bq[4];
-                {
-                    const int8_t *brow = a.B + ((tokbase + sl) * G + g) * kN + hb * 64;
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk)
-                        bq[kk] = sl < nv ? *reinterpret_cast<const i32x4 *>(brow + 16 * kk) : (i32x4){0, 0, 0, 0};
-                }
-                i32x16 gi;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) gi[r] = 0;
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) gi = __builtin_amdgcn_mfma_i32_32x32x32_i8(bq[kk], ct[kk], gi, 0, 0, 0);
-
+            // intra-chunk term, block pairs (sb <= tb); the G^T tile of the next pair is issued before this one is
+            // scaled and narrowed so that the matrix core and the vector ALU overlap inside the wave
+            for (int sb = 0; sb < tb; ++sb) {  // strictly lower block pairs
+                load_bq(sb + 1, bq);
+                const i32x16 gn = gemm_g(bq);
+                const float rowf = __expf(cum_t - s_cum[sb * kBlk + kBlk - 1]) * kNarrow;
                 float lv[16];
-                if (sb < tb) {
-                    const float rowf = __expf(cum_t - s_cum[sb * kBlk + kBlk - 1]) * kNarrow;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
-                } else {
-#pragma unroll
-                    for (int rg = 0; rg < 4; ++rg) {
-                        const int s0 = 8 * rg + 4 * hb;  // four consecutive tokens of the block
-                        const f32x4 cs = *reinterpret_cast<const f32x4 *>(s_cum + sb * kBlk + s0);
-                        const f32x4 ds = *reinterpret_cast<const f32x4 *>(s_dt + sb * kBlk + s0);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float w = __expf(fminf(cum_t - cs[i], 0.0f)) * ds[i] * kNarrow;
-                            lv[4 * rg + i] = (s0 + i <= l32) ? (float)gi[4 * rg + i] * w : 0.0f;
-                        }
-                    }
-                }
+                for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const int col = sb * kBlk + 16 * ks + 8 * hb;
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt) {
-                        f16x8 xa;
-                        if (sb < tb) {
-                            xa = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
-                        } else {
-                            const u32x2 w = *reinterpret_cast<const u32x2 *>(s_xq + (pt * 32 + l32) * kXqStride + col);
-                            xa = i8x8_to_f16(w[0], w[1]);
-                        }
+                        const f16x8 xa = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
                         acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa, ks ? l1 : l0, acc[pt], 0, 0, 0);
+                    }
+                }
+                gi = gn;
+            }
+            {  // diagonal block pair: per-element decay, causal mask, plain x codes
+                float lv[16];
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int s0 = 8 * rg + 4 * hb;  // four consecutive tokens of the block
+                    const f32x4 cs = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + s0);
+                    const f32x4 ds = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + s0);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        // exponent forced to a huge negative value above the diagonal: weight exactly 0, no branch
+                        const float arg = (s0 + i <= l32) ? fminf(cum_t - cs[i], 0.0f) : -1.0e30f;
+                        lv[4 * rg + i] = (float)gi[4 * rg + i] * (__expf(arg) * ds[i] * kNarrow);
+                    }
+                }
+                const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const int col = tb * kBlk + 16 * ks + 8 * hb;
+#pragma unroll
+                    for (int pt = 0; pt < 2; ++pt) {
+                        const u32x2 w = *reinterpret_cast<const u32x2 *>(s_xq + (pt * 32 + l32) * kXqStride + col);
+                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(i8x8_to_f16(w[0], w[1]), ks ? l1 : l0, acc[pt], 0, 0, 0);
                     }
                 }
             }
@@ -367,29 +430,53 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
             __builtin_amdgcn_wave_barrier();
         }
 
-        // ---- state update, 32 tokens at a time: wave w owns states n in [32w, 32w+32) ----
-        float m_prev = 0.0f;
-        for (int sb = 0; sb < kNBlk; ++sb) {
-            if (sb * kBlk >= nv) break;  // the padded steps are identity steps
-            const float m = s_cum[sb * kBlk + kBlk - 1];
-            const float gdec = __expf(m - m_prev);
-            m_prev = m;
+        // ---- state update: wave w owns states n in [32w, 32w+32) ----
+        if (PRECISE) {
+            float m_prev = 0.0f;
+            for (int sb = 0; sb < kNBlk; ++sb) {
+                if (sb * kBlk >= nv) break;  // the padded steps are identity steps
+                const float m = s_cum[sb * kBlk + kBlk - 1];
+                const float gdec = __expf(m - m_prev);
+                m_prev = m;
 #pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
+                for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
+                    for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const int col = sb * kBlk + 16 * ks + 8 * hb;
-                const u32x2 w = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride + col);
-                const f16x8 bf = i8x8_to_f16(w[0], w[1]);
+                for (int ks = 0; ks < 2; ++ks) {
+                    const int col = sb * kBlk + 16 * ks + 8 * hb;
+                    const u32x2 w = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride + col);
+                    const f16x8 bf = i8x8_to_f16(w[0], w[1]);
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt) {
-                    const f16x8 xb = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
-                    st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb, st[pt], 0, 0, 0);
-                    if (PRECISE) {
+                    for (int pt = 0; pt < 2; ++pt) {
+                        const f16x8 xb = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
                         const f16x8 xlo = *reinterpret_cast<const f16x8 *>(s_xl + (pt * 32 + l32) * kXsStride + col);
+                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb, st[pt], 0, 0, 0);
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xlo, st[pt], 0, 0, 0);
+                    }
+                }
+            }
+        } else {
+            const float cum_last = s_cum[kQ - 1];  // padded steps leave cum flat, so this is cum at the last valid token
+            {
+                const float gdec = __expf(cum_last);
+#pragma unroll
+                for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
+            }
+            for (int sb = 0; sb < kNBlk; ++sb) {
+                if (sb * kBlk >= nv) break;
+                const _Float16 f = (_Float16)__expf(cum_last - s_cum[sb * kBlk + kBlk - 1]);
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const int col = sb * kBlk + 16 * ks + 8 * hb;
+                    const u32x2 w = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride + col);
+                    const f16x8 bf = i8x8_to_f16(w[0], w[1]) * f;
+#pragma unroll
+                    for (int pt = 0; pt < 2; ++pt) {
+                        const f16x8 xb = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
+                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb, st[pt], 0, 0, 0);
                     }
                 }
             }
