@@ -347,44 +347,74 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                 for (int r = 0; r < 16; ++r) acc[pt][r] = 0.0f;
             const _Float16 e_t = (_Float16)__expf(cum_t);  // per lane (token t); folded into the C operand
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const f16x8 cf =
-                    i8x8_to_f16((uint32_t)ct[kk >> 1][2 * (kk & 1)], (uint32_t)ct[kk >> 1][2 * (kk & 1) + 1]) * e_t;
+            for (int k4 = 0; k4 < 2; ++k4) {  // two batches of four k-steps: all LDS reads of a batch are issued first
+                f16x8 hf[4][2];
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt) {
-                    const f16x8 hf = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32) * kHsStride + hb * 64 + 8 * kk);
-                    acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf, cf, acc[pt], 0, 0, 0);
+                for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                    for (int pt = 0; pt < 2; ++pt)
+                        hf[kk][pt] = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32) * kHsStride + hb * 64 +
+                                                                     8 * (4 * k4 + kk));
+                __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const int k8 = 4 * k4 + kk;
+                    const f16x8 cf =
+                        i8x8_to_f16((uint32_t)ct[k8 >> 1][2 * (k8 & 1)], (uint32_t)ct[k8 >> 1][2 * (k8 & 1) + 1]) * e_t;
+#pragma unroll
+                    for (int pt = 0; pt < 2; ++pt)
+                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[kk][pt], cf, acc[pt], 0, 0, 0);
                 }
             }
 
             // intra-chunk term, block pairs (sb <= tb); the G^T tile of the next pair is issued before this one is
             // scaled and narrowed so that the matrix core and the vector ALU overlap inside the wave
             for (int sb = 0; sb < tb; ++sb) {  // strictly lower block pairs
+                // all LDS reads of the iteration first, then the next G^T tile (matrix core) under the scaling and
+                // narrowing of the current one (vector ALU), then the four Y^T products
                 load_bq(sb + 1, bq);
+                f16x8 xa[2][2];
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int pt = 0; pt < 2; ++pt)
+                        xa[ks][pt] = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + sb * kBlk +
+                                                                     16 * ks + 8 * hb);
+                const float m_sb = s_cum[sb * kBlk + kBlk - 1];
+                __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
                 const i32x16 gn = gemm_g(bq);
-                const float rowf = __expf(cum_t - s_cum[sb * kBlk + kBlk - 1]) * kNarrow;
+                const float rowf = __expf(cum_t - m_sb) * kNarrow;
                 float lv[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    const int col = sb * kBlk + 16 * ks + 8 * hb;
+                for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt) {
-                        const f16x8 xa = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
-                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa, ks ? l1 : l0, acc[pt], 0, 0, 0);
-                    }
-                }
+                    for (int pt = 0; pt < 2; ++pt)
+                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[ks][pt], ks ? l1 : l0, acc[pt], 0, 0, 0);
                 gi = gn;
             }
             {  // diagonal block pair: per-element decay, causal mask, plain x codes
+                u32x2 xw[2][2];
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int pt = 0; pt < 2; ++pt)
+                        xw[ks][pt] = *reinterpret_cast<const u32x2 *>(s_xq + (pt * 32 + l32) * kXqStride + tb * kBlk +
+                                                                     16 * ks + 8 * hb);
+                f32x4 cs4[4], ds4[4];
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {  // four consecutive tokens of the block per register group
+                    cs4[rg] = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + 8 * rg + 4 * hb);
+                    ds4[rg] = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + 8 * rg + 4 * hb);
+                }
+                __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
                 float lv[16];
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg) {
-                    const int s0 = 8 * rg + 4 * hb;  // four consecutive tokens of the block
-                    const f32x4 cs = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + s0);
-                    const f32x4 ds = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + s0);
+                    const int s0 = 8 * rg + 4 * hb;
+                    const f32x4 cs = cs4[rg], ds = ds4[rg];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         // exponent forced to a huge negative value above the diagonal: weight exactly 0, no branch
@@ -394,14 +424,11 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                 }
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    const int col = tb * kBlk + 16 * ks + 8 * hb;
+                for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt) {
-                        const u32x2 w = *reinterpret_cast<const u32x2 *>(s_xq + (pt * 32 + l32) * kXqStride + col);
-                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(i8x8_to_f16(w[0], w[1]), ks ? l1 : l0, acc[pt], 0, 0, 0);
-                    }
-                }
+                    for (int pt = 0; pt < 2; ++pt)
+                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(i8x8_to_f16(xw[ks][pt][0], xw[ks][pt][1]),
+                                                                         ks ? l1 : l0, acc[pt], 0, 0, 0);
             }
 
             // epilogue: scales, skip term, fp16, transposed through the wave's LDS tile, coalesced 16-byte stores
@@ -467,17 +494,25 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
             }
             for (int sb = 0; sb < kNBlk; ++sb) {
                 if (sb * kBlk >= nv) break;
-                const _Float16 f = (_Float16)__expf(cum_last - s_cum[sb * kBlk + kBlk - 1]);
+                u32x2 bw[2];
+                f16x8 xb[2][2];
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const int col = sb * kBlk + 16 * ks + 8 * hb;
-                    const u32x2 w = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride + col);
-                    const f16x8 bf = i8x8_to_f16(w[0], w[1]) * f;
+                    bw[ks] = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride + col);
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt) {
-                        const f16x8 xb = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
-                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb, st[pt], 0, 0, 0);
-                    }
+                    for (int pt = 0; pt < 2; ++pt)
+                        xb[ks][pt] = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
+                }
+                const float m_sb = s_cum[sb * kBlk + kBlk - 1];
+                __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
+                const _Float16 f = (_Float16)__expf(cum_last - m_sb);
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const f16x8 bf = i8x8_to_f16(bw[ks][0], bw[ks][1]) * f;
+#pragma unroll
+                    for (int pt = 0; pt < 2; ++pt)
+                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb[ks][pt], st[pt], 0, 0, 0);
                 }
             }
         }
