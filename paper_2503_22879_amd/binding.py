@@ -8,7 +8,7 @@ from dataclasses import dataclass
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libquamba_ssd.so")
+_LIB_PATH = os.environ.get("QUAMBA_SSD_LIBRARY", os.path.join(_PKG, "libquamba_ssd.so"))
 _lib = None
 
 FLAG_GENERIC_KERNEL = 0x1

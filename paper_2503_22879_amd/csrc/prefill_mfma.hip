@@ -169,12 +169,12 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
         const int tl = tb * kBlk + l32;
         const int8_t *crow = a.C + (((size_t)b * L + c * kQ + min(tl, nv - 1)) * G + g) * kN + hb * 64;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const i32x4 v = *reinterpret_cast<const i32x4 *>(crow + 16 * kk);
-            ct[kk] = tl < nv ? v : (i32x4){0, 0, 0, 0};
-        }
+        for (int kk = 0; kk < 4; ++kk) ct[kk] = *reinterpret_cast<const i32x4 *>(crow + 16 * kk);
     };
-    auto issue_loads = [&](int c) {
+    // Vector-memory results return in issue order, so the loads are issued in the order they are consumed
+    // (C rows of the second block of this chunk, x and dt of the next chunk, B of the next chunk, C rows of the
+    // first block of the next chunk) and spread over the compute phase instead of flooding the queue at once.
+    auto issue_x_loads = [&](int c) {
         const int t0 = c * kQ;
         const int nv = min(kQ, L - t0);
         const size_t tokbase = (size_t)b * L + t0;
@@ -182,27 +182,30 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
             const int s4 = tid >> 2, p16 = tid & 3;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int s = 4 * s4 + k;  // rows past the end are read from the last valid row and zeroed
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(a.x + ((tokbase + min(s, nv - 1)) * H + h) * kP + 16 * p16);
-                xr[k] = s < nv ? v : (u32x4){0u, 0u, 0u, 0u};
+                // rows past the end are read from the last valid row; they are zeroed where they are consumed, so
+                // that nothing here waits for the data
+                const int s = min(4 * s4 + k, nv - 1);
+                xr[k] = *reinterpret_cast<const u32x4 *>(a.x + ((tokbase + s) * H + h) * kP + 16 * p16);
             }
         }
+        dtv = a.dt[(tokbase + min(tid, nv - 1)) * H + h];
+    };
+    auto issue_b_loads = [&](int c) {
+        const int t0 = c * kQ;
+        const int nv = min(kQ, L - t0);
+        const size_t tokbase = (size_t)b * L + t0;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int item = tid + kThreads * i, s4 = item >> 3, n16 = item & 7;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int s = 4 * s4 + k;
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(a.B + ((tokbase + min(s, nv - 1)) * G + g) * kN + 16 * n16);
-                br[i][k] = s < nv ? v : (u32x4){0u, 0u, 0u, 0u};
+                const int s = min(4 * s4 + k, nv - 1);
+                br[i][k] = *reinterpret_cast<const u32x4 *>(a.B + ((tokbase + s) * G + g) * kN + 16 * n16);
             }
         }
-        {
-            const float v = a.dt[(tokbase + min(tid, nv - 1)) * H + h];
-            dtv = tid < nv ? v : 0.0f;
-        }
     };
-    issue_loads(0);
+    issue_x_loads(0);
+    issue_b_loads(0);
     load_c_rows(0, wave, cA);
 
     for (int c = 0; c < nchunks; ++c) {
@@ -211,6 +214,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
         const size_t tokbase = (size_t)b * L + t0;
 
         // ---- inclusive prefix sum of dt*A over the chunk ----
+        if (tid >= nv) dtv = 0.0f;  // padded steps: dt = 0
         float scan = dtv * Ah;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -251,7 +255,9 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
             }
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4) {
-                const uint32_t rows[4] = {xr[0][c4], xr[1][c4], xr[2][c4], xr[3][c4]};
+                uint32_t rows[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) rows[k] = s0 + k < nv ? xr[k][c4] : 0u;
                 uint32_t col[4];
                 transpose4x4(rows, col);
 #pragma unroll
@@ -279,6 +285,9 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
         for (int i = 0; i < 2; ++i) {
             const int item = tid + kThreads * i, s4 = item >> 3, n16 = item & 7;
             const int q = tok_pos(4 * s4);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (4 * s4 + k >= nv) br[i][k] = (u32x4){0u, 0u, 0u, 0u};
             if (!PRECISE) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
@@ -296,9 +305,8 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
         }
         __syncthreads();
 
-        // the next chunk's global loads fly while this chunk is computed
-        if (c + 1 < nchunks) issue_loads(c + 1);
         load_c_rows(c, kNBlk - 1 - wave, cB);
+        if (c + 1 < nchunks) issue_x_loads(c + 1);  // the next chunk's global loads fly while this chunk is computed
 
         // ---- outputs: each wave owns the 32-token blocks tb = wave and 7 - wave (equal causal work) ----
         for (int which = 0; which < 2; ++which) {
@@ -307,8 +315,11 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
             const int tl = tb * kBlk + l32;  // this lane's token inside the chunk
             i32x4 ct[4];
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) ct[kk] = which ? cB[kk] : cA[kk];
-            if (which == 0 && c + 1 < nchunks) load_c_rows(c + 1, wave, cA);  // consumed in the next chunk
+            for (int kk = 0; kk < 4; ++kk) ct[kk] = tl < nv ? (which ? cB[kk] : cA[kk]) : (i32x4){0, 0, 0, 0};
+            if (which == 1 && c + 1 < nchunks) {  // the first block is done: its C registers are free
+                issue_b_loads(c + 1);
+                load_c_rows(c + 1, wave, cA);
+            }
             const float cum_t = s_cum[tl];
 
             // B rows of block sb as the A operand of G^T (from LDS, or from global on the two-term state path)
