@@ -1,9 +1,10 @@
 // Chunked prefill of the 8-bit SSD on the gfx950 matrix cores.
 //
-// One workgroup (4 waves) owns one (sequence, head) and walks its chunks of Q = 256 tokens in order; the head's
-// state never leaves the chip.  Per chunk, with a_t = dt_t A_h, cum_t its inclusive prefix sum inside the chunk,
-// 32-token blocks tb / sb, and m_sb = cum at the last token of block sb (so cum_t <= m_sb <= cum_s whenever s lies
-// in block sb and t in a later block: every exponent below is <= 0):
+// One workgroup (4 waves) owns one (sequence, head) and walks it in chunks of kQ = 128 tokens; the head's state
+// never leaves the chip.  Its LDS footprint (< 80 KB) lets two workgroups share a compute unit, so that each SIMD
+// holds two waves whose matrix-core, vector-ALU and memory phases overlap.  Per chunk, with a_t = dt_t A_h, cum_t
+// its inclusive prefix sum inside the chunk, 32-token blocks tb / sb, and m_sb = cum at the last token of block
+// sb (so cum_t <= m_sb <= cum_s whenever s lies in block sb and t in a later block: every exponent is <= 0):
 //
 //   G^T[s,t]   = sum_n Bq[s,n] Cq[t,n]                                   int8 MFMA 32x32x32, int32 (exact)
 //   x'[s,p]    = xq[s,p] * exp(m_sb - cum_s) * dt_s                      fp16, staged once per chunk in LDS
@@ -17,7 +18,8 @@
 //
 // which is Eq. 2 with A-dot = exp(dt A), B-dot = dt B (Section 3.2) regrouped; the quantization scales of
 // Section 4.1 enter only in the epilogue because x enters linearly and channel-wise and B, C have one scale per
-// state group.  int8 codes are exact in fp16; G (|G| <= 2^21) is scaled by 2^-7 in fp32 before it is narrowed.
+// state group.  The result does not depend on the chunk length, so the caller's `chunk` is not used here.
+// int8 codes are exact in fp16; G (|G| <= 2^21) is scaled by 2^-7 in fp32 before it is narrowed.
 // The MFMA output layout (a lane holds one column and 16 rows) equals the operand layout (a lane holds one
 // row/column and 8 or 16 consecutive k) up to a fixed permutation of k, so G^T tiles feed the next MFMA straight
 // from registers; x^T and B^T are stored in LDS with that permutation (bits 2 and 3 of the token index swapped).
@@ -36,33 +38,31 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kP = 64, kN = 128, kQ = 256, kBlk = 32, kNBlk = kQ / kBlk;
+constexpr int kP = 64, kN = 128, kQ = 128, kBlk = 32, kNBlk = kQ / kBlk;
 constexpr int kThreads = 256;
-constexpr int kXqStride = 264;  // bytes per row of xq^T [p][token]
-constexpr int kBtStride = 264;  // bytes per row of Bq^T [n][token]
-constexpr int kXsStride = 264;  // halves per row of x'^T [p][token]
+constexpr int kXqStride = 136;  // bytes per row of xq^T [p][token]
+constexpr int kBtStride = 136;  // bytes per row of Bq^T [n][token]
+constexpr int kXsStride = 136;  // halves per row of x'^T [p][token]
 constexpr int kHsStride = 136;  // halves per row of H [p][n]
-constexpr int kYsStride = 72;   // halves per row of the per-wave y staging tile [t][p]
 constexpr int kBqStride = 144;  // bytes per row of Bq [token][n] (operand of the G^T product)
 constexpr float kNarrow = 1.0f / 128.0f;  // applied to G and H before narrowing to fp16; undone in the epilogue
 
 // LDS map (bytes)
-constexpr int kOffCum = 0;                                  // float[256]
-constexpr int kOffDt = kOffCum + 4 * kQ;                    // float[256]
-constexpr int kOffSx = kOffDt + 4 * kQ;                     // float[64]
-constexpr int kOffWt = kOffSx + 4 * kP;                     // float[4] (+pad)
-constexpr int kOffXq = kOffWt + 64;                         // int8 [64][264]
-constexpr int kOffBt = kOffXq + kP * kXqStride;             // int8 [128][264]
-constexpr int kOffHs = kOffBt + kN * kBtStride;             // fp16 [64][136]
-constexpr int kOffYs = kOffHs + 2 * kP * kHsStride;         // fp16 [4][32][72]
-constexpr int kOffXs = kOffYs + 2 * 4 * kBlk * kYsStride;   // fp16 [64][264]
-constexpr int kOffVar = kOffXs + 2 * kP * kXsStride;        // fast path: Bq row-major int8 [256][144];
-                                                            // two-term state path: low halves of x', fp16 [64][264]
-constexpr int kLdsFast = kOffVar + kQ * kBqStride;
-constexpr int kLdsPrecise = kOffVar + 2 * kP * kXsStride;
-static_assert(kOffXq % 16 == 0 && kOffBt % 16 == 0 && kOffHs % 16 == 0 && kOffYs % 16 == 0 && kOffXs % 16 == 0 &&
-                  kOffVar % 16 == 0, "LDS arrays must be 16-byte aligned");
-static_assert(kLdsPrecise <= 160 * 1024 && kLdsFast <= 160 * 1024, "exceeds the LDS of a gfx950 compute unit");
+constexpr int kOffCum = 0;                             // float[128]
+constexpr int kOffDt = kOffCum + 4 * kQ;               // float[128]
+constexpr int kOffSx = kOffDt + 4 * kQ;                // float[64]
+constexpr int kOffWt = kOffSx + 4 * kP;                // float[4] (+pad)
+constexpr int kOffXq = kOffWt + 64;                    // int8 [64][136]
+constexpr int kOffBt = kOffXq + kP * kXqStride;        // int8 [128][136]
+constexpr int kOffBq = kOffBt + kN * kBtStride;        // int8 [128][144]
+constexpr int kOffHs = kOffBq + kQ * kBqStride;        // fp16 [64][136]
+constexpr int kOffXs = kOffHs + 2 * kP * kHsStride;    // fp16 [64][136]
+constexpr int kOffXl = kOffXs + 2 * kP * kXsStride;    // fp16 [64][136]  low halves of x' (two-term state path only)
+constexpr int kLdsFast = kOffXl;
+constexpr int kLdsPrecise = kOffXl + 2 * kP * kXsStride;
+static_assert(kOffXq % 16 == 0 && kOffBt % 16 == 0 && kOffBq % 16 == 0 && kOffHs % 16 == 0 && kOffXs % 16 == 0 &&
+                  kOffXl % 16 == 0, "LDS arrays must be 16-byte aligned");
+static_assert(kLdsFast <= 80 * 1024, "two workgroups must fit the 160 KB LDS of a gfx950 compute unit");
 
 // Storage position of token s of the chunk inside an LDS row: bits 2 and 3 swapped (see file comment).
 __device__ __forceinline__ int tok_pos(int s) { return (s & ~12) | ((s & 4) << 1) | ((s & 8) >> 1); }
@@ -103,8 +103,23 @@ __device__ __forceinline__ f16x8 pack_f16x8(const float v[8])
     return r;
 }
 
+// Workgroup -> (sequence, head).  Hardware hands consecutive workgroup ids to the 8 XCDs round-robin, each XCD with
+// its own L2.  When the number of (sequence, state group) units is a multiple of 8, all heads of a unit are put on
+// one XCD, so that the B and C rows they share are fetched into one L2 instead of eight.
+__device__ __forceinline__ int block_to_bh(const SsdArgs &a)
+{
+    const int H = a.s.nheads, G = a.s.ngroups, hpg = H / G;
+    const int units = a.s.batch * G;
+    const int i = blockIdx.x;
+    if (units % 8 != 0) return i;
+    const int x = i & 7, slot = i >> 3;
+    const int u = x + 8 * (slot / hpg), hl = slot % hpg;
+    const int b = u / G, g = u - b * G;
+    return b * H + g * hpg + hl;
+}
+
 template <bool PRECISE>
-__global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
+__global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *s_cum = reinterpret_cast<float *>(smem + kOffCum);
@@ -113,18 +128,17 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
     float *s_wt = reinterpret_cast<float *>(smem + kOffWt);
     unsigned char *s_xq = smem + kOffXq;
     unsigned char *s_bt = smem + kOffBt;
+    unsigned char *s_bq = smem + kOffBq;
     _Float16 *s_hs = reinterpret_cast<_Float16 *>(smem + kOffHs);
     _Float16 *s_xs = reinterpret_cast<_Float16 *>(smem + kOffXs);
-    _Float16 *s_xl = reinterpret_cast<_Float16 *>(smem + kOffVar);  // PRECISE only
-    unsigned char *s_bq = smem + kOffVar;                           // !PRECISE only
+    _Float16 *s_xl = reinterpret_cast<_Float16 *>(smem + kOffXl);  // PRECISE only
 
     const int L = a.s.seqlen, H = a.s.nheads, G = a.s.ngroups;
-    const int bh = blockIdx.x;
+    const int bh = block_to_bh(a);
     const int b = bh / H, h = bh - b * H, g = h / (H / G);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps block indices in scalar registers
     const int l32 = lane & 31, hb = lane >> 5;
-    _Float16 *s_ys = reinterpret_cast<_Float16 *>(smem + kOffYs) + wave * kBlk * kYsStride;
 
     const float Ah = a.A[h];
     const float Dh = a.D ? a.D[h] : 0.0f;
@@ -158,62 +172,51 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
 
     const int nchunks = (L + kQ - 1) / kQ;
 
-    // Registers that carry one chunk's global loads from the point of issue (during the previous chunk's
-    // compute phase) to the staging phase: x codes (1 item: 4 tokens x 16 channels), B codes (2 items: 4 tokens x
-    // 16 states), dt of token tid, and the C rows of this wave's two 32-token output blocks.
-    u32x4 xr[4], br[2][4];
-    i32x4 cA[4], cB[4];
-    float dtv;
-    auto load_c_rows = [&](int c, int tb, i32x4(&ct)[4]) {
-        const int nv = min(kQ, L - c * kQ);
-        const int tl = tb * kBlk + l32;
-        const int8_t *crow = a.C + (((size_t)b * L + c * kQ + min(tl, nv - 1)) * G + g) * kN + hb * 64;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) ct[kk] = *reinterpret_cast<const i32x4 *>(crow + 16 * kk);
-    };
-    // Vector-memory results return in issue order, so the loads are issued in the order they are consumed
-    // (C rows of the second block of this chunk, x and dt of the next chunk, B of the next chunk, C rows of the
-    // first block of the next chunk) and spread over the compute phase instead of flooding the queue at once.
-    auto issue_x_loads = [&](int c) {
+    // Registers that carry one chunk's global loads from the point of issue (the previous chunk's compute phase)
+    // to the staging phase: x codes (4 tokens x 8 channels), B codes (4 tokens x 16 states), dt of token tid and
+    // the C rows of this wave's 32-token output block.  Rows past the end of the sequence are read from the last
+    // valid row and zeroed where they are consumed, so that nothing waits for data at the point of issue.
+    // Vector-memory results return in issue order, hence the loads are issued in the order they are consumed.
+    u32x2 xr[4];
+    u32x4 br[4];
+    i32x4 cn[4];
+    float dtv = 0.0f;
+    auto issue_loads = [&](int c) {
         const int t0 = c * kQ;
         const int nv = min(kQ, L - t0);
         const size_t tokbase = (size_t)b * L + t0;
         {
-            const int s4 = tid >> 2, p16 = tid & 3;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                // rows past the end are read from the last valid row; they are zeroed where they are consumed, so
-                // that nothing here waits for the data
-                const int s = min(4 * s4 + k, nv - 1);
-                xr[k] = *reinterpret_cast<const u32x4 *>(a.x + ((tokbase + s) * H + h) * kP + 16 * p16);
-            }
-        }
-        dtv = a.dt[(tokbase + min(tid, nv - 1)) * H + h];
-    };
-    auto issue_b_loads = [&](int c) {
-        const int t0 = c * kQ;
-        const int nv = min(kQ, L - t0);
-        const size_t tokbase = (size_t)b * L + t0;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int item = tid + kThreads * i, s4 = item >> 3, n16 = item & 7;
+            const int s4 = tid >> 3, p8 = tid & 7;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int s = min(4 * s4 + k, nv - 1);
-                br[i][k] = *reinterpret_cast<const u32x4 *>(a.B + ((tokbase + s) * G + g) * kN + 16 * n16);
+                xr[k] = *reinterpret_cast<const u32x2 *>(a.x + ((tokbase + s) * H + h) * kP + 8 * p8);
             }
         }
+        if (tid < kQ) dtv = a.dt[(tokbase + min(tid, nv - 1)) * H + h];
+        {
+            const int s4 = tid >> 3, n16 = tid & 7;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int s = min(4 * s4 + k, nv - 1);
+                br[k] = *reinterpret_cast<const u32x4 *>(a.B + ((tokbase + s) * G + g) * kN + 16 * n16);
+            }
+        }
+        {
+            const int tl = min(((wave + c) & (kNBlk - 1)) * kBlk + l32, nv - 1);
+            const int8_t *crow = a.C + ((tokbase + tl) * G + g) * kN + hb * 64;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) cn[kk] = *reinterpret_cast<const i32x4 *>(crow + 16 * kk);
+        }
     };
-    issue_x_loads(0);
-    issue_b_loads(0);
-    load_c_rows(0, wave, cA);
+    issue_loads(0);
 
     for (int c = 0; c < nchunks; ++c) {
         const int t0 = c * kQ;
         const int nv = min(kQ, L - t0);  // valid tokens of this chunk
         const size_t tokbase = (size_t)b * L + t0;
 
-        // ---- inclusive prefix sum of dt*A over the chunk ----
+        // ---- inclusive prefix sum of dt*A over the chunk (waves 0 and 1 hold the 128 tokens) ----
         if (tid >= nv) dtv = 0.0f;  // padded steps: dt = 0
         float scan = dtv * Ah;
 #pragma unroll
@@ -221,7 +224,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
             const float o = __shfl_up(scan, off, 64);
             if (lane >= off) scan += o;
         }
-        if (lane == 63) s_wt[wave] = scan;
+        if (lane == 63 && wave < 2) s_wt[wave] = scan;
 
         // carried state -> LDS as fp16 (operand of the C.H product of this chunk)
 #pragma unroll
@@ -234,17 +237,15 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                 *reinterpret_cast<f16x4 *>(s_hs + (pt * 32 + l32) * kHsStride + 32 * wave + 8 * rg + 4 * hb) = v;
             }
         __syncthreads();
-        {
-            float offs = 0.0f;
-            for (int w = 0; w < wave; ++w) offs += s_wt[w];
-            s_cum[tid] = scan + offs;
+        if (tid < kQ) {
+            s_cum[tid] = scan + (wave ? s_wt[0] : 0.0f);
             s_dt[tid] = dtv;
         }
         __syncthreads();
 
         // ---- x^T (codes and scaled fp16) and B^T (codes) into LDS, token positions permuted; B row-major ----
         {
-            const int s4 = tid >> 2, p16 = tid & 3;
+            const int s4 = tid >> 3, p8 = tid & 7;
             const int s0 = 4 * s4, q = tok_pos(s0);
             const float m = s_cum[(s0 & ~31) + 31];
             float colf[4], c128[4];
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                 c128[k] = -128.0f * colf[k];
             }
 #pragma unroll
-            for (int c4 = 0; c4 < 4; ++c4) {
+            for (int c4 = 0; c4 < 2; ++c4) {
                 uint32_t rows[4];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) rows[k] = s0 + k < nv ? xr[k][c4] : 0u;
@@ -262,7 +263,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                 transpose4x4(rows, col);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int p = 16 * p16 + 4 * c4 + j;
+                    const int p = 8 * p8 + 4 * c4 + j;
                     *reinterpret_cast<uint32_t *>(s_xq + p * kXqStride + q) = col[j];
                     const uint32_t u = col[j] ^ 0x80808080u;
                     float v[4];
@@ -281,21 +282,17 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                 }
             }
         }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int item = tid + kThreads * i, s4 = item >> 3, n16 = item & 7;
+        {
+            const int s4 = tid >> 3, n16 = tid & 7;
             const int q = tok_pos(4 * s4);
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (4 * s4 + k >= nv) br[i][k] = (u32x4){0u, 0u, 0u, 0u};
-            if (!PRECISE) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    *reinterpret_cast<u32x4 *>(s_bq + (4 * s4 + k) * kBqStride + 16 * n16) = br[i][k];
+            for (int k = 0; k < 4; ++k) {
+                if (4 * s4 + k >= nv) br[k] = (u32x4){0u, 0u, 0u, 0u};
+                *reinterpret_cast<u32x4 *>(s_bq + (4 * s4 + k) * kBqStride + 16 * n16) = br[k];
             }
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4) {
-                const uint32_t rows[4] = {br[i][0][c4], br[i][1][c4], br[i][2][c4], br[i][3][c4]};
+                const uint32_t rows[4] = {br[0][c4], br[1][c4], br[2][c4], br[3][c4]};
                 uint32_t col[4];
                 transpose4x4(rows, col);
 #pragma unroll
@@ -303,40 +300,26 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                     *reinterpret_cast<uint32_t *>(s_bt + (16 * n16 + 4 * c4 + j) * kBtStride + q) = col[j];
             }
         }
+        // this wave's output block rotates with the chunk index so that the causal work (tb + 1 block pairs)
+        // evens out over four chunks
+        const int tb = (wave + c) & (kNBlk - 1);
+        const int tl = tb * kBlk + l32;  // this lane's token inside the chunk
+        i32x4 ct[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) ct[kk] = tl < nv ? cn[kk] : (i32x4){0, 0, 0, 0};
         __syncthreads();
 
-        load_c_rows(c, kNBlk - 1 - wave, cB);
-        if (c + 1 < nchunks) issue_x_loads(c + 1);  // the next chunk's global loads fly while this chunk is computed
+        if (c + 1 < nchunks) issue_loads(c + 1);  // the next chunk's global loads fly while this chunk is computed
 
-        // ---- outputs: each wave owns the 32-token blocks tb = wave and 7 - wave (equal causal work) ----
-        for (int which = 0; which < 2; ++which) {
-            const int tb = which ? (kNBlk - 1 - wave) : wave;
-            if (tb * kBlk >= nv) continue;  // only in the last chunk: nothing is prefetched after it
-            const int tl = tb * kBlk + l32;  // this lane's token inside the chunk
-            i32x4 ct[4];
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) ct[kk] = tl < nv ? (which ? cB[kk] : cA[kk]) : (i32x4){0, 0, 0, 0};
-            if (which == 1 && c + 1 < nchunks) {  // the first block is done: its C registers are free
-                issue_b_loads(c + 1);
-                load_c_rows(c + 1, wave, cA);
-            }
+        // ---- outputs of block tb ----
+        if (tb * kBlk < nv) {
             const float cum_t = s_cum[tl];
 
-            // B rows of block sb as the A operand of G^T (from LDS, or from global on the two-term state path)
+            // B rows of block sb as the A operand of G^T
             auto load_bq = [&](int sb, i32x4(&bq)[4]) {
-                if (!PRECISE) {
-                    const unsigned char *row = s_bq + (sb * kBlk + l32) * kBqStride + hb * 64;
+                const unsigned char *row = s_bq + (sb * kBlk + l32) * kBqStride + hb * 64;
 #pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) bq[kk] = *reinterpret_cast<const i32x4 *>(row + 16 * kk);
-                } else {
-                    const int sl = sb * kBlk + l32;
-                    const int8_t *brow = a.B + ((tokbase + min(sl, nv - 1)) * G + g) * kN + hb * 64;
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) {
-                        const i32x4 v = *reinterpret_cast<const i32x4 *>(brow + 16 * kk);
-                        bq[kk] = sl < nv ? v : (i32x4){0, 0, 0, 0};
-                    }
-                }
+                for (int kk = 0; kk < 4; ++kk) bq[kk] = *reinterpret_cast<const i32x4 *>(row + 16 * kk);
             };
             auto gemm_g = [&](const i32x4(&bq)[4]) {
                 i32x16 gi;
@@ -350,7 +333,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
             load_bq(0, bq);
             i32x16 gi = gemm_g(bq);
 
-            // carried-state term: Y^T[p,t] = exp(cum_t) * sum_n H[p,n] Cq[t,n]
+            // carried-state term: Y^T[p,t] = sum_n H[p,n] (exp(cum_t) Cq[t,n])
             f32x16 acc[2];
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt)
@@ -381,8 +364,6 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
             // intra-chunk term, block pairs (sb <= tb); the G^T tile of the next pair is issued before this one is
             // scaled and narrowed so that the matrix core and the vector ALU overlap inside the wave
             for (int sb = 0; sb < tb; ++sb) {  // strictly lower block pairs
-                // all LDS reads of the iteration first, then the next G^T tile (matrix core) under the scaling and
-                // narrowing of the current one (vector ALU), then the four Y^T products
                 load_bq(sb + 1, bq);
                 f16x8 xa[2][2];
 #pragma unroll
@@ -392,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                         xa[ks][pt] = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + sb * kBlk +
                                                                      16 * ks + 8 * hb);
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
-                __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
+                __builtin_amdgcn_sched_barrier(0);
                 const i32x16 gn = gemm_g(bq);
                 const float rowf = __expf(cum_t - m_sb) * kNarrow;
                 float lv[16];
@@ -420,17 +401,16 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                     cs4[rg] = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + 8 * rg + 4 * hb);
                     ds4[rg] = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + 8 * rg + 4 * hb);
                 }
-                __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
+                __builtin_amdgcn_sched_barrier(0);
                 float lv[16];
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg) {
                     const int s0 = 8 * rg + 4 * hb;
-                    const f32x4 cs = cs4[rg], ds = ds4[rg];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         // exponent forced to a huge negative value above the diagonal: weight exactly 0, no branch
-                        const float arg = (s0 + i <= l32) ? fminf(cum_t - cs[i], 0.0f) : -1.0e30f;
-                        lv[4 * rg + i] = (float)gi[4 * rg + i] * (__expf(arg) * ds[i] * kNarrow);
+                        const float arg = (s0 + i <= l32) ? fminf(cum_t - cs4[rg][i], 0.0f) : -1.0e30f;
+                        lv[4 * rg + i] = (float)gi[4 * rg + i] * (__expf(arg) * ds4[rg][i] * kNarrow);
                     }
                 }
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
@@ -442,30 +422,37 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                                                                          ks ? l1 : l0, acc[pt], 0, 0, 0);
             }
 
-            // epilogue: scales, skip term, fp16, transposed through the wave's LDS tile, coalesced 16-byte stores
+            // epilogue: scales and skip term in fp32, narrowing to fp16; a lane holds 4 consecutive channels of token
+            // t per register group, and one exchange with the lane 32 positions away (same token) turns two such
+            // groups into 8 consecutive channels, so that every lane stores 16 bytes and a token row gets 32
             const int tq = tok_pos(tl);
+            uint16_t *yrow = a.y + ((tokbase + min(tl, nv - 1)) * H + h) * kP;
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    f16x4 o;
+                for (int j = 0; j < 2; ++j) {
+                    uint32_t w[2][2];  // [register group 2j, 2j+1][dword]
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int p = pt * 32 + 8 * rg + 4 * hb + i;
-                        const float xc = (float)(signed char)s_xq[p * kXqStride + tq];
-                        o[i] = (_Float16)(s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc));
+                    for (int e = 0; e < 2; ++e) {
+                        const int rg = 2 * j + e;
+                        f16x4 o;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int p = pt * 32 + 8 * rg + 4 * hb + i;
+                            const float xc = (float)(signed char)s_xq[p * kXqStride + tq];
+                            o[i] = (_Float16)(s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc));
+                        }
+                        const u32x2 ow = __builtin_bit_cast(u32x2, o);
+                        w[e][0] = ow[0];
+                        w[e][1] = ow[1];
                     }
-                    *reinterpret_cast<f16x4 *>(s_ys + l32 * kYsStride + pt * 32 + 8 * rg + 4 * hb) = o;
+                    // lanes 0..31 end up with group 2j of both half-waves (channels 16j .. 16j+7 of this p tile),
+                    // lanes 32..63 with group 2j+1 (channels 16j+8 .. 16j+15)
+                    const auto s0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                    const auto s1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                    const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
+                    if (tl < nv) *reinterpret_cast<u32x4 *>(yrow + pt * 32 + 16 * j + 8 * hb) = v;
                 }
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = 8 * i + (lane >> 3), c8 = lane & 7;
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(s_ys + row * kYsStride + 8 * c8);
-                const int tok = tb * kBlk + row;
-                if (tok < nv) *reinterpret_cast<u32x4 *>(a.y + ((tokbase + tok) * H + h) * kP + 8 * c8) = v;
-            }
-            __builtin_amdgcn_wave_barrier();
         }
 
         // ---- state update: wave w owns states n in [32w, 32w+32) ----
@@ -516,7 +503,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
                         xb[ks][pt] = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
                 }
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
-                __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
+                __builtin_amdgcn_sched_barrier(0);
                 const _Float16 f = (_Float16)__expf(cum_last - m_sb);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
@@ -549,10 +536,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma_kernel(SsdArgs a)
 
 }  // namespace
 
-bool prefill_mfma_supports(const quamba_ssd_shape_t &s)
-{
-    return s.headdim == kP && s.d_state == kN && s.chunk == kQ;
-}
+bool prefill_mfma_supports(const quamba_ssd_shape_t &s) { return s.headdim == kP && s.d_state == kN; }
 
 hipError_t launch_prefill_mfma(const SsdArgs &a, hipStream_t stream)
 {
