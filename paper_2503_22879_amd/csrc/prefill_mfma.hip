@@ -125,7 +125,6 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     float *s_cum = reinterpret_cast<float *>(smem + kOffCum);
     float *s_dt = reinterpret_cast<float *>(smem + kOffDt);
     float *s_sx = reinterpret_cast<float *>(smem + kOffSx);
-    float *s_wt = reinterpret_cast<float *>(smem + kOffWt);
     unsigned char *s_xq = smem + kOffXq;
     unsigned char *s_bt = smem + kOffBt;
     unsigned char *s_bq = smem + kOffBq;
@@ -144,9 +143,27 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     const float Dh = a.D ? a.D[h] : 0.0f;
     const float sB = a.B_scales[g], sC = a.C_scales[g];
     const float y_scale = sB * sC * (1.0f / kNarrow);
+    // Skip term D x[t,p]: x^T of the diagonal block is already an MFMA operand, so one more product with a scaled
+    // identity, D/y_scale * delta(s,t) split into two fp16 terms, adds it to the accumulators exactly (to 2^-22).
+    // When D/y_scale would leave the fp16 range (extreme scales), the term is added in the epilogue from LDS instead.
+    const float d_acc = Dh / y_scale;
+    const bool d_by_mfma = fabsf(d_acc) < 3.0e4f;
 
-    if (tid < kP) s_sx[tid] = x_scale_lookup(a, h, tid);
+    if (tid < kP) s_sx[tid] = x_scale_lookup(a, h, tid) * (d_by_mfma ? y_scale : 1.0f);
     __syncthreads();
+    f16x8 dhot[2][2];  // [hi, lo][k-step]: the lane's column t = l32 of the scaled identity, in operand order
+    {
+        const _Float16 dhi = (_Float16)(d_by_mfma ? d_acc : 0.0f);
+        const _Float16 dlo = (_Float16)(d_by_mfma ? d_acc - (float)dhi : 0.0f);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool on = (16 * ks + 8 * (j >> 2) + 4 * hb + (j & 3)) == l32;  // token of k-slot j
+                dhot[0][ks][j] = on ? dhi : (_Float16)0.0f;
+                dhot[1][ks][j] = on ? dlo : (_Float16)0.0f;
+            }
+    }
 
     // Carried state in x-code * B-code units (true state = s_x(p) s_B * st).  Wave w owns states n in
     // [32w, 32w+32); st[pt][r]: p = 32 pt + l32, n = 32 w + 8 (r/4) + 4 hb + r%4.
@@ -159,7 +176,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt) {
             const int p = pt * 32 + l32;
-            const float inv = 1.0f / (s_sx[p] * sB);
+            const float inv = (d_by_mfma ? y_scale : 1.0f) / (s_sx[p] * sB);
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 const int n0 = 32 * wave + 8 * rg + 4 * hb;
@@ -180,31 +197,36 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     u32x2 xr[4];
     u32x4 br[4];
     i32x4 cn[4];
-    float dtv = 0.0f;
+    float dt0 = 0.0f, dt1 = 0.0f;  // wave 0 only: dt of tokens 2*lane and 2*lane + 1
+    // Addresses are a wave-uniform 64-bit base (advanced per chunk) plus a 32-bit lane offset that does not change
+    // from chunk to chunk; only the last, partial chunk needs the offsets of the rows past the end redirected.
+    const uint32_t x_row = (uint32_t)H * kP, b_row = (uint32_t)G * kN, dt_row = (uint32_t)H * 4u;
     auto issue_loads = [&](int c) {
         const int t0 = c * kQ;
         const int nv = min(kQ, L - t0);
         const size_t tokbase = (size_t)b * L + t0;
-        {
-            const int s4 = tid >> 3, p8 = tid & 7;
+        const int8_t *xbase = a.x + (tokbase * H + h) * kP;
+        const int8_t *bbase = a.B + (tokbase * G + g) * kN;
+        const int8_t *cbase = a.C + (tokbase * G + g) * kN;
+        const char *dbase = reinterpret_cast<const char *>(a.dt + tokbase * H + h);
+        const int s4 = tid >> 3, c8 = tid & 7;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int s = min(4 * s4 + k, nv - 1);
-                xr[k] = *reinterpret_cast<const u32x2 *>(a.x + ((tokbase + s) * H + h) * kP + 8 * p8);
-            }
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t row = (uint32_t)min(4 * s4 + k, nv - 1);
+            xr[k] = *reinterpret_cast<const u32x2 *>(xbase + (row * x_row + 8u * c8));
         }
-        if (tid < kQ) dtv = a.dt[(tokbase + min(tid, nv - 1)) * H + h];
-        {
-            const int s4 = tid >> 3, n16 = tid & 7;
+        if (wave == 0) {
+            dt0 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane, nv - 1) * dt_row);
+            dt1 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane + 1, nv - 1) * dt_row);
+        }
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int s = min(4 * s4 + k, nv - 1);
-                br[k] = *reinterpret_cast<const u32x4 *>(a.B + ((tokbase + s) * G + g) * kN + 16 * n16);
-            }
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t row = (uint32_t)min(4 * s4 + k, nv - 1);
+            br[k] = *reinterpret_cast<const u32x4 *>(bbase + (row * b_row + 16u * c8));
         }
         {
-            const int tl = min(((wave + c) & (kNBlk - 1)) * kBlk + l32, nv - 1);
-            const int8_t *crow = a.C + ((tokbase + tl) * G + g) * kN + hb * 64;
+            const uint32_t row = (uint32_t)min(((wave + c) & (kNBlk - 1)) * kBlk + l32, nv - 1);
+            const int8_t *crow = cbase + (row * b_row + 64u * hb);
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) cn[kk] = *reinterpret_cast<const i32x4 *>(crow + 16 * kk);
         }
@@ -216,15 +238,20 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         const int nv = min(kQ, L - t0);  // valid tokens of this chunk
         const size_t tokbase = (size_t)b * L + t0;
 
-        // ---- inclusive prefix sum of dt*A over the chunk (waves 0 and 1 hold the 128 tokens) ----
-        if (tid >= nv) dtv = 0.0f;  // padded steps: dt = 0
-        float scan = dtv * Ah;
+        // ---- inclusive prefix sum of dt*A over the chunk: wave 0, two tokens per lane, no cross-wave step ----
+        if (wave == 0) {
+            if (2 * lane >= nv) dt0 = 0.0f;  // padded steps: dt = 0
+            if (2 * lane + 1 >= nv) dt1 = 0.0f;
+            const float a0 = dt0 * Ah, a1 = dt1 * Ah;
+            float scan = a0 + a1;
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const float o = __shfl_up(scan, off, 64);
-            if (lane >= off) scan += o;
+            for (int off = 1; off < 64; off <<= 1) {
+                const float o = __shfl_up(scan, off, 64);
+                if (lane >= off) scan += o;
+            }
+            *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(scan - a1, scan);
+            *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(dt0, dt1);
         }
-        if (lane == 63 && wave < 2) s_wt[wave] = scan;
 
         // carried state -> LDS as fp16 (operand of the C.H product of this chunk)
 #pragma unroll
@@ -237,21 +264,18 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 *reinterpret_cast<f16x4 *>(s_hs + (pt * 32 + l32) * kHsStride + 32 * wave + 8 * rg + 4 * hb) = v;
             }
         __syncthreads();
-        if (tid < kQ) {
-            s_cum[tid] = scan + (wave ? s_wt[0] : 0.0f);
-            s_dt[tid] = dtv;
-        }
-        __syncthreads();
 
         // ---- x^T (codes and scaled fp16) and B^T (codes) into LDS, token positions permuted; B row-major ----
         {
             const int s4 = tid >> 3, p8 = tid & 7;
             const int s0 = 4 * s4, q = tok_pos(s0);
             const float m = s_cum[(s0 & ~31) + 31];
+            const f32x4 cum4 = *reinterpret_cast<const f32x4 *>(s_cum + s0);
+            const f32x4 dt4 = *reinterpret_cast<const f32x4 *>(s_dt + s0);
             float colf[4], c128[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                colf[k] = __expf(m - s_cum[s0 + k]) * s_dt[s0 + k];
+                colf[k] = __expf(m - cum4[k]) * dt4[k];
                 c128[k] = -128.0f * colf[k];
             }
 #pragma unroll
@@ -341,18 +365,18 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int r = 0; r < 16; ++r) acc[pt][r] = 0.0f;
             const _Float16 e_t = (_Float16)__expf(cum_t);  // per lane (token t); folded into the C operand
 #pragma unroll
-            for (int k4 = 0; k4 < 2; ++k4) {  // two batches of four k-steps: all LDS reads of a batch are issued first
-                f16x8 hf[4][2];
+            for (int k2 = 0; k2 < 4; ++k2) {  // batches of two k-steps: all LDS reads of a batch are issued first
+                f16x8 hf[2][2];
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
+                for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
                         hf[kk][pt] = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32) * kHsStride + hb * 64 +
-                                                                     8 * (4 * k4 + kk));
+                                                                     8 * (2 * k2 + kk));
                 __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const int k8 = 4 * k4 + kk;
+                for (int kk = 0; kk < 2; ++kk) {
+                    const int k8 = 2 * k2 + kk;
                     const f16x8 cf =
                         i8x8_to_f16((uint32_t)ct[k8 >> 1][2 * (k8 & 1)], (uint32_t)ct[k8 >> 1][2 * (k8 & 1) + 1]) * e_t;
 #pragma unroll
@@ -417,42 +441,75 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt)
-                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(i8x8_to_f16(xw[ks][pt][0], xw[ks][pt][1]),
-                                                                         ks ? l1 : l0, acc[pt], 0, 0, 0);
+                    for (int pt = 0; pt < 2; ++pt) {
+                        const f16x8 xf = i8x8_to_f16(xw[ks][pt][0], xw[ks][pt][1]);
+                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, ks ? l1 : l0, acc[pt], 0, 0, 0);
+                        if (d_by_mfma) {
+                            acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, dhot[0][ks], acc[pt], 0, 0, 0);
+                            acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, dhot[1][ks], acc[pt], 0, 0, 0);
+                        }
+                    }
             }
 
             // epilogue: scales and skip term in fp32, narrowing to fp16; a lane holds 4 consecutive channels of token
             // t per register group, and one exchange with the lane 32 positions away (same token) turns two such
             // groups into 8 consecutive channels, so that every lane stores 16 bytes and a token row gets 32
-            const int tq = tok_pos(tl);
             uint16_t *yrow = a.y + ((tokbase + min(tl, nv - 1)) * H + h) * kP;
+            if (d_by_mfma) {
 #pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
+                for (int pt = 0; pt < 2; ++pt) {
+                    f32x4 k4[4];  // s_x(h,p) * y_scale of the lane's 16 channels of this p tile
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    uint32_t w[2][2];  // [register group 2j, 2j+1][dword]
+                    for (int rg = 0; rg < 4; ++rg)
+                        k4[rg] = *reinterpret_cast<const f32x4 *>(s_sx + pt * 32 + 8 * rg + 4 * hb);
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const int rg = 2 * j + e;
-                        f16x4 o;
+                    for (int j = 0; j < 2; ++j) {
+                        uint32_t w[2][2];  // [register group 2j, 2j+1][dword]
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int p = pt * 32 + 8 * rg + 4 * hb + i;
-                            const float xc = (float)(signed char)s_xq[p * kXqStride + tq];
-                            o[i] = (_Float16)(s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc));
+                        for (int e = 0; e < 2; ++e) {
+                            const int rg = 2 * j + e;
+                            f16x4 o;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) o[i] = (_Float16)(k4[rg][i] * acc[pt][4 * rg + i]);
+                            const u32x2 ow = __builtin_bit_cast(u32x2, o);
+                            w[e][0] = ow[0];
+                            w[e][1] = ow[1];
                         }
-                        const u32x2 ow = __builtin_bit_cast(u32x2, o);
-                        w[e][0] = ow[0];
-                        w[e][1] = ow[1];
+                        // lanes 0..31 end up with group 2j of both half-waves (channels 16j .. 16j+7 of this p
+                        // tile), lanes 32..63 with group 2j+1 (channels 16j+8 .. 16j+15)
+                        const auto s0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                        const auto s1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                        const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
+                        if (tl < nv) *reinterpret_cast<u32x4 *>(yrow + pt * 32 + 16 * j + 8 * hb) = v;
                     }
-                    // lanes 0..31 end up with group 2j of both half-waves (channels 16j .. 16j+7 of this p tile),
-                    // lanes 32..63 with group 2j+1 (channels 16j+8 .. 16j+15)
-                    const auto s0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
-                    const auto s1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
-                    const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
-                    if (tl < nv) *reinterpret_cast<u32x4 *>(yrow + pt * 32 + 16 * j + 8 * hb) = v;
                 }
+            } else {
+                const int tq = tok_pos(tl);
+#pragma unroll
+                for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        uint32_t w[2][2];
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            const int rg = 2 * j + e;
+                            f16x4 o;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int p = pt * 32 + 8 * rg + 4 * hb + i;
+                                const float xc = (float)(signed char)s_xq[p * kXqStride + tq];
+                                o[i] = (_Float16)(s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc));
+                            }
+                            const u32x2 ow = __builtin_bit_cast(u32x2, o);
+                            w[e][0] = ow[0];
+                            w[e][1] = ow[1];
+                        }
+                        const auto s0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                        const auto s1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                        const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
+                        if (tl < nv) *reinterpret_cast<u32x4 *>(yrow + pt * 32 + 16 * j + 8 * hb) = v;
+                    }
+            }
         }
 
         // ---- state update: wave w owns states n in [32w, 32w+32) ----
@@ -490,8 +547,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
             }
-            for (int sb = 0; sb < kNBlk; ++sb) {
-                if (sb * kBlk >= nv) break;
+#pragma unroll
+            for (int sb = 0; sb < kNBlk; ++sb) {  // blocks past the end hold zeros in x' (dt = 0): they add nothing
                 u32x2 bw[2];
                 f16x8 xb[2][2];
 #pragma unroll
@@ -521,7 +578,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt) {
             const int p = pt * 32 + l32;
-            const float sc = s_sx[p] * sB;
+            const float sc = s_sx[p] * sB / (d_by_mfma ? y_scale : 1.0f);
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 const int n0 = 32 * wave + 8 * rg + 4 * hb;
