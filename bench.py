@@ -94,6 +94,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode leg")
     ap.add_argument("--precise-state", action="store_true", help="also return the final fp32 state (two-term state path)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of 256 MiB three times (read 256 MiB + write 256 MiB each): the "
+                         "known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by sequence or by "
@@ -206,6 +209,14 @@ def main() -> int:
                          "unit": "GB/s", "frac": dgbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get("m2_8b_decode")},
             "finite": bool(torch.isfinite(state).all().item()),
         }
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"bytes_read": 256 << 20, "bytes_written": 256 << 20, "launches": 3}
 
     print(json.dumps(out))
     return 0

@@ -3,8 +3,7 @@
 // The step is a pure stream over the state (read 4 B + write 4 B per element, 3 FMAs), so the kernel is built
 // around HBM: one workgroup per (sequence, head), every lane owns 16-byte pieces of state rows, all of a lane's
 // loads are issued before any arithmetic, the d_state reduction of y stays in registers (cross-lane adds), and
-// the per-row input x and the per-row output y go through a few hundred bytes of LDS so that the global
-// accesses to x and y are single coalesced transactions.
+// the de-quantized per-row input x is staged once through a few hundred bytes of LDS.
 #include "quamba_internal.h"
 
 namespace quamba {
@@ -20,12 +19,24 @@ __device__ __forceinline__ uint16_t f32_to_f16_bits(float v)
     return __builtin_bit_cast(uint16_t, h);
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
 // Sum over groups of LANES consecutive lanes (LANES a power of two <= 64); every lane of a group gets the sum.
+// Steps inside a row of 16 lanes are data-parallel-primitive moves fused into the adds (no LDS traffic): swap
+// inside pairs, swap pairs inside quads, mirror inside 8, mirror inside 16; the step across rows is one swizzle.
 template <int LANES>
 __device__ __forceinline__ float group_sum(float v)
 {
-#pragma unroll
-    for (int off = LANES / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (LANES >= 2) v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+    if (LANES >= 4) v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+    if (LANES >= 8) v += dpp_move<0x141>(v);  // row_half_mirror
+    if (LANES >= 16) v += dpp_move<0x140>(v); // row_mirror
+    if (LANES >= 32) v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));  // lane ^ 16
+    if (LANES >= 64) v += __shfl_xor(v, 32, 64);
     return v;
 }
 
@@ -46,8 +57,7 @@ __global__ __launch_bounds__(kThreads) void decode_vec_kernel(SsdArgs a)
     constexpr int RPI = 64 / LPR;  // rows per wave-wide load
     extern __shared__ float lds[];
     const int P = a.s.headdim, H = a.s.nheads, G = a.s.ngroups;
-    float *xv = lds;      // [P]
-    float *ys = lds + P;  // [P]
+    float *xv = lds;  // [P]
 
     const int bh = blockIdx.x;
     const int b = bh / H, h = bh - b * H, g = h / (H / G);
@@ -65,39 +75,45 @@ __global__ __launch_bounds__(kThreads) void decode_vec_kernel(SsdArgs a)
     const float4 Bv = make_float4(sB * bq.x, sB * bq.y, sB * bq.z, sB * bq.w);  // dt * B_t (B-dot of Sec. 3.2)
     const float4 Cv = make_float4(sC * cq.x, sC * cq.y, sC * cq.z, sC * cq.w);
 
+    bool staged = false;
     for (int p0 = wave * RPI * ROWS; p0 < P; p0 += kWaves * RPI * ROWS) {
+        // all of the lane's loads first, unconditionally (rows past the end re-read the last row and are not stored)
         f32x4 v[ROWS];
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
-            const int p = p0 + i * RPI + sub;
-            if (p < P) v[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(st + (size_t)p * N));
+            const int p = min(p0 + i * RPI + sub, P - 1);
+            v[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(st + (size_t)p * N));
         }
-        if (p0 == wave * RPI * ROWS) {  // first trip: stage x while the state loads are in flight
+        if (!staged) {  // first trip: stage x while the state loads are in flight
             stage_x(a, bh, h, xv);
             __syncthreads();
+            staged = true;
         }
+        float part[ROWS];
+#pragma unroll
+        for (int i = 0; i < ROWS; ++i) {
+            const int p = min(p0 + i * RPI + sub, P - 1);
+            const float x = xv[p];
+            v[i].x = fmaf(dA, v[i].x, Bv.x * x);
+            v[i].y = fmaf(dA, v[i].y, Bv.y * x);
+            v[i].z = fmaf(dA, v[i].z, Bv.z * x);
+            v[i].w = fmaf(dA, v[i].w, Bv.w * x);
+            if (p0 + i * RPI + sub < P)
+                __builtin_nontemporal_store(v[i], reinterpret_cast<f32x4 *>(st + (size_t)p * N));
+            part[i] = fmaf(Cv.x, v[i].x, fmaf(Cv.y, v[i].y, fmaf(Cv.z, v[i].z, Cv.w * v[i].w)));
+        }
+#pragma unroll
+        for (int i = 0; i < ROWS; ++i) part[i] = group_sum<LPR>(part[i]);
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
             const int p = p0 + i * RPI + sub;
-            if (p < P) {
-                const float x = xv[p];
-                v[i].x = fmaf(dA, v[i].x, Bv.x * x);
-                v[i].y = fmaf(dA, v[i].y, Bv.y * x);
-                v[i].z = fmaf(dA, v[i].z, Bv.z * x);
-                v[i].w = fmaf(dA, v[i].w, Bv.w * x);
-                __builtin_nontemporal_store(v[i], reinterpret_cast<f32x4 *>(st + (size_t)p * N));
-                float part = fmaf(Cv.x, v[i].x, fmaf(Cv.y, v[i].y, fmaf(Cv.z, v[i].z, Cv.w * v[i].w)));
-                part = group_sum<LPR>(part);  // all LPR lanes of a row take the same branch
-                if (j == 0) ys[p] = fmaf(Dh, x, part);
-            }
+            if (j == 0 && p < P) a.y[(size_t)bh * P + p] = f32_to_f16_bits(fmaf(Dh, xv[p], part[i]));
         }
     }
-    if (P <= wave * RPI * ROWS) {  // a wave that owned no row still joins the barrier of the first trip
+    if (!staged) {  // a wave that owned no row still joins the barrier
         stage_x(a, bh, h, xv);
         __syncthreads();
     }
-    __syncthreads();
-    for (int p = threadIdx.x; p < P; p += kThreads) a.y[(size_t)bh * P + p] = f32_to_f16_bits(ys[p]);
 }
 
 // Any d_state: one wave per row, lanes stride over the states.
@@ -140,7 +156,7 @@ hipError_t launch_vec(const SsdArgs &a, hipStream_t stream)
     constexpr int LPR = N / 4, RPI = 64 / LPR;
     constexpr int ROWS = (RPI * 8 * kWaves <= 64) ? 8 : (RPI * 4 * kWaves <= 64 ? 4 : (RPI <= 8 ? 2 : 1));
     const dim3 grid((unsigned)(a.s.batch * a.s.nheads));
-    const size_t lds = sizeof(float) * 2 * (size_t)a.s.headdim;
+    const size_t lds = sizeof(float) * (size_t)a.s.headdim;
     hipLaunchKernelGGL((decode_vec_kernel<N, ROWS>), grid, dim3(kThreads), lds, stream, a);
     return hipGetLastError();
 }

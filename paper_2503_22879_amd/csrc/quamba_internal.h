@@ -25,17 +25,19 @@ struct SsdArgs {
     uint16_t *y;               // fp16 bits
 };
 
-// Scale of channel position p of head h: walk the cluster boundary tables (Section 4.1: m x n scales per group).
+// Scale of channel position p of head h from the cluster boundary tables (Section 4.1: m x n scales per group).
+// The cluster index is the number of boundaries at or below the position, so all boundary loads are independent
+// (three dependent memory round trips in total instead of one per boundary).
 __device__ __forceinline__ float x_scale_lookup(const SsdArgs &a, int h, int p)
 {
     const int hpg = a.s.nheads / a.s.ngroups;
     const int g = h / hpg, hl = h - g * hpg;
     const int m = a.s.n_head_clusters, n = a.s.n_chan_clusters;
     int i = 0;
-    while (i < m - 1 && hl >= a.head_cluster_end[g * m + i]) ++i;
+    for (int k = 0; k < m - 1; ++k) i += hl >= a.head_cluster_end[g * m + k] ? 1 : 0;
     const int base = (g * m + i) * n;
     int j = 0;
-    while (j < n - 1 && p >= a.chan_cluster_end[base + j]) ++j;
+    for (int k = 0; k < n - 1; ++k) j += p >= a.chan_cluster_end[base + k] ? 1 : 0;
     return a.x_scales[base + j];
 }
 
