@@ -67,6 +67,13 @@ static_assert(kLdsFast <= 80 * 1024, "two workgroups must fit the 160 KB LDS of 
 // Storage position of token s of the chunk inside an LDS row: bits 2 and 3 swapped (see file comment).
 __device__ __forceinline__ int tok_pos(int s) { return (s & ~12) | ((s & 4) << 1) | ((s & 8) >> 1); }
 
+// Bank swizzles: XOR masks on the (permuted) token position of an LDS row, a function of the row index, so that
+// the staging writes of one wave-wide instruction hit distinct banks.  Readers apply the same mask; it is uniform
+// over the 16 lanes that read together.
+__device__ __forceinline__ int xq_swz(int p) { return ((p >> 5) & 1) << 5; }  // x codes: 32 tokens (bytes)
+__device__ __forceinline__ int xs_swz(int p) { return ((p >> 4) & 3) << 4; }  // scaled x: 16, 32 or 48 tokens
+__device__ __forceinline__ int bt_swz(int n) { return ((n >> 5) & 1) << 6; }  // B^T codes: 64 tokens (bytes)
+
 // 8 int8 codes (two dwords, lowest address first) -> 8 exact fp16 values: byte^0x80 placed under the fp16
 // pattern of 1024 gives 1024 + (code + 128); subtract 1152.
 __device__ __forceinline__ f16x8 i8x8_to_f16(uint32_t w0, uint32_t w1)
@@ -151,18 +158,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 
     if (tid < kP) s_sx[tid] = x_scale_lookup(a, h, tid) * (d_by_mfma ? y_scale : 1.0f);
     __syncthreads();
-    f16x8 dhot[2][2];  // [hi, lo][k-step]: the lane's column t = l32 of the scaled identity, in operand order
+    // The lane's column t = l32 of the scaled identity has one non-zero entry, in k-slot (l32 & 3) + 4 * bit 3 of
+    // k-step bit 4, and only in the half-wave hb = bit 2; packed here as (k-step * 4 + dword) * 2 + half, or -1.
+    const int dslot = ((l32 >> 2) & 1) == hb ? (((l32 >> 4) * 4 + ((l32 >> 3) & 1) * 2 + ((l32 >> 1) & 1)) * 2 + (l32 & 1)) : -1;
+    uint32_t dpair;  // fp16 bits of the two terms of D / y_scale: hi in the low half, lo in the high half
     {
         const _Float16 dhi = (_Float16)(d_by_mfma ? d_acc : 0.0f);
         const _Float16 dlo = (_Float16)(d_by_mfma ? d_acc - (float)dhi : 0.0f);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bool on = (16 * ks + 8 * (j >> 2) + 4 * hb + (j & 3)) == l32;  // token of k-slot j
-                dhot[0][ks][j] = on ? dhi : (_Float16)0.0f;
-                dhot[1][ks][j] = on ? dlo : (_Float16)0.0f;
-            }
+        dpair = (uint32_t)__builtin_bit_cast(uint16_t, dhi) | ((uint32_t)__builtin_bit_cast(uint16_t, dlo) << 16);
     }
 
     // Carried state in x-code * B-code units (true state = s_x(p) s_B * st).  Wave w owns states n in
@@ -197,7 +200,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     u32x2 xr[4];
     u32x4 br[4];
     i32x4 cn[4];
-    float dt0 = 0.0f, dt1 = 0.0f;  // wave 0 only: dt of tokens 2*lane and 2*lane + 1
+    float dt0 = 0.0f, dt1 = 0.0f;  // dt of tokens 2*lane and 2*lane + 1 (every wave holds the whole chunk's dt)
+    // Staging lane maps, chosen so that the LDS writes of a wave-wide instruction fall into distinct banks:
+    // x: 8 channel groups x 8 token quads per wave; B: 4 state groups x 16 token quads per wave.
+    const int xs4 = tid >> 3, xp8 = tid & 7;
+    const int bs4 = ((lane >> 2) & 15) + 16 * (wave & 1), bn16 = (lane & 3) + 4 * (wave >> 1);
     // Addresses are a wave-uniform 64-bit base (advanced per chunk) plus a 32-bit lane offset that does not change
     // from chunk to chunk; only the last, partial chunk needs the offsets of the rows past the end redirected.
     const uint32_t x_row = (uint32_t)H * kP, b_row = (uint32_t)G * kN, dt_row = (uint32_t)H * 4u;
@@ -206,42 +213,48 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         const int nv = min(kQ, L - t0);
         const size_t tokbase = (size_t)b * L + t0;
         const int8_t *xbase = a.x + (tokbase * H + h) * kP;
-        const int8_t *bbase = a.B + (tokbase * G + g) * kN;
-        const int8_t *cbase = a.C + (tokbase * G + g) * kN;
         const char *dbase = reinterpret_cast<const char *>(a.dt + tokbase * H + h);
-        const int s4 = tid >> 3, c8 = tid & 7;
+        dt0 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane, nv - 1) * dt_row);
+        dt1 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane + 1, nv - 1) * dt_row);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const uint32_t row = (uint32_t)min(4 * s4 + k, nv - 1);
-            xr[k] = *reinterpret_cast<const u32x2 *>(xbase + (row * x_row + 8u * c8));
-        }
-        if (wave == 0) {
-            dt0 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane, nv - 1) * dt_row);
-            dt1 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane + 1, nv - 1) * dt_row);
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t row = (uint32_t)min(4 * s4 + k, nv - 1);
-            br[k] = *reinterpret_cast<const u32x4 *>(bbase + (row * b_row + 16u * c8));
-        }
-        {
-            const uint32_t row = (uint32_t)min(((wave + c) & (kNBlk - 1)) * kBlk + l32, nv - 1);
-            const int8_t *crow = cbase + (row * b_row + 64u * hb);
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) cn[kk] = *reinterpret_cast<const i32x4 *>(crow + 16 * kk);
+            const uint32_t row = (uint32_t)min(4 * xs4 + k, nv - 1);
+            xr[k] = *reinterpret_cast<const u32x2 *>(xbase + (row * x_row + 8u * xp8));
         }
     };
+    // C rows of this wave's output block of chunk c.  k-step kk of the G^T product covers states 32 kk + 16 hb +
+    // [0,16): the two half-waves read adjacent 16-byte pieces of a C row (half as many memory requests as 64
+    // contiguous bytes per lane).  Issued, with the B rows (mostly L2 hits: 16 heads share them), after the output
+    // phase of the previous chunk, when registers are free; B first, because staging consumes it first.
+    auto issue_c_loads = [&](int c) {
+        const int t0 = c * kQ;
+        const int nv = min(kQ, L - t0);
+        const int8_t *bbase = a.B + (((size_t)b * L + t0) * G + g) * kN;
+        const int8_t *cbase = a.C + (((size_t)b * L + t0) * G + g) * kN;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t row = (uint32_t)min(4 * bs4 + k, nv - 1);
+            br[k] = *reinterpret_cast<const u32x4 *>(bbase + (row * b_row + 16u * bn16));
+        }
+        const uint32_t row = (uint32_t)min(((wave + c) & (kNBlk - 1)) * kBlk + l32, nv - 1);
+        const int8_t *crow = cbase + (row * b_row + 16u * hb);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) cn[kk] = *reinterpret_cast<const i32x4 *>(crow + 32 * kk);
+    };
     issue_loads(0);
+    issue_c_loads(0);
 
     for (int c = 0; c < nchunks; ++c) {
         const int t0 = c * kQ;
         const int nv = min(kQ, L - t0);  // valid tokens of this chunk
         const size_t tokbase = (size_t)b * L + t0;
 
-        // ---- inclusive prefix sum of dt*A over the chunk: wave 0, two tokens per lane, no cross-wave step ----
-        if (wave == 0) {
-            if (2 * lane >= nv) dt0 = 0.0f;  // padded steps: dt = 0
-            if (2 * lane + 1 >= nv) dt1 = 0.0f;
+        // ---- inclusive prefix sum of dt*A over the chunk: every wave redundantly, two tokens per lane, so that the
+        // staging below needs no barrier; wave 0 publishes cum and dt in LDS for the phases after the barrier ----
+        if (2 * lane >= nv) dt0 = 0.0f;  // padded steps: dt = 0
+        if (2 * lane + 1 >= nv) dt1 = 0.0f;
+        float cum0, cum1;  // prefix sums at tokens 2*lane and 2*lane + 1
+        {
             const float a0 = dt0 * Ah, a1 = dt1 * Ah;
             float scan = a0 + a1;
 #pragma unroll
@@ -249,7 +262,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 const float o = __shfl_up(scan, off, 64);
                 if (lane >= off) scan += o;
             }
-            *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(scan - a1, scan);
+            cum0 = scan - a1;
+            cum1 = scan;
+        }
+        if (wave == 0) {
+            *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
             *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(dt0, dt1);
         }
 
@@ -263,21 +280,26 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int i = 0; i < 4; ++i) v[i] = (_Float16)(st[pt][4 * rg + i] * kNarrow);
                 *reinterpret_cast<f16x4 *>(s_hs + (pt * 32 + l32) * kHsStride + 32 * wave + 8 * rg + 4 * hb) = v;
             }
-        __syncthreads();
 
         // ---- x^T (codes and scaled fp16) and B^T (codes) into LDS, token positions permuted; B row-major ----
         {
-            const int s4 = tid >> 3, p8 = tid & 7;
-            const int s0 = 4 * s4, q = tok_pos(s0);
-            const float m = s_cum[(s0 & ~31) + 31];
-            const f32x4 cum4 = *reinterpret_cast<const f32x4 *>(s_cum + s0);
-            const f32x4 dt4 = *reinterpret_cast<const f32x4 *>(s_dt + s0);
+            const int s0 = 4 * xs4, q = tok_pos(s0);
+            // cum and dt of tokens s0 .. s0+3 sit in lanes 2*xs4 and 2*xs4 + 1 of this wave; m in the lane of the
+            // block's last token
+            const int l0 = 2 * xs4, lm = ((s0 & ~31) >> 1) + 15;
+            const float cumq[4] = {__shfl(cum0, l0, 64), __shfl(cum1, l0, 64), __shfl(cum0, l0 + 1, 64),
+                                   __shfl(cum1, l0 + 1, 64)};
+            const float dtq[4] = {__shfl(dt0, l0, 64), __shfl(dt1, l0, 64), __shfl(dt0, l0 + 1, 64),
+                                  __shfl(dt1, l0 + 1, 64)};
+            const float m = __shfl(cum1, lm, 64);
             float colf[4], c128[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                colf[k] = __expf(m - cum4[k]) * dt4[k];
+                colf[k] = __expf(m - cumq[k]) * dtq[k];
                 c128[k] = -128.0f * colf[k];
             }
+            // bank swizzles of the two x arrays (readers apply the same): codes, 32 bytes by bit 5 of the channel;
+            // scaled fp16, 16 tokens times bits 4..5 of the channel
 #pragma unroll
             for (int c4 = 0; c4 < 2; ++c4) {
                 uint32_t rows[4];
@@ -287,8 +309,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 transpose4x4(rows, col);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int p = 8 * p8 + 4 * c4 + j;
-                    *reinterpret_cast<uint32_t *>(s_xq + p * kXqStride + q) = col[j];
+                    const int p = 8 * xp8 + 4 * c4 + j;
+                    *reinterpret_cast<uint32_t *>(s_xq + p * kXqStride + (q ^ xq_swz(p))) = col[j];
                     const uint32_t u = col[j] ^ 0x80808080u;
                     float v[4];
 #pragma unroll
@@ -296,23 +318,22 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     f16x4 hi;
 #pragma unroll
                     for (int k = 0; k < 4; ++k) hi[k] = (_Float16)v[k];
-                    *reinterpret_cast<f16x4 *>(s_xs + p * kXsStride + q) = hi;
+                    *reinterpret_cast<f16x4 *>(s_xs + p * kXsStride + (q ^ xs_swz(p))) = hi;
                     if (PRECISE) {
                         f16x4 lo;
 #pragma unroll
                         for (int k = 0; k < 4; ++k) lo[k] = (_Float16)(v[k] - (float)hi[k]);
-                        *reinterpret_cast<f16x4 *>(s_xl + p * kXsStride + q) = lo;
+                        *reinterpret_cast<f16x4 *>(s_xl + p * kXsStride + (q ^ xs_swz(p))) = lo;
                     }
                 }
             }
         }
         {
-            const int s4 = tid >> 3, n16 = tid & 7;
-            const int q = tok_pos(4 * s4);
+            const int q = tok_pos(4 * bs4);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                if (4 * s4 + k >= nv) br[k] = (u32x4){0u, 0u, 0u, 0u};
-                *reinterpret_cast<u32x4 *>(s_bq + (4 * s4 + k) * kBqStride + 16 * n16) = br[k];
+                if (4 * bs4 + k >= nv) br[k] = (u32x4){0u, 0u, 0u, 0u};
+                *reinterpret_cast<u32x4 *>(s_bq + (4 * bs4 + k) * kBqStride + 16 * bn16) = br[k];
             }
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4) {
@@ -320,8 +341,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 uint32_t col[4];
                 transpose4x4(rows, col);
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    *reinterpret_cast<uint32_t *>(s_bt + (16 * n16 + 4 * c4 + j) * kBtStride + q) = col[j];
+                for (int j = 0; j < 4; ++j) {
+                    const int n = 16 * bn16 + 4 * c4 + j;
+                    *reinterpret_cast<uint32_t *>(s_bt + n * kBtStride + (q ^ bt_swz(n))) = col[j];
+                }
             }
         }
         // this wave's output block rotates with the chunk index so that the causal work (tb + 1 block pairs)
@@ -331,6 +354,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         i32x4 ct[4];
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) ct[kk] = tl < nv ? cn[kk] : (i32x4){0, 0, 0, 0};
+        // the C rows must be taken out of their load registers here (the empty asm pins the selects to this point):
+        // a wait placed after the next chunk's loads are issued would wait for those as well
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(ct[kk]));
         __syncthreads();
 
         if (c + 1 < nchunks) issue_loads(c + 1);  // the next chunk's global loads fly while this chunk is computed
@@ -341,9 +368,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 
             // B rows of block sb as the A operand of G^T
             auto load_bq = [&](int sb, i32x4(&bq)[4]) {
-                const unsigned char *row = s_bq + (sb * kBlk + l32) * kBqStride + hb * 64;
+                const unsigned char *row = s_bq + (sb * kBlk + l32) * kBqStride + hb * 16;
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) bq[kk] = *reinterpret_cast<const i32x4 *>(row + 16 * kk);
+                for (int kk = 0; kk < 4; ++kk) bq[kk] = *reinterpret_cast<const i32x4 *>(row + 32 * kk);
             };
             auto gemm_g = [&](const i32x4(&bq)[4]) {
                 i32x16 gi;
@@ -371,8 +398,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
-                        hf[kk][pt] = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32) * kHsStride + hb * 64 +
-                                                                     8 * (2 * k2 + kk));
+                        hf[kk][pt] = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32) * kHsStride + 32 * k2 +
+                                                                     16 * hb + 8 * kk);
                 __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
 #pragma unroll
                 for (int kk = 0; kk < 2; ++kk) {
@@ -394,16 +421,19 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
-                        xa[ks][pt] = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + sb * kBlk +
-                                                                     16 * ks + 8 * hb);
+                        xa[ks][pt] = *reinterpret_cast<const f16x8 *>(
+                            s_xs + (pt * 32 + l32) * kXsStride + ((sb * kBlk + 16 * ks + 8 * hb) ^ xs_swz(pt * 32 + l32)));
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);
-                const i32x16 gn = gemm_g(bq);
+                // the current tile is narrowed before the next one is issued, so that both can share registers (the
+                // other wave of the SIMD fills the matrix core meanwhile)
                 const float rowf = __expf(cum_t - m_sb) * kNarrow;
                 float lv[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
+                __builtin_amdgcn_sched_barrier(0);
+                const i32x16 gn = gemm_g(bq);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -417,8 +447,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
-                        xw[ks][pt] = *reinterpret_cast<const u32x2 *>(s_xq + (pt * 32 + l32) * kXqStride + tb * kBlk +
-                                                                     16 * ks + 8 * hb);
+                        xw[ks][pt] = *reinterpret_cast<const u32x2 *>(
+                            s_xq + (pt * 32 + l32) * kXqStride + ((tb * kBlk + 16 * ks + 8 * hb) ^ xq_swz(pt * 32 + l32)));
                 f32x4 cs4[4], ds4[4];
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg) {  // four consecutive tokens of the block per register group
@@ -438,6 +468,24 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     }
                 }
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
+                f16x8 dhot[2][2];  // [hi, lo][k-step], rebuilt per chunk from two registers
+                {
+                    int slot = dslot;
+                    asm volatile("" : "+v"(slot));  // opaque: keeps the 16 operand registers from living across chunks
+                    const uint32_t dh = dpair & 0xffffu, dl = dpair >> 16;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        u32x4 wh, wl;
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            const int at = (ks * 4 + d) * 2;
+                            wh[d] = slot == at ? dh : (slot == at + 1 ? dh << 16 : 0u);
+                            wl[d] = slot == at ? dl : (slot == at + 1 ? dl << 16 : 0u);
+                        }
+                        dhot[0][ks] = __builtin_bit_cast(f16x8, wh);
+                        dhot[1][ks] = __builtin_bit_cast(f16x8, wl);
+                    }
+                }
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -497,7 +545,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
                                 const int p = pt * 32 + 8 * rg + 4 * hb + i;
-                                const float xc = (float)(signed char)s_xq[p * kXqStride + tq];
+                                const float xc = (float)(signed char)s_xq[p * kXqStride + (tq ^ xq_swz(p))];
                                 o[i] = (_Float16)(s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc));
                             }
                             const u32x2 ow = __builtin_bit_cast(u32x2, o);
@@ -511,6 +559,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     }
             }
         }
+
+        if (c + 1 < nchunks) issue_c_loads(c + 1);
 
         // ---- state update: wave w owns states n in [32w, 32w+32) ----
         if (PRECISE) {
@@ -527,12 +577,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const int col = sb * kBlk + 16 * ks + 8 * hb;
-                    const u32x2 w = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride + col);
+                    const u32x2 w = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride +
+                                                                    (col ^ bt_swz(32 * wave + l32)));
                     const f16x8 bf = i8x8_to_f16(w[0], w[1]);
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt) {
-                        const f16x8 xb = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
-                        const f16x8 xlo = *reinterpret_cast<const f16x8 *>(s_xl + (pt * 32 + l32) * kXsStride + col);
+                        const int xcol = col ^ xs_swz(pt * 32 + l32);
+                        const f16x8 xb = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + xcol);
+                        const f16x8 xlo = *reinterpret_cast<const f16x8 *>(s_xl + (pt * 32 + l32) * kXsStride + xcol);
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb, st[pt], 0, 0, 0);
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xlo, st[pt], 0, 0, 0);
                     }
@@ -554,10 +606,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const int col = sb * kBlk + 16 * ks + 8 * hb;
-                    bw[ks] = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride + col);
+                    bw[ks] = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride +
+                                                              (col ^ bt_swz(32 * wave + l32)));
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
-                        xb[ks][pt] = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + col);
+                        xb[ks][pt] = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride +
+                                                                     (col ^ xs_swz(pt * 32 + l32)));
                 }
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);

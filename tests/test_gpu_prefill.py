@@ -137,6 +137,43 @@ def test_dt_zero_and_permutation_invariance(gpu_lib):
     assert np.array_equal(y2, y1[:, :, hp][..., cp]) and np.array_equal(h2, h1[:, hp][:, :, cp])
 
 
+def test_tiny_scales_take_the_epilogue_skip_term(gpu_lib):
+    """With s_B s_C ~ 1e-10 the skip coefficient D / (s_B s_C 128) leaves the fp16 range, so the MFMA kernel must add
+    D x in its epilogue instead of through the matrix core; y is then dominated by D x and must still match."""
+    s = W.CONFIGS["m2_130m"].with_(seqlen=300)
+    sc, prob, _ = make_problem(s, 9, calib_tokens=256)
+    sc.B_scales = (sc.B_scales * 0 + 1e-5).astype(np.float32)
+    sc.C_scales = (sc.C_scales * 0 + 1e-5).astype(np.float32)
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"])
+    yg, hg = run_prefill(gpu_lib, s, sc, prob)
+    check(yg, hg, yref, href, "tiny B/C scales")
+    # and the opposite extreme: large B/C scales, D = 0 (pure SSM output)
+    sc.B_scales = (sc.B_scales * 0 + 0.5).astype(np.float32)
+    sc.C_scales = (sc.C_scales * 0 + 0.25).astype(np.float32)
+    sc.x_scales = (sc.x_scales * 1e-3).astype(np.float32)
+    p0 = dict(prob); p0["D"] = None
+    yref, href, _ = oracle.ref_prefill(sc, p0["x"], p0["B"], p0["C"], p0["dt"], p0["A"], None)
+    yg, hg = run_prefill(gpu_lib, s, sc, p0)
+    check(yg, hg, yref, href, "large B/C scales, no D")
+
+
+def test_precise_flag_without_final_state(gpu_lib):
+    """QUAMBA_FLAG_PRECISE_STATE selects the two-term state path even when no final state is returned."""
+    s = W.CONFIGS["m2_130m"].with_(seqlen=700)
+    sc, prob, _ = make_problem(s, 10, calib_tokens=256)
+    yref, _, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"], want_state=False)
+    yg, _ = run_prefill(gpu_lib, s, sc, prob, flags=0x2, want_state=False)
+    check(yg, None, yref, None, "precise flag, no state")
+
+
+def test_prefill_is_deterministic(gpu_lib):
+    s = W.CONFIGS["m2_130m"].with_(seqlen=512)
+    sc, prob, _ = make_problem(s, 11, calib_tokens=256)
+    y1, h1 = run_prefill(gpu_lib, s, sc, prob)
+    y2, h2 = run_prefill(gpu_lib, s, sc, prob)
+    assert np.array_equal(y1, y2) and np.array_equal(h1, h2)
+
+
 def test_prefill_then_decode_matches_longer_prefill(gpu_lib):
     """The final state is the resumable object: prefill(L) + k decode steps == prefill(L + k)."""
     import torch
