@@ -102,6 +102,26 @@ __device__ __forceinline__ void transpose4x4(const uint32_t r[4], uint32_t c[4])
     c[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
 }
 
+template <int CTRL, int ROW_MASK, bool BOUND>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, BOUND));
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves only (no LDS round trips):
+// shifts by 1, 2, 4, 8 inside each row of 16 lanes (zero fill), then the last lane of row 0/2 is added to row 1/3
+// and the last lane of row 1 to rows 2 and 3.
+__device__ __forceinline__ float wave_inclusive_scan(float v)
+{
+    v += dpp_f32<0x111, 0xf, true>(v);   // row_shr:1
+    v += dpp_f32<0x112, 0xf, true>(v);   // row_shr:2
+    v += dpp_f32<0x114, 0xf, true>(v);   // row_shr:4
+    v += dpp_f32<0x118, 0xf, true>(v);   // row_shr:8
+    v += dpp_f32<0x142, 0xa, false>(v);  // row_bcast:15 into rows 1 and 3
+    v += dpp_f32<0x143, 0xc, false>(v);  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 __device__ __forceinline__ f16x8 pack_f16x8(const float v[8])
 {
     f16x8 r;
@@ -150,24 +170,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     const float Dh = a.D ? a.D[h] : 0.0f;
     const float sB = a.B_scales[g], sC = a.C_scales[g];
     const float y_scale = sB * sC * (1.0f / kNarrow);
-    // Skip term D x[t,p]: x^T of the diagonal block is already an MFMA operand, so one more product with a scaled
-    // identity, D/y_scale * delta(s,t) split into two fp16 terms, adds it to the accumulators exactly (to 2^-22).
+    // Skip term D x[t,p]: the diagonal block multiplies exact x codes by L[t,s], so adding D/y_scale to L[t,t]
+    // (in fp32, before L is narrowed to fp16 like every other entry) makes the matrix core add D x for free.
     // When D/y_scale would leave the fp16 range (extreme scales), the term is added in the epilogue from LDS instead.
     const float d_acc = Dh / y_scale;
     const bool d_by_mfma = fabsf(d_acc) < 3.0e4f;
 
     if (tid < kP) s_sx[tid] = x_scale_lookup(a, h, tid) * (d_by_mfma ? y_scale : 1.0f);
     __syncthreads();
-    // The lane's column t = l32 of the scaled identity has one non-zero entry, in k-slot (l32 & 3) + 4 * bit 3 of
-    // k-step bit 4, and only in the half-wave hb = bit 2; packed here as (k-step * 4 + dword) * 2 + half, or -1.
-    const int dslot = ((l32 >> 2) & 1) == hb ? (((l32 >> 4) * 4 + ((l32 >> 3) & 1) * 2 + ((l32 >> 1) & 1)) * 2 + (l32 & 1)) : -1;
-    uint32_t dpair;  // fp16 bits of the two terms of D / y_scale: hi in the low half, lo in the high half
-    {
-        const _Float16 dhi = (_Float16)(d_by_mfma ? d_acc : 0.0f);
-        const _Float16 dlo = (_Float16)(d_by_mfma ? d_acc - (float)dhi : 0.0f);
-        dpair = (uint32_t)__builtin_bit_cast(uint16_t, dhi) | ((uint32_t)__builtin_bit_cast(uint16_t, dlo) << 16);
-    }
-
     // Carried state in x-code * B-code units (true state = s_x(p) s_B * st).  Wave w owns states n in
     // [32w, 32w+32); st[pt][r]: p = 32 pt + l32, n = 32 w + 8 (r/4) + 4 hb + r%4.
     f32x16 st[2];
@@ -256,12 +266,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         float cum0, cum1;  // prefix sums at tokens 2*lane and 2*lane + 1
         {
             const float a0 = dt0 * Ah, a1 = dt1 * Ah;
-            float scan = a0 + a1;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const float o = __shfl_up(scan, off, 64);
-                if (lane >= off) scan += o;
-            }
+            const float scan = wave_inclusive_scan(a0 + a1);
             cum0 = scan - a1;
             cum1 = scan;
         }
@@ -464,38 +469,17 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     for (int i = 0; i < 4; ++i) {
                         // exponent forced to a huge negative value above the diagonal: weight exactly 0, no branch
                         const float arg = (s0 + i <= l32) ? fminf(cum_t - cs4[rg][i], 0.0f) : -1.0e30f;
-                        lv[4 * rg + i] = (float)gi[4 * rg + i] * (__expf(arg) * ds4[rg][i] * kNarrow);
+                        const float dd = (d_by_mfma && s0 + i == l32) ? d_acc : 0.0f;  // skip term on the diagonal
+                        lv[4 * rg + i] = fmaf((float)gi[4 * rg + i], __expf(arg) * ds4[rg][i] * kNarrow, dd);
                     }
                 }
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
-                f16x8 dhot[2][2];  // [hi, lo][k-step], rebuilt per chunk from two registers
-                {
-                    int slot = dslot;
-                    asm volatile("" : "+v"(slot));  // opaque: keeps the 16 operand registers from living across chunks
-                    const uint32_t dh = dpair & 0xffffu, dl = dpair >> 16;
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) {
-                        u32x4 wh, wl;
-#pragma unroll
-                        for (int d = 0; d < 4; ++d) {
-                            const int at = (ks * 4 + d) * 2;
-                            wh[d] = slot == at ? dh : (slot == at + 1 ? dh << 16 : 0u);
-                            wl[d] = slot == at ? dl : (slot == at + 1 ? dl << 16 : 0u);
-                        }
-                        dhot[0][ks] = __builtin_bit_cast(f16x8, wh);
-                        dhot[1][ks] = __builtin_bit_cast(f16x8, wl);
-                    }
-                }
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt) {
                         const f16x8 xf = i8x8_to_f16(xw[ks][pt][0], xw[ks][pt][1]);
                         acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, ks ? l1 : l0, acc[pt], 0, 0, 0);
-                        if (d_by_mfma) {
-                            acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, dhot[0][ks], acc[pt], 0, 0, 0);
-                            acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, dhot[1][ks], acc[pt], 0, 0, 0);
-                        }
                     }
             }
 
