@@ -3,7 +3,7 @@
 // The step is a pure stream over the state (read 4 B + write 4 B per element, 3 FMAs), so the kernel is built
 // around HBM: one workgroup per (sequence, head), every lane owns 16-byte pieces of state rows, all of a lane's
 // loads are issued before any arithmetic, the d_state reduction of y stays in registers (cross-lane adds), and
-// the de-quantized per-row input x is staged once through a few hundred bytes of LDS.
+// the de-quantized per-row input x is staged through a few hundred bytes of LDS by each wave for its own rows.
 #include "quamba_internal.h"
 
 namespace quamba {
@@ -50,7 +50,9 @@ __device__ __forceinline__ void stage_x(const SsdArgs &a, int bh, int h, float *
 
 // Fast path: d_state = N (multiple of 4, N/4 a power of two <= 64).  A row of N floats is covered by N/4 lanes with
 // one float4 each; a wave covers 64/(N/4) rows per load instruction and keeps ROWS such instructions in flight.
-template <int N, int ROWS>
+// FULL: headdim is a multiple of the rows one pass of the workgroup covers, so no row needs clamping or masking and
+// the row addresses are one base plus compile-time offsets.
+template <int N, int ROWS, bool FULL>
 __global__ __launch_bounds__(kThreads) void decode_vec_kernel(SsdArgs a)
 {
     constexpr int LPR = N / 4;     // lanes per row
@@ -75,30 +77,33 @@ __global__ __launch_bounds__(kThreads) void decode_vec_kernel(SsdArgs a)
     const float4 Bv = make_float4(sB * bq.x, sB * bq.y, sB * bq.z, sB * bq.w);  // dt * B_t (B-dot of Sec. 3.2)
     const float4 Cv = make_float4(sC * cq.x, sC * cq.y, sC * cq.z, sC * cq.w);
 
-    bool staged = false;
     for (int p0 = wave * RPI * ROWS; p0 < P; p0 += kWaves * RPI * ROWS) {
         // all of the lane's loads first, unconditionally (rows past the end re-read the last row and are not stored)
         f32x4 v[ROWS];
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
-            const int p = min(p0 + i * RPI + sub, P - 1);
+            const int p = FULL ? p0 + i * RPI + sub : min(p0 + i * RPI + sub, P - 1);
             v[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(st + (size_t)p * N));
         }
-        if (!staged) {  // first trip: stage x while the state loads are in flight
-            stage_x(a, bh, h, xv);
-            __syncthreads();
-            staged = true;
+        // de-quantized x of the rows of this trip, staged by the wave for itself while its state loads are in
+        // flight: no workgroup barrier, the waves never wait for each other (LDS accesses of one wave stay in order)
+        for (int r = lane; r < RPI * ROWS; r += 64) {
+            const int p = p0 + r;
+            if (FULL || p < P) xv[p] = x_scale_lookup(a, h, p) * (float)a.x[(size_t)bh * P + p];
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         float part[ROWS];
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
-            const int p = min(p0 + i * RPI + sub, P - 1);
+            const int p = FULL ? p0 + i * RPI + sub : min(p0 + i * RPI + sub, P - 1);
             const float x = xv[p];
             v[i].x = fmaf(dA, v[i].x, Bv.x * x);
             v[i].y = fmaf(dA, v[i].y, Bv.y * x);
             v[i].z = fmaf(dA, v[i].z, Bv.z * x);
             v[i].w = fmaf(dA, v[i].w, Bv.w * x);
-            if (p0 + i * RPI + sub < P)
+            if (FULL || p0 + i * RPI + sub < P)
                 __builtin_nontemporal_store(v[i], reinterpret_cast<f32x4 *>(st + (size_t)p * N));
             part[i] = fmaf(Cv.x, v[i].x, fmaf(Cv.y, v[i].y, fmaf(Cv.z, v[i].z, Cv.w * v[i].w)));
         }
@@ -107,12 +112,8 @@ __global__ __launch_bounds__(kThreads) void decode_vec_kernel(SsdArgs a)
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
             const int p = p0 + i * RPI + sub;
-            if (j == 0 && p < P) a.y[(size_t)bh * P + p] = f32_to_f16_bits(fmaf(Dh, xv[p], part[i]));
+            if (j == 0 && (FULL || p < P)) a.y[(size_t)bh * P + p] = f32_to_f16_bits(fmaf(Dh, xv[p], part[i]));
         }
-    }
-    if (!staged) {  // a wave that owned no row still joins the barrier
-        stage_x(a, bh, h, xv);
-        __syncthreads();
     }
 }
 
@@ -154,10 +155,13 @@ template <int N>
 hipError_t launch_vec(const SsdArgs &a, hipStream_t stream)
 {
     constexpr int LPR = N / 4, RPI = 64 / LPR;
-    constexpr int ROWS = (RPI * 8 * kWaves <= 64) ? 8 : (RPI * 4 * kWaves <= 64 ? 4 : (RPI <= 8 ? 2 : 1));
+    constexpr int ROWS = (RPI * 4 * kWaves <= 64) ? 4 : (RPI <= 8 ? 2 : 1);  // rows per lane in flight per trip
     const dim3 grid((unsigned)(a.s.batch * a.s.nheads));
     const size_t lds = sizeof(float) * (size_t)a.s.headdim;
-    hipLaunchKernelGGL((decode_vec_kernel<N, ROWS>), grid, dim3(kThreads), lds, stream, a);
+    if (a.s.headdim % (kWaves * RPI * ROWS) == 0)
+        hipLaunchKernelGGL((decode_vec_kernel<N, ROWS, true>), grid, dim3(kThreads), lds, stream, a);
+    else
+        hipLaunchKernelGGL((decode_vec_kernel<N, ROWS, false>), grid, dim3(kThreads), lds, stream, a);
     return hipGetLastError();
 }
 
