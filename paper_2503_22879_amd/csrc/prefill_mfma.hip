@@ -64,6 +64,9 @@ static_assert(kOffXq % 16 == 0 && kOffBt % 16 == 0 && kOffBq % 16 == 0 && kOffHs
                   kOffXl % 16 == 0, "LDS arrays must be 16-byte aligned");
 static_assert(kLdsFast <= 80 * 1024, "two workgroups must fit the 160 KB LDS of a gfx950 compute unit");
 
+// 2^x by the hardware instruction (prefix sums are carried in log2 units, so no multiply by log2 e is needed).
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // Storage position of token s of the chunk inside an LDS row: bits 2 and 3 swapped (see file comment).
 __device__ __forceinline__ int tok_pos(int s) { return (s & ~12) | ((s & 4) << 1) | ((s & 8) >> 1); }
 
@@ -166,7 +169,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps block indices in scalar registers
     const int l32 = lane & 31, hb = lane >> 5;
 
-    const float Ah = a.A[h];
+    const float Ah = a.A[h] * 1.44269504088896340736f;  // log2(e): prefix sums are kept in log2 units (exp2 below)
     const float Dh = a.D ? a.D[h] : 0.0f;
     const float sB = a.B_scales[g], sC = a.C_scales[g];
     const float y_scale = sB * sC * (1.0f / kNarrow);
@@ -272,7 +275,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         }
         if (wave == 0) {
             *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
-            *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(dt0, dt1);
+            *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(dt0 * kNarrow, dt1 * kNarrow);  // pre-narrowed
         }
 
         // carried state -> LDS as fp16 (operand of the C.H product of this chunk)
@@ -300,7 +303,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             float colf[4], c128[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                colf[k] = __expf(m - cumq[k]) * dtq[k];
+                colf[k] = exp2_fast(m - cumq[k]) * dtq[k];
                 c128[k] = -128.0f * colf[k];
             }
             // bank swizzles of the two x arrays (readers apply the same): codes, 32 bytes by bit 5 of the channel;
@@ -309,7 +312,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             for (int c4 = 0; c4 < 2; ++c4) {
                 uint32_t rows[4];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) rows[k] = s0 + k < nv ? xr[k][c4] : 0u;
+                for (int k = 0; k < 4; ++k) rows[k] = xr[k][c4];
+                if (nv < kQ) {  // partial last chunk: rows past the end are zero
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) rows[k] = s0 + k < nv ? rows[k] : 0u;
+                }
                 uint32_t col[4];
                 transpose4x4(rows, col);
 #pragma unroll
@@ -335,11 +342,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         }
         {
             const int q = tok_pos(4 * bs4);
+            if (nv < kQ) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if (4 * bs4 + k >= nv) br[k] = (u32x4){0u, 0u, 0u, 0u};
-                *reinterpret_cast<u32x4 *>(s_bq + (4 * bs4 + k) * kBqStride + 16 * bn16) = br[k];
+                for (int k = 0; k < 4; ++k)
+                    if (4 * bs4 + k >= nv) br[k] = (u32x4){0u, 0u, 0u, 0u};
             }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                *reinterpret_cast<u32x4 *>(s_bq + (4 * bs4 + k) * kBqStride + 16 * bn16) = br[k];
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4) {
                 const uint32_t rows[4] = {br[0][c4], br[1][c4], br[2][c4], br[3][c4]};
@@ -358,7 +368,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         const int tl = tb * kBlk + l32;  // this lane's token inside the chunk
         i32x4 ct[4];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) ct[kk] = tl < nv ? cn[kk] : (i32x4){0, 0, 0, 0};
+        for (int kk = 0; kk < 4; ++kk) ct[kk] = cn[kk];
+        if (nv < kQ) {
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) ct[kk] = tl < nv ? ct[kk] : (i32x4){0, 0, 0, 0};
+        }
         // the C rows must be taken out of their load registers here (the empty asm pins the selects to this point):
         // a wait placed after the next chunk's loads are issued would wait for those as well
 #pragma unroll
@@ -395,7 +409,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[pt][r] = 0.0f;
-            const _Float16 e_t = (_Float16)__expf(cum_t);  // per lane (token t); folded into the C operand
+            const _Float16 e_t = (_Float16)exp2_fast(cum_t);  // per lane (token t); folded into the C operand
 #pragma unroll
             for (int k2 = 0; k2 < 4; ++k2) {  // batches of two k-steps: all LDS reads of a batch are issued first
                 f16x8 hf[2][2];
@@ -432,7 +446,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 __builtin_amdgcn_sched_barrier(0);
                 // the current tile is narrowed before the next one is issued, so that both can share registers (the
                 // other wave of the SIMD fills the matrix core meanwhile)
-                const float rowf = __expf(cum_t - m_sb) * kNarrow;
+                const float rowf = exp2_fast(cum_t - m_sb) * kNarrow;
                 float lv[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
@@ -468,9 +482,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         // exponent forced to a huge negative value above the diagonal: weight exactly 0, no branch
-                        const float arg = (s0 + i <= l32) ? fminf(cum_t - cs4[rg][i], 0.0f) : -1.0e30f;
+                        // cum is non-increasing (dt >= 0, A <= 0), so the exponent is <= 0 on and below the diagonal
+                        const float arg = (s0 + i <= l32) ? cum_t - cs4[rg][i] : -1.0e30f;
                         const float dd = (d_by_mfma && s0 + i == l32) ? d_acc : 0.0f;  // skip term on the diagonal
-                        lv[4 * rg + i] = fmaf((float)gi[4 * rg + i], __expf(arg) * ds4[rg][i] * kNarrow, dd);
+                        lv[4 * rg + i] = fmaf((float)gi[4 * rg + i], exp2_fast(arg) * ds4[rg][i], dd);
                     }
                 }
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
@@ -552,7 +567,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             for (int sb = 0; sb < kNBlk; ++sb) {
                 if (sb * kBlk >= nv) break;  // the padded steps are identity steps
                 const float m = s_cum[sb * kBlk + kBlk - 1];
-                const float gdec = __expf(m - m_prev);
+                const float gdec = exp2_fast(m - m_prev);
                 m_prev = m;
 #pragma unroll
                 for (int pt = 0; pt < 2; ++pt)
@@ -577,7 +592,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         } else {
             const float cum_last = s_cum[kQ - 1];  // padded steps leave cum flat, so this is cum at the last valid token
             {
-                const float gdec = __expf(cum_last);
+                const float gdec = exp2_fast(cum_last);
 #pragma unroll
                 for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
@@ -599,7 +614,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 }
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);
-                const _Float16 f = (_Float16)__expf(cum_last - m_sb);
+                const _Float16 f = (_Float16)exp2_fast(cum_last - m_sb);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const f16x8 bf = i8x8_to_f16(bw[ks][0], bw[ks][1]) * f;
