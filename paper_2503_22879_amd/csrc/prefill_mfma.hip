@@ -181,8 +181,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 
     if (tid < kP) s_sx[tid] = x_scale_lookup(a, h, tid) * (d_by_mfma ? y_scale : 1.0f);
     __syncthreads();
-    // Carried state in x-code * B-code units (true state = s_x(p) s_B * st).  Wave w owns states n in
+    // Carried state in x-code * B-code units times kStScale (true state = s_x(p) s_B * st / kStScale): on the fast
+    // path the state is carried already narrowed by 2^-7, so that its fp16 copy for the C.H product needs no multiply
+    // (the factor rides on the per-block weight of the B operand instead).  Wave w owns states n in
     // [32w, 32w+32); st[pt][r]: p = 32 pt + l32, n = 32 w + 8 (r/4) + 4 hb + r%4.
+    constexpr float kStScale = PRECISE ? 1.0f : kNarrow;
     f32x16 st[2];
 #pragma unroll
     for (int pt = 0; pt < 2; ++pt)
@@ -192,7 +195,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt) {
             const int p = pt * 32 + l32;
-            const float inv = (d_by_mfma ? y_scale : 1.0f) / (s_sx[p] * sB);
+            const float inv = kStScale * (d_by_mfma ? y_scale : 1.0f) / (s_sx[p] * sB);
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 const int n0 = 32 * wave + 8 * rg + 4 * hb;
@@ -285,7 +288,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             for (int rg = 0; rg < 4; ++rg) {
                 f16x4 v;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = (_Float16)(st[pt][4 * rg + i] * kNarrow);
+                for (int i = 0; i < 4; ++i) v[i] = (_Float16)(st[pt][4 * rg + i] * (kNarrow / kStScale));
                 *reinterpret_cast<f16x4 *>(s_hs + (pt * 32 + l32) * kHsStride + 32 * wave + 8 * rg + 4 * hb) = v;
             }
 
@@ -614,7 +617,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 }
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);
-                const _Float16 f = (_Float16)exp2_fast(cum_last - m_sb);
+                const _Float16 f = (_Float16)(exp2_fast(cum_last - m_sb) * kStScale);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const f16x8 bf = i8x8_to_f16(bw[ks][0], bw[ks][1]) * f;
@@ -631,7 +634,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt) {
             const int p = pt * 32 + l32;
-            const float sc = s_sx[p] * sB / (d_by_mfma ? y_scale : 1.0f);
+            const float sc = s_sx[p] * sB / ((d_by_mfma ? y_scale : 1.0f) * kStScale);
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 const int n0 = 32 * wave + 8 * rg + 4 * hb;
