@@ -22,7 +22,10 @@
 // int8 codes are exact in fp16; G (|G| <= 2^21) is scaled by 2^-7 in fp32 before it is narrowed.
 // The MFMA output layout (a lane holds one column and 16 rows) equals the operand layout (a lane holds one
 // row/column and 8 or 16 consecutive k) up to a fixed permutation of k, so G^T tiles feed the next MFMA straight
-// from registers; x^T and B^T are stored in LDS with that permutation (bits 2 and 3 of the token index swapped).
+// from registers.  x, x' and B sit in LDS token-major, exactly as they arrive (no transposes on the vector ALU); the
+// operands that need the token index as k (x^T, x'^T, B^T) are fetched with the transposing LDS loads
+// (ds_read_b64_tr_b8 / _tr_b16), whose source lanes address whole token rows; the rows are stored with bits 2 and 3
+// of the token index swapped so that the 8 tokens of one k group are 8 consecutive rows.
 #include "quamba_internal.h"
 
 namespace quamba {
@@ -40,11 +43,12 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kP = 64, kN = 128, kQ = 128, kBlk = 32, kNBlk = kQ / kBlk;
 constexpr int kThreads = 256;
-constexpr int kXqStride = 136;  // bytes per row of xq^T [p][token]
-constexpr int kBtStride = 136;  // bytes per row of Bq^T [n][token]
-constexpr int kXsStride = 136;  // halves per row of x'^T [p][token]
+// Row pitches: with 4-byte banks, the 8 token rows x 16 bytes a group of 16 lanes fetches from xq or Bq, and the 4 token
+// rows x 32 bytes it fetches from x', fall into distinct banks (pitch = 20, 36 and 40 banks).
+constexpr int kXqStride = 80;   // bytes per row of xq [token][p]
+constexpr int kXsStride = 80;   // halves per row of x' [token][p]
 constexpr int kHsStride = 136;  // halves per row of H [p][n]
-constexpr int kBqStride = 144;  // bytes per row of Bq [token][n] (operand of the G^T product)
+constexpr int kBqStride = 144;  // bytes per row of Bq [token][n]
 constexpr float kNarrow = 1.0f / 128.0f;  // applied to G and H before narrowing to fp16; undone in the epilogue
 
 // LDS map (bytes)
@@ -52,30 +56,46 @@ constexpr int kOffCum = 0;                             // float[128]
 constexpr int kOffDt = kOffCum + 4 * kQ;               // float[128]
 constexpr int kOffSx = kOffDt + 4 * kQ;                // float[64]
 constexpr int kOffWt = kOffSx + 4 * kP;                // float[4] (+pad)
-constexpr int kOffXq = kOffWt + 64;                    // int8 [64][136]
-constexpr int kOffBt = kOffXq + kP * kXqStride;        // int8 [128][136]
-constexpr int kOffBq = kOffBt + kN * kBtStride;        // int8 [128][144]
+constexpr int kOffXq = kOffWt + 64;                    // int8 [128][80]
+constexpr int kOffBq = kOffXq + kQ * kXqStride;        // int8 [128][144]
 constexpr int kOffHs = kOffBq + kQ * kBqStride;        // fp16 [64][136]
-constexpr int kOffXs = kOffHs + 2 * kP * kHsStride;    // fp16 [64][136]
-constexpr int kOffXl = kOffXs + 2 * kP * kXsStride;    // fp16 [64][136]  low halves of x' (two-term state path only)
+constexpr int kOffXs = kOffHs + 2 * kP * kHsStride;    // fp16 [128][80]
+constexpr int kOffXl = kOffXs + 2 * kQ * kXsStride;    // fp16 [128][80]  low halves of x' (two-term state path only)
 constexpr int kLdsFast = kOffXl;
-constexpr int kLdsPrecise = kOffXl + 2 * kP * kXsStride;
-static_assert(kOffXq % 16 == 0 && kOffBt % 16 == 0 && kOffBq % 16 == 0 && kOffHs % 16 == 0 && kOffXs % 16 == 0 &&
-                  kOffXl % 16 == 0, "LDS arrays must be 16-byte aligned");
+constexpr int kLdsPrecise = kOffXl + 2 * kQ * kXsStride;
+static_assert(kOffXq % 16 == 0 && kOffBq % 16 == 0 && kOffHs % 16 == 0 && kOffXs % 16 == 0 && kOffXl % 16 == 0,
+              "LDS arrays must be 16-byte aligned");
 static_assert(kLdsFast <= 80 * 1024, "two workgroups must fit the 160 KB LDS of a gfx950 compute unit");
 
 // 2^x by the hardware instruction (prefix sums are carried in log2 units, so no multiply by log2 e is needed).
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Storage position of token s of the chunk inside an LDS row: bits 2 and 3 swapped (see file comment).
+// LDS row of token s of the chunk: bits 2 and 3 swapped (see file comment).
 __device__ __forceinline__ int tok_pos(int s) { return (s & ~12) | ((s & 4) << 1) | ((s & 8) >> 1); }
 
-// Bank swizzles: XOR masks on the (permuted) token position of an LDS row, a function of the row index, so that
-// the staging writes of one wave-wide instruction hit distinct banks.  Readers apply the same mask; it is uniform
-// over the 16 lanes that read together.
-__device__ __forceinline__ int xq_swz(int p) { return ((p >> 5) & 1) << 5; }  // x codes: 32 tokens (bytes)
-__device__ __forceinline__ int xs_swz(int p) { return ((p >> 4) & 3) << 4; }  // scaled x: 16, 32 or 48 tokens
-__device__ __forceinline__ int bt_swz(int n) { return ((n >> 5) & 1) << 6; }  // B^T codes: 64 tokens (bytes)
+// Transposing LDS loads.  Inside each group of 16 lanes, result byte j of lane i comes from the 8 bytes addressed by
+// lane 2j + (i >> 3), byte i & 7 (8-bit form); result half j of lane i from the 8 bytes addressed by lane
+// 4j + (i >> 2), half i & 3 (16-bit form).  With source lane 2j + q pointing at (token row j, 8 columns starting at
+// 8q), resp. 4j + q at (token row j, 4 columns starting at 4q), lane i receives column i of 8 (resp. 4) token rows:
+// the layout of an MFMA operand whose k index is the token.
+typedef int v2i_lds __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x2 lds_read_tr8(const unsigned char *p)
+{
+    return __builtin_bit_cast(
+        u32x2, __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i_lds *)(p)));
+}
+__device__ __forceinline__ f16x4 lds_read_tr16(const unsigned char *p)
+{
+    typedef short v4s_lds __attribute__((ext_vector_type(4)));
+    return __builtin_bit_cast(
+        f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_lds *)(p)));
+}
+// 8 tokens x one column of fp16 x' (two 4-token transposing loads, token rows r .. r+7 of the lane group)
+__device__ __forceinline__ f16x8 lds_read_tr16x8(const unsigned char *p)
+{
+    const f16x4 lo = lds_read_tr16(p), hi = lds_read_tr16(p + 4 * 2 * kXsStride);
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
 
 // 8 int8 codes (two dwords, lowest address first) -> 8 exact fp16 values: byte^0x80 placed under the fp16
 // pattern of 1024 gives 1024 + (code + 128); subtract 1152.
@@ -90,19 +110,6 @@ __device__ __forceinline__ f16x8 i8x8_to_f16(uint32_t w0, uint32_t w1)
     r.h[2] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x64646464u, w1, 0x04010400u)) - bias;
     r.h[3] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x64646464u, w1, 0x04030402u)) - bias;
     return r.v;
-}
-
-// 4x4 byte transpose: r[k] holds 4 consecutive columns of row k; c[j] gets column j of rows 0..3.
-__device__ __forceinline__ void transpose4x4(const uint32_t r[4], uint32_t c[4])
-{
-    const uint32_t t0 = __builtin_amdgcn_perm(r[1], r[0], 0x05010400u);
-    const uint32_t t1 = __builtin_amdgcn_perm(r[1], r[0], 0x07030602u);
-    const uint32_t t2 = __builtin_amdgcn_perm(r[3], r[2], 0x05010400u);
-    const uint32_t t3 = __builtin_amdgcn_perm(r[3], r[2], 0x07030602u);
-    c[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
-    c[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
-    c[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
-    c[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
 }
 
 template <int CTRL, int ROW_MASK, bool BOUND>
@@ -156,11 +163,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     float *s_dt = reinterpret_cast<float *>(smem + kOffDt);
     float *s_sx = reinterpret_cast<float *>(smem + kOffSx);
     unsigned char *s_xq = smem + kOffXq;
-    unsigned char *s_bt = smem + kOffBt;
     unsigned char *s_bq = smem + kOffBq;
     _Float16 *s_hs = reinterpret_cast<_Float16 *>(smem + kOffHs);
-    _Float16 *s_xs = reinterpret_cast<_Float16 *>(smem + kOffXs);
-    _Float16 *s_xl = reinterpret_cast<_Float16 *>(smem + kOffXl);  // PRECISE only
+    unsigned char *s_xs = smem + kOffXs;  // fp16 rows, addressed in bytes
+    unsigned char *s_xl = smem + kOffXl;  // PRECISE only
 
     const int L = a.s.seqlen, H = a.s.nheads, G = a.s.ngroups;
     const int bh = block_to_bh(a);
@@ -168,6 +174,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps block indices in scalar registers
     const int l32 = lane & 31, hb = lane >> 5;
+    // Two workgroups share a compute unit, wave w of each on SIMD w (workgroups i and i + 8 land on one compute unit:
+    // consecutive ids go round the 8 XCDs).  The causal work of a wave grows with its block index, so every other
+    // workgroup of an XCD walks its blocks in the opposite order: a SIMD then holds a long and a short block at a
+    // time instead of two long or two short ones.
+    const int rot_flip = ((blockIdx.x >> 3) & 1) ? (kNBlk - 1) : 0;
 
     const float Ah = a.A[h] * 1.44269504088896340736f;  // log2(e): prefix sums are kept in log2 units (exp2 below)
     const float Dh = a.D ? a.D[h] : 0.0f;
@@ -178,6 +189,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     // When D/y_scale would leave the fp16 range (extreme scales), the term is added in the epilogue from LDS instead.
     const float d_acc = Dh / y_scale;
     const bool d_by_mfma = fabsf(d_acc) < 3.0e4f;
+    const float d_sel = d_by_mfma ? d_acc : 0.0f;
 
     if (tid < kP) s_sx[tid] = x_scale_lookup(a, h, tid) * (d_by_mfma ? y_scale : 1.0f);
     __syncthreads();
@@ -217,10 +229,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     u32x4 br[4];
     i32x4 cn[4];
     float dt0 = 0.0f, dt1 = 0.0f;  // dt of tokens 2*lane and 2*lane + 1 (every wave holds the whole chunk's dt)
-    // Staging lane maps, chosen so that the LDS writes of a wave-wide instruction fall into distinct banks:
-    // x: 8 channel groups x 8 token quads per wave; B: 4 state groups x 16 token quads per wave.
+    // Staging lane maps: a thread takes 4 consecutive tokens and 8 channels of x (8 lanes cover a 64-byte row), resp.
+    // 16 states of B (8 lanes cover a 128-byte row).
     const int xs4 = tid >> 3, xp8 = tid & 7;
-    const int bs4 = ((lane >> 2) & 15) + 16 * (wave & 1), bn16 = (lane & 3) + 4 * (wave >> 1);
+    const int bs4 = tid >> 3, bn16 = tid & 7;
     // Addresses are a wave-uniform 64-bit base (advanced per chunk) plus a 32-bit lane offset that does not change
     // from chunk to chunk; only the last, partial chunk needs the offsets of the rows past the end redirected.
     const uint32_t x_row = (uint32_t)H * kP, b_row = (uint32_t)G * kN, dt_row = (uint32_t)H * 4u;
@@ -252,7 +264,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             const uint32_t row = (uint32_t)min(4 * bs4 + k, nv - 1);
             br[k] = *reinterpret_cast<const u32x4 *>(bbase + (row * b_row + 16u * bn16));
         }
-        const uint32_t row = (uint32_t)min(((wave + c) & (kNBlk - 1)) * kBlk + l32, nv - 1);
+        const uint32_t row = (uint32_t)min((((wave + c) & (kNBlk - 1)) ^ rot_flip) * kBlk + l32, nv - 1);
         const int8_t *crow = cbase + (row * b_row + 16u * hb);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) cn[kk] = *reinterpret_cast<const i32x4 *>(crow + 32 * kk);
@@ -292,9 +304,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 *reinterpret_cast<f16x4 *>(s_hs + (pt * 32 + l32) * kHsStride + 32 * wave + 8 * rg + 4 * hb) = v;
             }
 
-        // ---- x^T (codes and scaled fp16) and B^T (codes) into LDS, token positions permuted; B row-major ----
+        // ---- x codes, x' (fp16) and B codes into LDS, token-major, token rows permuted ----
         {
-            const int s0 = 4 * xs4, q = tok_pos(s0);
+            const int s0 = 4 * xs4, row0 = tok_pos(s0);
             // cum and dt of tokens s0 .. s0+3 sit in lanes 2*xs4 and 2*xs4 + 1 of this wave; m in the lane of the
             // block's last token
             const int l0 = 2 * xs4, lm = ((s0 & ~31) >> 1) + 15;
@@ -303,48 +315,36 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             const float dtq[4] = {__shfl(dt0, l0, 64), __shfl(dt1, l0, 64), __shfl(dt0, l0 + 1, 64),
                                   __shfl(dt1, l0 + 1, 64)};
             const float m = __shfl(cum1, lm, 64);
-            float colf[4], c128[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                colf[k] = exp2_fast(m - cumq[k]) * dtq[k];
-                c128[k] = -128.0f * colf[k];
-            }
-            // bank swizzles of the two x arrays (readers apply the same): codes, 32 bytes by bit 5 of the channel;
-            // scaled fp16, 16 tokens times bits 4..5 of the channel
-#pragma unroll
-            for (int c4 = 0; c4 < 2; ++c4) {
-                uint32_t rows[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) rows[k] = xr[k][c4];
+                u32x2 w = xr[k];
                 if (nv < kQ) {  // partial last chunk: rows past the end are zero
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) rows[k] = s0 + k < nv ? rows[k] : 0u;
+                    if (s0 + k >= nv) w = (u32x2){0u, 0u};
                 }
-                uint32_t col[4];
-                transpose4x4(rows, col);
+                const float colf = exp2_fast(m - cumq[k]) * dtq[k];
+                *reinterpret_cast<u32x2 *>(s_xq + (row0 + k) * kXqStride + 8 * xp8) = w;
+                if (!PRECISE) {
+                    // exact fp16 codes times the fp16 weight of the token: one more rounding (2^-11 relative, of the
+                    // weight) than an fp32 product, well inside the budget of y
+                    const f16x8 v = i8x8_to_f16(w[0], w[1]) * (_Float16)colf;
+                    *reinterpret_cast<f16x8 *>(s_xs + ((row0 + k) * kXsStride + 8 * xp8) * 2) = v;
+                } else {
+                    const float c128 = -128.0f * colf;
+                    f16x8 hi, lo;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int p = 8 * xp8 + 4 * c4 + j;
-                    *reinterpret_cast<uint32_t *>(s_xq + p * kXqStride + (q ^ xq_swz(p))) = col[j];
-                    const uint32_t u = col[j] ^ 0x80808080u;
-                    float v[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) v[k] = fmaf((float)((u >> (8 * k)) & 0xffu), colf[k], c128[k]);
-                    f16x4 hi;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) hi[k] = (_Float16)v[k];
-                    *reinterpret_cast<f16x4 *>(s_xs + p * kXsStride + (q ^ xs_swz(p))) = hi;
-                    if (PRECISE) {
-                        f16x4 lo;
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) lo[k] = (_Float16)(v[k] - (float)hi[k]);
-                        *reinterpret_cast<f16x4 *>(s_xl + p * kXsStride + (q ^ xs_swz(p))) = lo;
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t u = (w[j >> 2] ^ 0x80808080u) >> (8 * (j & 3)) & 0xffu;
+                        const float v = fmaf((float)u, colf, c128);
+                        hi[j] = (_Float16)v;
+                        lo[j] = (_Float16)(v - (float)hi[j]);
                     }
+                    *reinterpret_cast<f16x8 *>(s_xs + ((row0 + k) * kXsStride + 8 * xp8) * 2) = hi;
+                    *reinterpret_cast<f16x8 *>(s_xl + ((row0 + k) * kXsStride + 8 * xp8) * 2) = lo;
                 }
             }
         }
         {
-            const int q = tok_pos(4 * bs4);
+            const int row0 = tok_pos(4 * bs4);
             if (nv < kQ) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
@@ -352,22 +352,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                *reinterpret_cast<u32x4 *>(s_bq + (4 * bs4 + k) * kBqStride + 16 * bn16) = br[k];
-#pragma unroll
-            for (int c4 = 0; c4 < 4; ++c4) {
-                const uint32_t rows[4] = {br[0][c4], br[1][c4], br[2][c4], br[3][c4]};
-                uint32_t col[4];
-                transpose4x4(rows, col);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int n = 16 * bn16 + 4 * c4 + j;
-                    *reinterpret_cast<uint32_t *>(s_bt + n * kBtStride + (q ^ bt_swz(n))) = col[j];
-                }
-            }
+                *reinterpret_cast<u32x4 *>(s_bq + (row0 + k) * kBqStride + 16 * bn16) = br[k];
         }
         // this wave's output block rotates with the chunk index so that the causal work (tb + 1 block pairs)
         // evens out over four chunks
-        const int tb = (wave + c) & (kNBlk - 1);
+        const int tb = ((wave + c) & (kNBlk - 1)) ^ rot_flip;
         const int tl = tb * kBlk + l32;  // this lane's token inside the chunk
         i32x4 ct[4];
 #pragma unroll
@@ -386,11 +375,21 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 
         // ---- outputs of block tb ----
         if (tb * kBlk < nv) {
-            const float cum_t = s_cum[tl];
+            // LDS addresses of this phase are rebuilt from a lane index the compiler must treat as new in every chunk:
+            // kept in registers across the whole chunk loop they would push other values into scratch memory
+            int lane_a = lane;
+            asm volatile("" : "+v"(lane_a));
+            const int l32a = lane_a & 31, hba = lane_a >> 5;
+            // source-lane roles of the transposing loads (see lds_read_tr8 / lds_read_tr16): token row of the lane
+            // inside a k group of 8 tokens, and its first column inside the 32 columns of the operand
+            const int i16 = lane_a & 15, c16 = (lane_a >> 4) & 1;
+            const unsigned char *xq_src = s_xq + (8 * hba + (i16 >> 1)) * kXqStride + 16 * c16 + 8 * (i16 & 1);
+            const unsigned char *xs_src = s_xs + ((8 * hba + (i16 >> 2)) * kXsStride + 16 * c16 + 4 * (i16 & 3)) * 2;
+            const float cum_t = s_cum[tb * kBlk + l32a];
 
             // B rows of block sb as the A operand of G^T
             auto load_bq = [&](int sb, i32x4(&bq)[4]) {
-                const unsigned char *row = s_bq + (sb * kBlk + l32) * kBqStride + hb * 16;
+                const unsigned char *row = s_bq + (sb * kBlk + tok_pos(l32a)) * kBqStride + hba * 16;
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) bq[kk] = *reinterpret_cast<const i32x4 *>(row + 32 * kk);
             };
@@ -420,8 +419,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
-                        hf[kk][pt] = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32) * kHsStride + 32 * k2 +
-                                                                     16 * hb + 8 * kk);
+                        hf[kk][pt] = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32a) * kHsStride + 32 * k2 +
+                                                                     16 * hba + 8 * kk);
                 __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
 #pragma unroll
                 for (int kk = 0; kk < 2; ++kk) {
@@ -443,8 +442,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
-                        xa[ks][pt] = *reinterpret_cast<const f16x8 *>(
-                            s_xs + (pt * 32 + l32) * kXsStride + ((sb * kBlk + 16 * ks + 8 * hb) ^ xs_swz(pt * 32 + l32)));
+                        xa[ks][pt] = lds_read_tr16x8(xs_src + ((sb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);
                 // the current tile is narrowed before the next one is issued, so that both can share registers (the
@@ -469,13 +467,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
-                        xw[ks][pt] = *reinterpret_cast<const u32x2 *>(
-                            s_xq + (pt * 32 + l32) * kXqStride + ((tb * kBlk + 16 * ks + 8 * hb) ^ xq_swz(pt * 32 + l32)));
+                        xw[ks][pt] = lds_read_tr8(xq_src + (tb * kBlk + 16 * ks) * kXqStride + 32 * pt);
                 f32x4 cs4[4], ds4[4];
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg) {  // four consecutive tokens of the block per register group
-                    cs4[rg] = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + 8 * rg + 4 * hb);
-                    ds4[rg] = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + 8 * rg + 4 * hb);
+                    cs4[rg] = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + 8 * rg + 4 * hba);
+                    ds4[rg] = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + 8 * rg + 4 * hba);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 float lv[16];
@@ -487,7 +484,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                         // exponent forced to a huge negative value above the diagonal: weight exactly 0, no branch
                         // cum is non-increasing (dt >= 0, A <= 0), so the exponent is <= 0 on and below the diagonal
                         const float arg = (s0 + i <= l32) ? cum_t - cs4[rg][i] : -1.0e30f;
-                        const float dd = (d_by_mfma && s0 + i == l32) ? d_acc : 0.0f;  // skip term on the diagonal
+                        float dd = (s0 + i == l32) ? d_sel : 0.0f;  // skip term on the diagonal
+                        asm volatile("" : "+v"(dd));  // selected here, not kept in 16 registers across the chunk loop
                         lv[4 * rg + i] = fmaf((float)gi[4 * rg + i], exp2_fast(arg) * ds4[rg][i], dd);
                     }
                 }
@@ -511,7 +509,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     f32x4 k4[4];  // s_x(h,p) * y_scale of the lane's 16 channels of this p tile
 #pragma unroll
                     for (int rg = 0; rg < 4; ++rg)
-                        k4[rg] = *reinterpret_cast<const f32x4 *>(s_sx + pt * 32 + 8 * rg + 4 * hb);
+                        k4[rg] = *reinterpret_cast<const f32x4 *>(s_sx + pt * 32 + 8 * rg + 4 * hba);
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         uint32_t w[2][2];  // [register group 2j, 2j+1][dword]
@@ -547,7 +545,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
                                 const int p = pt * 32 + 8 * rg + 4 * hb + i;
-                                const float xc = (float)(signed char)s_xq[p * kXqStride + (tq ^ xq_swz(p))];
+                                const float xc = (float)(signed char)s_xq[tq * kXqStride + p];
                                 o[i] = (_Float16)(s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc));
                             }
                             const u32x2 ow = __builtin_bit_cast(u32x2, o);
@@ -565,6 +563,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         if (c + 1 < nchunks) issue_c_loads(c + 1);
 
         // ---- state update: wave w owns states n in [32w, 32w+32) ----
+        // source-lane roles of the transposing loads, rebuilt per chunk like the addresses of the output phase
+        int lane_s = lane;
+        asm volatile("" : "+v"(lane_s));
+        const int i16s = lane_s & 15, c16s = (lane_s >> 4) & 1, hbs = lane_s >> 5;
+        const unsigned char *bq_src = s_bq + (8 * hbs + (i16s >> 1)) * kBqStride + 32 * wave + 16 * c16s + 8 * (i16s & 1);
+        const int xs_off = ((8 * hbs + (i16s >> 2)) * kXsStride + 16 * c16s + 4 * (i16s & 3)) * 2;
         if (PRECISE) {
             float m_prev = 0.0f;
             for (int sb = 0; sb < kNBlk; ++sb) {
@@ -578,15 +582,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
-                    const int col = sb * kBlk + 16 * ks + 8 * hb;
-                    const u32x2 w = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride +
-                                                                    (col ^ bt_swz(32 * wave + l32)));
+                    const int row = sb * kBlk + 16 * ks;
+                    const u32x2 w = lds_read_tr8(bq_src + row * kBqStride);
                     const f16x8 bf = i8x8_to_f16(w[0], w[1]);
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt) {
-                        const int xcol = col ^ xs_swz(pt * 32 + l32);
-                        const f16x8 xb = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride + xcol);
-                        const f16x8 xlo = *reinterpret_cast<const f16x8 *>(s_xl + (pt * 32 + l32) * kXsStride + xcol);
+                        const int off = xs_off + (row * kXsStride + 32 * pt) * 2;
+                        const f16x8 xb = lds_read_tr16x8(s_xs + off);
+                        const f16x8 xlo = lds_read_tr16x8(s_xl + off);
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb, st[pt], 0, 0, 0);
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xlo, st[pt], 0, 0, 0);
                     }
@@ -607,13 +610,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 f16x8 xb[2][2];
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
-                    const int col = sb * kBlk + 16 * ks + 8 * hb;
-                    bw[ks] = *reinterpret_cast<const u32x2 *>(s_bt + (32 * wave + l32) * kBtStride +
-                                                              (col ^ bt_swz(32 * wave + l32)));
+                    const int row = sb * kBlk + 16 * ks;
+                    bw[ks] = lds_read_tr8(bq_src + row * kBqStride);
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
-                        xb[ks][pt] = *reinterpret_cast<const f16x8 *>(s_xs + (pt * 32 + l32) * kXsStride +
-                                                                     (col ^ xs_swz(pt * 32 + l32)));
+                        xb[ks][pt] = lds_read_tr16x8(s_xs + xs_off + (row * kXsStride + 32 * pt) * 2);
                 }
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);
