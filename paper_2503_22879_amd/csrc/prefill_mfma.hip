@@ -54,7 +54,8 @@ constexpr float kNarrow = 1.0f / 128.0f;  // applied to G and H before narrowing
 // LDS map (bytes)
 constexpr int kOffCum = 0;                             // float[128]
 constexpr int kOffDt = kOffCum + 4 * kQ;               // float[128]
-constexpr int kOffSx = kOffDt + 4 * kQ;                // float[64]
+constexpr int kOffW2 = kOffDt + 4 * kQ;                // float[128]
+constexpr int kOffSx = kOffW2 + 4 * kQ;                // float[64]
 constexpr int kOffWt = kOffSx + 4 * kP;                // float[4] (+pad)
 constexpr int kOffXq = kOffWt + 64;                    // int8 [128][80]
 constexpr int kOffBq = kOffXq + kQ * kXqStride;        // int8 [128][144]
@@ -161,6 +162,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *s_cum = reinterpret_cast<float *>(smem + kOffCum);
     float *s_dt = reinterpret_cast<float *>(smem + kOffDt);
+    float *s_w2 = reinterpret_cast<float *>(smem + kOffW2);
     float *s_sx = reinterpret_cast<float *>(smem + kOffSx);
     unsigned char *s_xq = smem + kOffXq;
     unsigned char *s_bq = smem + kOffBq;
@@ -254,20 +256,27 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     // [0,16): the two half-waves read adjacent 16-byte pieces of a C row (half as many memory requests as 64
     // contiguous bytes per lane).  Issued, with the B rows (mostly L2 hits: 16 heads share them), after the output
     // phase of the previous chunk, when registers are free; B first, because staging consumes it first.
-    auto issue_c_loads = [&](int c) {
+    // Part k (0..3) of them: one B row and one 32-byte piece of the C row per lane, so that the memory instructions
+    // can be spread over the state update instead of queueing up behind each other.
+    auto issue_b_load = [&](int c, int k) {
         const int t0 = c * kQ;
         const int nv = min(kQ, L - t0);
         const int8_t *bbase = a.B + (((size_t)b * L + t0) * G + g) * kN;
+        const uint32_t row = (uint32_t)min(4 * bs4 + k, nv - 1);
+        br[k] = *reinterpret_cast<const u32x4 *>(bbase + (row * b_row + 16u * bn16));
+    };
+    auto issue_cn_load = [&](int c, int kk) {
+        const int t0 = c * kQ;
+        const int nv = min(kQ, L - t0);
         const int8_t *cbase = a.C + (((size_t)b * L + t0) * G + g) * kN;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t row = (uint32_t)min(4 * bs4 + k, nv - 1);
-            br[k] = *reinterpret_cast<const u32x4 *>(bbase + (row * b_row + 16u * bn16));
-        }
         const uint32_t row = (uint32_t)min((((wave + c) & (kNBlk - 1)) ^ rot_flip) * kBlk + l32, nv - 1);
-        const int8_t *crow = cbase + (row * b_row + 16u * hb);
+        cn[kk] = *reinterpret_cast<const i32x4 *>(cbase + (row * b_row + 16u * hb) + 32 * kk);
+    };
+    auto issue_c_loads = [&](int c) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) cn[kk] = *reinterpret_cast<const i32x4 *>(crow + 32 * kk);
+        for (int k = 0; k < 4; ++k) issue_b_load(c, k);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) issue_cn_load(c, kk);
     };
     issue_loads(0);
     issue_c_loads(0);
@@ -291,6 +300,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         if (wave == 0) {
             *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
             *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(dt0 * kNarrow, dt1 * kNarrow);  // pre-narrowed
+            // column weights of the diagonal blocks: dt_s 2^-7 exp2(R - cum_s), R = prefix sum in front of the token's
+            // 32-token block (they may overflow under extreme decay; the diagonal block then does not use them)
+            const float rb = __shfl(cum1, (lane & ~15) - 1, 64);
+            const float R = lane >= 16 ? rb : 0.0f;
+            *reinterpret_cast<float2 *>(s_w2 + 2 * lane) =
+                make_float2(exp2_fast(R - cum0) * dt0 * kNarrow, exp2_fast(R - cum1) * dt1 * kNarrow);
         }
 
         // carried state -> LDS as fp16 (operand of the C.H product of this chunk)
@@ -454,6 +469,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
                 __builtin_amdgcn_sched_barrier(0);
                 const i32x16 gn = gemm_g(bq);
+                __builtin_amdgcn_sched_barrier(0);  // the next tile first: its conversion then overlaps the products below
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -468,25 +484,52 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
                         xw[ks][pt] = lds_read_tr8(xq_src + (tb * kBlk + 16 * ks) * kXqStride + 32 * pt);
-                f32x4 cs4[4], ds4[4];
-#pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {  // four consecutive tokens of the block per register group
-                    cs4[rg] = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + 8 * rg + 4 * hba);
-                    ds4[rg] = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + 8 * rg + 4 * hba);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+                // R: prefix sum in front of the block, m: at its last token.  When the decay across the block stays below
+                // 2^64 the weight exp2(cum_t - cum_s) dt_s is the product of a row factor and the staged column weights
+                // (both inside the fp32 range); otherwise every element takes its own exponential.
+                const float R = tb > 0 ? s_cum[tb * kBlk - 1] : 0.0f;
+                const float m_tb = s_cum[tb * kBlk + kBlk - 1];
+                const bool factored = __builtin_amdgcn_readfirstlane((R - m_tb) < 64.0f);
                 float lv[16];
+                if (factored) {
+                    f32x4 w4[4];
 #pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    const int s0 = 8 * rg + 4 * hb;
+                    for (int rg = 0; rg < 4; ++rg)
+                        w4[rg] = *reinterpret_cast<const f32x4 *>(s_w2 + tb * kBlk + 8 * rg + 4 * hba);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const float e_row = exp2_fast(cum_t - R);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        // exponent forced to a huge negative value above the diagonal: weight exactly 0, no branch
-                        // cum is non-increasing (dt >= 0, A <= 0), so the exponent is <= 0 on and below the diagonal
-                        const float arg = (s0 + i <= l32) ? cum_t - cs4[rg][i] : -1.0e30f;
-                        float dd = (s0 + i == l32) ? d_sel : 0.0f;  // skip term on the diagonal
-                        asm volatile("" : "+v"(dd));  // selected here, not kept in 16 registers across the chunk loop
-                        lv[4 * rg + i] = fmaf((float)gi[4 * rg + i], exp2_fast(arg) * ds4[rg][i], dd);
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const int s0 = 8 * rg + 4 * hb;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float wgt = (s0 + i <= l32) ? e_row * w4[rg][i] : 0.0f;  // causal mask
+                            float dd = (s0 + i == l32) ? d_sel : 0.0f;  // skip term on the diagonal
+                            asm volatile("" : "+v"(dd));  // selected here, not kept in 16 registers across the chunk loop
+                            lv[4 * rg + i] = fmaf((float)gi[4 * rg + i], wgt, dd);
+                        }
+                    }
+                } else {
+                    f32x4 cs4[4], ds4[4];
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {  // four consecutive tokens of the block per register group
+                        cs4[rg] = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + 8 * rg + 4 * hba);
+                        ds4[rg] = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + 8 * rg + 4 * hba);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const int s0 = 8 * rg + 4 * hb;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            // exponent forced to a huge negative value above the diagonal: weight exactly 0, no branch
+                            // cum is non-increasing (dt >= 0, A <= 0): the exponent is <= 0 on and below the diagonal
+                            const float arg = (s0 + i <= l32) ? cum_t - cs4[rg][i] : -1.0e30f;
+                            float dd = (s0 + i == l32) ? d_sel : 0.0f;  // skip term on the diagonal
+                            asm volatile("" : "+v"(dd));  // selected here, not kept in 16 registers across the chunk loop
+                            lv[4 * rg + i] =
+                                fmaf((float)gi[4 * rg + i], exp2_fast(arg) * ds4[rg][i], dd);
+                        }
                     }
                 }
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
@@ -560,7 +603,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             }
         }
 
-        if (c + 1 < nchunks) issue_c_loads(c + 1);
+        if (PRECISE && c + 1 < nchunks) issue_c_loads(c + 1);
 
         // ---- state update: wave w owns states n in [32w, 32w+32) ----
         // source-lane roles of the transposing loads, rebuilt per chunk like the addresses of the output phase
@@ -618,6 +661,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 }
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);
+                if (c + 1 < nchunks) issue_b_load(c + 1, sb);  // staging consumes B first, and loads return in order
+                __builtin_amdgcn_sched_barrier(0);
                 const _Float16 f = (_Float16)(exp2_fast(cum_last - m_sb) * kStScale);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
@@ -626,6 +671,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     for (int pt = 0; pt < 2; ++pt)
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb[ks][pt], st[pt], 0, 0, 0);
                 }
+            }
+            if (c + 1 < nchunks) {
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) issue_cn_load(c + 1, kk);
             }
         }
         __syncthreads();

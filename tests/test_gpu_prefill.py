@@ -161,6 +161,26 @@ def test_tiny_scales_take_the_epilogue_skip_term(gpu_lib):
     check(yg, hg, yref, href, "large B/C scales, no D")
 
 
+def test_extreme_decay_takes_the_per_element_diagonal(gpu_lib):
+    """Decay of more than 2^64 across a 32-token block: the row/column factorisation of the diagonal block's weights
+    would leave the fp32 range, so the kernel must fall back to one exponential per element.  Heads alternate between
+    mild and extreme decay (dt scaled by 40 on odd heads), both with and without the final state."""
+    s = W.CONFIGS["m2_130m"].with_(seqlen=600)
+    sc, prob, _ = make_problem(s, 12, calib_tokens=256)
+    p1 = dict(prob)
+    dt = prob["dt"].copy()
+    dt[:, :, 1::2] *= 40.0
+    p1["dt"] = dt
+    a_log2 = -(dt * prob["A"][None, None, :]) * 1.4426950408889634      # decay per token, log2 units
+    blk = a_log2[:, :576].reshape(s.batch, 18, 32, s.nheads).sum(axis=2)
+    assert blk[:, :, 1::2].min() > 64.0 and blk[:, :, 0::2].max() < 64.0  # both branches are exercised
+    for want_state in (True, False):
+        yref, href, _ = oracle.ref_prefill(sc, p1["x"], p1["B"], p1["C"], p1["dt"], p1["A"], p1["D"],
+                                           want_state=want_state)
+        yg, hg = run_prefill(gpu_lib, s, sc, p1, want_state=want_state)
+        check(yg, hg, yref, href if want_state else None, f"extreme decay, state={want_state}")
+
+
 def test_precise_flag_without_final_state(gpu_lib):
     """QUAMBA_FLAG_PRECISE_STATE selects the two-term state path even when no final state is returned."""
     s = W.CONFIGS["m2_130m"].with_(seqlen=700)
