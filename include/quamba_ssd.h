@@ -50,6 +50,10 @@ typedef enum quamba_status {
 #define QUAMBA_FLAG_PRECISE_STATE 0x2u  /* prefill: compute chunk states with a two-term (hi+lo) fp16 split so
                                            that final_state meets 1e-4 of its max; implied when final_state
                                            is requested, settable to get the same arithmetic without it       */
+#define QUAMBA_FLAG_NO_CHANNEL_SPLIT 0x4u /* prefill: keep one workgroup per (sequence, head) even when the batch
+                                           has fewer heads than the device has compute units (by default such
+                                           batches give every head two workgroups of 32 channels each); the
+                                           results of the two launch shapes agree to rounding                  */
 
 typedef struct quamba_ssd_shape_t {
     int32_t batch;           /* sequences                                                             */

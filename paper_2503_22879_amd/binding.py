@@ -13,6 +13,7 @@ _lib = None
 
 FLAG_GENERIC_KERNEL = 0x1
 FLAG_PRECISE_STATE = 0x2
+FLAG_NO_CHANNEL_SPLIT = 0x4
 
 EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "quamba_ssd_decode_step",
                     "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x",

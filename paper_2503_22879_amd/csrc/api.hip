@@ -11,7 +11,8 @@ int check_shape(const quamba_ssd_shape_t *s, bool prefill)
         s->n_head_clusters <= 0 || s->n_chan_clusters <= 0)
         return QUAMBA_ESHAPE;
     if (s->nheads % s->ngroups) return QUAMBA_ESHAPE;
-    if (s->flags & ~(QUAMBA_FLAG_GENERIC_KERNEL | QUAMBA_FLAG_PRECISE_STATE)) return QUAMBA_EINVAL;
+    if (s->flags & ~(QUAMBA_FLAG_GENERIC_KERNEL | QUAMBA_FLAG_PRECISE_STATE | QUAMBA_FLAG_NO_CHANNEL_SPLIT))
+        return QUAMBA_EINVAL;
     if ((int64_t)s->batch * s->nheads > 0x7fffffffLL) return QUAMBA_ESHAPE;
     if (prefill) {
         if (s->seqlen <= 0 || s->chunk <= 0) return QUAMBA_ESHAPE;

@@ -144,11 +144,10 @@ __device__ __forceinline__ f16x8 pack_f16x8(const float v[8])
 // Workgroup -> (sequence, head).  Hardware hands consecutive workgroup ids to the 8 XCDs round-robin, each XCD with
 // its own L2.  When the number of (sequence, state group) units is a multiple of 8, all heads of a unit are put on
 // one XCD, so that the B and C rows they share are fetched into one L2 instead of eight.
-__device__ __forceinline__ int block_to_bh(const SsdArgs &a)
+__device__ __forceinline__ int block_to_bh(const SsdArgs &a, int i)
 {
     const int H = a.s.nheads, G = a.s.ngroups, hpg = H / G;
     const int units = a.s.batch * G;
-    const int i = blockIdx.x;
     if (units % 8 != 0) return i;
     const int x = i & 7, slot = i >> 3;
     const int u = x + 8 * (slot / hpg), hl = slot % hpg;
@@ -156,9 +155,13 @@ __device__ __forceinline__ int block_to_bh(const SsdArgs &a)
     return b * H + g * hpg + hl;
 }
 
-template <bool PRECISE>
+// PT: 32-channel tiles per workgroup.  2: one workgroup per (sequence, head).  1: two workgroups per head, each with
+// half of the channels, its own half of the state and its own copy of the G^T work; chosen when there are fewer
+// heads in the batch than compute units, so that the whole chip works on short batches.
+template <bool PRECISE, int PT>
 __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 {
+    constexpr int kPw = 32 * PT;  // channels of this workgroup
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *s_cum = reinterpret_cast<float *>(smem + kOffCum);
     float *s_dt = reinterpret_cast<float *>(smem + kOffDt);
@@ -171,7 +174,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     unsigned char *s_xl = smem + kOffXl;  // PRECISE only
 
     const int L = a.s.seqlen, H = a.s.nheads, G = a.s.ngroups;
-    const int bh = block_to_bh(a);
+    // with two workgroups per head, ids i and i + 8 (same XCD, and the same compute unit when two workgroups fit one)
+    // take the two halves of a head
+    const int bid = blockIdx.x;
+    const int p_base = PT == 2 ? 0 : 32 * ((bid >> 3) & 1);
+    const int bh = block_to_bh(a, PT == 2 ? bid : ((bid & 7) | ((bid >> 4) << 3)));
     const int b = bh / H, h = bh - b * H, g = h / (H / G);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps block indices in scalar registers
@@ -180,7 +187,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     // consecutive ids go round the 8 XCDs).  The causal work of a wave grows with its block index, so every other
     // workgroup of an XCD walks its blocks in the opposite order: a SIMD then holds a long and a short block at a
     // time instead of two long or two short ones.
-    const int rot_flip = ((blockIdx.x >> 3) & 1) ? (kNBlk - 1) : 0;
+    const int rot_flip = ((bid >> 3) & 1) ? (kNBlk - 1) : 0;
 
     const float Ah = a.A[h] * 1.44269504088896340736f;  // log2(e): prefix sums are kept in log2 units (exp2 below)
     const float Dh = a.D ? a.D[h] : 0.0f;
@@ -193,27 +200,28 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     const bool d_by_mfma = fabsf(d_acc) < 3.0e4f;
     const float d_sel = d_by_mfma ? d_acc : 0.0f;
 
-    if (tid < kP) s_sx[tid] = x_scale_lookup(a, h, tid) * (d_by_mfma ? y_scale : 1.0f);
+    if (tid < kPw) s_sx[tid] = x_scale_lookup(a, h, p_base + tid) * (d_by_mfma ? y_scale : 1.0f);
     __syncthreads();
     // Carried state in x-code * B-code units times kStScale (true state = s_x(p) s_B * st / kStScale): on the fast
     // path the state is carried already narrowed by 2^-7, so that its fp16 copy for the C.H product needs no multiply
     // (the factor rides on the per-block weight of the B operand instead).  Wave w owns states n in
     // [32w, 32w+32); st[pt][r]: p = 32 pt + l32, n = 32 w + 8 (r/4) + 4 hb + r%4.
     constexpr float kStScale = PRECISE ? 1.0f : kNarrow;
-    f32x16 st[2];
+    f32x16 st[PT];
 #pragma unroll
-    for (int pt = 0; pt < 2; ++pt)
+    for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) st[pt][r] = 0.0f;
     if (a.init_state) {
 #pragma unroll
-        for (int pt = 0; pt < 2; ++pt) {
+        for (int pt = 0; pt < PT; ++pt) {
             const int p = pt * 32 + l32;
             const float inv = kStScale * (d_by_mfma ? y_scale : 1.0f) / (s_sx[p] * sB);
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 const int n0 = 32 * wave + 8 * rg + 4 * hb;
-                const f32x4 v = *reinterpret_cast<const f32x4 *>(a.init_state + ((size_t)bh * kP + p) * kN + n0);
+                const f32x4 v =
+                    *reinterpret_cast<const f32x4 *>(a.init_state + ((size_t)bh * kP + p_base + p) * kN + n0);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) st[pt][4 * rg + i] = v[i] * inv;
             }
@@ -227,12 +235,13 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     // the C rows of this wave's 32-token output block.  Rows past the end of the sequence are read from the last
     // valid row and zeroed where they are consumed, so that nothing waits for data at the point of issue.
     // Vector-memory results return in issue order, hence the loads are issued in the order they are consumed.
-    u32x2 xr[4];
+    typedef uint32_t xvec __attribute__((ext_vector_type(PT)));  // 4 PT x codes of one token
+    xvec xr[4];
     u32x4 br[4];
     i32x4 cn[4];
     float dt0 = 0.0f, dt1 = 0.0f;  // dt of tokens 2*lane and 2*lane + 1 (every wave holds the whole chunk's dt)
-    // Staging lane maps: a thread takes 4 consecutive tokens and 8 channels of x (8 lanes cover a 64-byte row), resp.
-    // 16 states of B (8 lanes cover a 128-byte row).
+    // Staging lane maps: a thread takes 4 consecutive tokens and 4 PT channels of x (8 lanes cover a row of this
+    // workgroup's channels), resp. 16 states of B (8 lanes cover a 128-byte row).
     const int xs4 = tid >> 3, xp8 = tid & 7;
     const int bs4 = tid >> 3, bn16 = tid & 7;
     // Addresses are a wave-uniform 64-bit base (advanced per chunk) plus a 32-bit lane offset that does not change
@@ -242,14 +251,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         const int t0 = c * kQ;
         const int nv = min(kQ, L - t0);
         const size_t tokbase = (size_t)b * L + t0;
-        const int8_t *xbase = a.x + (tokbase * H + h) * kP;
+        const int8_t *xbase = a.x + (tokbase * H + h) * kP + p_base;
         const char *dbase = reinterpret_cast<const char *>(a.dt + tokbase * H + h);
         dt0 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane, nv - 1) * dt_row);
         dt1 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane + 1, nv - 1) * dt_row);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint32_t row = (uint32_t)min(4 * xs4 + k, nv - 1);
-            xr[k] = *reinterpret_cast<const u32x2 *>(xbase + (row * x_row + 8u * xp8));
+            xr[k] = *reinterpret_cast<const xvec *>(xbase + (row * x_row + (uint32_t)(4 * PT) * xp8));
         }
     };
     // C rows of this wave's output block of chunk c.  k-step kk of the G^T product covers states 32 kk + 16 hb +
@@ -310,7 +319,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 
         // carried state -> LDS as fp16 (operand of the C.H product of this chunk)
 #pragma unroll
-        for (int pt = 0; pt < 2; ++pt)
+        for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 f16x4 v;
@@ -332,29 +341,37 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             const float m = __shfl(cum1, lm, 64);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                u32x2 w = xr[k];
+                xvec w = xr[k];
                 if (nv < kQ) {  // partial last chunk: rows past the end are zero
-                    if (s0 + k >= nv) w = (u32x2){0u, 0u};
+                    if (s0 + k >= nv) w = (xvec)(0u);
                 }
                 const float colf = exp2_fast(m - cumq[k]) * dtq[k];
-                *reinterpret_cast<u32x2 *>(s_xq + (row0 + k) * kXqStride + 8 * xp8) = w;
+                *reinterpret_cast<xvec *>(s_xq + (row0 + k) * kXqStride + 4 * PT * xp8) = w;
+                unsigned char *xs_row = s_xs + ((row0 + k) * kXsStride + 4 * PT * xp8) * 2;
                 if (!PRECISE) {
                     // exact fp16 codes times the fp16 weight of the token: one more rounding (2^-11 relative, of the
                     // weight) than an fp32 product, well inside the budget of y
-                    const f16x8 v = i8x8_to_f16(w[0], w[1]) * (_Float16)colf;
-                    *reinterpret_cast<f16x8 *>(s_xs + ((row0 + k) * kXsStride + 8 * xp8) * 2) = v;
+                    const f16x8 v = i8x8_to_f16(w[0], w[PT - 1]) * (_Float16)colf;
+                    if (PT == 2)
+                        *reinterpret_cast<f16x8 *>(xs_row) = v;
+                    else
+                        *reinterpret_cast<f16x4 *>(xs_row) = __builtin_shufflevector(v, v, 0, 1, 2, 3);
                 } else {
                     const float c128 = -128.0f * colf;
-                    f16x8 hi, lo;
+                    unsigned char *xl_row = s_xl + ((row0 + k) * kXsStride + 4 * PT * xp8) * 2;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const uint32_t u = (w[j >> 2] ^ 0x80808080u) >> (8 * (j & 3)) & 0xffu;
-                        const float v = fmaf((float)u, colf, c128);
-                        hi[j] = (_Float16)v;
-                        lo[j] = (_Float16)(v - (float)hi[j]);
+                    for (int q = 0; q < PT; ++q) {
+                        f16x4 hi, lo;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const uint32_t u = (w[q] ^ 0x80808080u) >> (8 * j) & 0xffu;
+                            const float v = fmaf((float)u, colf, c128);
+                            hi[j] = (_Float16)v;
+                            lo[j] = (_Float16)(v - (float)hi[j]);
+                        }
+                        *reinterpret_cast<f16x4 *>(xs_row + 8 * q) = hi;
+                        *reinterpret_cast<f16x4 *>(xl_row + 8 * q) = lo;
                     }
-                    *reinterpret_cast<f16x8 *>(s_xs + ((row0 + k) * kXsStride + 8 * xp8) * 2) = hi;
-                    *reinterpret_cast<f16x8 *>(s_xl + ((row0 + k) * kXsStride + 8 * xp8) * 2) = lo;
                 }
             }
         }
@@ -421,19 +438,19 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             i32x16 gi = gemm_g(bq);
 
             // carried-state term: Y^T[p,t] = sum_n H[p,n] (exp(cum_t) Cq[t,n])
-            f32x16 acc[2];
+            f32x16 acc[PT];
 #pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
+            for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[pt][r] = 0.0f;
             const _Float16 e_t = (_Float16)exp2_fast(cum_t);  // per lane (token t); folded into the C operand
 #pragma unroll
             for (int k2 = 0; k2 < 4; ++k2) {  // batches of two k-steps: all LDS reads of a batch are issued first
-                f16x8 hf[2][2];
+                f16x8 hf[2][PT];
 #pragma unroll
                 for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt)
+                    for (int pt = 0; pt < PT; ++pt)
                         hf[kk][pt] = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32a) * kHsStride + 32 * k2 +
                                                                      16 * hba + 8 * kk);
                 __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
@@ -443,7 +460,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     const f16x8 cf =
                         i8x8_to_f16((uint32_t)ct[k8 >> 1][2 * (k8 & 1)], (uint32_t)ct[k8 >> 1][2 * (k8 & 1) + 1]) * e_t;
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt)
+                    for (int pt = 0; pt < PT; ++pt)
                         acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[kk][pt], cf, acc[pt], 0, 0, 0);
                 }
             }
@@ -452,11 +469,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             // scaled and narrowed so that the matrix core and the vector ALU overlap inside the wave
             for (int sb = 0; sb < tb; ++sb) {  // strictly lower block pairs
                 load_bq(sb + 1, bq);
-                f16x8 xa[2][2];
+                f16x8 xa[2][PT];
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt)
+                    for (int pt = 0; pt < PT; ++pt)
                         xa[ks][pt] = lds_read_tr16x8(xs_src + ((sb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);
@@ -473,16 +490,16 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt)
+                    for (int pt = 0; pt < PT; ++pt)
                         acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[ks][pt], ks ? l1 : l0, acc[pt], 0, 0, 0);
                 gi = gn;
             }
             {  // diagonal block pair: per-element decay, causal mask, plain x codes
-                u32x2 xw[2][2];
+                u32x2 xw[2][PT];
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt)
+                    for (int pt = 0; pt < PT; ++pt)
                         xw[ks][pt] = lds_read_tr8(xq_src + (tb * kBlk + 16 * ks) * kXqStride + 32 * pt);
                 // R: prefix sum in front of the block, m: at its last token.  When the decay across the block stays below
                 // 2^64 the weight exp2(cum_t - cum_s) dt_s is the product of a row factor and the staged column weights
@@ -536,7 +553,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt) {
+                    for (int pt = 0; pt < PT; ++pt) {
                         const f16x8 xf = i8x8_to_f16(xw[ks][pt][0], xw[ks][pt][1]);
                         acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, ks ? l1 : l0, acc[pt], 0, 0, 0);
                     }
@@ -545,10 +562,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             // epilogue: scales and skip term in fp32, narrowing to fp16; a lane holds 4 consecutive channels of token
             // t per register group, and one exchange with the lane 32 positions away (same token) turns two such
             // groups into 8 consecutive channels, so that every lane stores 16 bytes and a token row gets 32
-            uint16_t *yrow = a.y + ((tokbase + min(tl, nv - 1)) * H + h) * kP;
+            uint16_t *yrow = a.y + ((tokbase + min(tl, nv - 1)) * H + h) * kP + p_base;
             if (d_by_mfma) {
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt) {
+                for (int pt = 0; pt < PT; ++pt) {
                     f32x4 k4[4];  // s_x(h,p) * y_scale of the lane's 16 channels of this p tile
 #pragma unroll
                     for (int rg = 0; rg < 4; ++rg)
@@ -577,7 +594,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             } else {
                 const int tq = tok_pos(tl);
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt)
+                for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         uint32_t w[2][2];
@@ -620,7 +637,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 const float gdec = exp2_fast(m - m_prev);
                 m_prev = m;
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt)
+                for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
 #pragma unroll
@@ -629,7 +646,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     const u32x2 w = lds_read_tr8(bq_src + row * kBqStride);
                     const f16x8 bf = i8x8_to_f16(w[0], w[1]);
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt) {
+                    for (int pt = 0; pt < PT; ++pt) {
                         const int off = xs_off + (row * kXsStride + 32 * pt) * 2;
                         const f16x8 xb = lds_read_tr16x8(s_xs + off);
                         const f16x8 xlo = lds_read_tr16x8(s_xl + off);
@@ -643,20 +660,20 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             {
                 const float gdec = exp2_fast(cum_last);
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt)
+                for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
             }
 #pragma unroll
             for (int sb = 0; sb < kNBlk; ++sb) {  // blocks past the end hold zeros in x' (dt = 0): they add nothing
                 u32x2 bw[2];
-                f16x8 xb[2][2];
+                f16x8 xb[2][PT];
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const int row = sb * kBlk + 16 * ks;
                     bw[ks] = lds_read_tr8(bq_src + row * kBqStride);
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt)
+                    for (int pt = 0; pt < PT; ++pt)
                         xb[ks][pt] = lds_read_tr16x8(s_xs + xs_off + (row * kXsStride + 32 * pt) * 2);
                 }
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
@@ -668,7 +685,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int ks = 0; ks < 2; ++ks) {
                     const f16x8 bf = i8x8_to_f16(bw[ks][0], bw[ks][1]) * f;
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt)
+                    for (int pt = 0; pt < PT; ++pt)
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb[ks][pt], st[pt], 0, 0, 0);
                 }
             }
@@ -682,7 +699,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 
     if (a.state) {
 #pragma unroll
-        for (int pt = 0; pt < 2; ++pt) {
+        for (int pt = 0; pt < PT; ++pt) {
             const int p = pt * 32 + l32;
             const float sc = s_sx[p] * sB / ((d_by_mfma ? y_scale : 1.0f) * kStScale);
 #pragma unroll
@@ -691,7 +708,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 f32x4 v;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[i] = st[pt][4 * rg + i] * sc;
-                *reinterpret_cast<f32x4 *>(a.state + ((size_t)bh * kP + p) * kN + n0) = v;
+                *reinterpret_cast<f32x4 *>(a.state + ((size_t)bh * kP + p_base + p) * kN + n0) = v;
             }
         }
     }
@@ -701,22 +718,44 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 
 bool prefill_mfma_supports(const quamba_ssd_shape_t &s) { return s.headdim == kP && s.d_state == kN; }
 
+namespace {
+
+template <bool PRECISE, int PT>
+hipError_t launch_scan(const SsdArgs &a, hipStream_t stream)
+{
+    constexpr int lds = PRECISE ? kLdsPrecise : kLdsFast;
+    const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT)));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((prefill_mfma_kernel<PRECISE, PT>), grid, dim3(kThreads), lds, stream, a);
+    return hipGetLastError();
+}
+
+// Compute units of the current device (cached per device id).
+int compute_units()
+{
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+}  // namespace
+
 hipError_t launch_prefill_mfma(const SsdArgs &a, hipStream_t stream)
 {
     const bool precise = a.state != nullptr || (a.s.flags & QUAMBA_FLAG_PRECISE_STATE);
-    const dim3 grid((unsigned)(a.s.batch * a.s.nheads));
-    if (precise) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPrecise);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(prefill_mfma_kernel<true>, grid, dim3(kThreads), kLdsPrecise, stream, a);
-    } else {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsFast);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(prefill_mfma_kernel<false>, grid, dim3(kThreads), kLdsFast, stream, a);
-    }
-    return hipGetLastError();
+    // fewer (sequence, head) pairs than compute units: give every head two workgroups (half of the channels each)
+    const bool split = !(a.s.flags & QUAMBA_FLAG_NO_CHANNEL_SPLIT) &&
+                       (int64_t)a.s.batch * a.s.nheads <= (int64_t)compute_units();
+    if (precise) return split ? launch_scan<true, 1>(a, stream) : launch_scan<true, 2>(a, stream);
+    return split ? launch_scan<false, 1>(a, stream) : launch_scan<false, 2>(a, stream);
 }
 
 }  // namespace quamba

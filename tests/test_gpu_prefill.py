@@ -45,6 +45,7 @@ def check(yg, hg, yref, href, what=""):
 
 
 GENERIC = 0x1
+NO_SPLIT = 0x4    # one workgroup per head even for small batches (the default splits a head's channels over two)
 
 
 @pytest.mark.parametrize("flags", [0, GENERIC])
@@ -57,7 +58,7 @@ def test_tiny_config(gpu_lib, flags):
     check(yg, hg, yref, href, f"tiny flags={flags}")
 
 
-@pytest.mark.parametrize("flags", [0, GENERIC])
+@pytest.mark.parametrize("flags", [0, GENERIC, NO_SPLIT])
 @pytest.mark.parametrize("with_D", [True, False])
 def test_130m_shape(gpu_lib, flags, with_D):
     """configs[1]: Mamba2-130M-shaped layer, seqlen 2048, 24 heads, d_state 128, chunk 256, 4x4 clusters."""
@@ -68,7 +69,7 @@ def test_130m_shape(gpu_lib, flags, with_D):
     check(yg, hg, yref, href, f"130m flags={flags} D={with_D}")
 
 
-@pytest.mark.parametrize("flags", [0, GENERIC])
+@pytest.mark.parametrize("flags", [0, GENERIC, NO_SPLIT])
 @pytest.mark.parametrize("L", [1, 5, 63, 257, 300, 777])
 def test_ragged_lengths_and_init_state(gpu_lib, flags, L):
     """Sequence lengths that are not multiples of the chunk (several tiles + a ragged tail), with an initial state."""
@@ -103,7 +104,7 @@ def test_exact_integer_case(gpu_lib):
     sc = oracle.Scales.ones(2, 8, 64)
     yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"])
     assert np.abs(yref).max() < 2048 and np.abs(yref).max() > 4
-    for flags in (0, GENERIC):
+    for flags in (0, GENERIC, NO_SPLIT):
         yg, hg = run_prefill(gpu_lib, s, sc, prob, flags)
         assert np.array_equal(yg, yref) and np.array_equal(hg, href), f"flags={flags}"
 
@@ -174,11 +175,11 @@ def test_extreme_decay_takes_the_per_element_diagonal(gpu_lib):
     a_log2 = -(dt * prob["A"][None, None, :]) * 1.4426950408889634      # decay per token, log2 units
     blk = a_log2[:, :576].reshape(s.batch, 18, 32, s.nheads).sum(axis=2)
     assert blk[:, :, 1::2].min() > 64.0 and blk[:, :, 0::2].max() < 64.0  # both branches are exercised
-    for want_state in (True, False):
+    for want_state, flags in ((True, 0), (False, 0), (False, NO_SPLIT)):
         yref, href, _ = oracle.ref_prefill(sc, p1["x"], p1["B"], p1["C"], p1["dt"], p1["A"], p1["D"],
                                            want_state=want_state)
-        yg, hg = run_prefill(gpu_lib, s, sc, p1, want_state=want_state)
-        check(yg, hg, yref, href if want_state else None, f"extreme decay, state={want_state}")
+        yg, hg = run_prefill(gpu_lib, s, sc, p1, flags=flags, want_state=want_state)
+        check(yg, hg, yref, href if want_state else None, f"extreme decay, state={want_state}, flags={flags}")
 
 
 def test_precise_flag_without_final_state(gpu_lib):
