@@ -1,8 +1,9 @@
 // Chunked prefill of the 8-bit SSD on the gfx950 matrix cores.
 //
-// One workgroup (4 waves) owns one (sequence, head) and walks it in chunks of kQ = 128 tokens; the head's state
-// never leaves the chip.  Its LDS footprint (< 80 KB) lets two workgroups share a compute unit, so that each SIMD
-// holds two waves whose matrix-core, vector-ALU and memory phases overlap.  Per chunk, with a_t = dt_t A_h, cum_t
+// One workgroup (4 waves) owns one (sequence, head), or half of a head's channels when the batch is too small to
+// fill the chip, and walks it in chunks of kQ = 128 tokens; the head's state never leaves the chip.  Its LDS
+// footprint (< 80 KB on the fast path) lets two workgroups share a compute unit, so that each SIMD holds two
+// waves whose matrix-core, vector-ALU and memory phases overlap.  Per chunk, with a_t = dt_t A_h, cum_t
 // its inclusive prefix sum inside the chunk, 32-token blocks tb / sb, and m_sb = cum at the last token of block
 // sb (so cum_t <= m_sb <= cum_s whenever s lies in block sb and t in a later block: every exponent is <= 0):
 //
