@@ -44,30 +44,34 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kP = 64, kN = 128, kQ = 128, kBlk = 32, kNBlk = kQ / kBlk;
 constexpr int kThreads = 256;
-// Row pitches: with 4-byte banks, the 8 token rows x 16 bytes a group of 16 lanes fetches from xq or Bq, and the 4 token
-// rows x 32 bytes it fetches from x', fall into distinct banks (pitch = 20, 36 and 40 banks).
-constexpr int kXqStride = 80;   // bytes per row of xq [token][p]
-constexpr int kXsStride = 80;   // halves per row of x' [token][p]
 constexpr int kHsStride = 136;  // halves per row of H [p][n]
 constexpr int kBqStride = 144;  // bytes per row of Bq [token][n]
 constexpr float kNarrow = 1.0f / 128.0f;  // applied to G and H before narrowing to fp16; undone in the epilogue
 
-// LDS map (bytes)
-constexpr int kOffCum = 0;                             // float[128]
-constexpr int kOffDt = kOffCum + 4 * kQ;               // float[128]
-constexpr int kOffW2 = kOffDt + 4 * kQ;                // float[128]
-constexpr int kOffSx = kOffW2 + 4 * kQ;                // float[64]
-constexpr int kOffWt = kOffSx + 4 * kP;                // float[4] (+pad)
-constexpr int kOffXq = kOffWt + 64;                    // int8 [128][80]
-constexpr int kOffBq = kOffXq + kQ * kXqStride;        // int8 [128][144]
-constexpr int kOffHs = kOffBq + kQ * kBqStride;        // fp16 [64][136]
-constexpr int kOffXs = kOffHs + 2 * kP * kHsStride;    // fp16 [128][80]
-constexpr int kOffXl = kOffXs + 2 * kQ * kXsStride;    // fp16 [128][80]  low halves of x' (two-term state path only)
-constexpr int kLdsFast = kOffXl;
-constexpr int kLdsPrecise = kOffXl + 2 * kQ * kXsStride;
-static_assert(kOffXq % 16 == 0 && kOffBq % 16 == 0 && kOffHs % 16 == 0 && kOffXs % 16 == 0 && kOffXl % 16 == 0,
-              "LDS arrays must be 16-byte aligned");
-static_assert(kLdsFast <= 80 * 1024, "two workgroups must fit the 160 KB LDS of a gfx950 compute unit");
+// LDS map (bytes) for PT 32-channel tiles per workgroup.  Row pitches: with 4-byte banks, the 8 token rows x 16 bytes
+// a group of 16 lanes fetches from xq or Bq, and the 4 token rows x 32 bytes it fetches from x', fall into distinct
+// banks (pitches of 20 / 12, 36 and 40 / 24 banks).
+template <int PT>
+struct Lds {
+    static constexpr int kPw = 32 * PT;                      // channels of the workgroup
+    static constexpr int kXqStride = PT == 2 ? 80 : 48;      // bytes per row of xq [token][p]
+    static constexpr int kXsStride = PT == 2 ? 80 : 48;      // halves per row of x' [token][p]
+    static constexpr int kOffCum = 0;                        // float[128]
+    static constexpr int kOffDt = kOffCum + 4 * kQ;          // float[128]
+    static constexpr int kOffW2 = kOffDt + 4 * kQ;           // float[128]
+    static constexpr int kOffSx = kOffW2 + 4 * kQ;           // float[64]
+    static constexpr int kOffXq = kOffSx + 4 * kP + 64;      // int8 [128][kXqStride]
+    static constexpr int kOffBq = kOffXq + kQ * kXqStride;   // int8 [128][144]
+    static constexpr int kOffHs = kOffBq + kQ * kBqStride;   // fp16 [kPw][136]
+    static constexpr int kOffXs = kOffHs + 2 * kPw * kHsStride;  // fp16 [128][kXsStride]
+    static constexpr int kOffXl = kOffXs + 2 * kQ * kXsStride;   // fp16 [128][kXsStride]  low halves of x' (two-term path)
+    static constexpr int kFast = kOffXl;
+    static constexpr int kPrecise = kOffXl + 2 * kQ * kXsStride;
+    static_assert(kOffXq % 16 == 0 && kOffBq % 16 == 0 && kOffHs % 16 == 0 && kOffXs % 16 == 0 && kOffXl % 16 == 0,
+                  "LDS arrays must be 16-byte aligned");
+};
+static_assert(Lds<2>::kFast <= 80 * 1024 && Lds<1>::kPrecise <= 80 * 1024,
+              "two workgroups must fit the 160 KB LDS of a gfx950 compute unit");
 
 // 2^x by the hardware instruction (prefix sums are carried in log2 units, so no multiply by log2 e is needed).
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -93,9 +97,10 @@ __device__ __forceinline__ f16x4 lds_read_tr16(const unsigned char *p)
         f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_lds *)(p)));
 }
 // 8 tokens x one column of fp16 x' (two 4-token transposing loads, token rows r .. r+7 of the lane group)
+template <int PITCH_HALVES>
 __device__ __forceinline__ f16x8 lds_read_tr16x8(const unsigned char *p)
 {
-    const f16x4 lo = lds_read_tr16(p), hi = lds_read_tr16(p + 4 * 2 * kXsStride);
+    const f16x4 lo = lds_read_tr16(p), hi = lds_read_tr16(p + 4 * 2 * PITCH_HALVES);
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
@@ -162,17 +167,19 @@ __device__ __forceinline__ int block_to_bh(const SsdArgs &a, int i)
 template <bool PRECISE, int PT>
 __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 {
-    constexpr int kPw = 32 * PT;  // channels of this workgroup
+    typedef Lds<PT> LY;
+    constexpr int kPw = LY::kPw;  // channels of this workgroup
+    constexpr int kXqStride = LY::kXqStride, kXsStride = LY::kXsStride;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    float *s_cum = reinterpret_cast<float *>(smem + kOffCum);
-    float *s_dt = reinterpret_cast<float *>(smem + kOffDt);
-    float *s_w2 = reinterpret_cast<float *>(smem + kOffW2);
-    float *s_sx = reinterpret_cast<float *>(smem + kOffSx);
-    unsigned char *s_xq = smem + kOffXq;
-    unsigned char *s_bq = smem + kOffBq;
-    _Float16 *s_hs = reinterpret_cast<_Float16 *>(smem + kOffHs);
-    unsigned char *s_xs = smem + kOffXs;  // fp16 rows, addressed in bytes
-    unsigned char *s_xl = smem + kOffXl;  // PRECISE only
+    float *s_cum = reinterpret_cast<float *>(smem + LY::kOffCum);
+    float *s_dt = reinterpret_cast<float *>(smem + LY::kOffDt);
+    float *s_w2 = reinterpret_cast<float *>(smem + LY::kOffW2);
+    float *s_sx = reinterpret_cast<float *>(smem + LY::kOffSx);
+    unsigned char *s_xq = smem + LY::kOffXq;
+    unsigned char *s_bq = smem + LY::kOffBq;
+    _Float16 *s_hs = reinterpret_cast<_Float16 *>(smem + LY::kOffHs);
+    unsigned char *s_xs = smem + LY::kOffXs;  // fp16 rows, addressed in bytes
+    unsigned char *s_xl = smem + LY::kOffXl;  // PRECISE only
 
     const int L = a.s.seqlen, H = a.s.nheads, G = a.s.ngroups;
     // with two workgroups per head, ids i and i + 8 (same XCD, and the same compute unit when two workgroups fit one)
@@ -475,7 +482,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt)
-                        xa[ks][pt] = lds_read_tr16x8(xs_src + ((sb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
+                        xa[ks][pt] = lds_read_tr16x8<kXsStride>(xs_src + ((sb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);
                 // the current tile is narrowed before the next one is issued, so that both can share registers (the
@@ -649,8 +656,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt) {
                         const int off = xs_off + (row * kXsStride + 32 * pt) * 2;
-                        const f16x8 xb = lds_read_tr16x8(s_xs + off);
-                        const f16x8 xlo = lds_read_tr16x8(s_xl + off);
+                        const f16x8 xb = lds_read_tr16x8<kXsStride>(s_xs + off);
+                        const f16x8 xlo = lds_read_tr16x8<kXsStride>(s_xl + off);
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb, st[pt], 0, 0, 0);
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xlo, st[pt], 0, 0, 0);
                     }
@@ -675,7 +682,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     bw[ks] = lds_read_tr8(bq_src + row * kBqStride);
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt)
-                        xb[ks][pt] = lds_read_tr16x8(s_xs + xs_off + (row * kXsStride + 32 * pt) * 2);
+                        xb[ks][pt] = lds_read_tr16x8<kXsStride>(s_xs + xs_off + (row * kXsStride + 32 * pt) * 2);
                 }
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);
@@ -724,7 +731,7 @@ namespace {
 template <bool PRECISE, int PT>
 hipError_t launch_scan(const SsdArgs &a, hipStream_t stream)
 {
-    constexpr int lds = PRECISE ? kLdsPrecise : kLdsFast;
+    constexpr int lds = PRECISE ? Lds<PT>::kPrecise : Lds<PT>::kFast;
     const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT)));
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
