@@ -47,7 +47,7 @@ typedef enum quamba_status {
 /* flags of quamba_ssd_shape_t */
 #define QUAMBA_FLAG_GENERIC_KERNEL 0x1u /* prefill: use the shape-agnostic sequential kernel even where the
                                            chunked MFMA kernel applies (a cross-check, not a fast path)      */
-#define QUAMBA_FLAG_PRECISE_STATE 0x2u  /* prefill: compute chunk states with a two-term (hi+lo) fp16 split so
+#define QUAMBA_FLAG_PRECISE_STATE 0x2u  /* prefill: compute chunk states with a two-term fp16 product so       
                                            that final_state meets 1e-4 of its max; implied when final_state
                                            is requested, settable to get the same arithmetic without it       */
 #define QUAMBA_FLAG_NO_CHANNEL_SPLIT 0x4u /* prefill: keep one workgroup per (sequence, head) even when the batch

@@ -13,8 +13,12 @@
 //   diagonal block (sb = tb):           Y^T[p,t] += xq^T[p,s] * (G^T[s,t] * exp(cum_t - cum_s) dt_s [s <= t])
 //   carried state:                      Y^T[p,t] += sum_n H[p,n] (exp(cum_t) Cq[t,n])               fp16 MFMA
 //   state:   H <- exp(cum_last) H + sum_sb sum_{s in sb} x'[s,:]^T (exp(cum_last - m_sb) Bq[s,:])   fp16 MFMA
-//            (when the final state is returned: H <- exp(m_sb - m_{sb-1}) H + x'^T Bq block by block in fp32,
-//             with x' split into two fp16 terms, so that the state meets 1e-4 of its maximum)
+//            (when the final state is returned, it has to meet 1e-4 of its maximum, which a product rounded to fp16
+//             cannot: the token weight w_s = exp(m_sb - cum_s) dt_s is split as wq_s (1 + d_s), wq_s its first 4
+//             bits, so that x'[s,p] = xq[s,p] wq_s is exact in fp16 (7 + 4 bits); the factor 1 + d_s, |d_s| <= 1/16,
+//             goes into the other operand: the intra-chunk score columns are scaled by it before narrowing, and the
+//             state takes two terms, H <- exp(m_sb - m_{sb-1}) H + x'^T Bq + x'^T (d_s Bq), block by block in fp32,
+//             the first exact, the second rounded at 2^-16 of the total)
 //   y[t,p]     = s_x(h,p) * (s_B s_C * Y[t,p] + D_h xq[t,p])             fp32 epilogue, fp16 store
 //
 // which is Eq. 2 with A-dot = exp(dt A), B-dot = dt B (Section 3.2) regrouped; the quantization scales of
@@ -59,19 +63,18 @@ struct Lds {
     static constexpr int kOffCum = 0;                        // float[128]
     static constexpr int kOffDt = kOffCum + 4 * kQ;          // float[128]
     static constexpr int kOffW2 = kOffDt + 4 * kQ;           // float[128]
-    static constexpr int kOffSx = kOffW2 + 4 * kQ;           // float[64]
+    static constexpr int kOffD1 = kOffW2 + 4 * kQ;           // float[128]  1 + d_s (two-term path)
+    static constexpr int kOffDh = kOffD1 + 4 * kQ;           // fp16[128]   d_s (two-term path)
+    static constexpr int kOffSx = kOffDh + 2 * kQ;           // float[64]
     static constexpr int kOffXq = kOffSx + 4 * kP + 64;      // int8 [128][kXqStride]
     static constexpr int kOffBq = kOffXq + kQ * kXqStride;   // int8 [128][144]
     static constexpr int kOffHs = kOffBq + kQ * kBqStride;   // fp16 [kPw][136]
     static constexpr int kOffXs = kOffHs + 2 * kPw * kHsStride;  // fp16 [128][kXsStride]
-    static constexpr int kOffXl = kOffXs + 2 * kQ * kXsStride;   // fp16 [128][kXsStride]  low halves of x' (two-term path)
-    static constexpr int kFast = kOffXl;
-    static constexpr int kPrecise = kOffXl + 2 * kQ * kXsStride;
-    static_assert(kOffXq % 16 == 0 && kOffBq % 16 == 0 && kOffHs % 16 == 0 && kOffXs % 16 == 0 && kOffXl % 16 == 0,
+    static constexpr int kBytes = kOffXs + 2 * kQ * kXsStride;
+    static_assert(kOffXq % 16 == 0 && kOffBq % 16 == 0 && kOffHs % 16 == 0 && kOffXs % 16 == 0,
                   "LDS arrays must be 16-byte aligned");
 };
-static_assert(Lds<2>::kFast <= 80 * 1024 && Lds<1>::kPrecise <= 80 * 1024,
-              "two workgroups must fit the 160 KB LDS of a gfx950 compute unit");
+static_assert(Lds<2>::kBytes <= 80 * 1024, "two workgroups must fit the 160 KB LDS of a gfx950 compute unit");
 
 // 2^x by the hardware instruction (prefix sums are carried in log2 units, so no multiply by log2 e is needed).
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -179,7 +182,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     unsigned char *s_bq = smem + LY::kOffBq;
     _Float16 *s_hs = reinterpret_cast<_Float16 *>(smem + LY::kOffHs);
     unsigned char *s_xs = smem + LY::kOffXs;  // fp16 rows, addressed in bytes
-    unsigned char *s_xl = smem + LY::kOffXl;  // PRECISE only
+    float *s_d1 = reinterpret_cast<float *>(smem + LY::kOffD1);        // PRECISE only
+    _Float16 *s_dh = reinterpret_cast<_Float16 *>(smem + LY::kOffDh);  // PRECISE only
 
     const int L = a.s.seqlen, H = a.s.nheads, G = a.s.ngroups;
     // with two workgroups per head, ids i and i + 8 (same XCD, and the same compute unit when two workgroups fit one)
@@ -365,21 +369,20 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     else
                         *reinterpret_cast<f16x4 *>(xs_row) = __builtin_shufflevector(v, v, 0, 1, 2, 3);
                 } else {
-                    const float c128 = -128.0f * colf;
-                    unsigned char *xl_row = s_xl + ((row0 + k) * kXsStride + 4 * PT * xp8) * 2;
-#pragma unroll
-                    for (int q = 0; q < PT; ++q) {
-                        f16x4 hi, lo;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const uint32_t u = (w[q] ^ 0x80808080u) >> (8 * j) & 0xffu;
-                            const float v = fmaf((float)u, colf, c128);
-                            hi[j] = (_Float16)v;
-                            lo[j] = (_Float16)(v - (float)hi[j]);
-                        }
-                        *reinterpret_cast<f16x4 *>(xs_row + 8 * q) = hi;
-                        *reinterpret_cast<f16x4 *>(xl_row + 8 * q) = lo;
+                    // the weight rounded to 4 significant bits: codes (7 bits) times it are exact in fp16; the rest,
+                    // 1 + d with |d| <= 1/16, is published for the other operands
+                    const float wq =
+                        __builtin_bit_cast(float, (__builtin_bit_cast(uint32_t, colf) + 0x00080000u) & 0xfff00000u);
+                    const _Float16 dh = (_Float16)(wq > 0.0f ? (colf - wq) / wq : 0.0f);
+                    if (xp8 == 0) {
+                        s_dh[s0 + k] = dh;
+                        s_d1[s0 + k] = 1.0f + (float)dh;
                     }
+                    const f16x8 v = i8x8_to_f16(w[0], w[PT - 1]) * (_Float16)wq;
+                    if (PT == 2)
+                        *reinterpret_cast<f16x8 *>(xs_row) = v;
+                    else
+                        *reinterpret_cast<f16x4 *>(xs_row) = __builtin_shufflevector(v, v, 0, 1, 2, 3);
                 }
             }
         }
@@ -489,8 +492,17 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 // other wave of the SIMD fills the matrix core meanwhile)
                 const float rowf = exp2_fast(cum_t - m_sb) * kNarrow;
                 float lv[16];
+                if (PRECISE) {  // x' carries only the leading bits of the token weights: the rest scales the columns here
 #pragma unroll
-                for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(s_d1 + sb * kBlk + 8 * rg + 4 * hba);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) lv[4 * rg + i] = (float)gi[4 * rg + i] * (rowf * d4[i]);
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
+                }
                 const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
                 __builtin_amdgcn_sched_barrier(0);
                 const i32x16 gn = gemm_g(bq);
@@ -652,14 +664,17 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int ks = 0; ks < 2; ++ks) {
                     const int row = sb * kBlk + 16 * ks;
                     const u32x2 w = lds_read_tr8(bq_src + row * kBqStride);
+                    // d of the 8 tokens of this k group: tokens row + 4 hb + [0,4) and row + 8 + 4 hb + [0,4)
+                    const f16x4 dlo = *reinterpret_cast<const f16x4 *>(s_dh + row + 4 * hbs);
+                    const f16x4 dhi = *reinterpret_cast<const f16x4 *>(s_dh + row + 8 + 4 * hbs);
                     const f16x8 bf = i8x8_to_f16(w[0], w[1]);
+                    const f16x8 bfd = bf * __builtin_shufflevector(dlo, dhi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt) {
                         const int off = xs_off + (row * kXsStride + 32 * pt) * 2;
                         const f16x8 xb = lds_read_tr16x8<kXsStride>(s_xs + off);
-                        const f16x8 xlo = lds_read_tr16x8<kXsStride>(s_xl + off);
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb, st[pt], 0, 0, 0);
-                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xlo, st[pt], 0, 0, 0);
+                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bfd, xb, st[pt], 0, 0, 0);
                     }
                 }
             }
@@ -731,7 +746,7 @@ namespace {
 template <bool PRECISE, int PT>
 hipError_t launch_scan(const SsdArgs &a, hipStream_t stream)
 {
-    constexpr int lds = PRECISE ? Lds<PT>::kPrecise : Lds<PT>::kFast;
+    constexpr int lds = Lds<PT>::kBytes;
     const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT)));
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
