@@ -80,6 +80,9 @@ def test_ragged_lengths_and_init_state(gpu_lib, flags, L):
                                        init_state=h0.astype(np.float32).astype(np.float64))
     yg, hg = run_prefill(gpu_lib, s, sc, prob, flags, init_state=h0)
     check(yg, hg, yref, href, f"L={L} flags={flags}")
+    if flags != GENERIC:  # without the final state the matrix-core path takes its single-term state update
+        yg, _ = run_prefill(gpu_lib, s, sc, prob, flags, init_state=h0, want_state=False)
+        check(yg, None, yref, None, f"L={L} flags={flags}, no final state")
 
 
 @pytest.mark.parametrize("P,N,H,G,Q", [(64, 64, 4, 2, 128), (32, 128, 4, 1, 64), (64, 32, 6, 3, 256), (48, 24, 4, 2, 32),
