@@ -189,8 +189,22 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     // with two workgroups per head, ids i and i + 8 (same XCD, and the same compute unit when two workgroups fit one)
     // take the two halves of a head
     const int bid = blockIdx.x;
-    const int p_base = PT == 2 ? 0 : 32 * ((bid >> 3) & 1);
-    const int bh = block_to_bh(a, PT == 2 ? bid : ((bid & 7) | ((bid >> 4) << 3)));
+    int pair = bid, half = 0;  // index of the (sequence, head) pair before the XCD mapping; channel half
+    if (PT == 1) {
+        // complete groups of 8 pairs take 16 consecutive ids (8 first halves, 8 second halves); the last, incomplete
+        // group of r pairs takes the remaining 2 r ids (r first halves, r second halves)
+        const int npairs = a.s.batch * H, full = npairs >> 3;
+        if (bid < 16 * full) {
+            pair = (bid & 7) | ((bid >> 4) << 3);
+            half = (bid >> 3) & 1;
+        } else {
+            const int t = bid - 16 * full, r = npairs - 8 * full;
+            pair = 8 * full + t % r;
+            half = t / r;
+        }
+    }
+    const int p_base = 32 * half;
+    const int bh = block_to_bh(a, pair);
     const int b = bh / H, h = bh - b * H, g = h / (H / G);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps block indices in scalar registers

@@ -95,6 +95,29 @@ def test_other_shapes(gpu_lib, P, N, H, G, Q):
     check(yg, hg, yref, href, f"P{P} N{N} H{H} G{G} Q{Q}")
 
 
+@pytest.mark.parametrize("seed", [101, 102, 103, 104, 105, 106, 107, 108])
+def test_seeded_random_problems(gpu_lib, seed):
+    """Seeded draws of batch, length, heads, groups, clusters, D, initial state, final state and launch shape on the
+    matrix-core path (headdim 64, d_state 128): lengths from one token to a dozen chunks with ragged tails."""
+    rng = np.random.default_rng(seed)
+    G = int(rng.choice([1, 2, 4]))
+    H = G * int(rng.choice([1, 2, 3, 6]))
+    L = int(rng.integers(1, 1500))
+    s = W.LayerShape(f"r{seed}", int(rng.integers(1, 4)), L, H, 64, 128, G, 256, int(rng.choice([1, 2, 4])),
+                     int(rng.choice([1, 2, 4])))
+    s = s.with_(m=min(s.m, H // G))
+    sc, prob, _ = make_problem(s, seed, calib_tokens=256, with_D=bool(rng.integers(0, 2)))
+    h0 = W.draw_state(s, seed).astype(np.float64) if rng.integers(0, 2) else None
+    want_state = bool(rng.integers(0, 2))
+    flags = int(rng.choice([0, NO_SPLIT]))
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"],
+                                       init_state=None if h0 is None else h0.astype(np.float32).astype(np.float64),
+                                       want_state=want_state)
+    yg, hg = run_prefill(gpu_lib, s, sc, prob, flags, init_state=h0, want_state=want_state)
+    check(yg, hg, yref, href if want_state else None,
+          f"seed {seed}: b={s.batch} L={L} H={H} G={G} m={s.m} n={s.n} state={want_state} flags={flags}")
+
+
 def test_exact_integer_case(gpu_lib):
     """A = 0, dt = 1, all scales 1, small integers: y is an exact integer (< 2048, exact in fp16) and so is the state."""
     rng = np.random.default_rng(8)
