@@ -118,6 +118,19 @@ def test_seeded_random_problems(gpu_lib, seed):
           f"seed {seed}: b={s.batch} L={L} H={H} G={G} m={s.m} n={s.n} state={want_state} flags={flags}")
 
 
+@pytest.mark.parametrize("batch,H,G,L", [(8, 48, 8, 300), (5, 56, 7, 200), (3, 96, 8, 130)])
+def test_more_heads_than_compute_units(gpu_lib, batch, H, G, L):
+    """More (sequence, head) pairs than compute units: one workgroup per head, with the XCD-aware workgroup map
+    (number of (sequence, group) units a multiple of 8) and without it."""
+    s = W.LayerShape("wide", batch, L, H, 64, 128, G, 256, 2, 2)
+    sc, prob, _ = make_problem(s, 20 + batch, calib_tokens=256)
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"])
+    yg, hg = run_prefill(gpu_lib, s, sc, prob)
+    check(yg, hg, yref, href, f"b={batch} H={H} G={G} L={L}")
+    yg, _ = run_prefill(gpu_lib, s, sc, prob, want_state=False)
+    check(yg, None, yref, None, f"b={batch} H={H} G={G} L={L}, no final state")
+
+
 def test_exact_integer_case(gpu_lib):
     """A = 0, dt = 1, all scales 1, small integers: y is an exact integer (< 2048, exact in fp16) and so is the state."""
     rng = np.random.default_rng(8)
