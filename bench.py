@@ -160,16 +160,22 @@ def main() -> int:
         sc = oracle.Scales(s.m, s.n, hs.x_scales, hs.head_cluster_end, hs.chan_cluster_end, hs.B_scales, hs.C_scales)
         nseq = s.batch
         pairs = [(b, h) for b in range(nseq) for h in range(s.nheads)]
-        t0 = time.perf_counter()
-        yref, _, threads = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], A_np, D_np,
-                                              pairs=pairs, want_state=False)
-        cpu_s = time.perf_counter() - t0
+        # the whole prefill workload, repeated until about 10 s of wall time have gone by (at least twice: the first
+        # pass also pages the inputs in); the rate is that of the passes after the first
+        cpu_times = []
+        while len(cpu_times) < 2 or (sum(cpu_times) < 10.0 and len(cpu_times) < 40):
+            t0 = time.perf_counter()
+            yref, _, threads = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], A_np, D_np,
+                                                  pairs=pairs, want_state=False)
+            cpu_times.append(time.perf_counter() - t0)
+        cpu_s = sum(cpu_times[1:]) / (len(cpu_times) - 1)
         yg = y[:nseq].float().cpu().numpy().transpose(0, 2, 1, 3).reshape(len(pairs), s.seqlen, s.headdim)
         err = float(np.abs(yg - yref).max() / np.abs(yref).max())
         out["cpu_baseline"] = {"value": nseq * s.seqlen / cpu_s, "unit": "tokens/s", "cores": int(threads),
-                               "kind": "oracle", "seconds": cpu_s,
+                               "kind": "oracle", "seconds": cpu_s, "passes": len(cpu_times),
                                "sample": f"sequences 0..{nseq - 1} of the prefill workload, all {s.nheads} heads "
-                                         f"({nseq * s.seqlen} tokens), fp64 sequential scan"}
+                                         f"({nseq * s.seqlen} tokens), fp64 sequential scan; mean of the passes "
+                                         f"after the first, {sum(cpu_times):.1f} s of CPU wall time in total"}
         out["parity_spot_check"] = {"max_abs_err_over_max_abs_ref": err, "bar": 2e-3, "pairs": len(pairs)}
         del yref, yg
 
