@@ -8,18 +8,19 @@
 // sb (so cum_t <= m_sb <= cum_s whenever s lies in block sb and t in a later block: every exponent is <= 0):
 //
 //   G^T[s,t]   = sum_n Bq[s,n] Cq[t,n]                                   int8 MFMA 32x32x32, int32 (exact)
-//   x'[s,p]    = xq[s,p] * exp(m_sb - cum_s) * dt_s                      fp16, staged once per chunk in LDS
-//   off-diagonal block pair (sb < tb):  Y^T[p,t] += x'^T[p,s] * (G^T[s,t] * exp(cum_t - m_sb))      fp16 MFMA
-//   diagonal block (sb = tb):           Y^T[p,t] += xq^T[p,s] * (G^T[s,t] * exp(cum_t - cum_s) dt_s [s <= t])
+//   off-diagonal block pair (sb < tb):  Y^T[p,t] += xq^T[p,s] * (G^T[s,t] exp(cum_t - m_sb) * exp(m_sb - cum_s) dt_s)
+//   diagonal block (sb = tb):           Y^T[p,t] += xq^T[p,s] * (G^T[s,t] exp(cum_t - cum_s) dt_s [s <= t])
 //   carried state:                      Y^T[p,t] += sum_n H[p,n] (exp(cum_t) Cq[t,n])               fp16 MFMA
-//   state:   H <- exp(cum_last) H + sum_sb sum_{s in sb} x'[s,:]^T (exp(cum_last - m_sb) Bq[s,:])   fp16 MFMA
-//            (when the final state is returned, it has to meet 1e-4 of its maximum, which a product rounded to fp16
-//             cannot: the token weight w_s = exp(m_sb - cum_s) dt_s is split as wq_s (1 + d_s), wq_s its first 4
-//             bits, so that x'[s,p] = xq[s,p] wq_s is exact in fp16 (7 + 4 bits); the factor 1 + d_s, |d_s| <= 1/16,
-//             goes into the other operand: the intra-chunk score columns are scaled by it before narrowing, and the
-//             state takes two terms, H <- exp(m_sb - m_{sb-1}) H + x'^T Bq + x'^T (d_s Bq), block by block in fp32,
-//             the first exact, the second rounded at 2^-16 of the total)
+//   state:   H <- exp(cum_last) H + sum_s xq[s,:]^T (exp(cum_last - cum_s) dt_s Bq[s,:])            fp16 MFMA
 //   y[t,p]     = s_x(h,p) * (s_B s_C * Y[t,p] + D_h xq[t,p])             fp32 epilogue, fp16 store
+//
+// x is staged once per chunk as exact fp16 codes; every token weight sits on the other operand of its product: on the
+// columns of the narrowed score tiles (the row factor exp(cum_t - m_sb) is applied in fp32 before narrowing), and on
+// the rows of B in the state update.  When the final state is returned it has to meet 1e-4 of its maximum, which one
+// product rounded to fp16 cannot: the state then decays block by block in fp32, H <- exp(m_sb - m_{sb-1}) H + ..., and
+// the token weight w_s = exp(m_sb - cum_s) dt_s is split as wq_s (1 + d_s), wq_s = w_s rounded to 4 significant bits,
+// so that Bq wq_s is exact in fp16 (7 + 4 bits); the update takes two products, xq^T (wq_s Bq) and xq^T (d_s wq_s Bq),
+// the first exact, the second (|d_s| <= 1/16) rounded at 2^-16 of the total.
 //
 // which is Eq. 2 with A-dot = exp(dt A), B-dot = dt B (Section 3.2) regrouped; the quantization scales of
 // Section 4.1 enter only in the epilogue because x enters linearly and channel-wise and B, C have one scale per
@@ -51,6 +52,13 @@ constexpr int kThreads = 256;
 constexpr int kHsStride = 136;  // halves per row of H [p][n]
 constexpr int kBqStride = 144;  // bytes per row of Bq [token][n]
 constexpr float kNarrow = 1.0f / 128.0f;  // applied to G and H before narrowing to fp16; undone in the epilogue
+// Scales that keep every fp16 operand in the normal range.  x is staged as fp16 codes times kXs; the output
+// accumulators hold the output in code units times 2^-7 kAcc; the state accumulators the state times 2^-7 (kNarrow).
+// Hence the token weights on the score columns carry kAcc / kXs = 1/4 (score tiles, up to 2^14 after their own 2^-7,
+// times dt / 4 stay finite for dt up to 16), those on the rows of B carry kNarrow / kXs = 1/8 (dt / 8 times the decay
+// is far from the subnormals), and the C operand of the carried-state product carries kAcc.
+constexpr float kXs = 1.0f / 16.0f;
+constexpr float kAcc = 1.0f / 64.0f;
 
 // LDS map (bytes) for PT 32-channel tiles per workgroup.  Row pitches: with 4-byte banks, the 8 token rows x 16 bytes
 // a group of 16 lanes fetches from xq or Bq, and the 4 token rows x 32 bytes it fetches from x', fall into distinct
@@ -58,21 +66,19 @@ constexpr float kNarrow = 1.0f / 128.0f;  // applied to G and H before narrowing
 template <int PT>
 struct Lds {
     static constexpr int kPw = 32 * PT;                      // channels of the workgroup
-    static constexpr int kXqStride = PT == 2 ? 80 : 48;      // bytes per row of xq [token][p]
-    static constexpr int kXsStride = PT == 2 ? 80 : 48;      // halves per row of x' [token][p]
-    static constexpr int kOffCum = 0;                        // float[128]
-    static constexpr int kOffDt = kOffCum + 4 * kQ;          // float[128]
-    static constexpr int kOffW2 = kOffDt + 4 * kQ;           // float[128]
-    static constexpr int kOffD1 = kOffW2 + 4 * kQ;           // float[128]  1 + d_s (two-term path)
-    static constexpr int kOffDh = kOffD1 + 4 * kQ;           // fp16[128]   d_s (two-term path)
-    static constexpr int kOffSx = kOffDh + 2 * kQ;           // float[64]
-    static constexpr int kOffXq = kOffSx + 4 * kP + 64;      // int8 [128][kXqStride]
-    static constexpr int kOffBq = kOffXq + kQ * kXqStride;   // int8 [128][144]
+    static constexpr int kXsStride = PT == 2 ? 80 : 48;      // halves per row of x [token][p]
+    static constexpr int kOffCum = 0;                        // float[128]  prefix sums (log2 units)
+    static constexpr int kOffDt = kOffCum + 4 * kQ;          // float[128]  dt 2^-7 / kXs
+    static constexpr int kOffW2 = kOffDt + 4 * kQ;           // float[128]  column weights of the diagonal blocks
+    static constexpr int kOffWe = kOffW2 + 4 * kQ;           // fp16[128]   token weights of the off-diagonal blocks
+    static constexpr int kOffWs = kOffWe + 2 * kQ;           // fp16[128]   token weights of the state update
+    static constexpr int kOffWd = kOffWs + 2 * kQ;           // fp16[128]   their residuals (two-term path)
+    static constexpr int kOffSx = kOffWd + 2 * kQ;           // float[64]
+    static constexpr int kOffBq = kOffSx + 4 * kP + 64;      // int8 [128][144]
     static constexpr int kOffHs = kOffBq + kQ * kBqStride;   // fp16 [kPw][136]
     static constexpr int kOffXs = kOffHs + 2 * kPw * kHsStride;  // fp16 [128][kXsStride]
     static constexpr int kBytes = kOffXs + 2 * kQ * kXsStride;
-    static_assert(kOffXq % 16 == 0 && kOffBq % 16 == 0 && kOffHs % 16 == 0 && kOffXs % 16 == 0,
-                  "LDS arrays must be 16-byte aligned");
+    static_assert(kOffBq % 16 == 0 && kOffHs % 16 == 0 && kOffXs % 16 == 0, "LDS arrays must be 16-byte aligned");
 };
 static_assert(Lds<2>::kBytes <= 80 * 1024, "two workgroups must fit the 160 KB LDS of a gfx950 compute unit");
 
@@ -119,6 +125,19 @@ __device__ __forceinline__ f16x8 i8x8_to_f16(uint32_t w0, uint32_t w1)
     r.h[1] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x64646464u, w0, 0x04030402u)) - bias;
     r.h[2] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x64646464u, w1, 0x04010400u)) - bias;
     r.h[3] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x64646464u, w1, 0x04030402u)) - bias;
+    return r.v;
+}
+
+// 4 int8 codes (one dword) -> fp16 values kXs * code, exact: byte^0x80 placed under the fp16 pattern of 64 (whose
+// last mantissa bit weighs 1/16) gives 64 + (code + 128) / 16; subtract 72.
+__device__ __forceinline__ f16x4 i8x4_to_f16_xs(uint32_t w)
+{
+    static_assert(kXs == 1.0f / 16.0f, "the bit pattern below encodes a step of 1/16");
+    const f16x2 bias = {(_Float16)72.0f, (_Float16)72.0f};
+    w ^= 0x80808080u;
+    union { f16x4 v; f16x2 h[2]; } r;
+    r.h[0] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x54545454u, w, 0x04010400u)) - bias;
+    r.h[1] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x54545454u, w, 0x04030402u)) - bias;
     return r.v;
 }
 
@@ -172,18 +191,18 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 {
     typedef Lds<PT> LY;
     constexpr int kPw = LY::kPw;  // channels of this workgroup
-    constexpr int kXqStride = LY::kXqStride, kXsStride = LY::kXsStride;
+    constexpr int kXsStride = LY::kXsStride;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *s_cum = reinterpret_cast<float *>(smem + LY::kOffCum);
     float *s_dt = reinterpret_cast<float *>(smem + LY::kOffDt);
     float *s_w2 = reinterpret_cast<float *>(smem + LY::kOffW2);
+    _Float16 *s_we = reinterpret_cast<_Float16 *>(smem + LY::kOffWe);
+    _Float16 *s_ws = reinterpret_cast<_Float16 *>(smem + LY::kOffWs);
+    _Float16 *s_wd = reinterpret_cast<_Float16 *>(smem + LY::kOffWd);  // PRECISE only
     float *s_sx = reinterpret_cast<float *>(smem + LY::kOffSx);
-    unsigned char *s_xq = smem + LY::kOffXq;
     unsigned char *s_bq = smem + LY::kOffBq;
     _Float16 *s_hs = reinterpret_cast<_Float16 *>(smem + LY::kOffHs);
     unsigned char *s_xs = smem + LY::kOffXs;  // fp16 rows, addressed in bytes
-    float *s_d1 = reinterpret_cast<float *>(smem + LY::kOffD1);        // PRECISE only
-    _Float16 *s_dh = reinterpret_cast<_Float16 *>(smem + LY::kOffDh);  // PRECISE only
 
     const int L = a.s.seqlen, H = a.s.nheads, G = a.s.ngroups;
     // with two workgroups per head, ids i and i + 8 (same XCD, and the same compute unit when two workgroups fit one)
@@ -218,21 +237,21 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     const float Ah = a.A[h] * 1.44269504088896340736f;  // log2(e): prefix sums are kept in log2 units (exp2 below)
     const float Dh = a.D ? a.D[h] : 0.0f;
     const float sB = a.B_scales[g], sC = a.C_scales[g];
-    const float y_scale = sB * sC * (1.0f / kNarrow);
+    const float y_scale = sB * sC * (1.0f / (kNarrow * kAcc));  // output accumulator -> s_B s_C (x-code units)
     // Skip term D x[t,p]: the diagonal block multiplies exact x codes by L[t,s], so adding D/y_scale to L[t,t]
     // (in fp32, before L is narrowed to fp16 like every other entry) makes the matrix core add D x for free.
     // When D/y_scale would leave the fp16 range (extreme scales), the term is added in the epilogue from LDS instead.
-    const float d_acc = Dh / y_scale;
+    const float d_acc = Dh / (y_scale * kXs);  // it multiplies x codes staged times kXs
     const bool d_by_mfma = fabsf(d_acc) < 3.0e4f;
     const float d_sel = d_by_mfma ? d_acc : 0.0f;
 
     if (tid < kPw) s_sx[tid] = x_scale_lookup(a, h, p_base + tid) * (d_by_mfma ? y_scale : 1.0f);
     __syncthreads();
-    // Carried state in x-code * B-code units times kStScale (true state = s_x(p) s_B * st / kStScale): on the fast
-    // path the state is carried already narrowed by 2^-7, so that its fp16 copy for the C.H product needs no multiply
-    // (the factor rides on the per-block weight of the B operand instead).  Wave w owns states n in
-    // [32w, 32w+32); st[pt][r]: p = 32 pt + l32, n = 32 w + 8 (r/4) + 4 hb + r%4.
-    constexpr float kStScale = PRECISE ? 1.0f : kNarrow;
+    // Carried state in x-code * B-code units times kStScale (true state = s_x(p) s_B * st / kStScale): the state is
+    // carried already narrowed by 2^-7, so that its fp16 copy for the C.H product needs no multiply (the factor rides
+    // on the token weights of the B operand instead).  Wave w owns states n in [32w, 32w+32);
+    // st[pt][r]: p = 32 pt + l32, n = 32 w + 8 (r/4) + 4 hb + r%4.
+    constexpr float kStScale = kNarrow;
     f32x16 st[PT];
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt)
@@ -265,7 +284,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     xvec xr[4];
     u32x4 br[4];
     i32x4 cn[4];
-    float dt0 = 0.0f, dt1 = 0.0f;  // dt of tokens 2*lane and 2*lane + 1 (every wave holds the whole chunk's dt)
+    float dt0 = 0.0f, dt1 = 0.0f;  // dt of tokens 2*lane and 2*lane + 1 (first wave only)
     // Staging lane maps: a thread takes 4 consecutive tokens and 4 PT channels of x (8 lanes cover a row of this
     // workgroup's channels), resp. 16 states of B (8 lanes cover a 128-byte row).
     const int xs4 = tid >> 3, xp8 = tid & 7;
@@ -279,8 +298,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         const size_t tokbase = (size_t)b * L + t0;
         const int8_t *xbase = a.x + (tokbase * H + h) * kP + p_base;
         const char *dbase = reinterpret_cast<const char *>(a.dt + tokbase * H + h);
-        dt0 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane, nv - 1) * dt_row);
-        dt1 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane + 1, nv - 1) * dt_row);
+        if (wave == 0) {  // only the first wave needs dt: it computes every weight of the chunk
+            dt0 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane, nv - 1) * dt_row);
+            dt1 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane + 1, nv - 1) * dt_row);
+        }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint32_t row = (uint32_t)min(4 * xs4 + k, nv - 1);
@@ -321,26 +342,51 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
         const int nv = min(kQ, L - t0);  // valid tokens of this chunk
         const size_t tokbase = (size_t)b * L + t0;
 
-        // ---- inclusive prefix sum of dt*A over the chunk: every wave redundantly, two tokens per lane, so that the
-        // staging below needs no barrier; wave 0 publishes cum and dt in LDS for the phases after the barrier ----
-        if (2 * lane >= nv) dt0 = 0.0f;  // padded steps: dt = 0
-        if (2 * lane + 1 >= nv) dt1 = 0.0f;
-        float cum0, cum1;  // prefix sums at tokens 2*lane and 2*lane + 1
-        {
-            const float a0 = dt0 * Ah, a1 = dt1 * Ah;
-            const float scan = wave_inclusive_scan(a0 + a1);
-            cum0 = scan - a1;
-            cum1 = scan;
-        }
+        // ---- the first wave turns dt into everything the chunk needs of it: the inclusive prefix sum of dt*A (two
+        // tokens per lane, data-parallel-primitive moves only) and, per token s, the weights that stand between the x
+        // codes and their uses.  With m the prefix sum at the last token of the token's 32-token block, R the one in
+        // front of the block, cum_last the one at the end of the chunk:
+        //   we = dt exp2(m - cum_s) kAcc / kXs             off-diagonal blocks (row factor exp2(cum_t - m) 2^-7 per lane)
+        //   w2 = dt exp2(R - cum_s) 2^-7 kAcc / kXs        diagonal block (row factor exp2(cum_t - R))
+        //   ws = dt exp2(cum_last - cum_s) 2^-7 / kXs      state update of the single-term path
+        //   two-term path: the state decays block by block in fp32, its token weight dt exp2(m - cum_s) 2^-7 / kXs is
+        //   wq (1 + wd) with
+        //   wq rounded to 4 significant bits, so that B codes (7 bits) times wq are exact in fp16: ws = wq, wd
+        // All exponents are <= 0 except in w2, which may overflow under extreme decay (it is not used then). ----
         if (wave == 0) {
-            *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
-            *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(dt0 * kNarrow, dt1 * kNarrow);  // pre-narrowed
-            // column weights of the diagonal blocks: dt_s 2^-7 exp2(R - cum_s), R = prefix sum in front of the token's
-            // 32-token block (they may overflow under extreme decay; the diagonal block then does not use them)
+            if (2 * lane >= nv) dt0 = 0.0f;  // padded steps: dt = 0
+            if (2 * lane + 1 >= nv) dt1 = 0.0f;
+            const float a0 = dt0 * Ah, a1 = dt1 * Ah;
+            const float cum1 = wave_inclusive_scan(a0 + a1), cum0 = cum1 - a1;
+            const float m = __shfl(cum1, lane | 15, 64);
             const float rb = __shfl(cum1, (lane & ~15) - 1, 64);
             const float R = lane >= 16 ? rb : 0.0f;
+            const float d0 = dt0 * (kAcc / kXs), d1 = dt1 * (kAcc / kXs);      // weights towards the output accumulators
+            const float q0 = dt0 * (kNarrow / kXs), q1 = dt1 * (kNarrow / kXs);  // weights towards the state accumulators
+            const float e0 = exp2_fast(m - cum0), e1 = exp2_fast(m - cum1);
+            const float we0 = e0 * d0, we1 = e1 * d1;
+            *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
+            *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(d0 * kNarrow, d1 * kNarrow);
             *reinterpret_cast<float2 *>(s_w2 + 2 * lane) =
-                make_float2(exp2_fast(R - cum0) * dt0 * kNarrow, exp2_fast(R - cum1) * dt1 * kNarrow);
+                make_float2(exp2_fast(R - cum0) * d0 * kNarrow, exp2_fast(R - cum1) * d1 * kNarrow);
+            *reinterpret_cast<f16x2 *>(s_we + 2 * lane) = (f16x2){(_Float16)we0, (_Float16)we1};
+            if (!PRECISE) {
+                const float cum_last = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cum1), 63));
+                *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) =
+                    (f16x2){(_Float16)(exp2_fast(cum_last - cum0) * q0), (_Float16)(exp2_fast(cum_last - cum1) * q1)};
+            } else {
+                f16x2 wq, wd;
+                const float w[2] = {e0 * q0, e1 * q1};
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const float q =
+                        __builtin_bit_cast(float, (__builtin_bit_cast(uint32_t, w[i]) + 0x00080000u) & 0xfff00000u);
+                    wq[i] = (_Float16)q;
+                    wd[i] = (_Float16)(q > 0.0f ? (w[i] - q) / q : 0.0f);
+                }
+                *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) = wq;
+                *reinterpret_cast<f16x2 *>(s_wd + 2 * lane) = wd;
+            }
         }
 
         // carried state -> LDS as fp16 (operand of the C.H product of this chunk)
@@ -350,54 +396,22 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             for (int rg = 0; rg < 4; ++rg) {
                 f16x4 v;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = (_Float16)(st[pt][4 * rg + i] * (kNarrow / kStScale));
+                for (int i = 0; i < 4; ++i) v[i] = (_Float16)st[pt][4 * rg + i];
                 *reinterpret_cast<f16x4 *>(s_hs + (pt * 32 + l32) * kHsStride + 32 * wave + 8 * rg + 4 * hb) = v;
             }
 
-        // ---- x codes, x' (fp16) and B codes into LDS, token-major, token rows permuted ----
+        // ---- x (fp16 codes times kXs) and B codes into LDS, token-major, token rows permuted ----
         {
             const int s0 = 4 * xs4, row0 = tok_pos(s0);
-            // cum and dt of tokens s0 .. s0+3 sit in lanes 2*xs4 and 2*xs4 + 1 of this wave; m in the lane of the
-            // block's last token
-            const int l0 = 2 * xs4, lm = ((s0 & ~31) >> 1) + 15;
-            const float cumq[4] = {__shfl(cum0, l0, 64), __shfl(cum1, l0, 64), __shfl(cum0, l0 + 1, 64),
-                                   __shfl(cum1, l0 + 1, 64)};
-            const float dtq[4] = {__shfl(dt0, l0, 64), __shfl(dt1, l0, 64), __shfl(dt0, l0 + 1, 64),
-                                  __shfl(dt1, l0 + 1, 64)};
-            const float m = __shfl(cum1, lm, 64);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 xvec w = xr[k];
                 if (nv < kQ) {  // partial last chunk: rows past the end are zero
                     if (s0 + k >= nv) w = (xvec)(0u);
                 }
-                const float colf = exp2_fast(m - cumq[k]) * dtq[k];
-                *reinterpret_cast<xvec *>(s_xq + (row0 + k) * kXqStride + 4 * PT * xp8) = w;
                 unsigned char *xs_row = s_xs + ((row0 + k) * kXsStride + 4 * PT * xp8) * 2;
-                if (!PRECISE) {
-                    // exact fp16 codes times the fp16 weight of the token: one more rounding (2^-11 relative, of the
-                    // weight) than an fp32 product, well inside the budget of y
-                    const f16x8 v = i8x8_to_f16(w[0], w[PT - 1]) * (_Float16)colf;
-                    if (PT == 2)
-                        *reinterpret_cast<f16x8 *>(xs_row) = v;
-                    else
-                        *reinterpret_cast<f16x4 *>(xs_row) = __builtin_shufflevector(v, v, 0, 1, 2, 3);
-                } else {
-                    // the weight rounded to 4 significant bits: codes (7 bits) times it are exact in fp16; the rest,
-                    // 1 + d with |d| <= 1/16, is published for the other operands
-                    const float wq =
-                        __builtin_bit_cast(float, (__builtin_bit_cast(uint32_t, colf) + 0x00080000u) & 0xfff00000u);
-                    const _Float16 dh = (_Float16)(wq > 0.0f ? (colf - wq) / wq : 0.0f);
-                    if (xp8 == 0) {
-                        s_dh[s0 + k] = dh;
-                        s_d1[s0 + k] = 1.0f + (float)dh;
-                    }
-                    const f16x8 v = i8x8_to_f16(w[0], w[PT - 1]) * (_Float16)wq;
-                    if (PT == 2)
-                        *reinterpret_cast<f16x8 *>(xs_row) = v;
-                    else
-                        *reinterpret_cast<f16x4 *>(xs_row) = __builtin_shufflevector(v, v, 0, 1, 2, 3);
-                }
+#pragma unroll
+                for (int q = 0; q < PT; ++q) *reinterpret_cast<f16x4 *>(xs_row + 8 * q) = i8x4_to_f16_xs(w[q]);
             }
         }
         {
@@ -440,7 +454,6 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             // source-lane roles of the transposing loads (see lds_read_tr8 / lds_read_tr16): token row of the lane
             // inside a k group of 8 tokens, and its first column inside the 32 columns of the operand
             const int i16 = lane_a & 15, c16 = (lane_a >> 4) & 1;
-            const unsigned char *xq_src = s_xq + (8 * hba + (i16 >> 1)) * kXqStride + 16 * c16 + 8 * (i16 & 1);
             const unsigned char *xs_src = s_xs + ((8 * hba + (i16 >> 2)) * kXsStride + 16 * c16 + 4 * (i16 & 3)) * 2;
             const float cum_t = s_cum[tb * kBlk + l32a];
 
@@ -468,7 +481,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
             for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[pt][r] = 0.0f;
-            const _Float16 e_t = (_Float16)exp2_fast(cum_t);  // per lane (token t); folded into the C operand
+            const _Float16 e_t = (_Float16)(exp2_fast(cum_t) * kAcc);  // per lane (token t); folded into the C operand
 #pragma unroll
             for (int k2 = 0; k2 < 4; ++k2) {  // batches of two k-steps: all LDS reads of a batch are issued first
                 f16x8 hf[2][PT];
@@ -501,23 +514,20 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     for (int pt = 0; pt < PT; ++pt)
                         xa[ks][pt] = lds_read_tr16x8<kXsStride>(xs_src + ((sb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
                 const float m_sb = s_cum[sb * kBlk + kBlk - 1];
+                f16x4 wq4[4];  // weights of tokens 8 rg + 4 hb + [0,4) of block sb
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg)
+                    wq4[rg] = *reinterpret_cast<const f16x4 *>(s_we + sb * kBlk + 8 * rg + 4 * hba);
                 __builtin_amdgcn_sched_barrier(0);
                 // the current tile is narrowed before the next one is issued, so that both can share registers (the
                 // other wave of the SIMD fills the matrix core meanwhile)
                 const float rowf = exp2_fast(cum_t - m_sb) * kNarrow;
                 float lv[16];
-                if (PRECISE) {  // x' carries only the leading bits of the token weights: the rest scales the columns here
 #pragma unroll
-                    for (int rg = 0; rg < 4; ++rg) {
-                        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(s_d1 + sb * kBlk + 8 * rg + 4 * hba);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) lv[4 * rg + i] = (float)gi[4 * rg + i] * (rowf * d4[i]);
-                    }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
-                }
-                const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
+                for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
+                // narrowed, then times the weights of the lane's 16 tokens of block sb (x is staged without them)
+                const f16x8 l0 = pack_f16x8(lv) * __builtin_shufflevector(wq4[0], wq4[1], 0, 1, 2, 3, 4, 5, 6, 7);
+                const f16x8 l1 = pack_f16x8(lv + 8) * __builtin_shufflevector(wq4[2], wq4[3], 0, 1, 2, 3, 4, 5, 6, 7);
                 __builtin_amdgcn_sched_barrier(0);
                 const i32x16 gn = gemm_g(bq);
                 __builtin_amdgcn_sched_barrier(0);  // the next tile first: its conversion then overlaps the products below
@@ -529,12 +539,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 gi = gn;
             }
             {  // diagonal block pair: per-element decay, causal mask, plain x codes
-                u32x2 xw[2][PT];
+                f16x8 xd[2][PT];
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt)
-                        xw[ks][pt] = lds_read_tr8(xq_src + (tb * kBlk + 16 * ks) * kXqStride + 32 * pt);
+                        xd[ks][pt] = lds_read_tr16x8<kXsStride>(xs_src + ((tb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
                 // R: prefix sum in front of the block, m: at its last token.  When the decay across the block stays below
                 // 2^64 the weight exp2(cum_t - cum_s) dt_s is the product of a row factor and the staged column weights
                 // (both inside the fp32 range); otherwise every element takes its own exponential.
@@ -587,10 +597,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int pt = 0; pt < PT; ++pt) {
-                        const f16x8 xf = i8x8_to_f16(xw[ks][pt][0], xw[ks][pt][1]);
-                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, ks ? l1 : l0, acc[pt], 0, 0, 0);
-                    }
+                    for (int pt = 0; pt < PT; ++pt)
+                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xd[ks][pt], ks ? l1 : l0, acc[pt], 0, 0, 0);
             }
 
             // epilogue: scales and skip term in fp32, narrowing to fp16; a lane holds 4 consecutive channels of token
@@ -639,7 +647,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
                                 const int p = pt * 32 + 8 * rg + 4 * hb + i;
-                                const float xc = (float)(signed char)s_xq[tq * kXqStride + p];
+                                const float xc =
+                                    (float)reinterpret_cast<const _Float16 *>(s_xs)[tq * kXsStride + p] * (1.0f / kXs);
                                 o[i] = (_Float16)(s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc));
                             }
                             const u32x2 ow = __builtin_bit_cast(u32x2, o);
@@ -678,11 +687,15 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 for (int ks = 0; ks < 2; ++ks) {
                     const int row = sb * kBlk + 16 * ks;
                     const u32x2 w = lds_read_tr8(bq_src + row * kBqStride);
-                    // d of the 8 tokens of this k group: tokens row + 4 hb + [0,4) and row + 8 + 4 hb + [0,4)
-                    const f16x4 dlo = *reinterpret_cast<const f16x4 *>(s_dh + row + 4 * hbs);
-                    const f16x4 dhi = *reinterpret_cast<const f16x4 *>(s_dh + row + 8 + 4 * hbs);
-                    const f16x8 bf = i8x8_to_f16(w[0], w[1]);
-                    const f16x8 bfd = bf * __builtin_shufflevector(dlo, dhi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    // weights of the 8 tokens of this k group: tokens row + 4 hb + [0,4) and row + 8 + 4 hb + [0,4)
+                    const f16x8 wq = __builtin_shufflevector(*reinterpret_cast<const f16x4 *>(s_ws + row + 4 * hbs),
+                                                             *reinterpret_cast<const f16x4 *>(s_ws + row + 8 + 4 * hbs),
+                                                             0, 1, 2, 3, 4, 5, 6, 7);
+                    const f16x8 wd = __builtin_shufflevector(*reinterpret_cast<const f16x4 *>(s_wd + row + 4 * hbs),
+                                                             *reinterpret_cast<const f16x4 *>(s_wd + row + 8 + 4 * hbs),
+                                                             0, 1, 2, 3, 4, 5, 6, 7);
+                    const f16x8 bf = i8x8_to_f16(w[0], w[1]) * wq;  // exact: 7 bits times 4 bits
+                    const f16x8 bfd = bf * wd;                      // the small term, rounded
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt) {
                         const int off = xs_off + (row * kXsStride + 32 * pt) * 2;
@@ -693,9 +706,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                 }
             }
         } else {
-            const float cum_last = s_cum[kQ - 1];  // padded steps leave cum flat, so this is cum at the last valid token
             {
-                const float gdec = exp2_fast(cum_last);
+                const float gdec = exp2_fast(s_cum[kQ - 1]);  // padded steps leave cum flat: cum at the last valid token
 #pragma unroll
                 for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
@@ -704,23 +716,25 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
             for (int sb = 0; sb < kNBlk; ++sb) {  // blocks past the end hold zeros in x' (dt = 0): they add nothing
                 u32x2 bw[2];
-                f16x8 xb[2][PT];
+                f16x8 xb[2][PT], wv[2];
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const int row = sb * kBlk + 16 * ks;
                     bw[ks] = lds_read_tr8(bq_src + row * kBqStride);
+                    // weights of the 8 tokens of this k group: tokens row + 4 hb + [0,4) and row + 8 + 4 hb + [0,4)
+                    wv[ks] = __builtin_shufflevector(*reinterpret_cast<const f16x4 *>(s_ws + row + 4 * hbs),
+                                                     *reinterpret_cast<const f16x4 *>(s_ws + row + 8 + 4 * hbs),
+                                                     0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt)
                         xb[ks][pt] = lds_read_tr16x8<kXsStride>(s_xs + xs_off + (row * kXsStride + 32 * pt) * 2);
                 }
-                const float m_sb = s_cum[sb * kBlk + kBlk - 1];
                 __builtin_amdgcn_sched_barrier(0);
                 if (c + 1 < nchunks) issue_b_load(c + 1, sb);  // staging consumes B first, and loads return in order
                 __builtin_amdgcn_sched_barrier(0);
-                const _Float16 f = (_Float16)(exp2_fast(cum_last - m_sb) * kStScale);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
-                    const f16x8 bf = i8x8_to_f16(bw[ks][0], bw[ks][1]) * f;
+                    const f16x8 bf = i8x8_to_f16(bw[ks][0], bw[ks][1]) * wv[ks];
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt)
                         st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb[ks][pt], st[pt], 0, 0, 0);
