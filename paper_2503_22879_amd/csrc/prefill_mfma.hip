@@ -28,8 +28,8 @@
 // int8 codes are exact in fp16; G (|G| <= 2^21) is scaled by 2^-7 in fp32 before it is narrowed.
 // The MFMA output layout (a lane holds one column and 16 rows) equals the operand layout (a lane holds one
 // row/column and 8 or 16 consecutive k) up to a fixed permutation of k, so G^T tiles feed the next MFMA straight
-// from registers.  x, x' and B sit in LDS token-major, exactly as they arrive (no transposes on the vector ALU); the
-// operands that need the token index as k (x^T, x'^T, B^T) are fetched with the transposing LDS loads
+// from registers.  x and B sit in LDS token-major, exactly as they arrive (no transposes on the vector ALU); the
+// operands that need the token index as k (x^T, B^T) are fetched with the transposing LDS loads
 // (ds_read_b64_tr_b8 / _tr_b16), whose source lanes address whole token rows; the rows are stored with bits 2 and 3
 // of the token index swapped so that the 8 tokens of one k group are 8 consecutive rows.
 #include "quamba_internal.h"
@@ -61,7 +61,7 @@ constexpr float kXs = 1.0f / 16.0f;
 constexpr float kAcc = 1.0f / 64.0f;
 
 // LDS map (bytes) for PT 32-channel tiles per workgroup.  Row pitches: with 4-byte banks, the 8 token rows x 16 bytes
-// a group of 16 lanes fetches from xq or Bq, and the 4 token rows x 32 bytes it fetches from x', fall into distinct
+// a group of 16 lanes fetches from Bq, and the 4 token rows x 32 bytes it fetches from x, fall into distinct
 // banks (pitches of 20 / 12, 36 and 40 / 24 banks).
 template <int PT>
 struct Lds {
@@ -105,7 +105,7 @@ __device__ __forceinline__ f16x4 lds_read_tr16(const unsigned char *p)
     return __builtin_bit_cast(
         f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_lds *)(p)));
 }
-// 8 tokens x one column of fp16 x' (two 4-token transposing loads, token rows r .. r+7 of the lane group)
+// 8 tokens x one column of fp16 x (two 4-token transposing loads, token rows r .. r+7 of the lane group)
 template <int PITCH_HALVES>
 __device__ __forceinline__ f16x8 lds_read_tr16x8(const unsigned char *p)
 {
@@ -714,7 +714,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
                     for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
             }
 #pragma unroll
-            for (int sb = 0; sb < kNBlk; ++sb) {  // blocks past the end hold zeros in x' (dt = 0): they add nothing
+            for (int sb = 0; sb < kNBlk; ++sb) {  // blocks past the end hold zero weights (dt = 0): they add nothing
                 u32x2 bw[2];
                 f16x8 xb[2][PT], wv[2];
 #pragma unroll
