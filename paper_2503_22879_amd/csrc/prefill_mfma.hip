@@ -62,7 +62,7 @@ constexpr float kAcc = 1.0f / 64.0f;
 
 // LDS map (bytes) for PT 32-channel tiles per workgroup.  Row pitches: with 4-byte banks, the 8 token rows x 16 bytes
 // a group of 16 lanes fetches from Bq, and the 4 token rows x 32 bytes it fetches from x, fall into distinct
-// banks (pitches of 20 / 12, 36 and 40 / 24 banks).
+// banks (pitches of 36 and 40 / 24 banks).
 template <int PT>
 struct Lds {
     static constexpr int kPw = 32 * PT;                      // channels of the workgroup
