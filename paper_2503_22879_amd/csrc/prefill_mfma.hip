@@ -1,9 +1,12 @@
 // Chunked prefill of the 8-bit SSD on the gfx950 matrix cores.
 //
-// One workgroup (4 waves) owns one (sequence, head), or half of a head's channels when the batch is too small to
-// fill the chip, and walks it in chunks of kQ = 128 tokens; the head's state never leaves the chip.  Its LDS
-// footprint (< 80 KB on the fast path) lets two workgroups share a compute unit, so that each SIMD holds two
-// waves whose matrix-core, vector-ALU and memory phases overlap.  Per chunk, with a_t = dt_t A_h, cum_t
+// One workgroup (8 waves) owns one (sequence, head), or half of a head's channels when the batch is too small to
+// fill the chip, and walks it in chunks of kQ = 128 tokens; the head's state never leaves the chip.  The waves split
+// into two roles that run side by side between the two barriers of a chunk: waves 0..3 produce the outputs (each owns
+// one 32-token block of the chunk), waves 4..7 own the state (each a quarter of its columns): they stage the chunk into
+// LDS, compute the token weights, and update the state while the output waves work.  The LDS footprint (< 80 KB) and
+// the register budget (128 per lane) let two workgroups share a compute unit, so that each SIMD holds four waves (two
+// of each role) whose matrix-core, vector-ALU and memory phases overlap.  Per chunk, with a_t = dt_t A_h, cum_t
 // its inclusive prefix sum inside the chunk, 32-token blocks tb / sb, and m_sb = cum at the last token of block
 // sb (so cum_t <= m_sb <= cum_s whenever s lies in block sb and t in a later block: every exponent is <= 0):
 //
@@ -48,7 +51,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kP = 64, kN = 128, kQ = 128, kBlk = 32, kNBlk = kQ / kBlk;
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
 constexpr int kHsStride = 136;  // halves per row of H [p][n]
 constexpr int kBqStride = 144;  // bytes per row of Bq [token][n]
 constexpr float kNarrow = 1.0f / 128.0f;  // applied to G and H before narrowing to fp16; undone in the epilogue
@@ -86,6 +89,13 @@ static_assert(Lds<2>::kBytes <= 80 * 1024, "two workgroups must fit the 160 KB L
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // LDS row of token s of the chunk: bits 2 and 3 swapped (see file comment).
+// Lane index recomputed where it is called: the mask passes through an empty asm statement, so the compiler can neither
+// hoist the result out of a loop nor keep it in a register across one.
+__device__ __forceinline__ int fresh_lane() {
+    unsigned m = ~0u;
+    asm volatile("" : "+s"(m));
+    return (int)__builtin_amdgcn_mbcnt_hi(m, __builtin_amdgcn_mbcnt_lo(m, 0u));
+}
 __device__ __forceinline__ int tok_pos(int s) { return (s & ~12) | ((s & 4) << 1) | ((s & 8) >> 1); }
 
 // Transposing LDS loads.  Inside each group of 16 lanes, result byte j of lane i comes from the 8 bytes addressed by
@@ -144,7 +154,8 @@ __device__ __forceinline__ f16x4 i8x4_to_f16_xs(uint32_t w)
 template <int CTRL, int ROW_MASK, bool BOUND>
 __device__ __forceinline__ float dpp_f32(float v)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, BOUND));
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, BOUND));
 }
 
 // Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves only (no LDS round trips):
@@ -187,7 +198,7 @@ __device__ __forceinline__ int block_to_bh(const SsdArgs &a, int i)
 // half of the channels, its own half of the state and its own copy of the G^T work; chosen when there are fewer
 // heads in the batch than compute units, so that the whole chip works on short batches.
 template <bool PRECISE, int PT>
-__global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
+__global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
 {
     typedef Lds<PT> LY;
     constexpr int kPw = LY::kPw;  // channels of this workgroup
@@ -226,12 +237,15 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
     const int bh = block_to_bh(a, pair);
     const int b = bh / H, h = bh - b * H, g = h / (H / G);
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps block indices in scalar registers
+    // wave-uniform: keeps block indices in scalar registers
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool out_role = wave8 < 4;  // waves 0..3: outputs; waves 4..7: staging, token weights, state
+    const int wave = wave8 & 3;       // index inside the role (waves w and w + 4 share a SIMD)
+    const int tid4 = tid & 255;       // thread index inside the role
     const int l32 = lane & 31, hb = lane >> 5;
-    // Two workgroups share a compute unit, wave w of each on SIMD w (workgroups i and i + 8 land on one compute unit:
-    // consecutive ids go round the 8 XCDs).  The causal work of a wave grows with its block index, so every other
-    // workgroup of an XCD walks its blocks in the opposite order: a SIMD then holds a long and a short block at a
-    // time instead of two long or two short ones.
+    // The causal work of an output wave grows with its block index, and a wave's block rotates with the chunk index;
+    // every other group of 8 workgroup ids (one id per XCD) walks the blocks in the opposite order, so that the long
+    // and the short blocks of different workgroups are spread over the SIMDs.
     const int rot_flip = ((bid >> 3) & 1) ? (kNBlk - 1) : 0;
 
     const float Ah = a.A[h] * 1.44269504088896340736f;  // log2(e): prefix sums are kept in log2 units (exp2 below)
@@ -247,552 +261,559 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(SsdArgs a)
 
     if (tid < kPw) s_sx[tid] = x_scale_lookup(a, h, p_base + tid) * (d_by_mfma ? y_scale : 1.0f);
     __syncthreads();
-    // Carried state in x-code * B-code units times kStScale (true state = s_x(p) s_B * st / kStScale): the state is
-    // carried already narrowed by 2^-7, so that its fp16 copy for the C.H product needs no multiply (the factor rides
-    // on the token weights of the B operand instead).  Wave w owns states n in [32w, 32w+32);
-    // st[pt][r]: p = 32 pt + l32, n = 32 w + 8 (r/4) + 4 hb + r%4.
-    constexpr float kStScale = kNarrow;
-    f32x16 st[PT];
-#pragma unroll
-    for (int pt = 0; pt < PT; ++pt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st[pt][r] = 0.0f;
-    if (a.init_state) {
-#pragma unroll
-        for (int pt = 0; pt < PT; ++pt) {
-            const int p = pt * 32 + l32;
-            const float inv = kStScale * (d_by_mfma ? y_scale : 1.0f) / (s_sx[p] * sB);
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                const int n0 = 32 * wave + 8 * rg + 4 * hb;
-                const f32x4 v =
-                    *reinterpret_cast<const f32x4 *>(a.init_state + ((size_t)bh * kP + p_base + p) * kN + n0);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) st[pt][4 * rg + i] = v[i] * inv;
-            }
-        }
-    }
-
     const int nchunks = (L + kQ - 1) / kQ;
-
-    // Registers that carry one chunk's global loads from the point of issue (the previous chunk's compute phase)
-    // to the staging phase: x codes (4 tokens x 8 channels), B codes (4 tokens x 16 states), dt of token tid and
-    // the C rows of this wave's 32-token output block.  Rows past the end of the sequence are read from the last
-    // valid row and zeroed where they are consumed, so that nothing waits for data at the point of issue.
-    // Vector-memory results return in issue order, hence the loads are issued in the order they are consumed.
-    typedef uint32_t xvec __attribute__((ext_vector_type(PT)));  // 4 PT x codes of one token
-    xvec xr[4];
-    u32x4 br[4];
-    i32x4 cn[4];
-    float dt0 = 0.0f, dt1 = 0.0f;  // dt of tokens 2*lane and 2*lane + 1 (first wave only)
-    // Staging lane maps: a thread takes 4 consecutive tokens and 4 PT channels of x (8 lanes cover a row of this
-    // workgroup's channels), resp. 16 states of B (8 lanes cover a 128-byte row).
-    const int xs4 = tid >> 3, xp8 = tid & 7;
-    const int bs4 = tid >> 3, bn16 = tid & 7;
-    // Addresses are a wave-uniform 64-bit base (advanced per chunk) plus a 32-bit lane offset that does not change
-    // from chunk to chunk; only the last, partial chunk needs the offsets of the rows past the end redirected.
+    constexpr float kStScale = kNarrow;
     const uint32_t x_row = (uint32_t)H * kP, b_row = (uint32_t)G * kN, dt_row = (uint32_t)H * 4u;
-    auto issue_loads = [&](int c) {
-        const int t0 = c * kQ;
-        const int nv = min(kQ, L - t0);
-        const size_t tokbase = (size_t)b * L + t0;
-        const int8_t *xbase = a.x + (tokbase * H + h) * kP + p_base;
-        const char *dbase = reinterpret_cast<const char *>(a.dt + tokbase * H + h);
-        if (wave == 0) {  // only the first wave needs dt: it computes every weight of the chunk
-            dt0 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane, nv - 1) * dt_row);
-            dt1 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane + 1, nv - 1) * dt_row);
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t row = (uint32_t)min(4 * xs4 + k, nv - 1);
-            xr[k] = *reinterpret_cast<const xvec *>(xbase + (row * x_row + (uint32_t)(4 * PT) * xp8));
-        }
-    };
-    // C rows of this wave's output block of chunk c.  k-step kk of the G^T product covers states 32 kk + 16 hb +
-    // [0,16): the two half-waves read adjacent 16-byte pieces of a C row (half as many memory requests as 64
-    // contiguous bytes per lane).  Issued, with the B rows (mostly L2 hits: 16 heads share them), after the output
-    // phase of the previous chunk, when registers are free; B first, because staging consumes it first.
-    // Part k (0..3) of them: one B row and one 32-byte piece of the C row per lane, so that the memory instructions
-    // can be spread over the state update instead of queueing up behind each other.
-    auto issue_b_load = [&](int c, int k) {
-        const int t0 = c * kQ;
-        const int nv = min(kQ, L - t0);
-        const int8_t *bbase = a.B + (((size_t)b * L + t0) * G + g) * kN;
-        const uint32_t row = (uint32_t)min(4 * bs4 + k, nv - 1);
-        br[k] = *reinterpret_cast<const u32x4 *>(bbase + (row * b_row + 16u * bn16));
-    };
-    auto issue_cn_load = [&](int c, int kk) {
-        const int t0 = c * kQ;
-        const int nv = min(kQ, L - t0);
-        const int8_t *cbase = a.C + (((size_t)b * L + t0) * G + g) * kN;
-        const uint32_t row = (uint32_t)min((((wave + c) & (kNBlk - 1)) ^ rot_flip) * kBlk + l32, nv - 1);
-        cn[kk] = *reinterpret_cast<const i32x4 *>(cbase + (row * b_row + 16u * hb) + 32 * kk);
-    };
-    auto issue_c_loads = [&](int c) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) issue_b_load(c, k);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) issue_cn_load(c, kk);
-    };
-    issue_loads(0);
-    issue_c_loads(0);
+    typedef uint32_t xvec __attribute__((ext_vector_type(PT)));
 
-    for (int c = 0; c < nchunks; ++c) {
-        const int t0 = c * kQ;
-        const int nv = min(kQ, L - t0);  // valid tokens of this chunk
-        const size_t tokbase = (size_t)b * L + t0;
-
-        // ---- the first wave turns dt into everything the chunk needs of it: the inclusive prefix sum of dt*A (two
-        // tokens per lane, data-parallel-primitive moves only) and, per token s, the weights that stand between the x
-        // codes and their uses.  With m the prefix sum at the last token of the token's 32-token block, R the one in
-        // front of the block, cum_last the one at the end of the chunk:
-        //   we = dt exp2(m - cum_s) kAcc / kXs             off-diagonal blocks (row factor exp2(cum_t - m) 2^-7 per lane)
-        //   w2 = dt exp2(R - cum_s) 2^-7 kAcc / kXs        diagonal block (row factor exp2(cum_t - R))
-        //   ws = dt exp2(cum_last - cum_s) 2^-7 / kXs      state update of the single-term path
-        //   two-term path: the state decays block by block in fp32, its token weight dt exp2(m - cum_s) 2^-7 / kXs is
-        //   wq (1 + wd) with
-        //   wq rounded to 4 significant bits, so that B codes (7 bits) times wq are exact in fp16: ws = wq, wd
-        // All exponents are <= 0 except in w2, which may overflow under extreme decay (it is not used then). ----
-        if (wave == 0) {
-            if (2 * lane >= nv) dt0 = 0.0f;  // padded steps: dt = 0
-            if (2 * lane + 1 >= nv) dt1 = 0.0f;
-            const float a0 = dt0 * Ah, a1 = dt1 * Ah;
-            const float cum1 = wave_inclusive_scan(a0 + a1), cum0 = cum1 - a1;
-            const float m = __shfl(cum1, lane | 15, 64);
-            const float rb = __shfl(cum1, (lane & ~15) - 1, 64);
-            const float R = lane >= 16 ? rb : 0.0f;
-            const float d0 = dt0 * (kAcc / kXs), d1 = dt1 * (kAcc / kXs);      // weights towards the output accumulators
-            const float q0 = dt0 * (kNarrow / kXs), q1 = dt1 * (kNarrow / kXs);  // weights towards the state accumulators
-            const float e0 = exp2_fast(m - cum0), e1 = exp2_fast(m - cum1);
-            const float we0 = e0 * d0, we1 = e1 * d1;
-            *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
-            *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(d0 * kNarrow, d1 * kNarrow);
-            *reinterpret_cast<float2 *>(s_w2 + 2 * lane) =
-                make_float2(exp2_fast(R - cum0) * d0 * kNarrow, exp2_fast(R - cum1) * d1 * kNarrow);
-            *reinterpret_cast<f16x2 *>(s_we + 2 * lane) = (f16x2){(_Float16)we0, (_Float16)we1};
-            if (!PRECISE) {
-                const float cum_last = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cum1), 63));
-                *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) =
-                    (f16x2){(_Float16)(exp2_fast(cum_last - cum0) * q0), (_Float16)(exp2_fast(cum_last - cum1) * q1)};
-            } else {
-                f16x2 wq, wd;
-                const float w[2] = {e0 * q0, e1 * q1};
+    if (out_role) {
+        // ================= output waves: wave w produces the outputs of one 32-token block per chunk =================
+        // C rows of the wave's block of chunk c (operand of G^T, and, as fp16, of the carried-state product), loaded a
+        // chunk ahead.  k-step kk of the G^T product covers states 32 kk + 16 hb + [0,16): the two half-waves read
+        // adjacent 16-byte pieces of a C row.  Rows past the end of the sequence are read from the last valid row and
+        // zeroed where they are consumed.
+        i32x4 ct[4];
+        auto issue_c_rows = [&](int c) {
+            const int t0 = c * kQ;
+            const int nv = min(kQ, L - t0);
+            const int8_t *cbase = a.C + (((size_t)b * L + t0) * G + g) * kN;
+            const int ln = fresh_lane();
+            const uint32_t row = (uint32_t)min((((wave + c) & (kNBlk - 1)) ^ rot_flip) * kBlk + (ln & 31), nv - 1);
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const float q =
-                        __builtin_bit_cast(float, (__builtin_bit_cast(uint32_t, w[i]) + 0x00080000u) & 0xfff00000u);
-                    wq[i] = (_Float16)q;
-                    wd[i] = (_Float16)(q > 0.0f ? (w[i] - q) / q : 0.0f);
-                }
-                *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) = wq;
-                *reinterpret_cast<f16x2 *>(s_wd + 2 * lane) = wd;
-            }
-        }
-
-        // carried state -> LDS as fp16 (operand of the C.H product of this chunk)
-#pragma unroll
-        for (int pt = 0; pt < PT; ++pt)
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                f16x4 v;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = (_Float16)st[pt][4 * rg + i];
-                *reinterpret_cast<f16x4 *>(s_hs + (pt * 32 + l32) * kHsStride + 32 * wave + 8 * rg + 4 * hb) = v;
-            }
-
-        // ---- x (fp16 codes times kXs) and B codes into LDS, token-major, token rows permuted ----
-        {
-            const int s0 = 4 * xs4, row0 = tok_pos(s0);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                xvec w = xr[k];
-                if (nv < kQ) {  // partial last chunk: rows past the end are zero
-                    if (s0 + k >= nv) w = (xvec)(0u);
-                }
-                unsigned char *xs_row = s_xs + ((row0 + k) * kXsStride + 4 * PT * xp8) * 2;
-#pragma unroll
-                for (int q = 0; q < PT; ++q) *reinterpret_cast<f16x4 *>(xs_row + 8 * q) = i8x4_to_f16_xs(w[q]);
-            }
-        }
-        {
-            const int row0 = tok_pos(4 * bs4);
+            for (int kk = 0; kk < 4; ++kk)
+                ct[kk] = *reinterpret_cast<const i32x4 *>(cbase + (row * b_row + 16u * (ln >> 5)) + 32 * kk);
+        };
+        issue_c_rows(0);
+        for (int c = 0; c < nchunks; ++c) {
+            const int t0 = c * kQ;
+            const int nv = min(kQ, L - t0);
+            const size_t tokbase = (size_t)b * L + t0;
+            // this wave's output block rotates with the chunk index so that the causal work (tb + 1 block pairs)
+            // evens out over four chunks
+            const int tb = ((wave + c) & (kNBlk - 1)) ^ rot_flip;
+            const int tl = tb * kBlk + l32;  // this lane's token inside the chunk
             if (nv < kQ) {
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (4 * bs4 + k >= nv) br[k] = (u32x4){0u, 0u, 0u, 0u};
+                for (int kk = 0; kk < 4; ++kk) ct[kk] = tl < nv ? ct[kk] : (i32x4){0, 0, 0, 0};
             }
+            // the C rows must have arrived here (the empty asm pins the wait to this point): a wait placed after the
+            // next chunk's loads are issued would wait for those as well
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                *reinterpret_cast<u32x4 *>(s_bq + (row0 + k) * kBqStride + 16 * bn16) = br[k];
-        }
-        // this wave's output block rotates with the chunk index so that the causal work (tb + 1 block pairs)
-        // evens out over four chunks
-        const int tb = ((wave + c) & (kNBlk - 1)) ^ rot_flip;
-        const int tl = tb * kBlk + l32;  // this lane's token inside the chunk
-        i32x4 ct[4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) ct[kk] = cn[kk];
-        if (nv < kQ) {
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) ct[kk] = tl < nv ? ct[kk] : (i32x4){0, 0, 0, 0};
-        }
-        // the C rows must be taken out of their load registers here (the empty asm pins the selects to this point):
-        // a wait placed after the next chunk's loads are issued would wait for those as well
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(ct[kk]));
-        __syncthreads();
+            for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(ct[kk]));
+            __syncthreads();  // the state waves have staged the chunk: x, B, the token weights, the fp16 state
+            // ---- outputs of block tb ----
+            if (tb * kBlk < nv) {
+                // LDS addresses of this phase are rebuilt from a lane index the compiler must treat as new in every
+                // chunk: kept in registers across the whole chunk loop they would push other values into scratch memory
+                int lane_a = fresh_lane();
+                asm volatile("" : "+v"(lane_a));
+                const int l32a = lane_a & 31, hba = lane_a >> 5;
+                // source-lane roles of the transposing loads (see lds_read_tr8 / lds_read_tr16): token row of the lane
+                // inside a k group of 8 tokens, and its first column inside the 32 columns of the operand
+                const int i16 = lane_a & 15, c16 = (lane_a >> 4) & 1;
+                const unsigned char *xs_src =
+                    s_xs + ((8 * hba + (i16 >> 2)) * kXsStride + 16 * c16 + 4 * (i16 & 3)) * 2;
+                const float cum_t = s_cum[tb * kBlk + l32a];
 
-        if (c + 1 < nchunks) issue_loads(c + 1);  // the next chunk's global loads fly while this chunk is computed
+                // B rows of block sb as the A operand of G^T
+                auto load_bq = [&](int sb, i32x4(&bq)[4]) {
+                    const unsigned char *row = s_bq + (sb * kBlk + tok_pos(l32a)) * kBqStride + hba * 16;
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) bq[kk] = *reinterpret_cast<const i32x4 *>(row + 32 * kk);
+                };
+                auto gemm_g = [&](const i32x4(&bq)[4]) {
+                    i32x16 gi;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) gi[r] = 0;
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk)
+                        gi = __builtin_amdgcn_mfma_i32_32x32x32_i8(bq[kk], ct[kk], gi, 0, 0, 0);
+                    return gi;
+                };
+                i32x4 bq[4];
+                load_bq(0, bq);
+                i32x16 gi = gemm_g(bq);
 
-        // ---- outputs of block tb ----
-        if (tb * kBlk < nv) {
-            // LDS addresses of this phase are rebuilt from a lane index the compiler must treat as new in every chunk:
-            // kept in registers across the whole chunk loop they would push other values into scratch memory
-            int lane_a = lane;
-            asm volatile("" : "+v"(lane_a));
-            const int l32a = lane_a & 31, hba = lane_a >> 5;
-            // source-lane roles of the transposing loads (see lds_read_tr8 / lds_read_tr16): token row of the lane
-            // inside a k group of 8 tokens, and its first column inside the 32 columns of the operand
-            const int i16 = lane_a & 15, c16 = (lane_a >> 4) & 1;
-            const unsigned char *xs_src = s_xs + ((8 * hba + (i16 >> 2)) * kXsStride + 16 * c16 + 4 * (i16 & 3)) * 2;
-            const float cum_t = s_cum[tb * kBlk + l32a];
-
-            // B rows of block sb as the A operand of G^T
-            auto load_bq = [&](int sb, i32x4(&bq)[4]) {
-                const unsigned char *row = s_bq + (sb * kBlk + tok_pos(l32a)) * kBqStride + hba * 16;
+                // carried-state term: Y^T[p,t] = sum_n H[p,n] (exp(cum_t) Cq[t,n])
+                f32x16 acc[PT];
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) bq[kk] = *reinterpret_cast<const i32x4 *>(row + 32 * kk);
-            };
-            auto gemm_g = [&](const i32x4(&bq)[4]) {
-                i32x16 gi;
+                for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) gi[r] = 0;
+                    for (int r = 0; r < 16; ++r) acc[pt][r] = 0.0f;
+                // per lane (token t); folded into the C operand
+                const _Float16 e_t = (_Float16)(exp2_fast(cum_t) * kAcc);
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) gi = __builtin_amdgcn_mfma_i32_32x32x32_i8(bq[kk], ct[kk], gi, 0, 0, 0);
-                return gi;
-            };
-            i32x4 bq[4];
-            load_bq(0, bq);
-            i32x16 gi = gemm_g(bq);
-
-            // carried-state term: Y^T[p,t] = sum_n H[p,n] (exp(cum_t) Cq[t,n])
-            f32x16 acc[PT];
+                for (int k2 = 0; k2 < 4; ++k2) {  // batches of two k-steps: all LDS reads of a batch are issued first
+                    f16x8 hf[2][PT];
 #pragma unroll
-            for (int pt = 0; pt < PT; ++pt)
+                    for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[pt][r] = 0.0f;
-            const _Float16 e_t = (_Float16)(exp2_fast(cum_t) * kAcc);  // per lane (token t); folded into the C operand
+                        for (int pt = 0; pt < PT; ++pt)
+                            hf[kk][pt] = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32a) * kHsStride +
+                                                                         32 * k2 +
+                                                                         16 * hba + 8 * kk);
+                    // keep the LDS reads above in flight: nothing may be moved across
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int k2 = 0; k2 < 4; ++k2) {  // batches of two k-steps: all LDS reads of a batch are issued first
-                f16x8 hf[2][PT];
+                    for (int kk = 0; kk < 2; ++kk) {
+                        const int k8 = 2 * k2 + kk;
+                        const i32x4 c4 = ct[k8 >> 1];
+                        const f16x8 cf = i8x8_to_f16((uint32_t)c4[2 * (k8 & 1)], (uint32_t)c4[2 * (k8 & 1) + 1]) * e_t;
 #pragma unroll
-                for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-                        hf[kk][pt] = *reinterpret_cast<const f16x8 *>(s_hs + (pt * 32 + l32a) * kHsStride + 32 * k2 +
-                                                                     16 * hba + 8 * kk);
-                __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above in flight: nothing may be moved across
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const int k8 = 2 * k2 + kk;
-                    const f16x8 cf =
-                        i8x8_to_f16((uint32_t)ct[k8 >> 1][2 * (k8 & 1)], (uint32_t)ct[k8 >> 1][2 * (k8 & 1) + 1]) * e_t;
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[kk][pt], cf, acc[pt], 0, 0, 0);
+                        for (int pt = 0; pt < PT; ++pt)
+                            acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[kk][pt], cf, acc[pt], 0, 0, 0);
+                    }
                 }
-            }
 
-            // intra-chunk term, block pairs (sb <= tb); the G^T tile of the next pair is issued before this one is
-            // scaled and narrowed so that the matrix core and the vector ALU overlap inside the wave
-            for (int sb = 0; sb < tb; ++sb) {  // strictly lower block pairs
-                load_bq(sb + 1, bq);
-                f16x8 xa[2][PT];
+                // intra-chunk term, block pairs (sb <= tb); the G^T tile of the next pair is issued before this one is
+                // scaled and narrowed so that the matrix core and the vector ALU overlap inside the wave
+                for (int sb = 0; sb < tb; ++sb) {  // strictly lower block pairs
+                    load_bq(sb + 1, bq);
+                    f16x8 xa[2][PT];
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
+                    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-                        xa[ks][pt] = lds_read_tr16x8<kXsStride>(xs_src + ((sb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
-                const float m_sb = s_cum[sb * kBlk + kBlk - 1];
-                f16x4 wq4[4];  // weights of tokens 8 rg + 4 hb + [0,4) of block sb
-#pragma unroll
-                for (int rg = 0; rg < 4; ++rg)
-                    wq4[rg] = *reinterpret_cast<const f16x4 *>(s_we + sb * kBlk + 8 * rg + 4 * hba);
-                __builtin_amdgcn_sched_barrier(0);
-                // the current tile is narrowed before the next one is issued, so that both can share registers (the
-                // other wave of the SIMD fills the matrix core meanwhile)
-                const float rowf = exp2_fast(cum_t - m_sb) * kNarrow;
-                float lv[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
-                // narrowed, then times the weights of the lane's 16 tokens of block sb (x is staged without them)
-                const f16x8 l0 = pack_f16x8(lv) * __builtin_shufflevector(wq4[0], wq4[1], 0, 1, 2, 3, 4, 5, 6, 7);
-                const f16x8 l1 = pack_f16x8(lv + 8) * __builtin_shufflevector(wq4[2], wq4[3], 0, 1, 2, 3, 4, 5, 6, 7);
-                __builtin_amdgcn_sched_barrier(0);
-                const i32x16 gn = gemm_g(bq);
-                __builtin_amdgcn_sched_barrier(0);  // the next tile first: its conversion then overlaps the products below
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[ks][pt], ks ? l1 : l0, acc[pt], 0, 0, 0);
-                gi = gn;
-            }
-            {  // diagonal block pair: per-element decay, causal mask, plain x codes
-                f16x8 xd[2][PT];
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-                        xd[ks][pt] = lds_read_tr16x8<kXsStride>(xs_src + ((tb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
-                // R: prefix sum in front of the block, m: at its last token.  When the decay across the block stays below
-                // 2^64 the weight exp2(cum_t - cum_s) dt_s is the product of a row factor and the staged column weights
-                // (both inside the fp32 range); otherwise every element takes its own exponential.
-                const float R = tb > 0 ? s_cum[tb * kBlk - 1] : 0.0f;
-                const float m_tb = s_cum[tb * kBlk + kBlk - 1];
-                const bool factored = __builtin_amdgcn_readfirstlane((R - m_tb) < 64.0f);
-                float lv[16];
-                if (factored) {
-                    f32x4 w4[4];
+                        for (int pt = 0; pt < PT; ++pt)
+                            xa[ks][pt] = lds_read_tr16x8<kXsStride>(
+                                xs_src + ((sb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
+                    const float m_sb = s_cum[sb * kBlk + kBlk - 1];
+                    f16x4 wq4[4];  // weights of tokens 8 rg + 4 hb + [0,4) of block sb
 #pragma unroll
                     for (int rg = 0; rg < 4; ++rg)
-                        w4[rg] = *reinterpret_cast<const f32x4 *>(s_w2 + tb * kBlk + 8 * rg + 4 * hba);
+                        wq4[rg] = *reinterpret_cast<const f16x4 *>(s_we + sb * kBlk + 8 * rg + 4 * hba);
                     __builtin_amdgcn_sched_barrier(0);
-                    const float e_row = exp2_fast(cum_t - R);
+                    // the current tile is narrowed before the next one is issued, so that both can share registers (the
+                    // other wave of the SIMD fills the matrix core meanwhile)
+                    const float rowf = exp2_fast(cum_t - m_sb) * kNarrow;
+                    float lv[16];
 #pragma unroll
-                    for (int rg = 0; rg < 4; ++rg) {
-                        const int s0 = 8 * rg + 4 * hb;
+                    for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
+                    // narrowed, then times the weights of the lane's 16 tokens of block sb (x is staged without them)
+                    const f16x8 l0 = pack_f16x8(lv) * __builtin_shufflevector(wq4[0], wq4[1], 0, 1, 2, 3, 4, 5, 6, 7);
+                    const f16x8 l1 =
+                        pack_f16x8(lv + 8) * __builtin_shufflevector(wq4[2], wq4[3], 0, 1, 2, 3, 4, 5, 6, 7);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const i32x16 gn = gemm_g(bq);
+                    // the next tile first: its conversion then overlaps the products below
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float wgt = (s0 + i <= l32) ? e_row * w4[rg][i] : 0.0f;  // causal mask
-                            float dd = (s0 + i == l32) ? d_sel : 0.0f;  // skip term on the diagonal
-                            asm volatile("" : "+v"(dd));  // selected here, not kept in 16 registers across the chunk loop
-                            lv[4 * rg + i] = fmaf((float)gi[4 * rg + i], wgt, dd);
+                    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                        for (int pt = 0; pt < PT; ++pt)
+                            acc[pt] =
+                                __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[ks][pt], ks ? l1 : l0, acc[pt], 0, 0, 0);
+                    gi = gn;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (c + 1 < nchunks) issue_c_rows(c + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                {  // diagonal block pair: per-element decay, causal mask, plain x codes
+                    f16x8 xd[2][PT];
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                        for (int pt = 0; pt < PT; ++pt)
+                            xd[ks][pt] = lds_read_tr16x8<kXsStride>(
+                                xs_src + ((tb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
+                    // R: prefix sum in front of the block, m: at its last token.  When the decay across the block stays
+                    // below 2^64 the weight exp2(cum_t - cum_s) dt_s is the product of a row factor and the staged
+                    // column weights (both inside the fp32 range); otherwise every element takes its own exponential.
+                    const float R = tb > 0 ? s_cum[tb * kBlk - 1] : 0.0f;
+                    const float m_tb = s_cum[tb * kBlk + kBlk - 1];
+                    const bool factored = __builtin_amdgcn_readfirstlane((R - m_tb) < 64.0f);
+                    // the skip coefficient is made new per chunk for the compiler: the 16 selects below then stay here
+                    // (lane masks in scalar registers) instead of 16 loop-invariant vector registers
+                    float d_sel_c = d_sel;
+                    asm volatile("" : "+v"(d_sel_c));
+                    // four tokens s at a time, narrowed at once: the scheduling barriers keep the register groups apart
+                    // so that at most one group's temporaries are live
+                    f16x4 lq[4];
+                    if (factored) {
+                        const float e_row = exp2_fast(cum_t - R);
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg) {
+                            const int s0 = 8 * rg + 4 * hb;
+                            const f32x4 w4 = *reinterpret_cast<const f32x4 *>(s_w2 + tb * kBlk + 8 * rg + 4 * hba);
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const float wgt = (s0 + i <= l32) ? e_row * w4[i] : 0.0f;  // causal mask
+                                const float dd = (s0 + i == l32) ? d_sel_c : 0.0f;        // skip term on the diagonal
+                                lq[rg][i] = (_Float16)fmaf((float)gi[4 * rg + i], wgt, dd);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    } else {
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg) {  // four consecutive tokens of the block per register group
+                            const int s0 = 8 * rg + 4 * hb;
+                            const f32x4 cs4 = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + 8 * rg + 4 * hba);
+                            const f32x4 ds4 = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + 8 * rg + 4 * hba);
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                // exponent forced to a huge negative value above the diagonal: weight exactly 0, no
+                                // branch cum is non-increasing (dt >= 0, A <= 0): the exponent is <= 0 on and below the
+                                // diagonal
+                                const float arg = (s0 + i <= l32) ? cum_t - cs4[i] : -1.0e30f;
+                                const float dd = (s0 + i == l32) ? d_sel_c : 0.0f;  // skip term on the diagonal
+                                lq[rg][i] = (_Float16)fmaf((float)gi[4 * rg + i], exp2_fast(arg) * ds4[i], dd);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                    const f16x8 l0 = __builtin_shufflevector(lq[0], lq[1], 0, 1, 2, 3, 4, 5, 6, 7);
+                    const f16x8 l1 = __builtin_shufflevector(lq[2], lq[3], 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                        for (int pt = 0; pt < PT; ++pt)
+                            acc[pt] =
+                                __builtin_amdgcn_mfma_f32_32x32x16_f16(xd[ks][pt], ks ? l1 : l0, acc[pt], 0, 0, 0);
+                }
+
+                // epilogue: scales and skip term in fp32, narrowing to fp16; a lane holds 4 consecutive channels of
+                // token t per register group, and one exchange with the lane 32 positions away (same token) turns two
+                // such groups into 8 consecutive channels, so that every lane stores 16 bytes and a token row gets 32
+                uint16_t *yrow = a.y + ((tokbase + min(tl, nv - 1)) * H + h) * kP + p_base;
+                if (d_by_mfma) {
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt) {
+                        f32x4 k4[4];  // s_x(h,p) * y_scale of the lane's 16 channels of this p tile
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg)
+                            k4[rg] = *reinterpret_cast<const f32x4 *>(s_sx + pt * 32 + 8 * rg + 4 * hba);
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            uint32_t w[2][2];  // [register group 2j, 2j+1][dword]
+#pragma unroll
+                            for (int e = 0; e < 2; ++e) {
+                                const int rg = 2 * j + e;
+                                f16x4 o;
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) o[i] = (_Float16)(k4[rg][i] * acc[pt][4 * rg + i]);
+                                const u32x2 ow = __builtin_bit_cast(u32x2, o);
+                                w[e][0] = ow[0];
+                                w[e][1] = ow[1];
+                            }
+                            // lanes 0..31 end up with group 2j of both half-waves (channels 16j .. 16j+7 of this p
+                            // tile), lanes 32..63 with group 2j+1 (channels 16j+8 .. 16j+15)
+                            const auto s0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                            const auto s1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                            const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
+                            if (tl < nv) *reinterpret_cast<u32x4 *>(yrow + pt * 32 + 16 * j + 8 * hb) = v;
                         }
                     }
                 } else {
-                    f32x4 cs4[4], ds4[4];
-#pragma unroll
-                    for (int rg = 0; rg < 4; ++rg) {  // four consecutive tokens of the block per register group
-                        cs4[rg] = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + 8 * rg + 4 * hba);
-                        ds4[rg] = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + 8 * rg + 4 * hba);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int rg = 0; rg < 4; ++rg) {
-                        const int s0 = 8 * rg + 4 * hb;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            // exponent forced to a huge negative value above the diagonal: weight exactly 0, no branch
-                            // cum is non-increasing (dt >= 0, A <= 0): the exponent is <= 0 on and below the diagonal
-                            const float arg = (s0 + i <= l32) ? cum_t - cs4[rg][i] : -1.0e30f;
-                            float dd = (s0 + i == l32) ? d_sel : 0.0f;  // skip term on the diagonal
-                            asm volatile("" : "+v"(dd));  // selected here, not kept in 16 registers across the chunk loop
-                            lv[4 * rg + i] =
-                                fmaf((float)gi[4 * rg + i], exp2_fast(arg) * ds4[rg][i], dd);
-                        }
-                    }
-                }
-                const f16x8 l0 = pack_f16x8(lv), l1 = pack_f16x8(lv + 8);
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
+                    const int tq = tok_pos(tl);
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt)
-                        acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xd[ks][pt], ks ? l1 : l0, acc[pt], 0, 0, 0);
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            uint32_t w[2][2];
+#pragma unroll
+                            for (int e = 0; e < 2; ++e) {
+                                const int rg = 2 * j + e;
+                                f16x4 o;
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) {
+                                    const int p = pt * 32 + 8 * rg + 4 * hb + i;
+                                    const _Float16 *xrow = reinterpret_cast<const _Float16 *>(s_xs) + tq * kXsStride;
+                                    const float xc = (float)xrow[p] * (1.0f / kXs);
+                                    o[i] = (_Float16)(s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc));
+                                }
+                                const u32x2 ow = __builtin_bit_cast(u32x2, o);
+                                w[e][0] = ow[0];
+                                w[e][1] = ow[1];
+                            }
+                            const auto s0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                            const auto s1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                            const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
+                            if (tl < nv) *reinterpret_cast<u32x4 *>(yrow + pt * 32 + 16 * j + 8 * hb) = v;
+                        }
+                }
             }
 
-            // epilogue: scales and skip term in fp32, narrowing to fp16; a lane holds 4 consecutive channels of token
-            // t per register group, and one exchange with the lane 32 positions away (same token) turns two such
-            // groups into 8 consecutive channels, so that every lane stores 16 bytes and a token row gets 32
-            uint16_t *yrow = a.y + ((tokbase + min(tl, nv - 1)) * H + h) * kP + p_base;
-            if (d_by_mfma) {
+            else if (c + 1 < nchunks) issue_c_rows(c + 1);
+            __syncthreads();  // both roles are done with the chunk's LDS arrays
+        }
+    } else {
+        // ================= state waves: staging, token weights, state update ================= Carried state in x-code
+        // * B-code units times kStScale (true state = s_x(p) s_B * st / kStScale): the state is carried already
+        // narrowed by 2^-7, so that its fp16 copy for the C.H product needs no multiply (the factor rides on the token
+        // weights of the B operand instead).  Wave w owns states n in [32w, 32w+32); st[pt][r]: p = 32 pt + l32, n = 32
+        // w + 8 (r/4) + 4 hb + r%4.
+        f32x16 st[PT];
 #pragma unroll
-                for (int pt = 0; pt < PT; ++pt) {
-                    f32x4 k4[4];  // s_x(h,p) * y_scale of the lane's 16 channels of this p tile
+        for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
-                    for (int rg = 0; rg < 4; ++rg)
-                        k4[rg] = *reinterpret_cast<const f32x4 *>(s_sx + pt * 32 + 8 * rg + 4 * hba);
+            for (int r = 0; r < 16; ++r) st[pt][r] = 0.0f;
+        if (a.init_state) {
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        uint32_t w[2][2];  // [register group 2j, 2j+1][dword]
+            for (int pt = 0; pt < PT; ++pt) {
+                const int p = pt * 32 + l32;
+                const float inv = kStScale * (d_by_mfma ? y_scale : 1.0f) / (s_sx[p] * sB);
 #pragma unroll
-                        for (int e = 0; e < 2; ++e) {
-                            const int rg = 2 * j + e;
-                            f16x4 o;
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int n0 = 32 * wave + 8 * rg + 4 * hb;
+                    const f32x4 v =
+                        *reinterpret_cast<const f32x4 *>(a.init_state + ((size_t)bh * kP + p_base + p) * kN + n0);
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) o[i] = (_Float16)(k4[rg][i] * acc[pt][4 * rg + i]);
-                            const u32x2 ow = __builtin_bit_cast(u32x2, o);
-                            w[e][0] = ow[0];
-                            w[e][1] = ow[1];
+                    for (int i = 0; i < 4; ++i) st[pt][4 * rg + i] = v[i] * inv;
+                }
+            }
+        }
+
+
+        // Registers that carry one chunk's global loads from the point of issue (the start of the previous chunk's
+        // state update) to the staging phase: x codes (4 tokens x 4 PT channels), B codes (4 tokens x 16 states), and
+        // dt of tokens 2 lane, 2 lane + 1 (first wave only: it computes every weight of the chunk).  Rows past the end
+        // of the sequence are read from the last valid row and zeroed where they are consumed.  Vector-memory results
+        // return in issue order, hence the loads are issued in the order they are consumed.
+        xvec xr[4];
+        u32x4 br[4];
+        float dt0 = 0.0f, dt1 = 0.0f;
+        // Staging lane maps: a thread takes 4 consecutive tokens and 4 PT channels of x (8 lanes cover a row of this
+        // workgroup's channels), resp. 16 states of B (8 lanes cover a 128-byte row).
+        const int xs4 = tid4 >> 3, xp8 = tid4 & 7;
+        const int bs4 = tid4 >> 3, bn16 = tid4 & 7;
+        auto issue_loads = [&](int c) {
+            const int t0 = c * kQ;
+            const int nv = min(kQ, L - t0);
+            const size_t tokbase = (size_t)b * L + t0;
+            const int8_t *xbase = a.x + (tokbase * H + h) * kP + p_base;
+            const int8_t *bbase = a.B + (tokbase * G + g) * kN;
+            const char *dbase = reinterpret_cast<const char *>(a.dt + tokbase * H + h);
+            if (wave == 0) {
+                dt0 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane, nv - 1) * dt_row);
+                dt1 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane + 1, nv - 1) * dt_row);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t row = (uint32_t)min(4 * xs4 + k, nv - 1);
+                xr[k] = *reinterpret_cast<const xvec *>(xbase + (row * x_row + (uint32_t)(4 * PT) * xp8));
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t row = (uint32_t)min(4 * bs4 + k, nv - 1);
+                br[k] = *reinterpret_cast<const u32x4 *>(bbase + (row * b_row + 16u * bn16));
+            }
+        };
+        issue_loads(0);
+        for (int c = 0; c < nchunks; ++c) {
+            const int t0 = c * kQ;
+            const int nv = min(kQ, L - t0);
+            // ---- the first wave turns dt into everything the chunk needs of it: the inclusive prefix sum of dt*A
+            // (two tokens per lane, data-parallel-primitive moves only) and, per token s, the weights that stand
+            // between the x codes and their uses.  With m the prefix sum at the last token of the token's 32-token
+            // block, R the one in front of the block, cum_last the one at the end of the chunk:
+            //   we = dt exp2(m - cum_s) kAcc / kXs          off-diagonal blocks (row factor exp2(cum_t - m) 2^-7)
+            //   w2 = dt exp2(R - cum_s) 2^-7 kAcc / kXs     diagonal block (row factor exp2(cum_t - R))
+            //   ws = dt exp2(cum_last - cum_s) 2^-7 / kXs   state update of the single-term path
+            //   two-term path: the state decays block by block in fp32, its token weight dt exp2(m - cum_s) 2^-7 /
+            //   kXs is wq (1 + wd) with wq rounded to 4 significant bits, so that B codes (7 bits) times wq are exact
+            //   in fp16: ws = wq, wd
+            // All exponents are <= 0 except in w2, which may overflow under extreme decay (it is not used then). ----
+            if (wave == 0) {
+                if (2 * lane >= nv) dt0 = 0.0f;  // padded steps: dt = 0
+                if (2 * lane + 1 >= nv) dt1 = 0.0f;
+                const float a0 = dt0 * Ah, a1 = dt1 * Ah;
+                const float cum1 = wave_inclusive_scan(a0 + a1), cum0 = cum1 - a1;
+                const float m = __shfl(cum1, lane | 15, 64);
+                const float rb = __shfl(cum1, (lane & ~15) - 1, 64);
+                const float R = lane >= 16 ? rb : 0.0f;
+                // weights towards the output accumulators
+                const float d0 = dt0 * (kAcc / kXs), d1 = dt1 * (kAcc / kXs);
+                // weights towards the state accumulators
+                const float q0 = dt0 * (kNarrow / kXs), q1 = dt1 * (kNarrow / kXs);
+                const float e0 = exp2_fast(m - cum0), e1 = exp2_fast(m - cum1);
+                const float we0 = e0 * d0, we1 = e1 * d1;
+                *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
+                *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(d0 * kNarrow, d1 * kNarrow);
+                *reinterpret_cast<float2 *>(s_w2 + 2 * lane) =
+                    make_float2(exp2_fast(R - cum0) * d0 * kNarrow, exp2_fast(R - cum1) * d1 * kNarrow);
+                *reinterpret_cast<f16x2 *>(s_we + 2 * lane) = (f16x2){(_Float16)we0, (_Float16)we1};
+                if (!PRECISE) {
+                    const float cum_last =
+                        __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cum1), 63));
+                    *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) = (f16x2){(_Float16)(exp2_fast(cum_last - cum0) * q0),
+                                                                          (_Float16)(exp2_fast(cum_last - cum1) * q1)};
+                } else {
+                    f16x2 wq, wd;
+                    const float w[2] = {e0 * q0, e1 * q1};
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const float q =
+                            __builtin_bit_cast(float, (__builtin_bit_cast(uint32_t, w[i]) + 0x00080000u) & 0xfff00000u);
+                        wq[i] = (_Float16)q;
+                        wd[i] = (_Float16)(q > 0.0f ? (w[i] - q) / q : 0.0f);
+                    }
+                    *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) = wq;
+                    *reinterpret_cast<f16x2 *>(s_wd + 2 * lane) = wd;
+                }
+            }
+
+            // carried state -> LDS as fp16 (operand of the C.H product of this chunk)
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    f16x4 v;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = (_Float16)st[pt][4 * rg + i];
+                    *reinterpret_cast<f16x4 *>(s_hs + (pt * 32 + l32) * kHsStride + 32 * wave + 8 * rg + 4 * hb) = v;
+                }
+
+            // ---- x (fp16 codes times kXs) and B codes into LDS, token-major, token rows permuted ----
+            {
+                const int s0 = 4 * xs4, row0 = tok_pos(s0);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    xvec w = xr[k];
+                    if (nv < kQ) {  // partial last chunk: rows past the end are zero
+                        if (s0 + k >= nv) w = (xvec)(0u);
+                    }
+                    unsigned char *xs_row = s_xs + ((row0 + k) * kXsStride + 4 * PT * xp8) * 2;
+#pragma unroll
+                    for (int q = 0; q < PT; ++q) *reinterpret_cast<f16x4 *>(xs_row + 8 * q) = i8x4_to_f16_xs(w[q]);
+                }
+            }
+            {
+                const int row0 = tok_pos(4 * bs4);
+                if (nv < kQ) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (4 * bs4 + k >= nv) br[k] = (u32x4){0u, 0u, 0u, 0u};
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    *reinterpret_cast<u32x4 *>(s_bq + (row0 + k) * kBqStride + 16 * bn16) = br[k];
+            }
+            __syncthreads();  // the chunk is staged: the output waves start on it
+            if (c + 1 < nchunks) issue_loads(c + 1);  // the next chunk's global loads fly while this chunk is computed
+            // ---- state update: wave w owns states n in [32w, 32w+32) ----
+            // source-lane roles of the transposing loads, rebuilt per chunk like the addresses of the output phase
+            int lane_s = fresh_lane();
+            asm volatile("" : "+v"(lane_s));
+            const int i16s = lane_s & 15, c16s = (lane_s >> 4) & 1, hbs = lane_s >> 5;
+            const unsigned char *bq_src =
+                s_bq + (8 * hbs + (i16s >> 1)) * kBqStride + 32 * wave + 16 * c16s + 8 * (i16s & 1);
+            const int xs_off = ((8 * hbs + (i16s >> 2)) * kXsStride + 16 * c16s + 4 * (i16s & 3)) * 2;
+            if (PRECISE) {
+                float m_prev = 0.0f;
+                for (int sb = 0; sb < kNBlk; ++sb) {
+                    if (sb * kBlk >= nv) break;  // the padded steps are identity steps
+                    const float m = s_cum[sb * kBlk + kBlk - 1];
+                    const float gdec = exp2_fast(m - m_prev);
+                    m_prev = m;
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const int row = sb * kBlk + 16 * ks;
+                        const u32x2 w = lds_read_tr8(bq_src + row * kBqStride);
+                        // weights of the 8 tokens of this k group: tokens row + 4 hb + [0,4) and row + 8 + 4 hb + [0,4)
+                        const f16x4 *ws4 = reinterpret_cast<const f16x4 *>(s_ws + row + 4 * hbs);
+                        const f16x4 *wd4 = reinterpret_cast<const f16x4 *>(s_wd + row + 4 * hbs);
+                        const f16x8 wq = __builtin_shufflevector(ws4[0], ws4[2], 0, 1, 2, 3, 4, 5, 6, 7);
+                        const f16x8 wd = __builtin_shufflevector(wd4[0], wd4[2], 0, 1, 2, 3, 4, 5, 6, 7);
+                        const f16x8 bf = i8x8_to_f16(w[0], w[1]) * wq;  // exact: 7 bits times 4 bits
+                        const f16x8 bfd = bf * wd;                      // the small term, rounded
+#pragma unroll
+                        for (int pt = 0; pt < PT; ++pt) {
+                            const int off = xs_off + (row * kXsStride + 32 * pt) * 2;
+                            const f16x8 xb = lds_read_tr16x8<kXsStride>(s_xs + off);
+                            st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb, st[pt], 0, 0, 0);
+                            st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bfd, xb, st[pt], 0, 0, 0);
                         }
-                        // lanes 0..31 end up with group 2j of both half-waves (channels 16j .. 16j+7 of this p
-                        // tile), lanes 32..63 with group 2j+1 (channels 16j+8 .. 16j+15)
-                        const auto s0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
-                        const auto s1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
-                        const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
-                        if (tl < nv) *reinterpret_cast<u32x4 *>(yrow + pt * 32 + 16 * j + 8 * hb) = v;
                     }
                 }
             } else {
-                const int tq = tok_pos(tl);
+                {
+                    // padded steps leave cum flat: cum at the last valid token
+                    const float gdec = exp2_fast(s_cum[kQ - 1]);
 #pragma unroll
-                for (int pt = 0; pt < PT; ++pt)
+                    for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        uint32_t w[2][2];
+                        for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
+                }
 #pragma unroll
-                        for (int e = 0; e < 2; ++e) {
-                            const int rg = 2 * j + e;
-                            f16x4 o;
+                // blocks past the end hold zero weights (dt = 0): they add nothing
+                for (int sb = 0; sb < kNBlk; ++sb) {
+                    u32x2 bw[2];
+                    f16x8 xb[2][PT], wv[2];
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                const int p = pt * 32 + 8 * rg + 4 * hb + i;
-                                const float xc =
-                                    (float)reinterpret_cast<const _Float16 *>(s_xs)[tq * kXsStride + p] * (1.0f / kXs);
-                                o[i] = (_Float16)(s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc));
-                            }
-                            const u32x2 ow = __builtin_bit_cast(u32x2, o);
-                            w[e][0] = ow[0];
-                            w[e][1] = ow[1];
-                        }
-                        const auto s0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
-                        const auto s1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
-                        const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
-                        if (tl < nv) *reinterpret_cast<u32x4 *>(yrow + pt * 32 + 16 * j + 8 * hb) = v;
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const int row = sb * kBlk + 16 * ks;
+                        bw[ks] = lds_read_tr8(bq_src + row * kBqStride);
+                        // weights of the 8 tokens of this k group: tokens row + 4 hb + [0,4) and row + 8 + 4 hb + [0,4)
+                        wv[ks] = __builtin_shufflevector(*reinterpret_cast<const f16x4 *>(s_ws + row + 4 * hbs),
+                                                         *reinterpret_cast<const f16x4 *>(s_ws + row + 8 + 4 * hbs),
+                                                         0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                        for (int pt = 0; pt < PT; ++pt)
+                            xb[ks][pt] = lds_read_tr16x8<kXsStride>(s_xs + xs_off + (row * kXsStride + 32 * pt) * 2);
                     }
-            }
-        }
-
-        if (PRECISE && c + 1 < nchunks) issue_c_loads(c + 1);
-
-        // ---- state update: wave w owns states n in [32w, 32w+32) ----
-        // source-lane roles of the transposing loads, rebuilt per chunk like the addresses of the output phase
-        int lane_s = lane;
-        asm volatile("" : "+v"(lane_s));
-        const int i16s = lane_s & 15, c16s = (lane_s >> 4) & 1, hbs = lane_s >> 5;
-        const unsigned char *bq_src = s_bq + (8 * hbs + (i16s >> 1)) * kBqStride + 32 * wave + 16 * c16s + 8 * (i16s & 1);
-        const int xs_off = ((8 * hbs + (i16s >> 2)) * kXsStride + 16 * c16s + 4 * (i16s & 3)) * 2;
-        if (PRECISE) {
-            float m_prev = 0.0f;
-            for (int sb = 0; sb < kNBlk; ++sb) {
-                if (sb * kBlk >= nv) break;  // the padded steps are identity steps
-                const float m = s_cum[sb * kBlk + kBlk - 1];
-                const float gdec = exp2_fast(m - m_prev);
-                m_prev = m;
+                    // all LDS reads of the block are in flight before the first conversion
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int pt = 0; pt < PT; ++pt)
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const f16x8 bf = i8x8_to_f16(bw[ks][0], bw[ks][1]) * wv[ks];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    const int row = sb * kBlk + 16 * ks;
-                    const u32x2 w = lds_read_tr8(bq_src + row * kBqStride);
-                    // weights of the 8 tokens of this k group: tokens row + 4 hb + [0,4) and row + 8 + 4 hb + [0,4)
-                    const f16x8 wq = __builtin_shufflevector(*reinterpret_cast<const f16x4 *>(s_ws + row + 4 * hbs),
-                                                             *reinterpret_cast<const f16x4 *>(s_ws + row + 8 + 4 * hbs),
-                                                             0, 1, 2, 3, 4, 5, 6, 7);
-                    const f16x8 wd = __builtin_shufflevector(*reinterpret_cast<const f16x4 *>(s_wd + row + 4 * hbs),
-                                                             *reinterpret_cast<const f16x4 *>(s_wd + row + 8 + 4 * hbs),
-                                                             0, 1, 2, 3, 4, 5, 6, 7);
-                    const f16x8 bf = i8x8_to_f16(w[0], w[1]) * wq;  // exact: 7 bits times 4 bits
-                    const f16x8 bfd = bf * wd;                      // the small term, rounded
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt) {
-                        const int off = xs_off + (row * kXsStride + 32 * pt) * 2;
-                        const f16x8 xb = lds_read_tr16x8<kXsStride>(s_xs + off);
-                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb, st[pt], 0, 0, 0);
-                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bfd, xb, st[pt], 0, 0, 0);
+                        for (int pt = 0; pt < PT; ++pt)
+                            st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb[ks][pt], st[pt], 0, 0, 0);
                     }
                 }
             }
-        } else {
-            {
-                const float gdec = exp2_fast(s_cum[kQ - 1]);  // padded steps leave cum flat: cum at the last valid token
+            __syncthreads();  // the output waves are done with x, B, the weights and the fp16 state of this chunk
+        }
+
+        if (a.state) {
 #pragma unroll
-                for (int pt = 0; pt < PT; ++pt)
+            for (int pt = 0; pt < PT; ++pt) {
+                const int p = pt * 32 + l32;
+                const float sc = s_sx[p] * sB / ((d_by_mfma ? y_scale : 1.0f) * kStScale);
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
-            }
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int n0 = 32 * wave + 8 * rg + 4 * hb;
+                    f32x4 v;
 #pragma unroll
-            for (int sb = 0; sb < kNBlk; ++sb) {  // blocks past the end hold zero weights (dt = 0): they add nothing
-                u32x2 bw[2];
-                f16x8 xb[2][PT], wv[2];
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    const int row = sb * kBlk + 16 * ks;
-                    bw[ks] = lds_read_tr8(bq_src + row * kBqStride);
-                    // weights of the 8 tokens of this k group: tokens row + 4 hb + [0,4) and row + 8 + 4 hb + [0,4)
-                    wv[ks] = __builtin_shufflevector(*reinterpret_cast<const f16x4 *>(s_ws + row + 4 * hbs),
-                                                     *reinterpret_cast<const f16x4 *>(s_ws + row + 8 + 4 * hbs),
-                                                     0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-                        xb[ks][pt] = lds_read_tr16x8<kXsStride>(s_xs + xs_off + (row * kXsStride + 32 * pt) * 2);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                if (c + 1 < nchunks) issue_b_load(c + 1, sb);  // staging consumes B first, and loads return in order
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    const f16x8 bf = i8x8_to_f16(bw[ks][0], bw[ks][1]) * wv[ks];
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, xb[ks][pt], st[pt], 0, 0, 0);
+                    for (int i = 0; i < 4; ++i) v[i] = st[pt][4 * rg + i] * sc;
+                    *reinterpret_cast<f32x4 *>(a.state + ((size_t)bh * kP + p_base + p) * kN + n0) = v;
                 }
             }
-            if (c + 1 < nchunks) {
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) issue_cn_load(c + 1, kk);
-            }
         }
-        __syncthreads();
-    }
-
-    if (a.state) {
-#pragma unroll
-        for (int pt = 0; pt < PT; ++pt) {
-            const int p = pt * 32 + l32;
-            const float sc = s_sx[p] * sB / ((d_by_mfma ? y_scale : 1.0f) * kStScale);
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                const int n0 = 32 * wave + 8 * rg + 4 * hb;
-                f32x4 v;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = st[pt][4 * rg + i] * sc;
-                *reinterpret_cast<f32x4 *>(a.state + ((size_t)bh * kP + p_base + p) * kN + n0) = v;
-            }
         }
     }
-}
 
-}  // namespace
+    }  // namespace
 
-bool prefill_mfma_supports(const quamba_ssd_shape_t &s) { return s.headdim == kP && s.d_state == kN; }
+    bool prefill_mfma_supports(const quamba_ssd_shape_t &s) { return s.headdim == kP && s.d_state == kN; }
 
-namespace {
+    namespace {
 
-template <bool PRECISE, int PT>
-hipError_t launch_scan(const SsdArgs &a, hipStream_t stream)
-{
-    constexpr int lds = Lds<PT>::kBytes;
-    const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT)));
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_mfma_kernel<PRECISE, PT>), grid, dim3(kThreads), lds, stream, a);
-    return hipGetLastError();
-}
+    template <bool PRECISE, int PT>
+    hipError_t launch_scan(const SsdArgs &a, hipStream_t stream)
+    {
+        constexpr int lds = Lds<PT>::kBytes;
+        const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT)));
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((prefill_mfma_kernel<PRECISE, PT>), grid, dim3(kThreads), lds, stream, a);
+        return hipGetLastError();
+    }
 
-// Compute units of the current device (cached per device id).
-int compute_units()
-{
-    static int cached[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+    // Compute units of the current device (cached per device id).
+    int compute_units()
+    {
+        static int cached[64];
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+        if (cached[dev] == 0) {
+            int n = 0;
+            if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+            cached[dev] = n;
     }
     return cached[dev];
 }
