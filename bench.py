@@ -34,7 +34,7 @@ MFMA_I8_PEAK_TOPS = 5000.0     # dense int8
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, each scaled by its reading for a plain
 # 256 MiB device copy in the same run: factors 1.9998 and 1.0000); profiles/hbm_traffic_prefill_m2_8b_b4_and_decode_m2_8b.txt.
 # None for workloads that were not profiled.
-MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 453.3e6, "m2_8b_decode": 2162.2e6}
+MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 493.8e6, "m2_8b_decode": 2162.2e6}
 
 
 def prefill_algorithmic(s: W.LayerShape):
