@@ -119,6 +119,52 @@ int quamba_ssd_decode_step(const quamba_ssd_shape_t *shape, const quamba_ssd_sca
                            float *state, uint16_t *y, void *hip_stream);
 
 /*
+ * The same decode step on an 8-BIT CACHED STATE (Appendix E, "Quantizing cached SSM states"): the state is cached as
+ * int8 codes whose scales reuse the m x n (head cluster, channel range) cells of x and differ per state, i.e.
+ * d_state x m x n scales per state group.  One step de-quantizes the state (inverse of Eq. 1), applies Eq. 2, forms y
+ * from the updated state, and re-quantizes the state (Eq. 1) in place.
+ *   state_scales device fp32 [ngroups*m*n, d_state], all > 0 (quamba_state_scales produces them)
+ *   state_q      device int8 [batch, nheads, headdim, d_state], read and overwritten IN PLACE
+ *   everything else as in quamba_ssd_decode_step; dt >= 0 and A <= 0 are required (the decay is computed for
+ *   dt*A <= 0 only).
+ * The new code is decided in fp32, every operation rounded to nearest even on its own, in this order:
+ *   xv = s_x(h,p)*x;  dtx = dt*xv;  Bv = s_B[g]*B[n];  u = dtx*Bv;  hp = s[cell,n]*code;  d = dA*hp;  hn = d + u;
+ *   r = hn*(1/s[cell,n]);  code' = clamp(rint(r), -127, 127)   with ties to even,
+ * where dA = exp(dt*A) is evaluated as t = (dt*A)*log2(e) (fp32 constant 0x3FB8AA3B), k = rint(t), f = t - k,
+ * 2^f by Horner's rule on the fp32-rounded coefficients (ln 2)^i / i!, i = 7..0 (multiply and add rounded
+ * separately), times 2^k; 0 when t < -125.  y = sum_n (s_C[g]*C[n])*hn + D*xv in fp32, rounded to fp16.
+ * Errors: ENULL, ESHAPE, EHIP.
+ */
+int quamba_ssd_decode_step_q8(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                              const float *state_scales, const int8_t *x, const int8_t *B, const int8_t *C,
+                              const float *dt, const float *A, const float *D, int8_t *state_q, uint16_t *y,
+                              void *hip_stream);
+
+/*
+ * Eq. 1 on a device fp32 state with the scales of the cached state (what a prefill's final state goes through before
+ * it is cached in 8 bits): state_q = clamp(rint(state * (1/s[cell,n])), -127, 127), the reciprocal and the product
+ * rounded to fp32 one after the other, ties to even.
+ *   state device fp32 [batch, nheads, headdim, d_state]   state_q device int8, same shape (must not overlap state)
+ * Errors: ENULL, ESHAPE, EHIP.
+ */
+int quamba_ssd_quantize_state(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                              const float *state_scales, const float *state, int8_t *state_q, void *hip_stream);
+
+/*
+ * Static scales of the 8-bit cached state from calibrated maxima (absolute-maximum calibration, Appendix C,
+ * "Quantization setup"; cells of Appendix E).  HOST function, all pointers host memory.
+ *   head_cluster_end [ngroups*m], chan_cluster_end [ngroups*m*n]: as in quamba_ssd_scales_t
+ *   state_calib_absmax [nheads*headdim*d_state]: calibrated max |h| per state element, heads and channels in the
+ *                      reordered order
+ *   state_scales [ngroups*m*n*d_state] (written): (max over the heads and channel positions of the cell) / 127,
+ *                      1.0 for an empty or all-zero cell
+ * Errors: ENULL, ESHAPE, EINVAL (negative or non-finite maxima, boundaries out of range or decreasing).
+ */
+int quamba_state_scales(int32_t nheads, int32_t headdim, int32_t ngroups, int32_t m, int32_t n, int32_t d_state,
+                        const int32_t *head_cluster_end, const int32_t *chan_cluster_end,
+                        const float *state_calib_absmax, float *state_scales);
+
+/*
  * Offline sort-and-cluster (Section 4.1) and the index tables for cluster-aware weight reordering (Section 4.2).
  * HOST function, all pointers host memory.
  *   x_calib_absmax [nheads*headdim]  calibrated per-channel max|x| in the model's original order

@@ -16,6 +16,7 @@ FLAG_PRECISE_STATE = 0x2
 FLAG_NO_CHANNEL_SPLIT = 0x4
 
 EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "quamba_ssd_decode_step",
+                    "quamba_ssd_decode_step_q8", "quamba_ssd_quantize_state", "quamba_state_scales",
                     "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x",
                     "quamba_quantize_groups", "quamba_strerror")
 
@@ -59,6 +60,12 @@ def load_library():
             [C.c_size_t, C.c_void_p]
         lib.quamba_ssd_decode_step.restype = C.c_int
         lib.quamba_ssd_decode_step.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 9
+        lib.quamba_ssd_decode_step_q8.restype = C.c_int
+        lib.quamba_ssd_decode_step_q8.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 10
+        lib.quamba_ssd_quantize_state.restype = C.c_int
+        lib.quamba_ssd_quantize_state.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 4
+        lib.quamba_state_scales.restype = C.c_int
+        lib.quamba_state_scales.argtypes = [C.c_int32] * 6 + [C.c_void_p] * 4
         lib.quamba_reorder_params.restype = C.c_int
         lib.quamba_reorder_params.argtypes = [C.c_int32] * 5 + [C.c_uint64, C.c_int32] + [C.c_void_p] * 10
         lib.quamba_gather_rows.restype = C.c_int
@@ -170,6 +177,56 @@ def quamba_ssd_decode_step(shape: Shape, scales, x, B, Cm, dt, A, D, state, y, s
         _dp(y, torch.float16, (s.batch, s.nheads, s.headdim), "y"), _stream_ptr(stream))
     if rc != 0:
         raise QuambaError(rc, "quamba_ssd_decode_step")
+
+
+def quamba_ssd_decode_step_q8(shape: Shape, scales, state_scales, x, B, Cm, dt, A, D, state_q, y, stream=None) -> None:
+    """Enqueue one decode step on the 8-bit cached state; `state_q` (int8) is updated in place."""
+    import torch
+    s = shape
+    sc = scales.struct()
+    ncell = s.ngroups * s.n_head_clusters * s.n_chan_clusters
+    rc = load_library().quamba_ssd_decode_step_q8(
+        C.byref(s), C.byref(sc), _dp(state_scales, torch.float32, (ncell, s.d_state), "state_scales"),
+        _dp(x, torch.int8, (s.batch, s.nheads, s.headdim), "x"),
+        _dp(B, torch.int8, (s.batch, s.ngroups, s.d_state), "B"),
+        _dp(Cm, torch.int8, (s.batch, s.ngroups, s.d_state), "C"),
+        _dp(dt, torch.float32, (s.batch, s.nheads), "dt"),
+        _dp(A, torch.float32, (s.nheads,), "A"), _dp(D, torch.float32, (s.nheads,), "D"),
+        _dp(state_q, torch.int8, (s.batch, s.nheads, s.headdim, s.d_state), "state_q"),
+        _dp(y, torch.float16, (s.batch, s.nheads, s.headdim), "y"), _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_ssd_decode_step_q8")
+
+
+def quamba_ssd_quantize_state(shape: Shape, scales, state_scales, state, state_q, stream=None) -> None:
+    """Enqueue Eq. 1 on an fp32 device state with the scales of the 8-bit cache."""
+    import torch
+    s = shape
+    sc = scales.struct()
+    ncell = s.ngroups * s.n_head_clusters * s.n_chan_clusters
+    st_shape = (s.batch, s.nheads, s.headdim, s.d_state)
+    rc = load_library().quamba_ssd_quantize_state(
+        C.byref(s), C.byref(sc), _dp(state_scales, torch.float32, (ncell, s.d_state), "state_scales"),
+        _dp(state, torch.float32, st_shape, "state"), _dp(state_q, torch.int8, st_shape, "state_q"),
+        _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_ssd_quantize_state")
+
+
+def quamba_state_scales(nheads, headdim, ngroups, m, n, d_state, head_cluster_end, chan_cluster_end,
+                        state_calib_absmax) -> np.ndarray:
+    """Static scales of the 8-bit cached state from calibrated maxima [H,P,N] (host).  Returns [G*m*n, N] float32."""
+    he = np.ascontiguousarray(head_cluster_end, np.int32).reshape(-1)
+    ce = np.ascontiguousarray(chan_cluster_end, np.int32).reshape(-1)
+    mx = np.ascontiguousarray(state_calib_absmax, np.float32).reshape(-1)
+    if he.size != ngroups * m or ce.size != ngroups * m * n or mx.size != nheads * headdim * d_state:
+        raise ValueError("arrays do not match the shape")
+    out = np.empty((ngroups * m * n, d_state), np.float32)
+    rc = load_library().quamba_state_scales(nheads, headdim, ngroups, m, n, d_state, he.ctypes.data, ce.ctypes.data,
+                                            mx.ctypes.data, out.ctypes.data)
+    if rc != 0:
+        raise QuambaError(rc, "quamba_state_scales")
+    return out
 
 
 def quamba_reorder_params(nheads, headdim, ngroups, m, n, d_state, x_calib_absmax, B_calib_absmax,

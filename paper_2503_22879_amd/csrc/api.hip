@@ -102,6 +102,40 @@ extern "C" int quamba_ssd_decode_step(const quamba_ssd_shape_t *shape, const qua
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }
 
+extern "C" int quamba_ssd_decode_step_q8(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                         const float *state_scales, const int8_t *x, const int8_t *B,
+                                         const int8_t *C, const float *dt, const float *A, const float *D,
+                                         int8_t *state_q, uint16_t *y, void *hip_stream)
+{
+    if (!shape) return QUAMBA_ENULL;
+    int rc = check_scales(scales);
+    if (rc != QUAMBA_OK) return rc;
+    if (!state_scales || !x || !B || !C || !dt || !A || !state_q || !y) return QUAMBA_ENULL;
+    rc = check_shape(shape, false);
+    if (rc != QUAMBA_OK) return rc;
+    if (quamba::decode_q8_lds_bytes(*shape) > kMaxLdsBytes) return QUAMBA_ESHAPE;
+    const quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, A, D, nullptr, nullptr, y);
+    const hipError_t e = quamba::launch_decode_q8(a, state_scales, state_q, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
+extern "C" int quamba_ssd_quantize_state(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                         const float *state_scales, const float *state, int8_t *state_q,
+                                         void *hip_stream)
+{
+    if (!shape) return QUAMBA_ENULL;
+    int rc = check_scales(scales);
+    if (rc != QUAMBA_OK) return rc;
+    if (!state_scales || !state || !state_q) return QUAMBA_ENULL;
+    rc = check_shape(shape, false);
+    if (rc != QUAMBA_OK) return rc;
+    if (quamba::decode_q8_lds_bytes(*shape) > kMaxLdsBytes) return QUAMBA_ESHAPE;
+    const quamba::SsdArgs a = pack(shape, scales, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                   const_cast<float *>(state), nullptr);
+    const hipError_t e = quamba::launch_quantize_state(a, state_scales, state_q, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
 extern "C" const char *quamba_strerror(int status)
 {
     switch (status) {

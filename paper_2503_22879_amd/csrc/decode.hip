@@ -13,33 +13,6 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ uint16_t f32_to_f16_bits(float v)
-{
-    const _Float16 h = (_Float16)v;  // round to nearest even
-    return __builtin_bit_cast(uint16_t, h);
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
-}
-
-// Sum over groups of LANES consecutive lanes (LANES a power of two <= 64); every lane of a group gets the sum.
-// Steps inside a row of 16 lanes are data-parallel-primitive moves fused into the adds (no LDS traffic): swap
-// inside pairs, swap pairs inside quads, mirror inside 8, mirror inside 16; the step across rows is one swizzle.
-template <int LANES>
-__device__ __forceinline__ float group_sum(float v)
-{
-    if (LANES >= 2) v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
-    if (LANES >= 4) v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
-    if (LANES >= 8) v += dpp_move<0x141>(v);  // row_half_mirror
-    if (LANES >= 16) v += dpp_move<0x140>(v); // row_mirror
-    if (LANES >= 32) v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));  // lane ^ 16
-    if (LANES >= 64) v += __shfl_xor(v, 32, 64);
-    return v;
-}
-
 // De-quantized x of this head into LDS: xv[p] = s_x(h,p) * xq[p] (inverse of Eq. 1 with the m x n table).
 __device__ __forceinline__ void stage_x(const SsdArgs &a, int bh, int h, float *xv)
 {

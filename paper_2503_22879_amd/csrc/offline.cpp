@@ -1,5 +1,6 @@
 // Host-side, offline part of the library: sort-and-cluster (Section 4.1), the permutation tables used by the
-// cluster-aware weight reordering (Section 4.2), and the static-scale quantizer of Eq. 1.  No device code.
+// cluster-aware weight reordering (Section 4.2), the static-scale quantizer of Eq. 1, and the static scales of the
+// 8-bit cached state (Appendix E).  No device code.
 #include <algorithm>
 #include <cmath>
 #include <cstring>
@@ -275,5 +276,42 @@ extern "C" int quamba_quantize_groups(int64_t tokens, int32_t ngroups, int32_t d
             const size_t o = ((size_t)t * ngroups + g) * d_state;
             for (int k = 0; k < d_state; ++k) vq[o + k] = quantize_one(v[o + k], group_scales[g]);
         }
+    return QUAMBA_OK;
+}
+
+extern "C" int quamba_state_scales(int32_t nheads, int32_t headdim, int32_t ngroups, int32_t m, int32_t n,
+                                   int32_t d_state, const int32_t *head_cluster_end, const int32_t *chan_cluster_end,
+                                   const float *state_calib_absmax, float *state_scales)
+{
+    if (!head_cluster_end || !chan_cluster_end || !state_calib_absmax || !state_scales) return QUAMBA_ENULL;
+    const int H = nheads, P = headdim, G = ngroups, N = d_state;
+    if (H <= 0 || P <= 0 || G <= 0 || m <= 0 || n <= 0 || N <= 0 || H % G) return QUAMBA_ESHAPE;
+    const int hpg = H / G;
+    for (int c = 0; c < G * m; ++c) {
+        const int prev = c % m ? head_cluster_end[c - 1] : 0;
+        if (head_cluster_end[c] < prev || head_cluster_end[c] > hpg) return QUAMBA_EINVAL;
+    }
+    for (int c = 0; c < G * m * n; ++c) {
+        const int prev = c % n ? chan_cluster_end[c - 1] : 0;
+        if (chan_cluster_end[c] < prev || chan_cluster_end[c] > P) return QUAMBA_EINVAL;
+    }
+    const size_t total = (size_t)H * P * N;
+    for (size_t i = 0; i < total; ++i)
+        if (!(state_calib_absmax[i] >= 0.0f) || !std::isfinite(state_calib_absmax[i])) return QUAMBA_EINVAL;
+    // maximum per (cell, state) over the heads and channel positions the lookup assigns to the cell
+    std::vector<float> mx((size_t)G * m * n * N, 0.0f);
+    for (int h = 0; h < H; ++h) {
+        const int g = h / hpg, hl = h % hpg;
+        int i = 0;
+        while (i < m - 1 && hl >= head_cluster_end[g * m + i]) ++i;
+        const size_t base = ((size_t)g * m + i) * n;
+        for (int p = 0, j = 0; p < P; ++p) {
+            while (j < n - 1 && p >= chan_cluster_end[base + j]) ++j;
+            float *row = &mx[(base + j) * N];
+            const float *src = state_calib_absmax + ((size_t)h * P + p) * N;
+            for (int k = 0; k < N; ++k) row[k] = std::max(row[k], src[k]);
+        }
+    }
+    for (size_t i = 0; i < mx.size(); ++i) state_scales[i] = scale_of_max(mx[i]);
     return QUAMBA_OK;
 }

@@ -25,23 +25,64 @@ struct SsdArgs {
     uint16_t *y;               // fp16 bits
 };
 
-// Scale of channel position p of head h from the cluster boundary tables (Section 4.1: m x n scales per group).
-// The cluster index is the number of boundaries at or below the position, so all boundary loads are independent
-// (three dependent memory round trips in total instead of one per boundary).
-__device__ __forceinline__ float x_scale_lookup(const SsdArgs &a, int h, int p)
+// Index of the (group, head cluster, channel range) cell of channel position p of head h in the cluster boundary
+// tables (Section 4.1: m x n cells per group).  The cluster index is the number of boundaries at or below the
+// position, so all boundary loads are independent (three dependent memory round trips in total instead of one per
+// boundary).
+__device__ __forceinline__ int cell_lookup(const SsdArgs &a, int h, int p, int *first_cell_of_head = nullptr)
 {
     const int hpg = a.s.nheads / a.s.ngroups;
     const int g = h / hpg, hl = h - g * hpg;
     const int m = a.s.n_head_clusters, n = a.s.n_chan_clusters;
     int i = 0;
     for (int k = 0; k < m - 1; ++k) i += hl >= a.head_cluster_end[g * m + k] ? 1 : 0;
-    const int base = (g * m + i) * n;
+    const int base = (g * m + i) * n;  // the head cluster's n cells are base .. base + n - 1
+    if (first_cell_of_head) *first_cell_of_head = base;
     int j = 0;
     for (int k = 0; k < n - 1; ++k) j += p >= a.chan_cluster_end[base + k] ? 1 : 0;
-    return a.x_scales[base + j];
+    return base + j;
+}
+
+// Scale of channel position p of head h (Section 4.1: one scale per cell).
+__device__ __forceinline__ float x_scale_lookup(const SsdArgs &a, int h, int p)
+{
+    return a.x_scales[cell_lookup(a, h, p)];
+}
+
+// fp32 -> fp16 bits, round to nearest even.
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float v)
+{
+    const _Float16 h = (_Float16)v;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over groups of LANES consecutive lanes (LANES a power of two <= 64); every lane of a group gets the sum.
+// Steps inside a row of 16 lanes are data-parallel-primitive moves fused into the adds (no LDS traffic): swap
+// inside pairs, swap pairs inside quads, mirror inside 8, mirror inside 16; the step across rows is one swizzle.
+template <int LANES>
+__device__ __forceinline__ float group_sum(float v)
+{
+    if (LANES >= 2) v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+    if (LANES >= 4) v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+    if (LANES >= 8) v += dpp_move<0x141>(v);  // row_half_mirror
+    if (LANES >= 16) v += dpp_move<0x140>(v); // row_mirror
+    if (LANES >= 32)  // lane ^ 16
+        v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
+    if (LANES >= 64) v += __shfl_xor(v, 32, 64);
+    return v;
 }
 
 hipError_t launch_decode(const SsdArgs &a, hipStream_t stream);
+// 8-bit cached state (Appendix E): the step on int8 codes in place, and the quantizer of an fp32 state (a.state)
+hipError_t launch_decode_q8(const SsdArgs &a, const float *state_scales, int8_t *state_q, hipStream_t stream);
+hipError_t launch_quantize_state(const SsdArgs &a, const float *state_scales, int8_t *state_q, hipStream_t stream);
+size_t decode_q8_lds_bytes(const quamba_ssd_shape_t &s);
 hipError_t launch_prefill_generic(const SsdArgs &a, hipStream_t stream);
 bool prefill_mfma_supports(const quamba_ssd_shape_t &s);
 hipError_t launch_prefill_mfma(const SsdArgs &a, hipStream_t stream);

@@ -46,3 +46,12 @@ def host_scales(q, sc):
                         np.ascontiguousarray(sc.chan_cluster_end, np.int32),
                         np.ascontiguousarray(sc.B_scales, np.float32),
                         np.ascontiguousarray(sc.C_scales, np.float32))
+
+
+def make_state_cache(s: W.LayerShape, sc, r, seed: int, batch=None, calib_sequences: int = 8):
+    """Scales of the 8-bit cached state (oracle's calibration rule on a separate draw) and initial codes (oracle's
+    Eq. 1 on a seeded cached-state draw), both in the reordered order.  Returns (state_scales [cells,N], codes)."""
+    mx = W.reorder_state(W.draw_cached_state_calibration(s, seed, calib_sequences), r["head_perm"], r["chan_perm"])
+    ss = oracle.state_scales_from_absmax(sc, mx, s.ngroups)
+    st = W.reorder_state(W.draw_cached_state(s, seed, batch=batch), r["head_perm"], r["chan_perm"])
+    return ss, oracle.quantize_state(sc, ss, st, s.ngroups), st

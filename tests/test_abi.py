@@ -87,6 +87,27 @@ def test_decode_rejects_bad_arguments_without_a_device():
     assert _call_decode(_shape(seqlen=0, chunk=0), null_arg=0) == -1   # seqlen/chunk are ignored by decode
 
 
+def test_q8_entry_points_reject_bad_arguments_without_a_device():
+    lib = q.load_library()
+    dummy = C.create_string_buffer(64)
+    p = C.addressof(dummy)
+    from paper_2503_22879_amd.binding import _ScalesStruct
+    sc = _ScalesStruct(p, p, p, p, p)
+    ok = [p] * 10                          # state_scales x B C dt A D state_q y stream(NULL below)
+    for i in (0, 1, 2, 3, 4, 5, 7, 8):     # everything but D is required
+        args = list(ok[:9]); args[i] = None
+        assert lib.quamba_ssd_decode_step_q8(C.byref(_shape()), C.byref(sc), *args, None) == -1
+    assert lib.quamba_ssd_decode_step_q8(C.byref(_shape(nheads=5)), C.byref(sc), *ok[:9], None) == -2
+    assert lib.quamba_ssd_decode_step_q8(None, C.byref(sc), *ok[:9], None) == -1
+    # tables that cannot fit the LDS of a compute unit
+    assert lib.quamba_ssd_decode_step_q8(C.byref(_shape(d_state=8192, n_chan_clusters=4)), C.byref(sc), *ok[:9],
+                                         None) == -2
+    for i in range(3):                     # state_scales, state, state_q
+        args = [p, p, p]; args[i] = None
+        assert lib.quamba_ssd_quantize_state(C.byref(_shape()), C.byref(sc), *args, None) == -1
+    assert lib.quamba_ssd_quantize_state(C.byref(_shape(batch=0)), C.byref(sc), p, p, p, None) == -2
+
+
 def test_binding_fails_loudly_without_library(monkeypatch):
     import paper_2503_22879_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)

@@ -1,0 +1,180 @@
+"""GPU parity of the decode step on the 8-bit cached state (quamba_ssd_decode_step_q8, quamba_ssd_quantize_state)
+against the oracle, through the C ABI: the int8 codes bit for bit, y within the fp16 output tolerance."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from helpers import make_problem, make_decode_inputs, make_state_cache, to_shape, host_scales
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 2e-3      # max|y_gpu - y_ref| <= Y_TOL * max|y_ref|  (fp16 y, fp32 accumulation against fp64)
+
+
+def _setup(q, s, seed, batch, with_D=True):
+    import torch
+    sb = s.with_(batch=batch)
+    sc, prob, r = make_problem(sb.with_(seqlen=4), seed, calib_tokens=512, with_D=with_D)
+    ss, codes, st = make_state_cache(sb, sc, r, seed, batch=batch)
+    dev = dict(dsc=q.DeviceScales(host_scales(q, sc)), shape=to_shape(q, sb),
+               ss=torch.from_numpy(ss).cuda(), A=torch.from_numpy(prob["A"]).cuda(),
+               D=torch.from_numpy(prob["D"]).cuda() if with_D else None)
+    return sb, sc, prob, r, ss, codes, st, dev
+
+
+def _run_steps(q, s, steps, seed, batch, with_D=True):
+    import torch
+    sb, sc, prob, r, ss, codes, _, dev = _setup(q, s, seed, batch, with_D)
+    qs = torch.from_numpy(codes.copy()).cuda()
+    y = torch.full((batch, s.nheads, s.headdim), float("nan"), dtype=torch.float16, device="cuda")
+    ref = codes.copy()
+    worst = 0.0
+    changed = 0
+    for k in range(steps):
+        inp = make_decode_inputs(sb, sc, r, seed, k)
+        t = {n: torch.from_numpy(v).cuda() for n, v in inp.items()}
+        before = ref.copy()
+        q.quamba_ssd_decode_step_q8(dev["shape"], dev["dsc"], dev["ss"], t["x"], t["B"], t["C"], t["dt"], dev["A"],
+                                    dev["D"], qs, y)
+        yref = oracle.ref_decode_step_q8(sc, ss, inp["x"], inp["B"], inp["C"], inp["dt"], prob["A"],
+                                         prob["D"] if with_D else None, ref)
+        got = qs.cpu().numpy()
+        bad = np.argwhere(got != ref)
+        assert bad.size == 0, f"step {k}: {len(bad)} codes differ, first at {bad[0]}: {got[tuple(bad[0])]} vs {ref[tuple(bad[0])]}"
+        yg = y.cpu().numpy().astype(np.float64)
+        assert np.isfinite(yg).all()
+        ey = np.abs(yg - yref).max() / np.abs(yref).max()
+        worst = max(worst, ey)
+        assert ey <= Y_TOL, f"step {k}: y error {ey:.3e}"
+        changed += int((before != ref).sum())
+    assert changed > 0                      # the steps did move the cache
+    return worst
+
+
+def test_q8_decode_8b_shape_small_batch(gpu_lib):
+    s = W.CONFIGS["m2_8b_decode"]
+    e = _run_steps(gpu_lib, s, steps=6, seed=4, batch=3)
+    print(f"q8 decode 8B-shape b=3: y err {e:.2e}, codes bit-exact")
+
+
+def test_q8_decode_without_D(gpu_lib):
+    _run_steps(gpu_lib, W.CONFIGS["m2_8b_decode"], steps=2, seed=5, batch=2, with_D=False)
+
+
+@pytest.mark.parametrize("P,N,H,G", [(64, 16, 8, 1), (64, 64, 4, 2), (32, 256, 4, 4), (48, 32, 6, 3),
+                                     (20, 24, 4, 2), (7, 5, 3, 1), (128, 128, 2, 1), (40, 128, 4, 2)])
+def test_q8_decode_other_shapes(gpu_lib, P, N, H, G):
+    """Vector path for d_state in {16,32,64,128,256} (ragged headdim included) and the any-shape path."""
+    s = W.LayerShape("t", 2, 1, H, P, N, G, 64, 2, 3)
+    _run_steps(gpu_lib, s, steps=3, seed=6, batch=2)
+
+
+def test_q8_decode_clamps_like_the_oracle(gpu_lib):
+    """Scales calibrated far too small: most new codes saturate at +-127 on both sides."""
+    import torch
+    q = gpu_lib
+    s = W.CONFIGS["m2_130m"]
+    sb, sc, prob, r, ss, codes, _, dev = _setup(q, s, 8, 2)
+    ss_small = (ss * np.float32(1e-3)).astype(np.float32)
+    qs = torch.from_numpy(codes.copy()).cuda()
+    y = torch.empty((2, s.nheads, s.headdim), dtype=torch.float16, device="cuda")
+    inp = make_decode_inputs(sb, sc, r, 8, 0)
+    t = {n: torch.from_numpy(v).cuda() for n, v in inp.items()}
+    q.quamba_ssd_decode_step_q8(dev["shape"], dev["dsc"], torch.from_numpy(ss_small).cuda(), t["x"], t["B"], t["C"],
+                                t["dt"], dev["A"], dev["D"], qs, y)
+    ref = codes.copy()
+    oracle.ref_decode_step_q8(sc, ss_small, inp["x"], inp["B"], inp["C"], inp["dt"], prob["A"], prob["D"], ref)
+    assert np.array_equal(qs.cpu().numpy(), ref)
+    assert (np.abs(ref.astype(int)) == 127).mean() > 0.3
+
+
+def test_q8_decode_full_batch_sampled(gpu_lib):
+    """configs[4] at full size (batch 256, 256 MiB of codes), 8 steps, checked on 5 sampled sequences every step:
+    sequences are independent, so the oracle runs the sampled ones alone."""
+    import torch
+    q = gpu_lib
+    s = W.CONFIGS["m2_8b_decode"]
+    sc, prob, r = make_problem(s.with_(batch=1, seqlen=4), 4, calib_tokens=512)
+    ss, _, _ = make_state_cache(s.with_(batch=1), sc, r, 4, batch=1)
+    dsc = q.DeviceScales(host_scales(q, sc))
+    shape = to_shape(q, s)
+    A = torch.from_numpy(prob["A"]).cuda(); D = torch.from_numpy(prob["D"]).cuda()
+    gen = torch.Generator(device="cuda"); gen.manual_seed(4321)
+    qs = torch.randint(-127, 128, (s.batch, s.nheads, s.headdim, s.d_state), device="cuda", generator=gen,
+                       dtype=torch.int8)
+    sample = [0, 1, 100, 254, 255]
+    ref = qs[sample].cpu().numpy()
+    ssd = torch.from_numpy(ss).cuda()
+    y = torch.empty((s.batch, s.nheads, s.headdim), dtype=torch.float16, device="cuda")
+    for k in range(8):
+        inp = make_decode_inputs(s, sc, r, 4, k)
+        t = {n: torch.from_numpy(v).cuda() for n, v in inp.items()}
+        q.quamba_ssd_decode_step_q8(shape, dsc, ssd, t["x"], t["B"], t["C"], t["dt"], A, D, qs, y)
+        yref = oracle.ref_decode_step_q8(sc, ss, inp["x"][sample], inp["B"][sample], inp["C"][sample],
+                                         inp["dt"][sample], prob["A"], prob["D"], ref)
+        assert np.array_equal(qs[sample].cpu().numpy(), ref), f"step {k}"
+        yg = y[sample].cpu().numpy().astype(np.float64)
+        assert np.abs(yg - yref).max() <= Y_TOL * np.abs(yref).max(), f"step {k}"
+    assert torch.isfinite(y).all()
+
+
+@pytest.mark.parametrize("P,N,H,G", [(64, 128, 8, 2), (20, 24, 4, 2), (7, 5, 3, 1), (33, 16, 4, 1)])
+def test_quantize_state_bit_exact(gpu_lib, P, N, H, G):
+    """fp32 state -> codes of the cache: the 4-wide path, the scalar path (d_state not a multiple of 4), clamping."""
+    import torch
+    q = gpu_lib
+    s = W.LayerShape("t", 3, 1, H, P, N, G, 64, 2, 3)
+    sb, sc, prob, r, ss, codes, st, dev = _setup(q, s, 9, 3)
+    st = (st * np.float32(1.7)).astype(np.float32)                    # some values beyond the calibrated range
+    out = torch.zeros((3, H, P, N), dtype=torch.int8, device="cuda")
+    q.quamba_ssd_quantize_state(dev["shape"], dev["dsc"], dev["ss"], torch.from_numpy(st).cuda(), out)
+    want = oracle.quantize_state(sc, ss, st, G)
+    assert np.array_equal(out.cpu().numpy(), want)
+    assert (np.abs(want.astype(int)) == 127).any()
+
+
+def test_prefill_state_into_the_8bit_cache_and_on(gpu_lib):
+    """The flow of a generation: prefill returns the fp32 state, it is quantized into the cache, decode steps run on
+    the cache.  Every stage against its oracle, fed with the GPU's own previous stage (bit-exact stages compose)."""
+    import torch
+    q = gpu_lib
+    s = W.CONFIGS["m2_130m"].with_(batch=2, seqlen=300)
+    sc, prob, r = make_problem(s, 11)
+    dsc = q.DeviceScales(host_scales(q, sc))
+    shape = to_shape(q, s)
+    t = {k: (torch.from_numpy(v).cuda() if v is not None else None) for k, v in prob.items()}
+    y = torch.empty((2, s.seqlen, s.nheads, s.headdim), dtype=torch.float16, device="cuda")
+    fin = torch.empty((2, s.nheads, s.headdim, s.d_state), device="cuda")
+    q.quamba_ssd_prefill(shape, dsc, t["x"], t["B"], t["C"], t["dt"], t["A"], t["D"], None, y, fin, None)
+    fin_h = fin.cpu().numpy()
+    ss = oracle.state_scales_from_absmax(sc, np.abs(fin_h).max(axis=0) * np.float32(1.2), s.ngroups)
+    ssd = torch.from_numpy(ss).cuda()
+    qs = torch.empty(fin.shape, dtype=torch.int8, device="cuda")
+    q.quamba_ssd_quantize_state(shape, dsc, ssd, fin, qs)
+    ref = oracle.quantize_state(sc, ss, fin_h, s.ngroups)
+    assert np.array_equal(qs.cpu().numpy(), ref)
+    yd = torch.empty((2, s.nheads, s.headdim), dtype=torch.float16, device="cuda")
+    for k in range(3):
+        inp = make_decode_inputs(s, sc, r, 11, k)
+        d = {n: torch.from_numpy(v).cuda() for n, v in inp.items()}
+        q.quamba_ssd_decode_step_q8(shape, dsc, ssd, d["x"], d["B"], d["C"], d["dt"], t["A"], t["D"], qs, yd)
+        yref = oracle.ref_decode_step_q8(sc, ss, inp["x"], inp["B"], inp["C"], inp["dt"], prob["A"], prob["D"], ref)
+        assert np.array_equal(qs.cpu().numpy(), ref)
+        assert np.abs(yd.cpu().numpy().astype(np.float64) - yref).max() <= Y_TOL * np.abs(yref).max()
+
+
+def test_q8_decode_is_deterministic(gpu_lib):
+    import torch
+    q = gpu_lib
+    s = W.CONFIGS["m2_8b_decode"]
+    sb, sc, prob, r, ss, codes, _, dev = _setup(q, s, 7, 4)
+    inp = {n: torch.from_numpy(v).cuda() for n, v in make_decode_inputs(sb, sc, r, 7, 0).items()}
+    outs = []
+    for _ in range(2):
+        qs = torch.from_numpy(codes.copy()).cuda()
+        y = torch.empty((4, s.nheads, s.headdim), dtype=torch.float16, device="cuda")
+        q.quamba_ssd_decode_step_q8(dev["shape"], dev["dsc"], dev["ss"], inp["x"], inp["B"], inp["C"], inp["dt"],
+                                    dev["A"], dev["D"], qs, y)
+        outs.append((qs.cpu(), y.cpu()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])

@@ -81,3 +81,33 @@ def test_reorder_rejects_bad_input():
     with pytest.raises(q.QuambaError) as e:
         q.quamba_reorder_params(4, 8, 2, 2, 2, 4, bad, np.ones((2, 4)), np.ones((2, 4)))
     assert e.value.status == -5
+
+
+def test_state_scales_bit_exact_against_oracle_and_argument_checks():
+    """quamba_state_scales: cell maxima / 127 over the cells the lookup assigns (Appendix E), same as the oracle's."""
+    rng = np.random.default_rng(5)
+    for name in ("tiny", "m2_130m"):
+        s = W.CONFIGS[name]
+        xm, bm, cm = W.draw_calibration(s, tokens=256)
+        hp, cp, hs = q.quamba_reorder_params(s.nheads, s.headdim, s.ngroups, s.m, s.n, s.d_state, xm, bm, cm)
+        sc = oracle.Scales(s.m, s.n, hs.x_scales, hs.head_cluster_end, hs.chan_cluster_end, hs.B_scales, hs.C_scales)
+        mx = W.reorder_state(W.draw_cached_state_calibration(s, 3, sequences=2), hp, cp)
+        mx[:, :, 1] = 0                                           # a state that never fires: scale 1
+        got = q.quamba_state_scales(s.nheads, s.headdim, s.ngroups, s.m, s.n, s.d_state, hs.head_cluster_end,
+                                    hs.chan_cluster_end, mx)
+        want = oracle.state_scales_from_absmax(sc, mx, s.ngroups)
+        assert got.dtype == np.float32 and np.array_equal(got, want)
+        assert np.all(got[:, 1] == 1.0) and np.all(got > 0)
+    H, P, G, m, n, N = 4, 6, 2, 2, 2, 3
+    he = np.array([1, 2, 2, 2], np.int32); ce = np.array([3, 6] * 4, np.int32)
+    mx = rng.uniform(0, 1, (H, P, N)).astype(np.float32)
+    assert q.quamba_state_scales(H, P, G, m, n, N, he, ce, mx).shape == (G * m * n, N)
+    bad = mx.copy(); bad[0, 0, 0] = -1
+    with pytest.raises(q.QuambaError):
+        q.quamba_state_scales(H, P, G, m, n, N, he, ce, bad)
+    with pytest.raises(q.QuambaError):
+        q.quamba_state_scales(H, P, G, m, n, N, np.array([3, 2, 2, 2], np.int32), ce, mx)      # beyond the group
+    with pytest.raises(q.QuambaError):
+        q.quamba_state_scales(H, P, G, m, n, N, he, np.array([4, 3] * 4, np.int32), mx)       # decreasing
+    with pytest.raises(q.QuambaError):
+        q.quamba_state_scales(5, P, G, m, n, N, he, ce, np.zeros((5, P, N), np.float32))      # H % G

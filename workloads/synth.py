@@ -154,6 +154,37 @@ def draw_state(s: LayerShape, seed: int = 0, batch: int | None = None) -> np.nda
     return st
 
 
+def draw_cached_state(s: LayerShape, seed: int = 0, batch: int | None = None, stream: int = 21) -> np.ndarray:
+    """Cached SSM state [b,H,P,N] float32 with the structure a state built from x and B has: the magnitude of
+    element (h,p,n) follows the channel profile of x (rows, in the model's ORIGINAL head/channel order, like x) times
+    the per-state profile of B's group, times a standard normal draw and 0.1.  Stands in for the cached states of a
+    real checkpoint, whose rows follow the channel magnitudes of x (Appendix E)."""
+    g = _rng(seed, stream)
+    b = s.batch if batch is None else batch
+    sigma, _ = _channel_profile(s, seed)
+    prof = _group_profile(s, seed, 0)                                  # [G,N]
+    hpg = s.nheads // s.ngroups
+    st = g.standard_normal((b, s.nheads, s.headdim, s.d_state), dtype=np.float32)
+    st *= (0.1 * sigma).astype(np.float32)[None, :, :, None]
+    st *= np.repeat(prof, hpg, axis=0).astype(np.float32)[None, :, None, :]
+    return st
+
+
+def draw_cached_state_calibration(s: LayerShape, seed: int = 0, sequences: int = 8) -> np.ndarray:
+    """Per-element |state| maxima [H,P,N] over a separate draw of `sequences` cached states (original order)."""
+    return np.abs(draw_cached_state(s, seed + 5, batch=sequences, stream=22)).max(axis=0)
+
+
+def reorder_state(st: np.ndarray, head_perm: np.ndarray, chan_perm: np.ndarray) -> np.ndarray:
+    """Gather the head and channel axes of a [..., H, P, N] array into the sorted/clustered order (index gathers
+    only): new head i = old head head_perm[i], its channel position k = old channel chan_perm[i, k]."""
+    st = np.take(st, head_perm, axis=-3)
+    idx = chan_perm.astype(np.int64)[..., None]
+    idx = np.broadcast_to(idx.reshape((1,) * (st.ndim - 3) + idx.shape), st.shape[:-1] + (1,))
+    idx = np.broadcast_to(idx, st.shape)
+    return np.ascontiguousarray(np.take_along_axis(st, idx, axis=-2))
+
+
 def apply_reorder(raw: dict, head_perm: np.ndarray, chan_perm: np.ndarray) -> dict:
     """Gather x, dt, A, D into the sorted/clustered order (new index -> old index).
 
