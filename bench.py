@@ -34,7 +34,7 @@ MFMA_I8_PEAK_TOPS = 5000.0     # dense int8
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, each scaled by its reading for a plain
 # 256 MiB device copy in the same run: factors 1.9998 and 1.0000); profiles/hbm_traffic_prefill_m2_8b_b4_and_decode_m2_8b.txt.
 # None for workloads that were not profiled.
-MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 493.8e6, "m2_8b_decode": 2162.2e6}
+MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 494.2e6, "m2_8b_decode": 2162.2e6, "m2_8b_decode_q8": 550.8e6}
 
 
 def prefill_algorithmic(s: W.LayerShape):
@@ -46,9 +46,15 @@ def prefill_algorithmic(s: W.LayerShape):
     return f16_macs, i8_macs, nbytes
 
 
-def decode_bytes(s: W.LayerShape) -> float:
+# Arithmetic the 8-bit-state step must do per state element, one vector operation each: code -> float, times the
+# decayed scale, B-dot times x, add, times C into y (one fused multiply-add), times 1/scale, clamp, round-and-pack: 8.
+Q8_OPS_PER_ELEMENT = 8
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3: fp32 vector instructions per second x 64 lanes, unpacked, unfused
+
+
+def decode_bytes(s: W.LayerShape, state_bytes: int = 4) -> float:
     b, H, P, N, G = s.batch, s.nheads, s.headdim, s.d_state, s.ngroups
-    return float(2 * 4 * b * H * P * N + b * H * P + 2 * b * G * N + 4 * b * H + 2 * b * H * P)
+    return float(2 * state_bytes * b * H * P * N + b * H * P + 2 * b * G * N + 4 * b * H + 2 * b * H * P)
 
 
 def build_problem(q, s: W.LayerShape, seed: int):
@@ -215,6 +221,55 @@ def main() -> int:
             "roofline": {"kernel": "decode_vec_kernel", "bound": "hbm", "achieved": dgbs, "peak": HBM_PEAK_GBS,
                          "unit": "GB/s", "frac": dgbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get("m2_8b_decode")},
             "finite": bool(torch.isfinite(state).all().item()),
+        }
+
+        # ------------------------------------------------ decode on the 8-bit cached state (Appendix E)
+        del state
+        torch.cuda.empty_cache()
+        ncell = sd.ngroups * sd.m * sd.n
+        mx = W.reorder_state(W.draw_cached_state_calibration(sd, seed), dhp, dcp)
+        ss = q.quamba_state_scales(sd.nheads, sd.headdim, sd.ngroups, sd.m, sd.n, sd.d_state, dhs.head_cluster_end,
+                                   dhs.chan_cluster_end, mx)
+        assert ss.shape == (ncell, sd.d_state)
+        dss = torch.from_numpy(ss).to(dev)
+        # cached states of 32 sequences, drawn once and repeated over the batch, quantized by the library itself
+        rep = 32
+        st32 = torch.from_numpy(W.reorder_state(W.draw_cached_state(sd, seed, batch=rep), dhp, dcp)).to(dev)
+        qstate = torch.empty((sd.batch, sd.nheads, sd.headdim, sd.d_state), dtype=torch.int8, device=dev)
+        shape32 = q.Shape(**{f: (rep if f == "batch" else getattr(dshape, f)) for f, _ in dshape._fields_})
+        q32 = torch.empty((rep, sd.nheads, sd.headdim, sd.d_state), dtype=torch.int8, device=dev)
+        q.quamba_ssd_quantize_state(shape32, ddsc, dss, st32, q32)
+        for i0 in range(0, sd.batch, rep):
+            qstate[i0:i0 + rep].copy_(q32[:min(rep, sd.batch - i0)])
+        del st32, q32
+        counter[0] = 0
+
+        def decode_q8():
+            i = steps_in[counter[0] % nsets]
+            counter[0] += 1
+            q.quamba_ssd_decode_step_q8(dshape, ddsc, dss, i["x"], i["B"], i["C"], i["dt"], dA, dD, qstate, yd)
+
+        qms, qwall = time_region(torch, decode_q8, dsteps, max(args.warmup, 4))
+        qbytes = decode_bytes(sd, state_bytes=1)
+        qgbs = qbytes / (qms * 1e-3) / 1e9
+        elems = sd.batch * sd.nheads * sd.headdim * sd.d_state
+        qops = Q8_OPS_PER_ELEMENT * elems
+        out["decode_q8"] = {
+            "metric": "decode state update us/step, 8-bit cached state", "value": qms * 1e3, "unit": "us/step",
+            "steps": dsteps, "higher_is_better": False, "wall_us_per_step": qwall * 1e3,
+            "config": {"workload": "m2_8b_decode with an int8 cached state: batch 256, 128 heads x 64, d_state 128, "
+                                   "256 MiB of codes in place, 4x4 cells x 128 state scales per group"},
+            "roofline": {"kernel": "decode_q8_vec_kernel", "bound": "hbm", "achieved": qgbs, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": qgbs / HBM_PEAK_GBS,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get("m2_8b_decode_q8")},
+            "roofline_alu": {"kernel": "decode_q8_vec_kernel", "bound": "alu", "achieved": qops / (qms * 1e-3) / 1e12,
+                             "peak": ALU_PEAK_TOPS, "unit": "Top/s (fp32 vector instructions x 64 lanes)",
+                             "frac": qops / (qms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
+                             "note": "%d fp32 vector operations per state element; peak = 256 CUs x 4 SIMDs x 16 "
+                                     "lanes x 2.4 GHz, one unfused, unpacked operation per lane and cycle"
+                                     % Q8_OPS_PER_ELEMENT},
+            "speedup_over_fp32_state": dms / qms,
+            "codes_in_range": bool((qstate.abs() <= 127).all().item()),
         }
 
     if args.copy_calibration:

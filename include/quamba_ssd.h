@@ -128,7 +128,7 @@ int quamba_ssd_decode_step(const quamba_ssd_shape_t *shape, const quamba_ssd_sca
  *   everything else as in quamba_ssd_decode_step; dt >= 0 and A <= 0 are required (the decay is computed for
  *   dt*A <= 0 only).
  * The new code is decided in fp32, every operation rounded to nearest even on its own, in this order:
- *   xv = s_x(h,p)*x;  dtx = dt*xv;  Bv = s_B[g]*B[n];  u = dtx*Bv;  hp = s[cell,n]*code;  d = dA*hp;  hn = d + u;
+ *   xv = s_x(h,p)*x;  dtx = dt*xv;  Bv = s_B[g]*B[n];  u = dtx*Bv;  sd = dA*s[cell,n];  d = sd*code;  hn = d + u;
  *   r = hn*(1/s[cell,n]);  code' = clamp(rint(r), -127, 127)   with ties to even,
  * where dA = exp(dt*A) is evaluated as t = (dt*A)*log2(e) (fp32 constant 0x3FB8AA3B), k = rint(t), f = t - k,
  * 2^f by Horner's rule on the fp32-rounded coefficients (ln 2)^i / i!, i = 7..0 (multiply and add rounded

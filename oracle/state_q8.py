@@ -94,8 +94,8 @@ def ref_decode_step_q8(sc: Scales, state_scales, xq, Bq, Cq, dt, A, D, qstate):
     Per element, float32, every line one rounding:
         xv  = s_x(h,p) * x_code            dtx = dt * xv
         Bv  = s_B[g] * B_code              u   = dtx * Bv              (B-dot x of Eq. 2, B-dot = dt B, Section 3.2)
-        hp  = s[cell,n] * state_code                                    (inverse of Eq. 1)
-        d   = exp_f32(dt * A) * hp         hn  = d + u                  (Eq. 2)
+        sd  = exp_f32(dt * A) * s[cell,n]  d   = sd * state_code        (decay of Eq. 2 times the inverse of Eq. 1:
+                                           hn  = d + u                   the decayed scale is shared by the cell)
         r   = hn * (1 / s[cell,n])         code' = clamp(rint(r), -127, 127)   (Eq. 1)
     y[p] = sum_n (s_C[g] C_code[n]) hn + D xv, from the updated state before it is re-quantized; summed here in
     float64 (the output is compared within a tolerance, not bit for bit).
@@ -118,9 +118,9 @@ def ref_decode_step_q8(sc: Scales, state_scales, xq, Bq, Cq, dt, A, D, qstate):
     dtx = dt[:, :, None] * xv
     Bv = sB[None, :, None] * Bq.astype(F)[:, gidx, :]       # [b,H,N]
     u = dtx[:, :, :, None] * Bv[:, :, None, :]              # [b,H,P,N]
-    hp = s[None] * qstate.astype(F)
     dA = exp_f32(dt * A[None, :])                           # [b,H]
-    d = dA[:, :, None, None] * hp
+    sd = dA[:, :, None, None] * s[None]                     # [b,H,P,N]
+    d = sd * qstate.astype(F)
     hn = d + u
     r = hn * inv[None]
     qstate[...] = np.clip(np.rint(r), -127, 127).astype(np.int8)

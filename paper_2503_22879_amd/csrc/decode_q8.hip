@@ -4,13 +4,15 @@
 // The cached state is int8 codes; the scale of code (h, p, n) belongs to the (head cluster, channel range) cell of
 // (h, p) -- the m x n cells of x (Section 4.1) -- and to the state n.  A step reads a code, de-quantizes it (inverse of
 // Eq. 1), applies Eq. 2, adds the element to y, and writes the re-quantized code (Eq. 1) back: 1 B read + 1 B written
-// per state element instead of 4 B + 4 B, with about 11 vector instructions per element, which puts the kernel near
+// per state element instead of 4 B + 4 B, with about 8 vector instructions per element, which puts the kernel near
 // the point where the vector ALU and HBM take the same time.  One workgroup per (sequence, head); a lane owns 16
 // consecutive states of a row (one 16-byte load), the head's scale rows and their reciprocals sit in LDS.
 //
 // The new code is an integer decided by fp32 arithmetic, so every operation that leads to it is rounded on its own, in
 // a fixed order (the header states it); the compiler must not contract multiplies and adds, and the exponential of
 // the decay is a fixed sequence of such operations instead of a library call.
+#include <algorithm>
+
 #include "quamba_internal.h"
 
 // no fused multiply-add unless written as one: the quantization decision depends on the individual roundings
@@ -21,6 +23,8 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
+constexpr int kMaxSeqs = 16;  // sequences of one head a workgroup of the vector kernel may own
+constexpr size_t kLdsLimit = 160 * 1024;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -62,9 +66,30 @@ __device__ __forceinline__ uint32_t pack4(uint32_t m0, uint32_t m1, uint32_t m2,
     return lo | hi;
 }
 
+// Four values -> four codes in one dword: clamp, then the rounding add writes its low byte (the code) straight into
+// byte k of the result through the sub-dword destination select, so rounding and packing cost one instruction per code.
+__device__ __forceinline__ uint32_t codes4(float r0, float r1, float r2, float r3)
+{
+    const float c0 = __builtin_fminf(__builtin_fmaxf(r0, -127.0f), 127.0f);
+    const float c1 = __builtin_fminf(__builtin_fmaxf(r1, -127.0f), 127.0f);
+    const float c2 = __builtin_fminf(__builtin_fmaxf(r2, -127.0f), 127.0f);
+    const float c3 = __builtin_fminf(__builtin_fmaxf(r3, -127.0f), 127.0f);
+    const float magic = 12582912.0f;  // 1.5 * 2^23
+    uint32_t out;
+    asm("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD"
+        : "=v"(out) : "v"(c0), "v"(magic));
+    asm("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+        : "+v"(out) : "v"(c1), "v"(magic));
+    asm("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+        : "+v"(out) : "v"(c2), "v"(magic));
+    asm("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+        : "+v"(out) : "v"(c3), "v"(magic));
+    return out;
+}
+
 __device__ __forceinline__ float code_to_float(uint32_t w, int e) { return (float)(int)(int8_t)(w >> (8 * e)); }
 
-// LDS of a workgroup: xv[P] de-quantized x, cl[P] channel range of every row, s_tab[n][N] the head's scale rows,
+// LDS of a workgroup: xv[P] de-quantized x (or, without x, the scale s_x of every row), cl[P] channel range of every row, s_tab[n][N] the head's scale rows,
 // inv_tab[n][N] their reciprocals (correctly rounded divisions, done once per workgroup).
 // floats in front of the scale tables: xv and cl, rounded up so that the tables' rows can be read 16 bytes at a time
 __host__ __device__ inline size_t table_offset(int P) { return ((size_t)2 * P + 3) & ~(size_t)3; }
@@ -89,7 +114,7 @@ __device__ __forceinline__ Tables stage_tables(const SsdArgs &a, const float *st
     for (int p = threadIdx.x; p < P; p += kThreads) {
         const int cell = cell_lookup(a, h, p, &base);
         t.cl[p] = cell - base;
-        if (with_x) t.xv[p] = a.x_scales[cell] * (float)a.x[(size_t)bh * P + p];
+        t.xv[p] = with_x ? a.x_scales[cell] * (float)a.x[(size_t)bh * P + p] : a.x_scales[cell];
     }
     cell_lookup(a, h, 0, &base);  // threads beyond P need the head's first cell too
     const float *src = state_scales + (size_t)base * N;
@@ -105,79 +130,132 @@ __device__ __forceinline__ Tables stage_tables(const SsdArgs &a, const float *st
 // d_state = N with N/16 a power of two <= 64: a row of N codes is covered by N/16 lanes with 16 bytes each; a wave
 // covers 64/(N/16) rows per load instruction and keeps ROWS such loads in flight.  FULL: headdim is a multiple of the
 // rows one trip of the workgroup covers (no clamping or masking of rows).
+//
+// A workgroup owns one head and every gridDim.y-th slice of the batch; the grid is sized so that all workgroups are
+// resident at once (no tail of partly filled rounds).  Everything but the codes goes through LDS: once per workgroup
+// the head's scale rows, their reciprocals and the cell of every row; once per slice dt, the decay, the decayed scale
+// rows, x as fp32 codes, s_B B and C as fp32 codes.  The loop over the sequences of a slice then issues nothing but
+// the 16-byte code loads (one sequence ahead) and stores, so that the dependent look-ups, divisions and conversions
+// are paid once per workgroup or slice instead of once per 8 KB of state.
 template <int N, int ROWS, bool FULL>
-__global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, const float *state_scales, int8_t *state_q)
+__global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, const float *state_scales, int8_t *state_q,
+                                                                 int seqs_per_block)
 {
     constexpr int LPR = N / 16, RPI = 64 / LPR;
     extern __shared__ float lds[];
     const int P = a.s.headdim, H = a.s.nheads, G = a.s.ngroups;
-    const int bh = blockIdx.x;
-    const int b = bh / H, h = bh - b * H, g = h / (H / G);
+    const int h = blockIdx.x, g = h / (H / G);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane % LPR, sub = lane / LPR;
 
-    // the lane's state loads go first: rows past the end re-read the last row and are not stored
-    int8_t *st = state_q + (size_t)bh * P * N + 16 * j;
-    const Tables t = stage_tables(a, state_scales, bh, h, lds, true);
-
-    const float dt = a.dt[bh];
-    const float dA = exp_steps(dt * a.A[h]);
-    const float Dh = a.D ? a.D[h] : 0.0f;
+    // per-sequence arrays behind the head's tables
+    float *s_dt = lds + table_offset(P) + 2 * (size_t)a.s.n_chan_clusters * N;
+    float *s_dA = s_dt + kMaxSeqs;
+    float *s_xf = s_dA + kMaxSeqs;                     // [nb][P]  x codes as fp32
+    float *s_Bv = s_xf + (((size_t)seqs_per_block * P + 3) & ~(size_t)3);  // [nb][N]  s_B * B code (one rounding)
+    float *s_Cf = s_Bv + (size_t)seqs_per_block * N;   // [nb][N]  C codes as fp32 (s_C is applied to the sum)
+    float *s_sd = s_Cf + (size_t)seqs_per_block * N;   // [nb][n cells][N]  decay * scale: the decayed scale rows
+    const int nc = a.s.n_chan_clusters;
     const float sB = a.B_scales[g], sC = a.C_scales[g];
-    const u32x4 bq = *reinterpret_cast<const u32x4 *>(a.B + ((size_t)b * G + g) * N + 16 * j);
-    const u32x4 cq = *reinterpret_cast<const u32x4 *>(a.C + ((size_t)b * G + g) * N + 16 * j);
-    float Bv[16], Cv[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        Bv[e] = sB * code_to_float(bq[e >> 2], e & 3);
-        Cv[e] = sC * code_to_float(cq[e >> 2], e & 3);
+    const float Dh = a.D ? a.D[h] : 0.0f;
+    const Tables t = stage_tables(a, state_scales, 0, h, lds, false);  // xv holds s_x of every row; ends in a barrier
+
+    // the workgroup's slices of the batch: slice s covers sequences [s seqs_per_block, (s + 1) seqs_per_block)
+    const int nslices = (a.s.batch + seqs_per_block - 1) / seqs_per_block;
+    for (int slice = blockIdx.y; slice < nslices; slice += gridDim.y) {
+    const int b_begin = slice * seqs_per_block, b_end = min(b_begin + seqs_per_block, a.s.batch);
+    const int nb = b_end - b_begin;
+    if ((int)threadIdx.x < nb) {  // one decay per thread: the exponential is a long dependent chain
+        const float dt = a.dt[(size_t)(b_begin + threadIdx.x) * H + h];
+        s_dt[threadIdx.x] = dt;
+        s_dA[threadIdx.x] = exp_steps(dt * a.A[h]);
     }
+    for (int i = threadIdx.x; i < nb * P; i += kThreads) {
+        const int bb = i / P, p = i - bb * P;
+        s_xf[i] = (float)a.x[((size_t)(b_begin + bb) * H + h) * P + p];
+    }
+    for (int i = threadIdx.x; i < nb * N; i += kThreads) {
+        const int bb = i / N, n = i - bb * N;
+        const size_t o = ((size_t)(b_begin + bb) * G + g) * N + n;
+        s_Bv[i] = sB * (float)a.B[o];
+        s_Cf[i] = (float)a.C[o];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nb * nc * N; i += kThreads) s_sd[i] = s_dA[i / (nc * N)] * t.s_tab[i % (nc * N)];
+    __syncthreads();
 
     for (int p0 = wave * RPI * ROWS; p0 < P; p0 += kWaves * RPI * ROWS) {
-        u32x4 w[ROWS];
+        // per row of this trip: its scale rows and its x scale (the same for every sequence)
+        int prow[ROWS];
+        const float *srow[ROWS], *irow[ROWS];
+        float sx[ROWS];
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
-            const int p = FULL ? p0 + i * RPI + sub : min(p0 + i * RPI + sub, P - 1);
-            w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(st + (size_t)p * N));
+            prow[i] = FULL ? p0 + i * RPI + sub : min(p0 + i * RPI + sub, P - 1);
+            srow[i] = s_sd + t.cl[prow[i]] * N + 16 * j;  // of the slice's first sequence; the others nc * N apart
+            irow[i] = t.inv_tab + t.cl[prow[i]] * N + 16 * j;
+            sx[i] = t.xv[prow[i]];
         }
-        float part[ROWS];
+        auto load = [&](int b, u32x4(&w)[ROWS]) {
 #pragma unroll
-        for (int i = 0; i < ROWS; ++i) {
-            const int p = FULL ? p0 + i * RPI + sub : min(p0 + i * RPI + sub, P - 1);
-            const float dtx = dt * t.xv[p];
-            const float *srow = t.s_tab + t.cl[p] * N + 16 * j;
-            const float *irow = t.inv_tab + t.cl[p] * N + 16 * j;
-            float acc = 0.0f;
-            u32x4 out;
+            for (int i = 0; i < ROWS; ++i)
+                w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
+                    state_q + (((size_t)b * H + h) * P + prow[i]) * N + 16 * j));
+        };
+        u32x4 nxt[ROWS];
+        load(b_begin, nxt);
+        for (int bb = 0; bb < nb; ++bb) {
+            const int b = b_begin + bb;
+            u32x4 cur[ROWS];
+#pragma unroll
+            for (int i = 0; i < ROWS; ++i) cur[i] = nxt[i];
+            if (bb + 1 < nb) load(b + 1, nxt);
+            const float dt = s_dt[bb];
+            const size_t bh = (size_t)b * H + h;
+            float acc[ROWS], xv[ROWS], dtx[ROWS];
+            u32x4 out[ROWS];
+#pragma unroll
+            for (int i = 0; i < ROWS; ++i) {
+                xv[i] = sx[i] * s_xf[bb * P + prow[i]];
+                dtx[i] = dt * xv[i];
+                acc[i] = 0.0f;
+            }
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4 s4 = *reinterpret_cast<const f32x4 *>(srow + 4 * q4);
-                const f32x4 i4 = *reinterpret_cast<const f32x4 *>(irow + 4 * q4);
-                uint32_t m[4];
+                const f32x4 B4 = *reinterpret_cast<const f32x4 *>(s_Bv + bb * N + 16 * j + 4 * q4);
+                const f32x4 C4 = *reinterpret_cast<const f32x4 *>(s_Cf + bb * N + 16 * j + 4 * q4);
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int e = 4 * q4 + k;
-                    const float hp = s4[k] * code_to_float(w[i][q4], k);  // inverse of Eq. 1
-                    const float d = dA * hp;                               // Eq. 2: decay ...
-                    const float u = dtx * Bv[e];                           // ... plus B-dot x
-                    const float hn = d + u;
-                    acc = __builtin_fmaf(Cv[e], hn, acc);                  // y from the updated state
-                    m[k] = code_bits(hn * i4[k]);                          // Eq. 1
+                for (int i = 0; i < ROWS; ++i) {
+                    const f32x4 s4 = *reinterpret_cast<const f32x4 *>(srow[i] + (size_t)bb * nc * N + 4 * q4);
+                    const f32x4 i4 = *reinterpret_cast<const f32x4 *>(irow[i] + 4 * q4);
+                    float r[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float d = s4[k] * code_to_float(cur[i][q4], k);  // decayed scale * code: Eq. 2's decay
+                        const float u = dtx[i] * B4[k];                         // ... plus B-dot x
+                        const float hn = d + u;
+                        acc[i] = __builtin_fmaf(C4[k], hn, acc[i]);             // y from the updated state
+                        r[k] = hn * i4[k];                                      // Eq. 1
+                    }
+                    out[i][q4] = codes4(r[0], r[1], r[2], r[3]);
                 }
-                out[q4] = pack4(m[0], m[1], m[2], m[3]);
             }
-            if (FULL || p0 + i * RPI + sub < P)
-                __builtin_nontemporal_store(out, reinterpret_cast<u32x4 *>(st + (size_t)p * N));
-            part[i] = acc;
-        }
 #pragma unroll
-        for (int i = 0; i < ROWS; ++i) part[i] = group_sum<LPR>(part[i]);
+            for (int i = 0; i < ROWS; ++i)
+                if (FULL || p0 + i * RPI + sub < P)
+                    __builtin_nontemporal_store(out[i],
+                                                reinterpret_cast<u32x4 *>(state_q + (bh * P + prow[i]) * N + 16 * j));
 #pragma unroll
-        for (int i = 0; i < ROWS; ++i) {
-            const int p = p0 + i * RPI + sub;
-            if (j == 0 && (FULL || p < P))
-                a.y[(size_t)bh * P + p] = f32_to_f16_bits(__builtin_fmaf(Dh, t.xv[p], part[i]));
+            for (int i = 0; i < ROWS; ++i) acc[i] = group_sum<LPR>(acc[i]);
+#pragma unroll
+            for (int i = 0; i < ROWS; ++i) {
+                const int p = p0 + i * RPI + sub;
+                if (j == 0 && (FULL || p < P))
+                    a.y[bh * P + p] = f32_to_f16_bits(__builtin_fmaf(Dh, xv[i], sC * acc[i]));
+            }
         }
+    }
+    __syncthreads();  // every wave is done with the slice's arrays before the next slice overwrites them
     }
 }
 
@@ -202,8 +280,7 @@ __global__ __launch_bounds__(kThreads) void decode_q8_any_kernel(SsdArgs a, cons
         const float *srow = t.s_tab + t.cl[p] * N, *irow = t.inv_tab + t.cl[p] * N;
         float acc = 0.0f;
         for (int n = lane; n < N; n += 64) {
-            const float hp = srow[n] * (float)row[n];
-            const float d = dA * hp;
+            const float d = (dA * srow[n]) * (float)row[n];
             const float u = dtx * (sB * (float)Bq[n]);
             const float hn = d + u;
             acc = __builtin_fmaf(sC * (float)Cq[n], hn, acc);
@@ -243,26 +320,61 @@ __global__ __launch_bounds__(kThreads) void quantize_state_kernel(SsdArgs a, con
     }
 }
 
-template <typename K>
-hipError_t launch(K kernel, const SsdArgs &a, const float *ss, int8_t *q, size_t lds, hipStream_t stream)
+template <typename K, typename... Extra>
+hipError_t launch(K kernel, dim3 grid, const SsdArgs &a, const float *ss, int8_t *q, size_t lds, hipStream_t stream,
+                  Extra... extra)
 {
-    if (lds > 64 * 1024) {
+    if (lds > 48 * 1024) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.s.batch * a.s.nheads)), dim3(kThreads), lds, stream, a, ss, q);
+    hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, stream, a, ss, q, extra...);
     return hipGetLastError();
 }
 
+// Compute units of the current device (cached per device id).
+int compute_units()
+{
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+// Sequences per workgroup of the vector kernel: enough workgroups to fill the chip several times over (>= 4096 when
+// the batch allows), at most kMaxSeqs, the per-sequence arrays within 64 KB of LDS, a grid y dimension <= 65535.
+// Returns 0 when no choice fits (the caller then takes the any-shape kernel).
+size_t vec_lds_bytes(const quamba_ssd_shape_t &s, int seqs);
+int seqs_per_block(const quamba_ssd_shape_t &s)
+{
+    const int64_t pairs = (int64_t)s.batch * s.nheads;
+    int n = (int)std::min<int64_t>(kMaxSeqs, std::max<int64_t>(1, pairs / 4096));
+    while (n > 1 && vec_lds_bytes(s, n) > 64 * 1024) --n;
+    if (vec_lds_bytes(s, n) > kLdsLimit || (s.batch + n - 1) / n > 65535) return 0;
+    return n;
+}
+
 template <int N>
-hipError_t launch_vec(const SsdArgs &a, const float *ss, int8_t *q, size_t lds, hipStream_t stream)
+hipError_t launch_vec(const SsdArgs &a, const float *ss, int8_t *q, int spb, hipStream_t stream)
 {
     constexpr int RPI = 64 / (N / 16);
     const int P = a.s.headdim;
-    if (P % (kWaves * RPI * 2) == 0) return launch(decode_q8_vec_kernel<N, 2, true>, a, ss, q, lds, stream);
-    if (P % (kWaves * RPI) == 0) return launch(decode_q8_vec_kernel<N, 1, true>, a, ss, q, lds, stream);
-    return launch(decode_q8_vec_kernel<N, 1, false>, a, ss, q, lds, stream);
+    const size_t lds = vec_lds_bytes(a.s, spb);
+    // all workgroups resident at once: 4 waves of up to 128 registers each allow 4 workgroups per compute unit
+    // (one wave of each per SIMD), the LDS footprint may allow fewer
+    const int nslices = (a.s.batch + spb - 1) / spb;
+    const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, kLdsLimit / lds));
+    const int want_y = (compute_units() * per_cu + a.s.nheads - 1) / a.s.nheads;
+    const dim3 grid((unsigned)a.s.nheads, (unsigned)std::max(1, std::min(nslices, want_y)));
+    if (P % (kWaves * RPI * 2) == 0) return launch(decode_q8_vec_kernel<N, 2, true>, grid, a, ss, q, lds, stream, spb);
+    if (P % (kWaves * RPI) == 0) return launch(decode_q8_vec_kernel<N, 1, true>, grid, a, ss, q, lds, stream, spb);
+    return launch(decode_q8_vec_kernel<N, 1, false>, grid, a, ss, q, lds, stream, spb);
 }
 
 }  // namespace
@@ -272,22 +384,34 @@ size_t decode_q8_lds_bytes(const quamba_ssd_shape_t &s)
     return sizeof(float) * (table_offset(s.headdim) + 2 * (size_t)s.n_chan_clusters * s.d_state);
 }
 
+namespace {
+
+// LDS of the vector kernel with `seqs` sequences per workgroup: the head's tables plus the per-sequence arrays.
+size_t vec_lds_bytes(const quamba_ssd_shape_t &s, int seqs)
+{
+    const size_t xf = ((size_t)seqs * s.headdim + 3) & ~(size_t)3;
+    return decode_q8_lds_bytes(s) +
+           sizeof(float) * (2 * kMaxSeqs + xf + (2 + (size_t)s.n_chan_clusters) * seqs * s.d_state);
+}
+
+}  // namespace
+
 hipError_t launch_decode_q8(const SsdArgs &a, const float *state_scales, int8_t *state_q, hipStream_t stream)
 {
-    const size_t lds = decode_q8_lds_bytes(a.s);
-    const bool al = reinterpret_cast<uintptr_t>(state_q) % 16 == 0 && reinterpret_cast<uintptr_t>(a.B) % 16 == 0 &&
-                    reinterpret_cast<uintptr_t>(a.C) % 16 == 0;
-    if (al) {
+    const bool al = reinterpret_cast<uintptr_t>(state_q) % 16 == 0;
+    const int spb = seqs_per_block(a.s);
+    if (al && spb > 0) {
         switch (a.s.d_state) {
-            case 16: return launch_vec<16>(a, state_scales, state_q, lds, stream);
-            case 32: return launch_vec<32>(a, state_scales, state_q, lds, stream);
-            case 64: return launch_vec<64>(a, state_scales, state_q, lds, stream);
-            case 128: return launch_vec<128>(a, state_scales, state_q, lds, stream);
-            case 256: return launch_vec<256>(a, state_scales, state_q, lds, stream);
+            case 16: return launch_vec<16>(a, state_scales, state_q, spb, stream);
+            case 32: return launch_vec<32>(a, state_scales, state_q, spb, stream);
+            case 64: return launch_vec<64>(a, state_scales, state_q, spb, stream);
+            case 128: return launch_vec<128>(a, state_scales, state_q, spb, stream);
+            case 256: return launch_vec<256>(a, state_scales, state_q, spb, stream);
             default: break;
         }
     }
-    return launch(decode_q8_any_kernel, a, state_scales, state_q, lds, stream);
+    return launch(decode_q8_any_kernel, dim3((unsigned)(a.s.batch * a.s.nheads)), a, state_scales, state_q,
+                  decode_q8_lds_bytes(a.s), stream);
 }
 
 hipError_t launch_quantize_state(const SsdArgs &a, const float *state_scales, int8_t *state_q, hipStream_t stream)
@@ -295,8 +419,9 @@ hipError_t launch_quantize_state(const SsdArgs &a, const float *state_scales, in
     const size_t lds = decode_q8_lds_bytes(a.s);
     const bool vec = a.s.d_state % 4 == 0 && reinterpret_cast<uintptr_t>(a.state) % 16 == 0 &&
                      reinterpret_cast<uintptr_t>(state_q) % 4 == 0;
-    return vec ? launch(quantize_state_kernel<true>, a, state_scales, state_q, lds, stream)
-               : launch(quantize_state_kernel<false>, a, state_scales, state_q, lds, stream);
+    const dim3 grid((unsigned)(a.s.batch * a.s.nheads));
+    return vec ? launch(quantize_state_kernel<true>, grid, a, state_scales, state_q, lds, stream)
+               : launch(quantize_state_kernel<false>, grid, a, state_scales, state_q, lds, stream);
 }
 
 }  // namespace quamba
