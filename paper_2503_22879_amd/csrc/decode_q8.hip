@@ -135,7 +135,7 @@ __device__ __forceinline__ Tables stage_tables(const SsdArgs &a, const float *st
 // resident at once (no tail of partly filled rounds).  Everything but the codes goes through LDS: once per workgroup
 // the head's scale rows, their reciprocals and the cell of every row; once per slice dt, the decay, the decayed scale
 // rows, x as fp32 codes, s_B B and C as fp32 codes.  The loop over the sequences of a slice then issues nothing but
-// the 16-byte code loads (one sequence ahead) and stores, so that the dependent look-ups, divisions and conversions
+// the 16-byte code loads (two sequences ahead) and stores, so that the dependent look-ups, divisions and conversions
 // are paid once per workgroup or slice instead of once per 8 KB of state.
 template <int N, int ROWS, bool FULL>
 __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, const float *state_scales, int8_t *state_q,
@@ -202,14 +202,19 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
                 w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
                     state_q + (((size_t)b * H + h) * P + prow[i]) * N + 16 * j));
         };
-        u32x4 nxt[ROWS];
+        // the codes of the next two sequences are always in flight while one is computed
+        u32x4 nxt[ROWS], nxt2[ROWS];
         load(b_begin, nxt);
+        if (nb > 1) load(b_begin + 1, nxt2);
         for (int bb = 0; bb < nb; ++bb) {
             const int b = b_begin + bb;
             u32x4 cur[ROWS];
 #pragma unroll
-            for (int i = 0; i < ROWS; ++i) cur[i] = nxt[i];
-            if (bb + 1 < nb) load(b + 1, nxt);
+            for (int i = 0; i < ROWS; ++i) {
+                cur[i] = nxt[i];
+                nxt[i] = nxt2[i];
+            }
+            if (bb + 2 < nb) load(b + 2, nxt2);
             const float dt = s_dt[bb];
             const size_t bh = (size_t)b * H + h;
             float acc[ROWS], xv[ROWS], dtx[ROWS];
