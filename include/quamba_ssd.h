@@ -119,6 +119,44 @@ int quamba_ssd_decode_step(const quamba_ssd_shape_t *shape, const quamba_ssd_sca
                            float *state, uint16_t *y, void *hip_stream);
 
 /*
+ * Optional 8-bit side inputs of the SSD kernels (Section 5.2 lists x, the step size, B, C and z as the kernel's 8-bit
+ * loads).  Host struct of device pointers.
+ *   z        int8, laid out like x ([batch, seqlen, nheads, headdim] for prefill, [batch, nheads, headdim] for decode),
+ *            reordered like x; the output becomes y * SiLU(z_scale * z) (Section 3.2: the optional residual branch z
+ *            multiplies the SSM output y = C h + D x before the output projection).  NULL: no gate.
+ *   dt_q     int8, laid out like dt: Eq. 1 codes of the step size's pre-activation; the step size becomes
+ *            softplus(dt_scale * dt_q + dt_bias[h]) (Section 3.2) and the fp32 `dt` argument is ignored (may be
+ *            NULL).  NULL: `dt` is used as is.
+ *   dt_bias  fp32 [nheads] or NULL (zero); only read with dt_q.
+ */
+typedef struct quamba_ssd_gate_t {
+    const int8_t *z;
+    float z_scale;
+    const int8_t *dt_q;
+    float dt_scale;
+    const float *dt_bias;
+} quamba_ssd_gate_t;
+
+/*
+ * quamba_ssd_prefill / quamba_ssd_decode_step / quamba_ssd_decode_step_q8 with the side inputs above; `gate` may be
+ * NULL (then they are the plain entry points).  Everything else as documented there.  The 8-bit-state step takes the
+ * gate only: its re-quantization decision is defined on the caller's fp32 dt, so dt_q must be NULL there (EINVAL).
+ * Errors: as the plain entry points, plus EINVAL for non-finite or non-positive scales.
+ */
+int quamba_ssd_prefill_gated(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                             const quamba_ssd_gate_t *gate, const int8_t *x, const int8_t *B, const int8_t *C,
+                             const float *dt, const float *A, const float *D, const float *init_state, uint16_t *y,
+                             float *final_state, void *workspace, size_t workspace_bytes, void *hip_stream);
+int quamba_ssd_decode_step_gated(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                 const quamba_ssd_gate_t *gate, const int8_t *x, const int8_t *B, const int8_t *C,
+                                 const float *dt, const float *A, const float *D, float *state, uint16_t *y,
+                                 void *hip_stream);
+int quamba_ssd_decode_step_q8_gated(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                    const quamba_ssd_gate_t *gate, const float *state_scales, const int8_t *x,
+                                    const int8_t *B, const int8_t *C, const float *dt, const float *A, const float *D,
+                                    int8_t *state_q, uint16_t *y, void *hip_stream);
+
+/*
  * The same decode step on an 8-BIT CACHED STATE (Appendix E, "Quantizing cached SSM states"): the state is cached as
  * int8 codes whose scales reuse the m x n (head cluster, channel range) cells of x and differ per state, i.e.
  * d_state x m x n scales per state group.  One step de-quantizes the state (inverse of Eq. 1), applies Eq. 2, forms y

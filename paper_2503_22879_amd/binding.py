@@ -17,6 +17,7 @@ FLAG_NO_CHANNEL_SPLIT = 0x4
 
 EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "quamba_ssd_decode_step",
                     "quamba_ssd_decode_step_q8", "quamba_ssd_quantize_state", "quamba_state_scales",
+                    "quamba_ssd_prefill_gated", "quamba_ssd_decode_step_gated", "quamba_ssd_decode_step_q8_gated",
                     "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x",
                     "quamba_quantize_groups", "quamba_strerror")
 
@@ -40,6 +41,29 @@ class _ScalesStruct(C.Structure):
                 ("B_scales", C.c_void_p), ("C_scales", C.c_void_p)]
 
 
+class _GateStruct(C.Structure):
+    """quamba_ssd_gate_t"""
+    _fields_ = [("z", C.c_void_p), ("z_scale", C.c_float), ("dt_q", C.c_void_p), ("dt_scale", C.c_float),
+                ("dt_bias", C.c_void_p)]
+
+
+@dataclass
+class Gate:
+    """Optional 8-bit side inputs (device tensors): gate codes z with their scale, and / or the codes of the step
+    size's pre-activation with their scale and the per-head bias."""
+    z: object = None
+    z_scale: float = 0.0
+    dt_q: object = None
+    dt_scale: float = 0.0
+    dt_bias: object = None
+
+    def struct(self, z_shape, dt_shape, nheads) -> _GateStruct:
+        import torch
+        return _GateStruct(_dp(self.z, torch.int8, z_shape, "gate.z"), float(self.z_scale),
+                           _dp(self.dt_q, torch.int8, dt_shape, "gate.dt_q"), float(self.dt_scale),
+                           _dp(self.dt_bias, torch.float32, (nheads,), "gate.dt_bias"))
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -60,6 +84,15 @@ def load_library():
             [C.c_size_t, C.c_void_p]
         lib.quamba_ssd_decode_step.restype = C.c_int
         lib.quamba_ssd_decode_step.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 9
+        lib.quamba_ssd_prefill_gated.restype = C.c_int
+        lib.quamba_ssd_prefill_gated.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct), C.POINTER(_GateStruct)] + \
+            [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]
+        lib.quamba_ssd_decode_step_gated.restype = C.c_int
+        lib.quamba_ssd_decode_step_gated.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct),
+                                                     C.POINTER(_GateStruct)] + [C.c_void_p] * 9
+        lib.quamba_ssd_decode_step_q8_gated.restype = C.c_int
+        lib.quamba_ssd_decode_step_q8_gated.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct),
+                                                        C.POINTER(_GateStruct)] + [C.c_void_p] * 10
         lib.quamba_ssd_decode_step_q8.restype = C.c_int
         lib.quamba_ssd_decode_step_q8.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 10
         lib.quamba_ssd_quantize_state.restype = C.c_int
@@ -138,11 +171,14 @@ def quamba_ssd_prefill_workspace_size(shape: Shape) -> int:
 
 
 def quamba_ssd_prefill(shape: Shape, scales, x, B, Cm, dt, A, D, init_state, y, final_state=None,
-                       workspace=None, stream=None) -> None:
-    """Enqueue the chunked prefill on `stream` (default: torch's current stream).  Tensors are torch device tensors."""
+                       workspace=None, stream=None, gate: Gate | None = None) -> None:
+    """Enqueue the chunked prefill on `stream` (default: torch's current stream).  Tensors are torch device tensors.
+    With `gate`, quamba_ssd_prefill_gated is called (dt may then be None if the gate carries the step-size codes)."""
     import torch
     s = shape
     sc = scales.struct()
+    if gate is not None:
+        return _prefill_gated(s, sc, gate, x, B, Cm, dt, A, D, init_state, y, final_state, workspace, stream)
     ws_ptr = _dp(workspace, name="workspace")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     st_shape = (s.batch, s.nheads, s.headdim, s.d_state)
@@ -161,11 +197,47 @@ def quamba_ssd_prefill(shape: Shape, scales, x, B, Cm, dt, A, D, init_state, y, 
         raise QuambaError(rc, "quamba_ssd_prefill")
 
 
-def quamba_ssd_decode_step(shape: Shape, scales, x, B, Cm, dt, A, D, state, y, stream=None) -> None:
-    """Enqueue one decode step; `state` is updated in place."""
+def _prefill_gated(s, sc, gate, x, B, Cm, dt, A, D, init_state, y, final_state, workspace, stream) -> None:
+    import torch
+    ws_ptr = _dp(workspace, name="workspace")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st_shape = (s.batch, s.nheads, s.headdim, s.d_state)
+    g = gate.struct((s.batch, s.seqlen, s.nheads, s.headdim), (s.batch, s.seqlen, s.nheads), s.nheads)
+    rc = load_library().quamba_ssd_prefill_gated(
+        C.byref(s), C.byref(sc), C.byref(g),
+        _dp(x, torch.int8, (s.batch, s.seqlen, s.nheads, s.headdim), "x"),
+        _dp(B, torch.int8, (s.batch, s.seqlen, s.ngroups, s.d_state), "B"),
+        _dp(Cm, torch.int8, (s.batch, s.seqlen, s.ngroups, s.d_state), "C"),
+        _dp(dt, torch.float32, (s.batch, s.seqlen, s.nheads), "dt"),
+        _dp(A, torch.float32, (s.nheads,), "A"), _dp(D, torch.float32, (s.nheads,), "D"),
+        _dp(init_state, torch.float32, st_shape, "init_state"),
+        _dp(y, torch.float16, (s.batch, s.seqlen, s.nheads, s.headdim), "y"),
+        _dp(final_state, torch.float32, st_shape, "final_state"),
+        ws_ptr, ws_bytes, _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_ssd_prefill_gated")
+
+
+def quamba_ssd_decode_step(shape: Shape, scales, x, B, Cm, dt, A, D, state, y, stream=None,
+                           gate: Gate | None = None) -> None:
+    """Enqueue one decode step; `state` is updated in place.  With `gate`, quamba_ssd_decode_step_gated is called."""
     import torch
     s = shape
     sc = scales.struct()
+    if gate is not None:
+        g = gate.struct((s.batch, s.nheads, s.headdim), (s.batch, s.nheads), s.nheads)
+        rc = load_library().quamba_ssd_decode_step_gated(
+            C.byref(s), C.byref(sc), C.byref(g),
+            _dp(x, torch.int8, (s.batch, s.nheads, s.headdim), "x"),
+            _dp(B, torch.int8, (s.batch, s.ngroups, s.d_state), "B"),
+            _dp(Cm, torch.int8, (s.batch, s.ngroups, s.d_state), "C"),
+            _dp(dt, torch.float32, (s.batch, s.nheads), "dt"),
+            _dp(A, torch.float32, (s.nheads,), "A"), _dp(D, torch.float32, (s.nheads,), "D"),
+            _dp(state, torch.float32, (s.batch, s.nheads, s.headdim, s.d_state), "state"),
+            _dp(y, torch.float16, (s.batch, s.nheads, s.headdim), "y"), _stream_ptr(stream))
+        if rc != 0:
+            raise QuambaError(rc, "quamba_ssd_decode_step_gated")
+        return
     rc = load_library().quamba_ssd_decode_step(
         C.byref(s), C.byref(sc),
         _dp(x, torch.int8, (s.batch, s.nheads, s.headdim), "x"),
@@ -179,12 +251,29 @@ def quamba_ssd_decode_step(shape: Shape, scales, x, B, Cm, dt, A, D, state, y, s
         raise QuambaError(rc, "quamba_ssd_decode_step")
 
 
-def quamba_ssd_decode_step_q8(shape: Shape, scales, state_scales, x, B, Cm, dt, A, D, state_q, y, stream=None) -> None:
-    """Enqueue one decode step on the 8-bit cached state; `state_q` (int8) is updated in place."""
+def quamba_ssd_decode_step_q8(shape: Shape, scales, state_scales, x, B, Cm, dt, A, D, state_q, y, stream=None,
+                              gate: Gate | None = None) -> None:
+    """Enqueue one decode step on the 8-bit cached state; `state_q` (int8) is updated in place.  With `gate` (z only),
+    quamba_ssd_decode_step_q8_gated is called."""
     import torch
     s = shape
     sc = scales.struct()
     ncell = s.ngroups * s.n_head_clusters * s.n_chan_clusters
+    if gate is not None:
+        g = gate.struct((s.batch, s.nheads, s.headdim), (s.batch, s.nheads), s.nheads)
+        rc = load_library().quamba_ssd_decode_step_q8_gated(
+            C.byref(s), C.byref(sc), C.byref(g),
+            _dp(state_scales, torch.float32, (ncell, s.d_state), "state_scales"),
+            _dp(x, torch.int8, (s.batch, s.nheads, s.headdim), "x"),
+            _dp(B, torch.int8, (s.batch, s.ngroups, s.d_state), "B"),
+            _dp(Cm, torch.int8, (s.batch, s.ngroups, s.d_state), "C"),
+            _dp(dt, torch.float32, (s.batch, s.nheads), "dt"),
+            _dp(A, torch.float32, (s.nheads,), "A"), _dp(D, torch.float32, (s.nheads,), "D"),
+            _dp(state_q, torch.int8, (s.batch, s.nheads, s.headdim, s.d_state), "state_q"),
+            _dp(y, torch.float16, (s.batch, s.nheads, s.headdim), "y"), _stream_ptr(stream))
+        if rc != 0:
+            raise QuambaError(rc, "quamba_ssd_decode_step_q8_gated")
+        return
     rc = load_library().quamba_ssd_decode_step_q8(
         C.byref(s), C.byref(sc), _dp(state_scales, torch.float32, (ncell, s.d_state), "state_scales"),
         _dp(x, torch.int8, (s.batch, s.nheads, s.headdim), "x"),

@@ -1,4 +1,6 @@
 // The C-ABI layer: argument validation (before anything is enqueued) and kernel dispatch.
+#include <cmath>
+
 #include "quamba_internal.h"
 
 namespace {
@@ -44,7 +46,25 @@ quamba::SsdArgs pack(const quamba_ssd_shape_t *s, const quamba_ssd_scales_t *sc,
     a.init_state = init;
     a.state = state;
     a.y = y;
+    a.z = nullptr; a.z_scale = 0.0f; a.dt_q = nullptr; a.dt_scale = 0.0f; a.dt_bias = nullptr;
     return a;
+}
+
+// Validates the optional side inputs and copies them into the launch arguments.  `dt` may be NULL only when the
+// step size comes as codes.
+int apply_gate(const quamba_ssd_gate_t *gate, const float *dt, quamba::SsdArgs *a)
+{
+    if (!gate || !gate->dt_q) {
+        if (!dt) return QUAMBA_ENULL;
+    } else {
+        if (!(gate->dt_scale > 0.0f) || !std::isfinite(gate->dt_scale)) return QUAMBA_EINVAL;
+        a->dt_q = gate->dt_q; a->dt_scale = gate->dt_scale; a->dt_bias = gate->dt_bias;
+    }
+    if (gate && gate->z) {
+        if (!(gate->z_scale > 0.0f) || !std::isfinite(gate->z_scale)) return QUAMBA_EINVAL;
+        a->z = gate->z; a->z_scale = gate->z_scale;
+    }
+    return QUAMBA_OK;
 }
 
 bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
@@ -70,18 +90,30 @@ extern "C" int quamba_ssd_prefill(const quamba_ssd_shape_t *shape, const quamba_
                                   const float *D, const float *init_state, uint16_t *y, float *final_state,
                                   void *workspace, size_t workspace_bytes, void *hip_stream)
 {
+    return quamba_ssd_prefill_gated(shape, scales, nullptr, x, B, C, dt, A, D, init_state, y, final_state, workspace,
+                                    workspace_bytes, hip_stream);
+}
+
+extern "C" int quamba_ssd_prefill_gated(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                        const quamba_ssd_gate_t *gate, const int8_t *x, const int8_t *B,
+                                        const int8_t *C, const float *dt, const float *A, const float *D,
+                                        const float *init_state, uint16_t *y, float *final_state, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream)
+{
     if (!shape) return QUAMBA_ENULL;
     int rc = check_scales(scales);
     if (rc != QUAMBA_OK) return rc;
-    if (!x || !B || !C || !dt || !A || !y) return QUAMBA_ENULL;
+    if (!x || !B || !C || !A || !y) return QUAMBA_ENULL;
     rc = check_shape(shape, true);
     if (rc != QUAMBA_OK) return rc;
     const size_t need = quamba_ssd_prefill_workspace_size(shape);
     if (workspace_bytes < need || (need && !workspace)) return QUAMBA_EWORKSPACE;
-    const bool mfma = use_mfma(shape, x, B, C, y, init_state, final_state);
+    const bool mfma = use_mfma(shape, x, B, C, y, init_state, final_state) && (!gate || aligned16(gate->z));
     if (!mfma && quamba::prefill_generic_lds_bytes(*shape) > kMaxLdsBytes) return QUAMBA_ESHAPE;
 
-    const quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, A, D, init_state, final_state, y);
+    quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, A, D, init_state, final_state, y);
+    rc = apply_gate(gate, dt, &a);
+    if (rc != QUAMBA_OK) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const hipError_t e = mfma ? quamba::launch_prefill_mfma(a, stream) : quamba::launch_prefill_generic(a, stream);
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
@@ -91,13 +123,23 @@ extern "C" int quamba_ssd_decode_step(const quamba_ssd_shape_t *shape, const qua
                                       const int8_t *x, const int8_t *B, const int8_t *C, const float *dt,
                                       const float *A, const float *D, float *state, uint16_t *y, void *hip_stream)
 {
+    return quamba_ssd_decode_step_gated(shape, scales, nullptr, x, B, C, dt, A, D, state, y, hip_stream);
+}
+
+extern "C" int quamba_ssd_decode_step_gated(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                            const quamba_ssd_gate_t *gate, const int8_t *x, const int8_t *B,
+                                            const int8_t *C, const float *dt, const float *A, const float *D,
+                                            float *state, uint16_t *y, void *hip_stream)
+{
     if (!shape) return QUAMBA_ENULL;
     int rc = check_scales(scales);
     if (rc != QUAMBA_OK) return rc;
-    if (!x || !B || !C || !dt || !A || !state || !y) return QUAMBA_ENULL;
+    if (!x || !B || !C || !A || !state || !y) return QUAMBA_ENULL;
     rc = check_shape(shape, false);
     if (rc != QUAMBA_OK) return rc;
-    const quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, A, D, nullptr, state, y);
+    quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, A, D, nullptr, state, y);
+    rc = apply_gate(gate, dt, &a);
+    if (rc != QUAMBA_OK) return rc;
     const hipError_t e = quamba::launch_decode(a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }
@@ -107,14 +149,27 @@ extern "C" int quamba_ssd_decode_step_q8(const quamba_ssd_shape_t *shape, const 
                                          const int8_t *C, const float *dt, const float *A, const float *D,
                                          int8_t *state_q, uint16_t *y, void *hip_stream)
 {
+    return quamba_ssd_decode_step_q8_gated(shape, scales, nullptr, state_scales, x, B, C, dt, A, D, state_q, y,
+                                           hip_stream);
+}
+
+extern "C" int quamba_ssd_decode_step_q8_gated(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                               const quamba_ssd_gate_t *gate, const float *state_scales,
+                                               const int8_t *x, const int8_t *B, const int8_t *C, const float *dt,
+                                               const float *A, const float *D, int8_t *state_q, uint16_t *y,
+                                               void *hip_stream)
+{
     if (!shape) return QUAMBA_ENULL;
+    if (gate && gate->dt_q) return QUAMBA_EINVAL;  // the re-quantization decision is defined on the fp32 dt
     int rc = check_scales(scales);
     if (rc != QUAMBA_OK) return rc;
     if (!state_scales || !x || !B || !C || !dt || !A || !state_q || !y) return QUAMBA_ENULL;
     rc = check_shape(shape, false);
     if (rc != QUAMBA_OK) return rc;
     if (quamba::decode_q8_lds_bytes(*shape) > kMaxLdsBytes) return QUAMBA_ESHAPE;
-    const quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, A, D, nullptr, nullptr, y);
+    quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, A, D, nullptr, nullptr, y);
+    rc = apply_gate(gate, dt, &a);
+    if (rc != QUAMBA_OK) return rc;
     const hipError_t e = quamba::launch_decode_q8(a, state_scales, state_q, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kThreads) void decode_vec_kernel(SsdArgs a)
 
     float *st = a.state + (size_t)bh * P * N + 4 * j;
 
-    const float dt = a.dt[bh];
+    const float dt = step_size(a, bh, h);
     const float dA = expf(dt * a.A[h]);
     const float Dh = a.D ? a.D[h] : 0.0f;
     const float sB = a.B_scales[g] * dt, sC = a.C_scales[g];
@@ -85,7 +85,10 @@ __global__ __launch_bounds__(kThreads) void decode_vec_kernel(SsdArgs a)
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
             const int p = p0 + i * RPI + sub;
-            if (j == 0 && (FULL || p < P)) a.y[(size_t)bh * P + p] = f32_to_f16_bits(fmaf(Dh, xv[p], part[i]));
+            if (j == 0 && (FULL || p < P)) {
+                const float gate = a.z ? silu_of_code(a.z_scale, a.z[(size_t)bh * P + p]) : 1.0f;  // y * SiLU(z)
+                a.y[(size_t)bh * P + p] = f32_to_f16_bits(fmaf(Dh, xv[p], part[i]) * gate);
+            }
         }
     }
 }
@@ -102,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void decode_any_kernel(SsdArgs a)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     stage_x(a, bh, h, xv);
     __syncthreads();
-    const float dt = a.dt[bh];
+    const float dt = step_size(a, bh, h);
     const float dA = expf(dt * a.A[h]);
     const float Dh = a.D ? a.D[h] : 0.0f;
     const float sB = a.B_scales[g] * dt, sC = a.C_scales[g];
@@ -121,7 +124,10 @@ __global__ __launch_bounds__(kThreads) void decode_any_kernel(SsdArgs a)
         if (lane == 0) ys[p] = fmaf(Dh, x, part);
     }
     __syncthreads();
-    for (int p = threadIdx.x; p < P; p += kThreads) a.y[(size_t)bh * P + p] = f32_to_f16_bits(ys[p]);
+    for (int p = threadIdx.x; p < P; p += kThreads) {
+        const float gate = a.z ? silu_of_code(a.z_scale, a.z[(size_t)bh * P + p]) : 1.0f;  // y * SiLU(z)
+        a.y[(size_t)bh * P + p] = f32_to_f16_bits(ys[p] * gate);
+    }
 }
 
 template <int N>

@@ -256,7 +256,10 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
             for (int i = 0; i < ROWS; ++i) {
                 const int p = p0 + i * RPI + sub;
                 if (j == 0 && (FULL || p < P))
-                    a.y[bh * P + p] = f32_to_f16_bits(__builtin_fmaf(Dh, xv[i], sC * acc[i]));
+                {
+                    const float gate = a.z ? silu_of_code(a.z_scale, a.z[bh * P + p]) : 1.0f;  // y * SiLU(z)
+                    a.y[bh * P + p] = f32_to_f16_bits(__builtin_fmaf(Dh, xv[i], sC * acc[i]) * gate);
+                }
             }
         }
     }
@@ -292,7 +295,10 @@ __global__ __launch_bounds__(kThreads) void decode_q8_any_kernel(SsdArgs a, cons
             row[n] = (int8_t)(code_bits(hn * irow[n]) & 0xffu);
         }
         acc = group_sum<64>(acc);
-        if (lane == 0) a.y[(size_t)bh * P + p] = f32_to_f16_bits(__builtin_fmaf(Dh, t.xv[p], acc));
+        if (lane == 0) {
+            const float gate = a.z ? silu_of_code(a.z_scale, a.z[(size_t)bh * P + p]) : 1.0f;  // y * SiLU(z)
+            a.y[(size_t)bh * P + p] = f32_to_f16_bits(__builtin_fmaf(Dh, t.xv[p], acc) * gate);
+        }
     }
 }
 

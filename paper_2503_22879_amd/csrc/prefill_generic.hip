@@ -54,11 +54,11 @@ __global__ __launch_bounds__(kThreads) void prefill_generic_kernel(SsdArgs a)
         }
         for (int e = tid; e < nt * N; e += kThreads) {
             const int t = e / N, n = e - t * N;
-            const float dt = a.dt[(tok0 + t) * H + h];
+            const float dt = step_size(a, (tok0 + t) * H + h, h);
             Bs[e] = dt * sB * (float)a.B[((tok0 + t) * G + g) * N + n];
             Cs[e] = sC * (float)a.C[((tok0 + t) * G + g) * N + n];
         }
-        for (int t = tid; t < nt; t += kThreads) dAs[t] = expf(a.dt[(tok0 + t) * H + h] * Ah);
+        for (int t = tid; t < nt; t += kThreads) dAs[t] = expf(step_size(a, (tok0 + t) * H + h, h) * Ah);
         __syncthreads();
         for (int p = wave; p < P; p += kWaves) {
             for (int t = 0; t < nt; ++t) {
@@ -76,8 +76,10 @@ __global__ __launch_bounds__(kThreads) void prefill_generic_kernel(SsdArgs a)
         __syncthreads();
         for (int e = tid; e < nt * P; e += kThreads) {
             const int t = e / P, p = e - t * P;
-            const _Float16 v = (_Float16)ys[e];
-            a.y[((tok0 + t) * H + h) * P + p] = __builtin_bit_cast(uint16_t, v);
+            const size_t o = ((tok0 + t) * H + h) * P + p;
+            const float gate = a.z ? silu_of_code(a.z_scale, a.z[o]) : 1.0f;  // y * SiLU(z), Section 3.2
+            const _Float16 v = (_Float16)(ys[e] * gate);
+            a.y[o] = __builtin_bit_cast(uint16_t, v);
         }
     }
     if (a.state) {

@@ -197,7 +197,8 @@ __device__ __forceinline__ int block_to_bh(const SsdArgs &a, int i)
 // PT: 32-channel tiles per workgroup.  2: one workgroup per (sequence, head).  1: two workgroups per head, each with
 // half of the channels, its own half of the state and its own copy of the G^T work; chosen when there are fewer
 // heads in the batch than compute units, so that the whole chip works on short batches.
-template <bool PRECISE, int PT>
+// GATED: the output is multiplied by SiLU(z) of the caller's int8 gate codes (Section 3.2) in the epilogue.
+template <bool PRECISE, int PT, bool GATED>
 __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
 {
     typedef Lds<PT> LY;
@@ -406,6 +407,17 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (c + 1 < nchunks) issue_c_rows(c + 1);
+                // gate codes of the lane's outputs: 4 consecutive channels (one dword) per register group, loaded here
+                // so that they have arrived when the epilogue needs them
+                uint32_t zq[PT][4];
+                if (GATED) {
+                    const int8_t *zrow = a.z + ((tokbase + min(tl, nv - 1)) * H + h) * kP + p_base + 4 * hb;
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg)
+                            zq[pt][rg] = *reinterpret_cast<const uint32_t *>(zrow + pt * 32 + 8 * rg);
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 {  // diagonal block pair: per-element decay, causal mask, plain x codes
                     f16x8 xd[2][PT];
@@ -489,7 +501,11 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                                 const int rg = 2 * j + e;
                                 f16x4 o;
 #pragma unroll
-                                for (int i = 0; i < 4; ++i) o[i] = (_Float16)(k4[rg][i] * acc[pt][4 * rg + i]);
+                                for (int i = 0; i < 4; ++i) {
+                                    float v = k4[rg][i] * acc[pt][4 * rg + i];
+                                    if (GATED) v *= silu_of_code(a.z_scale, (int8_t)(zq[pt][rg] >> (8 * i)));
+                                    o[i] = (_Float16)v;
+                                }
                                 const u32x2 ow = __builtin_bit_cast(u32x2, o);
                                 w[e][0] = ow[0];
                                 w[e][1] = ow[1];
@@ -518,7 +534,9 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                                     const int p = pt * 32 + 8 * rg + 4 * hb + i;
                                     const _Float16 *xrow = reinterpret_cast<const _Float16 *>(s_xs) + tq * kXsStride;
                                     const float xc = (float)xrow[p] * (1.0f / kXs);
-                                    o[i] = (_Float16)(s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc));
+                                    float v = s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc);
+                                    if (GATED) v *= silu_of_code(a.z_scale, (int8_t)(zq[pt][rg] >> (8 * i)));
+                                    o[i] = (_Float16)v;
                                 }
                                 const u32x2 ow = __builtin_bit_cast(u32x2, o);
                                 w[e][0] = ow[0];
@@ -583,8 +601,14 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
             const int8_t *bbase = a.B + (tokbase * G + g) * kN;
             const char *dbase = reinterpret_cast<const char *>(a.dt + tokbase * H + h);
             if (wave == 0) {
-                dt0 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane, nv - 1) * dt_row);
-                dt1 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane + 1, nv - 1) * dt_row);
+                if (a.dt_q) {  // codes of the pre-activation: kept as they arrive, turned into dt where they are used
+                    const int8_t *qbase = a.dt_q + tokbase * H + h;
+                    dt0 = __builtin_bit_cast(float, (int)qbase[(uint32_t)min(2 * lane, nv - 1) * (uint32_t)H]);
+                    dt1 = __builtin_bit_cast(float, (int)qbase[(uint32_t)min(2 * lane + 1, nv - 1) * (uint32_t)H]);
+                } else {
+                    dt0 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane, nv - 1) * dt_row);
+                    dt1 = *reinterpret_cast<const float *>(dbase + (uint32_t)min(2 * lane + 1, nv - 1) * dt_row);
+                }
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -613,6 +637,13 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
             //   in fp16: ws = wq, wd
             // All exponents are <= 0 except in w2, which may overflow under extreme decay (it is not used then). ----
             if (wave == 0) {
+                if (a.dt_q) {  // step size = softplus(s_dt * code + bias) (Section 3.2)
+                    const float bias = a.dt_bias ? a.dt_bias[h] : 0.0f;
+                    const float v0 = a.dt_scale * (float)__builtin_bit_cast(int, dt0) + bias;
+                    const float v1 = a.dt_scale * (float)__builtin_bit_cast(int, dt1) + bias;
+                    dt0 = fmaxf(v0, 0.0f) + log1pf(expf(-fabsf(v0)));
+                    dt1 = fmaxf(v1, 0.0f) + log1pf(expf(-fabsf(v1)));
+                }
                 if (2 * lane >= nv) dt0 = 0.0f;  // padded steps: dt = 0
                 if (2 * lane + 1 >= nv) dt1 = 0.0f;
                 const float a0 = dt0 * Ah, a1 = dt1 * Ah;
@@ -783,37 +814,43 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 }
             }
         }
-        }
     }
+}
 
-    }  // namespace
+}  // namespace
 
-    bool prefill_mfma_supports(const quamba_ssd_shape_t &s) { return s.headdim == kP && s.d_state == kN; }
+bool prefill_mfma_supports(const quamba_ssd_shape_t &s) { return s.headdim == kP && s.d_state == kN; }
 
-    namespace {
+namespace {
 
-    template <bool PRECISE, int PT>
-    hipError_t launch_scan(const SsdArgs &a, hipStream_t stream)
-    {
-        constexpr int lds = Lds<PT>::kBytes;
-        const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT)));
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((prefill_mfma_kernel<PRECISE, PT>), grid, dim3(kThreads), lds, stream, a);
-        return hipGetLastError();
-    }
+template <bool PRECISE, int PT, bool GATED>
+hipError_t launch_scan_gated(const SsdArgs &a, hipStream_t stream)
+{
+    constexpr int lds = Lds<PT>::kBytes;
+    const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT)));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT, GATED>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((prefill_mfma_kernel<PRECISE, PT, GATED>), grid, dim3(kThreads), lds, stream, a);
+    return hipGetLastError();
+}
 
-    // Compute units of the current device (cached per device id).
-    int compute_units()
-    {
-        static int cached[64];
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-        if (cached[dev] == 0) {
-            int n = 0;
-            if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-            cached[dev] = n;
+template <bool PRECISE, int PT>
+hipError_t launch_scan(const SsdArgs &a, hipStream_t stream)
+{
+    return a.z ? launch_scan_gated<PRECISE, PT, true>(a, stream) : launch_scan_gated<PRECISE, PT, false>(a, stream);
+}
+
+// Compute units of the current device (cached per device id).
+int compute_units()
+{
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
     }
     return cached[dev];
 }

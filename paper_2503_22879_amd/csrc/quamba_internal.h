@@ -23,7 +23,29 @@ struct SsdArgs {
     const float *init_state;   // may be null (prefill)
     float *state;              // decode: in/out; prefill: final state or null
     uint16_t *y;               // fp16 bits
+    // optional 8-bit side inputs (quamba_ssd_gate_t); all null / zero when absent
+    const int8_t *z;           // gate codes, laid out like x
+    float z_scale;
+    const int8_t *dt_q;        // codes of the step size's pre-activation, laid out like dt (dt is then unused)
+    float dt_scale;
+    const float *dt_bias;      // [nheads] or null
 };
+
+// Step size of (token or sequence) index idx of head h: the caller's fp32 dt, or softplus(s_dt * code + bias[h])
+// (Section 3.2: Delta = softplus(F(x)) with the bias) when the pre-activation comes as int8 codes.
+__device__ __forceinline__ float step_size(const SsdArgs &a, size_t idx, int h)
+{
+    if (!a.dt_q) return a.dt[idx];
+    const float v = a.dt_scale * (float)a.dt_q[idx] + (a.dt_bias ? a.dt_bias[h] : 0.0f);
+    return fmaxf(v, 0.0f) + log1pf(expf(-fabsf(v)));  // log(1 + exp(v)) without overflow
+}
+
+// SiLU(z) = z / (1 + exp(-z)) of a gate code (Section 3.2: the optional branch z multiplies the SSM output).
+__device__ __forceinline__ float silu_of_code(float z_scale, int code)
+{
+    const float z = z_scale * (float)code;
+    return z * __frcp_rn(1.0f + __expf(-z));
+}
 
 // Index of the (group, head cluster, channel range) cell of channel position p of head h in the cluster boundary
 // tables (Section 4.1: m x n cells per group).  The cluster index is the number of boundaries at or below the

@@ -55,3 +55,18 @@ def make_state_cache(s: W.LayerShape, sc, r, seed: int, batch=None, calib_sequen
     ss = oracle.state_scales_from_absmax(sc, mx, s.ngroups)
     st = W.reorder_state(W.draw_cached_state(s, seed, batch=batch), r["head_perm"], r["chan_perm"])
     return ss, oracle.quantize_state(sc, ss, st, s.ngroups), st
+
+
+def make_gate_inputs(s: W.LayerShape, r, seed: int, decode: bool = False, step: int = 0):
+    """int8 codes of the optional side inputs in the reordered order, quantized with the oracle's Eq. 1 and one static
+    scale per tensor (absolute maximum of the draw / 127).  Returns dict(z, z_scale, dt_q, dt_scale, dt_bias)."""
+    raw = W.draw_gate(s, seed, decode=decode, step=step)
+    hp, cp = r["head_perm"], r["chan_perm"]
+    z = np.take(raw["z"], hp, axis=-2)
+    z = np.take_along_axis(z, np.broadcast_to(cp, z.shape), axis=-1)
+    pre = np.take(raw["dt_pre"], hp, axis=-1)
+    bias = raw["dt_bias"][hp]
+    zs = np.float32(np.abs(raw["z"]).max() / 127.0)
+    ds = np.float32(np.abs(raw["dt_pre"]).max() / 127.0)
+    return {"z": oracle.quantize(z, zs), "z_scale": float(zs), "dt_q": oracle.quantize(pre, ds),
+            "dt_scale": float(ds), "dt_bias": np.ascontiguousarray(bias, np.float32)}

@@ -108,6 +108,29 @@ def test_q8_entry_points_reject_bad_arguments_without_a_device():
     assert lib.quamba_ssd_quantize_state(C.byref(_shape(batch=0)), C.byref(sc), p, p, p, None) == -2
 
 
+def test_gated_entry_points_reject_bad_arguments_without_a_device():
+    lib = q.load_library()
+    dummy = C.create_string_buffer(64)
+    p = C.addressof(dummy)
+    from paper_2503_22879_amd.binding import _ScalesStruct, _GateStruct
+    sc = _ScalesStruct(p, p, p, p, p)
+    pre = [p] * 10                                   # x B C dt A D init y final workspace
+    # dt may be NULL only when the gate carries the step-size codes
+    args = list(pre); args[3] = None
+    assert lib.quamba_ssd_prefill_gated(C.byref(_shape()), C.byref(sc), None, *args, 0, None) == -1
+    g = _GateStruct(None, 0.0, p, 0.0, None)          # codes with a zero scale
+    assert lib.quamba_ssd_prefill_gated(C.byref(_shape()), C.byref(sc), C.byref(g), *args, 0, None) == -5
+    g = _GateStruct(p, float("nan"), None, 0.0, None)  # gate with a non-finite scale
+    assert lib.quamba_ssd_prefill_gated(C.byref(_shape()), C.byref(sc), C.byref(g), *pre, 0, None) == -5
+    dec = [p] * 8                                     # x B C dt A D state y
+    g = _GateStruct(p, -1.0, None, 0.0, None)
+    assert lib.quamba_ssd_decode_step_gated(C.byref(_shape()), C.byref(sc), C.byref(g), *dec, None) == -5
+    args = list(dec); args[3] = None
+    assert lib.quamba_ssd_decode_step_gated(C.byref(_shape()), C.byref(sc), None, *args, None) == -1
+    g = _GateStruct(None, 0.0, p, 0.1, None)          # the 8-bit-state step refuses step-size codes
+    assert lib.quamba_ssd_decode_step_q8_gated(C.byref(_shape()), C.byref(sc), C.byref(g), p, *dec, None) == -5
+
+
 def test_binding_fails_loudly_without_library(monkeypatch):
     import paper_2503_22879_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)

@@ -154,6 +154,20 @@ def draw_state(s: LayerShape, seed: int = 0, batch: int | None = None) -> np.nda
     return st
 
 
+def draw_gate(s: LayerShape, seed: int = 0, decode: bool = False, step: int = 0) -> dict:
+    """Raw floats of the SSD kernel's optional side inputs, in the model's ORIGINAL head/channel order: the gate branch
+    z (standard normal times a per-channel magnitude, like x), the step size's pre-activation without its bias
+    (N(-3, 1) minus the bias) and the per-head bias (N(0, 0.5)).  decode=True draws one token ([b,H,P] / [b,H])."""
+    g = _rng(seed, 30 + (1000 + step if decode else 0))
+    gb = _rng(seed, 31)
+    tok = (s.batch,) if decode else (s.batch, s.seqlen)
+    zsig = np.exp(0.5 * _rng(seed, 32).standard_normal((s.nheads, s.headdim))).astype(np.float32)
+    z = g.standard_normal(tok + (s.nheads, s.headdim), dtype=np.float32) * zsig
+    bias = (0.5 * gb.standard_normal(s.nheads)).astype(np.float32)
+    pre = (g.standard_normal(tok + (s.nheads,), dtype=np.float32) - np.float32(3.0)) - bias
+    return {"z": z, "dt_pre": pre.astype(np.float32), "dt_bias": bias}
+
+
 def draw_cached_state(s: LayerShape, seed: int = 0, batch: int | None = None, stream: int = 21) -> np.ndarray:
     """Cached SSM state [b,H,P,N] float32 with the structure a state built from x and B has: the magnitude of
     element (h,p,n) follows the channel profile of x (rows, in the model's ORIGINAL head/channel order, like x) times
