@@ -101,6 +101,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode leg")
     ap.add_argument("--precise-state", action="store_true", help="also return the final fp32 state (two-term state path)")
+    ap.add_argument("--gated", action="store_true",
+                    help="prefill through quamba_ssd_prefill_gated: int8 gate z and int8 step-size codes (not the "
+                         "headline configuration; config.side_inputs says so)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 256 MiB three times (read 256 MiB + write 256 MiB each): the "
                          "known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
@@ -132,8 +135,23 @@ def main() -> int:
     fin = torch.empty((s.batch, s.nheads, s.headdim, s.d_state), device=dev) if args.precise_state else None
     ws = torch.empty(max(1, q.quamba_ssd_prefill_workspace_size(shape)), dtype=torch.uint8, device=dev)
 
+    gate = None
+    if args.gated:  # side inputs quantized with the library's host Eq. 1 entry point, one static scale per tensor
+        rawg = W.draw_gate(s, seed)
+        zr = np.take(rawg["z"], head_perm, axis=-2)
+        zr = np.take_along_axis(zr, np.broadcast_to(chan_perm, zr.shape), axis=-1)
+        zs = np.float32(np.abs(zr).max() / 127.0)
+        ds = np.float32(np.abs(rawg["dt_pre"]).max() / 127.0)
+        zq = q.quamba_quantize_groups(zr.reshape(-1, 1, s.nheads * s.headdim), np.array([zs], np.float32))
+        dq = q.quamba_quantize_groups(np.take(rawg["dt_pre"], head_perm, axis=-1).reshape(-1, 1, s.nheads),
+                                      np.array([ds], np.float32))
+        gate = q.Gate(z=torch.from_numpy(zq.reshape(zr.shape)).to(dev), z_scale=float(zs),
+                      dt_q=torch.from_numpy(dq.reshape(s.batch, s.seqlen, s.nheads)).to(dev), dt_scale=float(ds),
+                      dt_bias=torch.from_numpy(np.ascontiguousarray(rawg["dt_bias"][head_perm])).to(dev))
+        del rawg, zr, zq, dq
+
     def prefill():
-        q.quamba_ssd_prefill(shape, dsc, t["x"], t["B"], t["C"], t["dt"], A, D, None, y, fin, ws)
+        q.quamba_ssd_prefill(shape, dsc, t["x"], t["B"], t["C"], t["dt"], A, D, None, y, fin, ws, gate=gate)
 
     ms, wall_ms = time_region(torch, prefill, args.steps, args.warmup)
     tokens = s.batch * s.seqlen
@@ -151,7 +169,8 @@ def main() -> int:
         "config": {"workload": f"{s.name}: Mamba2-8B-shaped SSD layer prefill" if "8b" in s.name else s.name,
                    "batch": s.batch, "seqlen": s.seqlen, "nheads": s.nheads, "headdim": s.headdim,
                    "d_state": s.d_state, "ngroups": s.ngroups, "chunk": s.chunk, "clusters": f"{s.m}x{s.n} per group",
-                   "final_state": bool(args.precise_state)},
+                   "final_state": bool(args.precise_state),
+                   "side_inputs": "int8 gate z and int8 step-size codes" if args.gated else "none"},
         "roofline": {"kernel": "prefill_mfma_kernel", "bound": "mfma", "achieved": tflops,
                      "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_F16_PEAK_TFLOPS,
                      "traffic": traffic,

@@ -81,9 +81,14 @@ struct Lds {
     static constexpr int kOffHs = kOffBq + kQ * kBqStride;   // fp16 [kPw][136]
     static constexpr int kOffXs = kOffHs + 2 * kPw * kHsStride;  // fp16 [128][kXsStride]
     static constexpr int kBytes = kOffXs + 2 * kQ * kXsStride;
+    // gated variant only: the chunk's gate codes, int8 [128][kZsStride], plain token order
+    static constexpr int kZsStride = 32 * PT + 8;
+    static constexpr int kOffZs = kBytes;
+    static constexpr int kOffSilu = kOffZs + kQ * kZsStride;  // float[256]: SiLU of every possible gate code
+    static constexpr int kBytesGated = kOffSilu + 4 * 256;
     static_assert(kOffBq % 16 == 0 && kOffHs % 16 == 0 && kOffXs % 16 == 0, "LDS arrays must be 16-byte aligned");
 };
-static_assert(Lds<2>::kBytes <= 80 * 1024, "two workgroups must fit the 160 KB LDS of a gfx950 compute unit");
+static_assert(Lds<2>::kBytesGated <= 80 * 1024, "two workgroups must fit the 160 KB LDS of a gfx950 compute unit");
 
 // 2^x by the hardware instruction (prefix sums are carried in log2 units, so no multiply by log2 e is needed).
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -215,6 +220,9 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
     unsigned char *s_bq = smem + LY::kOffBq;
     _Float16 *s_hs = reinterpret_cast<_Float16 *>(smem + LY::kOffHs);
     unsigned char *s_xs = smem + LY::kOffXs;  // fp16 rows, addressed in bytes
+    unsigned char *s_zs = smem + LY::kOffZs;  // gate codes (GATED only)
+    float *s_silu = reinterpret_cast<float *>(smem + LY::kOffSilu);  // SiLU(z_scale * code), indexed by the code's byte
+    constexpr int kZsStride = LY::kZsStride;
 
     const int L = a.s.seqlen, H = a.s.nheads, G = a.s.ngroups;
     // with two workgroups per head, ids i and i + 8 (same XCD, and the same compute unit when two workgroups fit one)
@@ -261,6 +269,8 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
     const float d_sel = d_by_mfma ? d_acc : 0.0f;
 
     if (tid < kPw) s_sx[tid] = x_scale_lookup(a, h, p_base + tid) * (d_by_mfma ? y_scale : 1.0f);
+    // a gate code has 256 values: their SiLU is tabulated once (exp and reciprocal are quarter-rate instructions)
+    if (GATED && tid < 256) s_silu[tid] = silu_of_code(a.z_scale, (int8_t)tid);
     __syncthreads();
     const int nchunks = (L + kQ - 1) / kQ;
     constexpr float kStScale = kNarrow;
@@ -407,17 +417,6 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (c + 1 < nchunks) issue_c_rows(c + 1);
-                // gate codes of the lane's outputs: 4 consecutive channels (one dword) per register group, loaded here
-                // so that they have arrived when the epilogue needs them
-                uint32_t zq[PT][4];
-                if (GATED) {
-                    const int8_t *zrow = a.z + ((tokbase + min(tl, nv - 1)) * H + h) * kP + p_base + 4 * hb;
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-#pragma unroll
-                        for (int rg = 0; rg < 4; ++rg)
-                            zq[pt][rg] = *reinterpret_cast<const uint32_t *>(zrow + pt * 32 + 8 * rg);
-                }
                 __builtin_amdgcn_sched_barrier(0);
                 {  // diagonal block pair: per-element decay, causal mask, plain x codes
                     f16x8 xd[2][PT];
@@ -486,6 +485,17 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 // token t per register group, and one exchange with the lane 32 positions away (same token) turns two
                 // such groups into 8 consecutive channels, so that every lane stores 16 bytes and a token row gets 32
                 uint16_t *yrow = a.y + ((tokbase + min(tl, nv - 1)) * H + h) * kP + p_base;
+                // gate codes of the lane's outputs (staged by the state waves): 4 consecutive channels, one dword,
+                // per register group
+                uint32_t zq[PT][4];
+                if (GATED) {
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg)
+                            zq[pt][rg] =
+                                *reinterpret_cast<const uint32_t *>(s_zs + tl * kZsStride + pt * 32 + 8 * rg + 4 * hb);
+                }
                 if (d_by_mfma) {
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt) {
@@ -503,7 +513,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                                 for (int i = 0; i < 4; ++i) {
                                     float v = k4[rg][i] * acc[pt][4 * rg + i];
-                                    if (GATED) v *= silu_of_code(a.z_scale, (int8_t)(zq[pt][rg] >> (8 * i)));
+                                    if (GATED) v *= s_silu[(zq[pt][rg] >> (8 * i)) & 0xffu];
                                     o[i] = (_Float16)v;
                                 }
                                 const u32x2 ow = __builtin_bit_cast(u32x2, o);
@@ -535,7 +545,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                                     const _Float16 *xrow = reinterpret_cast<const _Float16 *>(s_xs) + tq * kXsStride;
                                     const float xc = (float)xrow[p] * (1.0f / kXs);
                                     float v = s_sx[p] * fmaf(y_scale, acc[pt][4 * rg + i], Dh * xc);
-                                    if (GATED) v *= silu_of_code(a.z_scale, (int8_t)(zq[pt][rg] >> (8 * i)));
+                                    if (GATED) v *= s_silu[(zq[pt][rg] >> (8 * i)) & 0xffu];
                                     o[i] = (_Float16)v;
                                 }
                                 const u32x2 ow = __builtin_bit_cast(u32x2, o);
@@ -588,6 +598,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
         // return in issue order, hence the loads are issued in the order they are consumed.
         xvec xr[4];
         u32x4 br[4];
+        xvec zr[4];  // gate codes, same rows and columns as xr (GATED only)
         float dt0 = 0.0f, dt1 = 0.0f;
         // Staging lane maps: a thread takes 4 consecutive tokens and 4 PT channels of x (8 lanes cover a row of this
         // workgroup's channels), resp. 16 states of B (8 lanes cover a 128-byte row).
@@ -614,6 +625,9 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
             for (int k = 0; k < 4; ++k) {
                 const uint32_t row = (uint32_t)min(4 * xs4 + k, nv - 1);
                 xr[k] = *reinterpret_cast<const xvec *>(xbase + (row * x_row + (uint32_t)(4 * PT) * xp8));
+                if (GATED)
+                    zr[k] = *reinterpret_cast<const xvec *>(a.z + (tokbase * H + h) * kP + p_base +
+                                                            (row * x_row + (uint32_t)(4 * PT) * xp8));
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -705,6 +719,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                     unsigned char *xs_row = s_xs + ((row0 + k) * kXsStride + 4 * PT * xp8) * 2;
 #pragma unroll
                     for (int q = 0; q < PT; ++q) *reinterpret_cast<f16x4 *>(xs_row + 8 * q) = i8x4_to_f16_xs(w[q]);
+                    if (GATED) *reinterpret_cast<xvec *>(s_zs + (s0 + k) * kZsStride + 4 * PT * xp8) = zr[k];
                 }
             }
             {
@@ -826,7 +841,7 @@ namespace {
 template <bool PRECISE, int PT, bool GATED>
 hipError_t launch_scan_gated(const SsdArgs &a, hipStream_t stream)
 {
-    constexpr int lds = Lds<PT>::kBytes;
+    constexpr int lds = GATED ? Lds<PT>::kBytesGated : Lds<PT>::kBytes;
     const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT)));
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT, GATED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
