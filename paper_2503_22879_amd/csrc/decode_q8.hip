@@ -170,18 +170,20 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
         s_dt[threadIdx.x] = dt;
         s_dA[threadIdx.x] = exp_steps(dt * a.A[h]);
     }
-    for (int i = threadIdx.x; i < nb * P; i += kThreads) {
-        const int bb = i / P, p = i - bb * P;
-        s_xf[i] = (float)a.x[((size_t)(b_begin + bb) * H + h) * P + p];
-    }
-    for (int i = threadIdx.x; i < nb * N; i += kThreads) {
-        const int bb = i / N, n = i - bb * N;
-        const size_t o = ((size_t)(b_begin + bb) * G + g) * N + n;
-        s_Bv[i] = sB * (float)a.B[o];
-        s_Cf[i] = (float)a.C[o];
+    // one wave per sequence at a time, lanes over the elements: no integer division in these loops
+    for (int bb = wave; bb < nb; bb += kWaves) {
+        const size_t bh = (size_t)(b_begin + bb) * H + h, bg = (size_t)(b_begin + bb) * G + g;
+        for (int p = lane; p < P; p += 64) s_xf[bb * P + p] = (float)a.x[bh * P + p];
+        for (int n = lane; n < N; n += 64) {
+            s_Bv[bb * N + n] = sB * (float)a.B[bg * N + n];
+            s_Cf[bb * N + n] = (float)a.C[bg * N + n];
+        }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < nb * nc * N; i += kThreads) s_sd[i] = s_dA[i / (nc * N)] * t.s_tab[i % (nc * N)];
+    for (int bb = 0; bb < nb; ++bb) {
+        const float dA = s_dA[bb];
+        for (int i = threadIdx.x; i < nc * N; i += kThreads) s_sd[bb * nc * N + i] = dA * t.s_tab[i];
+    }
     __syncthreads();
 
     for (int p0 = wave * RPI * ROWS; p0 < P; p0 += kWaves * RPI * ROWS) {
