@@ -52,6 +52,12 @@ Q8_OPS_PER_ELEMENT = 8
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3: fp32 vector instructions per second x 64 lanes, unpacked, unfused
 
 
+def HADAMARD_OPS_PER_VALUE(n: int) -> int:
+    """fp32 vector operations per value of the quantized Hadamard transform: one add or subtract per butterfly stage,
+    then the scale, the clamp and the rounding add of Eq. 1."""
+    return n.bit_length() - 1 + 3
+
+
 def decode_bytes(s: W.LayerShape, state_bytes: int = 4) -> float:
     b, H, P, N, G = s.batch, s.nheads, s.headdim, s.d_state, s.ngroups
     return float(2 * state_bytes * b * H * P * N + b * H * P + 2 * b * G * N + 4 * b * H + 2 * b * H * P)
@@ -100,6 +106,8 @@ def main() -> int:
     ap.add_argument("--workload", default="m2_8b_b4", choices=["m2_8b_b4", "m2_8b_b1", "m2_2p7b", "m2_130m"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode leg")
+    ap.add_argument("--no-hadamard", action="store_true",
+                    help="skip the quantized Hadamard transform of the prefill output")
     ap.add_argument("--precise-state", action="store_true", help="also return the final fp32 state (two-term state path)")
     ap.add_argument("--gated", action="store_true",
                     help="prefill through quamba_ssd_prefill_gated: int8 gate z and int8 step-size codes (not the "
@@ -203,6 +211,46 @@ def main() -> int:
                                          f"after the first, {sum(cpu_times):.1f} s of CPU wall time in total"}
         out["parity_spot_check"] = {"max_abs_err_over_max_abs_ref": err, "bar": 2e-3, "pairs": len(pairs)}
         del yref, yg
+
+    # ------------------------------------------------ quantized Hadamard transform of the prefill output (Section 4.2)
+    n_had = s.nheads * s.headdim
+    if not args.no_hadamard and n_had & (n_had - 1) == 0:
+        rows = s.batch * s.seqlen
+        # static scale of the transformed output: 4 standard deviations of a transformed value map to code 127
+        # (its variance is n times the mean square of y); the scale is an input of the method, not part of it
+        s_y = float(4.0 * (n_had * y.float().pow(2).mean()).sqrt().item() / 127.0)
+        yq = torch.empty((s.batch, s.seqlen, n_had), dtype=torch.int8, device=dev)
+        yflat = y.view(s.batch, s.seqlen, n_had)
+
+        def hadamard():
+            q.quamba_hadamard_quantize(yflat, s_y, yq)
+
+        hms, hwall = time_region(torch, hadamard, args.steps, max(args.warmup, 4))
+        hbytes = 3.0 * rows * n_had
+        hgbs = hbytes / (hms * 1e-3) / 1e9
+        hops = HADAMARD_OPS_PER_VALUE(n_had) * rows * n_had
+        out["hadamard"] = {
+            "metric": "quantized Hadamard transform us/call", "value": hms * 1e3, "unit": "us/call", "steps": args.steps,
+            "higher_is_better": False, "wall_us_per_call": hwall * 1e3,
+            "config": {"workload": "%s output: %d tokens x %d channels, fp16 in, int8 out, the scan's own y as input"
+                                   % (s.name, rows, n_had), "s_y": s_y},
+            "roofline": {"kernel": "hadamard_quantize_kernel", "bound": "hbm", "achieved": hgbs, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": hgbs / HBM_PEAK_GBS,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get(s.name + "_hadamard")},
+            "roofline_alu": {"kernel": "hadamard_quantize_kernel", "bound": "alu",
+                             "achieved": hops / (hms * 1e-3) / 1e12, "peak": ALU_PEAK_TOPS,
+                             "unit": "Top/s (fp32 vector instructions x 64 lanes)",
+                             "frac": hops / (hms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
+                             "note": "log2(n) butterfly operations + scale, clamp and rounding add per value"},
+            "saturated_fraction": float(((yq == 127) | (yq == -128)).float().mean().item()),
+        }
+        if not args.no_cpu:   # spot check against the oracle: 16 rows spread over the launch, codes bit for bit
+            import oracle
+            pick = torch.arange(0, rows, rows // 16, device=dev)
+            ref = oracle.hadamard_quantize(yflat.view(rows, n_had)[pick].cpu().numpy(), s_y)
+            out["hadamard"]["parity_spot_check"] = {
+                "rows": int(pick.numel()), "codes_differing": int((yq.view(rows, n_had)[pick].cpu().numpy() != ref).sum())}
+        del yq, yflat
 
     # ------------------------------------------------------------------ decode
     if not args.no_decode:

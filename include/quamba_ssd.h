@@ -203,6 +203,20 @@ int quamba_state_scales(int32_t nheads, int32_t headdim, int32_t ngroups, int32_
                         const float *state_calib_absmax, float *state_scales);
 
 /*
+ * Quantized Hadamard transform of the SSD output (Section 4.2, "Offline Hadamard matrix fusion" and "Efficient
+ * 4-bit/8-bit Mamba blocks"): out = Eq. 1 of (1/s_y) H_n y for every row, H_n the Sylvester-Hadamard matrix of order
+ * n (entries +-1, no normalisation), the 8-bit input of an output projection whose weight carries H_n offline.
+ *   y   device fp16 [rows, n] (the flattened [.., nheads*headdim] output of the scan, gated or not)
+ *   out device int8 [rows, n]; must not overlap y
+ *   n   a power of two, 2 <= n <= 16384;  s_y > 0 the static scale of the transformed output
+ * The transform is evaluated in fp32 as the radix-2 butterfly network with strides 1, 2, 4, ..., n/2 in this order
+ * (stage h replaces (v[i], v[i+h]), i & h == 0, by (v[i] + v[i+h], v[i] - v[i+h])), every operation rounded on its own;
+ * then code = clamp(rint(v * (1/s_y)), -128, 127) with 1/s_y and the product rounded to fp32, ties to even.
+ * Errors: ENULL, ESHAPE (n not a power of two or out of range, rows < 0 or > 2^31 - 1), EINVAL (s_y), EHIP.
+ */
+int quamba_hadamard_quantize(const uint16_t *y, int64_t rows, int32_t n, float s_y, int8_t *out, void *hip_stream);
+
+/*
  * Offline sort-and-cluster (Section 4.1) and the index tables for cluster-aware weight reordering (Section 4.2).
  * HOST function, all pointers host memory.
  *   x_calib_absmax [nheads*headdim]  calibrated per-channel max|x| in the model's original order

@@ -17,7 +17,7 @@ FLAG_NO_CHANNEL_SPLIT = 0x4
 
 EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "quamba_ssd_decode_step",
                     "quamba_ssd_decode_step_q8", "quamba_ssd_quantize_state", "quamba_state_scales",
-                    "quamba_ssd_prefill_gated", "quamba_ssd_decode_step_gated", "quamba_ssd_decode_step_q8_gated",
+                    "quamba_hadamard_quantize", "quamba_ssd_prefill_gated", "quamba_ssd_decode_step_gated", "quamba_ssd_decode_step_q8_gated",
                     "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x",
                     "quamba_quantize_groups", "quamba_strerror")
 
@@ -84,6 +84,8 @@ def load_library():
             [C.c_size_t, C.c_void_p]
         lib.quamba_ssd_decode_step.restype = C.c_int
         lib.quamba_ssd_decode_step.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 9
+        lib.quamba_hadamard_quantize.restype = C.c_int
+        lib.quamba_hadamard_quantize.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
         lib.quamba_ssd_prefill_gated.restype = C.c_int
         lib.quamba_ssd_prefill_gated.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct), C.POINTER(_GateStruct)] + \
             [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]
@@ -316,6 +318,19 @@ def quamba_state_scales(nheads, headdim, ngroups, m, n, d_state, head_cluster_en
     if rc != 0:
         raise QuambaError(rc, "quamba_state_scales")
     return out
+
+
+def quamba_hadamard_quantize(y, s_y: float, out, stream=None) -> None:
+    """Enqueue out = Eq.1((1/s_y) H_n y) over the last axis of the fp16 device tensor y (n a power of two)."""
+    import torch
+    n = y.shape[-1]
+    rows = y.numel() // max(1, n)
+    if rows == 0 and n > 0:
+        return                      # an empty tensor has no device pointer to pass
+    rc = load_library().quamba_hadamard_quantize(_dp(y, torch.float16, name="y"), rows, n, float(s_y),
+                                                 _dp(out, torch.int8, tuple(y.shape), "out"), _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_hadamard_quantize")
 
 
 def quamba_reorder_params(nheads, headdim, ngroups, m, n, d_state, x_calib_absmax, B_calib_absmax,

@@ -191,6 +191,16 @@ extern "C" int quamba_ssd_quantize_state(const quamba_ssd_shape_t *shape, const 
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }
 
+extern "C" int quamba_hadamard_quantize(const uint16_t *y, int64_t rows, int32_t n, float s_y, int8_t *out,
+                                        void *hip_stream)
+{
+    if (!y || !out) return QUAMBA_ENULL;
+    if (n < 2 || n > 16384 || (n & (n - 1)) || rows < 0 || rows > 0x7fffffffLL) return QUAMBA_ESHAPE;
+    if (!(s_y > 0.0f) || !std::isfinite(s_y)) return QUAMBA_EINVAL;
+    const hipError_t e = quamba::launch_hadamard_quantize(y, rows, n, s_y, out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
 extern "C" const char *quamba_strerror(int status)
 {
     switch (status) {

@@ -1,0 +1,245 @@
+// Quantized Hadamard transform of the SSD output (Section 4.2): out = Eq.1((1/s_y) H_n y) per row of n = 2^k values,
+// the 8-bit input of the output projection whose weight carries the matching H_n offline.
+//
+// The transform is the radix-2 butterfly network with strides 1, 2, 4, ..., n/2 in this order, in fp32, every add and
+// subtract rounded on its own (the codes are integers decided by these roundings, so the order is part of the
+// definition; the header states it).  One workgroup per row at a time.  For n >= 1024 a thread keeps 32 values in
+// registers and the network runs in three phases of up to 5 strides each, with the values redistributed through LDS
+// in between so that the strides of a phase are register-local: phase A on 32 consecutive values (strides 1..16),
+// phase B on values 32 apart (strides 32..512), phase C on values 1024 apart (strides 1024..n/2) for groups of
+// consecutive values, so that the codes leave as dwords.  The row is read once (fp16, 64 contiguous bytes per thread)
+// and written once (int8): 3 bytes of HBM traffic and 17 vector instructions (13 butterflies, a scale, a clamp, a
+// rounding add; no packed fp32) per value.  What bounds the kernel at n = 8192 is neither alone: a row's fp32 image
+// (33 KB of LDS) limits a compute unit to 4 rows in flight, and each row is a serial chain of three arithmetic
+// phases, two LDS exchanges (LDS writes run at about 80 bytes per clock per compute unit) and three barriers.
+#include "quamba_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace quamba {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to nearest even, the code is the sum's low byte
+
+// Eq. 1 with the bounds of an 8-bit code for one value (the paths without packing).
+__device__ __forceinline__ uint32_t code_byte(float r)
+{
+    const float c = __builtin_amdgcn_fmed3f(r, -128.0f, 127.0f);
+    return __builtin_bit_cast(uint32_t, c + kMagic) & 0xffu;
+}
+
+// The same for K = 2 or 4 values packed into the low bytes of a dword: the rounding add writes its low byte straight
+// into byte k of the result through the sub-dword destination select.
+template <int K>
+__device__ __forceinline__ uint32_t codes_packed(const float (&r)[4])
+{
+    float c[4];
+#pragma unroll
+    for (int k = 0; k < K; ++k) c[k] = __builtin_amdgcn_fmed3f(r[k], -128.0f, 127.0f);
+    uint32_t out;
+    asm("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD"
+        : "=v"(out) : "v"(c[0]), "v"(kMagic));
+    asm("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+        : "+v"(out) : "v"(c[1]), "v"(kMagic));
+    if (K == 4) {
+        asm("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(out) : "v"(c[2]), "v"(kMagic));
+        asm("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(out) : "v"(c[3]), "v"(kMagic));
+    }
+    return out;
+}
+
+// In-register butterflies of one phase: v[e], e = 0..31, strides 1..2^(BITS-1) on the register index.
+template <int BITS, int FIRST = 1>
+__device__ __forceinline__ void butterflies(float (&v)[32])
+{
+#pragma unroll
+    for (int h = FIRST; h < (1 << BITS); h <<= 1)
+#pragma unroll
+        for (int e = 0; e < 32; ++e)
+            if ((e & h) == 0) {
+                const float a = v[e], b = v[e + h];
+                v[e] = a + b;
+                v[e + h] = a - b;
+            }
+}
+
+// n = 2^LOGN, 10 <= LOGN <= 14, n/32 threads, as many workgroups as stay resident; each loops over rows
+// blockIdx.x, blockIdx.x + gridDim.x, ... and loads its next row (16 registers of packed fp16) while it works on the
+// current one, so the HBM latency of a row is hidden behind the arithmetic of the row before.
+template <int LOGN>
+__global__ __launch_bounds__(1 << (LOGN - 5)) void hadamard_quantize_kernel(const uint16_t *y, int8_t *out, int rows,
+                                                                            float inv_s)
+{
+    constexpr int N = 1 << LOGN;
+    constexpr int CB = LOGN - 10;       // strides of phase C
+    constexpr int NE = 1 << CB;         // values 1024 apart a thread holds in phase C
+    constexpr int CONSEC = 32 / NE;     // consecutive values per such position (2..32)
+    extern __shared__ float lds[];      // N + N/32 floats
+    const int t = threadIdx.x;
+    const int t_lo = t & 31, t_hi = t >> 5;
+    float v[32];
+    u32x4 nx[4];
+
+    int r = blockIdx.x;  // the launch has no more workgroups than rows
+    {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(y + (size_t)r * N + 32 * t);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) nx[q] = __builtin_nontemporal_load(src + q);
+    }
+    for (; r < rows; r += gridDim.x) {
+        // phase A: values 32 t + e;
+        // stride 1 straight from the packed fp16 pairs: the mixed-precision fused multiply-add takes both halves of a
+        // dword as fp16 sources, lo * 1.0 +- hi in fp32 with one rounding (conversion of fp16 to fp32 is exact, so
+        // this is the fp32 add or subtract of the converted values)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t w = nx[q][i];
+                asm("v_fma_mix_f32 %0, %1, 1.0, %1 op_sel:[0,0,1] op_sel_hi:[1,0,1]" : "=v"(v[8 * q + 2 * i]) : "v"(w));
+                asm("v_fma_mix_f32 %0, %1, 1.0, -%1 op_sel:[0,0,1] op_sel_hi:[1,0,1]"
+                    : "=v"(v[8 * q + 2 * i + 1]) : "v"(w));
+            }
+        if (r + (int)gridDim.x < rows) {
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(y + (size_t)(r + gridDim.x) * N + 32 * t);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) nx[q] = __builtin_nontemporal_load(src + q);
+        }
+        butterflies<5, 2>(v);
+        // through LDS with one float of padding per 32 (value i at i + (i >> 5)): both the writes of 32 consecutive
+        // values per thread and the reads 32 apart then fall on distinct banks
+        {
+            float *pa = lds + 33 * t;
+#pragma unroll
+            for (int e = 0; e < 32; ++e) pa[e] = v[e];
+            __syncthreads();
+            // phase B: values i = t_lo + 32 e + 1024 t_hi
+            const float *pb = lds + t_lo + 1056 * t_hi;
+#pragma unroll
+            for (int e = 0; e < 32; ++e) v[e] = pb[33 * e];
+        }
+        butterflies<5>(v);
+        __syncthreads();  // all reads of the padded layout are done before the plain one overwrites it
+        {
+            float *pb = lds + t_lo + 1024 * t_hi;
+#pragma unroll
+            for (int e = 0; e < 32; ++e) pb[32 * e] = v[e];
+        }
+        __syncthreads();
+
+        // phase C: CONSEC consecutive values at CONSEC t + 1024 e', e' = 0..NE-1; register index k * NE + e', so the
+        // strides 1024 .. n/2 are its low CB bits
+#pragma unroll
+        for (int ep = 0; ep < NE; ++ep)
+#pragma unroll
+            for (int k = 0; k < CONSEC; ++k) v[k * NE + ep] = (lds + CONSEC * t)[k + 1024 * ep];
+        butterflies<CB>(v);
+
+        // Eq. 1 and the store: CONSEC consecutive codes per e'
+        int8_t *orow = out + (size_t)r * N + CONSEC * t;
+#pragma unroll
+        for (int ep = 0; ep < NE; ++ep) {
+            if (CONSEC >= 4) {
+#pragma unroll
+                for (int k = 0; k < CONSEC; k += 4) {
+                    const float sc[4] = {v[k * NE + ep] * inv_s, v[(k + 1) * NE + ep] * inv_s,
+                                         v[(k + 2) * NE + ep] * inv_s, v[(k + 3) * NE + ep] * inv_s};
+                    __builtin_nontemporal_store(codes_packed<4>(sc),
+                                                reinterpret_cast<uint32_t *>(orow + 1024 * ep + k));
+                }
+            } else {
+                const float sc[4] = {v[ep] * inv_s, v[NE + ep] * inv_s, 0.0f, 0.0f};
+                *reinterpret_cast<uint16_t *>(orow + 1024 * ep) = (uint16_t)codes_packed<2>(sc);
+            }
+        }
+        __syncthreads();  // phase C has read the row before the next row's phase A writes
+    }
+}
+
+// Any power of two n <= 16384: the network stage by stage in LDS.
+__global__ __launch_bounds__(256) void hadamard_quantize_small_kernel(const uint16_t *y, int8_t *out, int n, float inv_s)
+{
+    extern __shared__ float lds[];
+    const size_t row = (size_t)blockIdx.x * n;
+    for (int i = threadIdx.x; i < n; i += 256) {
+        const _Float16 hv = __builtin_bit_cast(_Float16, y[row + i]);
+        lds[i] = (float)hv;
+    }
+    __syncthreads();
+    for (int h = 1; h < n; h <<= 1) {
+        for (int k = threadIdx.x; k < n / 2; k += 256) {
+            const int i = ((k & ~(h - 1)) << 1) | (k & (h - 1));  // k-th index with bit h clear
+            const float a = lds[i], b = lds[i + h];
+            lds[i] = a + b;
+            lds[i + h] = a - b;
+        }
+        __syncthreads();
+    }
+    for (int i = threadIdx.x; i < n; i += 256) out[row + i] = (int8_t)code_byte(lds[i] * inv_s);
+}
+
+template <int LOGN>
+hipError_t launch_fast(const uint16_t *y, int64_t rows, float inv_s, int8_t *out, hipStream_t stream)
+{
+    constexpr int N = 1 << LOGN;
+    constexpr int lds = (N + N / 32) * (int)sizeof(float);
+    // twice the workgroups that fit the device at once (measured best; one round of exactly resident workgroups
+    // is 10% slower), asked of the runtime once per order and device
+    static int resident[16] = {0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
+    if (!resident[dev]) {
+        if (lds > 48 * 1024) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(hadamard_quantize_kernel<LOGN>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return e;
+        }
+        int per_cu = 0, cus = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, hadamard_quantize_kernel<LOGN>, N / 32, lds);
+        if (e != hipSuccess) return e;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        resident[dev] = per_cu > 0 && cus > 0 ? 2 * per_cu * cus : 2048;
+    }
+    const unsigned grid = (unsigned)(rows < resident[dev] ? rows : resident[dev]);
+    hipLaunchKernelGGL(hadamard_quantize_kernel<LOGN>, dim3(grid), dim3(N / 32), lds, stream, y, out, (int)rows,
+                       inv_s);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_hadamard_quantize(const uint16_t *y, int64_t rows, int n, float s_y, int8_t *out, hipStream_t stream)
+{
+    if (rows == 0) return hipSuccess;
+    const float inv_s = 1.0f / s_y;  // correctly rounded fp32 division on the host
+    const bool al = reinterpret_cast<uintptr_t>(y) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 4 == 0;
+    if (al) {
+        switch (n) {
+            case 1024: return launch_fast<10>(y, rows, inv_s, out, stream);
+            case 2048: return launch_fast<11>(y, rows, inv_s, out, stream);
+            case 4096: return launch_fast<12>(y, rows, inv_s, out, stream);
+            case 8192: return launch_fast<13>(y, rows, inv_s, out, stream);
+            case 16384: return launch_fast<14>(y, rows, inv_s, out, stream);
+            default: break;
+        }
+    }
+    const int lds = n * (int)sizeof(float);
+    if (lds > 48 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(hadamard_quantize_small_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(hadamard_quantize_small_kernel, dim3((unsigned)rows), dim3(256), lds, stream, y, out, n, inv_s);
+    return hipGetLastError();
+}
+
+}  // namespace quamba

@@ -105,6 +105,8 @@ hipError_t launch_decode(const SsdArgs &a, hipStream_t stream);
 hipError_t launch_decode_q8(const SsdArgs &a, const float *state_scales, int8_t *state_q, hipStream_t stream);
 hipError_t launch_quantize_state(const SsdArgs &a, const float *state_scales, int8_t *state_q, hipStream_t stream);
 size_t decode_q8_lds_bytes(const quamba_ssd_shape_t &s);
+// Quantized Hadamard transform of rows of n = 2^k fp16 values (Section 4.2)
+hipError_t launch_hadamard_quantize(const uint16_t *y, int64_t rows, int n, float s_y, int8_t *out, hipStream_t stream);
 hipError_t launch_prefill_generic(const SsdArgs &a, hipStream_t stream);
 bool prefill_mfma_supports(const quamba_ssd_shape_t &s);
 hipError_t launch_prefill_mfma(const SsdArgs &a, hipStream_t stream);

@@ -137,3 +137,17 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libquamba_ssd.so")
     with pytest.raises(FileNotFoundError):
         b.load_library()
+
+
+def test_hadamard_rejects_bad_arguments_without_a_device():
+    lib = q.load_library()
+    dummy = C.create_string_buffer(64)
+    p = C.addressof(dummy)
+    f = lib.quamba_hadamard_quantize
+    assert f(None, 1, 64, 1.0, p, None) == -1 and f(p, 1, 64, 1.0, None, None) == -1
+    for n in (0, 1, 48, 3, 32768, -64):
+        assert f(p, 1, n, 1.0, p, None) == -2
+    assert f(p, -1, 64, 1.0, p, None) == -2 and f(p, 2 ** 31, 64, 1.0, p, None) == -2
+    for s in (0.0, -2.0, float("inf"), float("nan")):
+        assert f(p, 1, 64, s, p, None) == -5
+    assert f(p, 0, 64, 1.0, p, None) == 0          # no rows: nothing is launched

@@ -168,6 +168,20 @@ def draw_gate(s: LayerShape, seed: int = 0, decode: bool = False, step: int = 0)
     return {"z": z, "dt_pre": pre.astype(np.float32), "dt_bias": bias}
 
 
+def draw_ssd_output(rows: int, n: int, seed: int = 0, outlier_frac: float = 0.005):
+    """Output of the scan flattened to [rows, n] float16 (n = nheads * headdim) as the input of the quantized Hadamard
+    transform: standard normal times a log-normal per-channel magnitude, a fraction of the channels 20 times larger
+    (the outlier channels the transform spreads out).  Also returns the per-channel std [n] (float64), from which a
+    caller can set a static scale for the transformed values (their std is the root of the sum of squares)."""
+    g = _rng(seed, 40)
+    sigma = 0.05 * np.exp(0.5 * g.standard_normal(n))
+    k = int(round(n * outlier_frac))
+    if k:
+        sigma[g.choice(n, size=k, replace=False)] *= 20.0
+    y = _rng(seed, 41).standard_normal((rows, n), dtype=np.float32) * sigma.astype(np.float32)
+    return y.astype(np.float16), sigma
+
+
 def draw_cached_state(s: LayerShape, seed: int = 0, batch: int | None = None, stream: int = 21) -> np.ndarray:
     """Cached SSM state [b,H,P,N] float32 with the structure a state built from x and B has: the magnitude of
     element (h,p,n) follows the channel profile of x (rows, in the model's ORIGINAL head/channel order, like x) times
