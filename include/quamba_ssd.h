@@ -217,6 +217,36 @@ int quamba_state_scales(int32_t nheads, int32_t headdim, int32_t ngroups, int32_
 int quamba_hadamard_quantize(const uint16_t *y, int64_t rows, int32_t n, float s_y, int8_t *out, void *hip_stream);
 
 /*
+ * W8A8 causal convolution in front of the scan (Section 4.2, "Efficient 4-bit/8-bit Mamba blocks": the W8A8 causal
+ * convolution kernel; "Offline Hadamard matrix fusion" / reordering: its channels come in the sorted order, so its
+ * outputs are the SSD kernel's operands as they are).  Depthwise over time, 4 taps, over the concatenated channels
+ * [x | B | C] (Ct = nheads*headdim + 2*ngroups*d_state), then bias, SiLU and Eq. 1:
+ *   acc[t,c] = sum_{k=0..3} weight[c,k] * in[t-3+k, c]      (exact integers; tap 3 meets the current token; tokens
+ *                                                            before the sequence come from conv_state_in, else zero)
+ *   out[t,c] = Eq. 1 of SiLU(in_w_scale * acc + bias[c]) / s_out[c]
+ * with s_out the cell scale of (head, channel position) for x (Section 4.1, sort-and-cluster) and the state group's
+ * scale for B and C (per-state-group quantization).  The code is decided in fp32, every operation rounded on its own:
+ *   v = float(acc) * in_w_scale;  v = v + bias[c];  e = exp(-|v|);  den = 1 + e;  num = v >= 0 ? v : v * e;
+ *   a = num / den;  r = a * (1 / s_out[c]);  code = clamp(rint(r), -128, 127), ties to even;
+ * both divisions correctly rounded, and exp evaluated as t = z * log2(e) (fp32 constant 0x3FB8AA3B), k = rint(t),
+ * f = t - k, a degree-7 Horner polynomial in f with separately rounded multiplies and adds (coefficients the fp32
+ * roundings of (ln 2)^i / i!), scaled by 2^k, and 0 for t < -125.
+ *   in             device int8 [batch, seqlen, Ct]          weight  device int8 [Ct, 4]
+ *   bias           device fp32 [Ct] or NULL                 in_w_scale = (input scale) * (weight scale) > 0
+ *   conv_state_in  device int8 [batch, 3, Ct] or NULL (the 3 input tokens before the sequence, oldest first)
+ *   conv_state_out device int8 [batch, 3, Ct] or NULL: the last 3 input tokens after this call (for seqlen < 3 the tail
+ *                  of the old state moves up); may be the same buffer as conv_state_in only when seqlen <= 32
+ *   x_out device int8 [batch, seqlen, nheads, headdim];  B_out, C_out device int8 [batch, seqlen, ngroups, d_state]
+ * shape: batch, seqlen, nheads, headdim, d_state, ngroups and the cluster counts are used; scales as for the prefill.
+ * Shapes with headdim and d_state multiples of 16 and 16-byte aligned tensors take the vector kernel, others a
+ * one-thread-per-channel kernel with the same results.
+ * Errors: ENULL, ESHAPE, EINVAL (in_w_scale; aliased states with seqlen > 32), EHIP.
+ */
+int quamba_conv1d_q8(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales, const int8_t *in,
+                     const int8_t *weight, const float *bias, float in_w_scale, const int8_t *conv_state_in,
+                     int8_t *x_out, int8_t *B_out, int8_t *C_out, int8_t *conv_state_out, void *hip_stream);
+
+/*
  * Offline sort-and-cluster (Section 4.1) and the index tables for cluster-aware weight reordering (Section 4.2).
  * HOST function, all pointers host memory.
  *   x_calib_absmax [nheads*headdim]  calibrated per-channel max|x| in the model's original order

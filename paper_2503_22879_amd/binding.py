@@ -17,7 +17,7 @@ FLAG_NO_CHANNEL_SPLIT = 0x4
 
 EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "quamba_ssd_decode_step",
                     "quamba_ssd_decode_step_q8", "quamba_ssd_quantize_state", "quamba_state_scales",
-                    "quamba_hadamard_quantize", "quamba_ssd_prefill_gated", "quamba_ssd_decode_step_gated", "quamba_ssd_decode_step_q8_gated",
+                    "quamba_hadamard_quantize", "quamba_conv1d_q8", "quamba_ssd_prefill_gated", "quamba_ssd_decode_step_gated", "quamba_ssd_decode_step_q8_gated",
                     "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x",
                     "quamba_quantize_groups", "quamba_strerror")
 
@@ -84,6 +84,9 @@ def load_library():
             [C.c_size_t, C.c_void_p]
         lib.quamba_ssd_decode_step.restype = C.c_int
         lib.quamba_ssd_decode_step.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 9
+        lib.quamba_conv1d_q8.restype = C.c_int
+        lib.quamba_conv1d_q8.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct), C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_float] + [C.c_void_p] * 6
         lib.quamba_hadamard_quantize.restype = C.c_int
         lib.quamba_hadamard_quantize.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
         lib.quamba_ssd_prefill_gated.restype = C.c_int
@@ -318,6 +321,23 @@ def quamba_state_scales(nheads, headdim, ngroups, m, n, d_state, head_cluster_en
     if rc != 0:
         raise QuambaError(rc, "quamba_state_scales")
     return out
+
+
+def quamba_conv1d_q8(shape: Shape, scales: DeviceScales, xBC, weight, bias, in_w_scale: float, x_out, B_out, C_out,
+                     conv_state_in=None, conv_state_out=None, stream=None) -> None:
+    """Enqueue the W8A8 causal convolution + SiLU + Eq. 1 that produces the scan's int8 x, B and C (device tensors)."""
+    import torch
+    b, L, H, P, G, N = shape.batch, shape.seqlen, shape.nheads, shape.headdim, shape.ngroups, shape.d_state
+    Ct = H * P + 2 * G * N
+    sc = scales.struct()
+    rc = load_library().quamba_conv1d_q8(
+        C.byref(shape), C.byref(sc), _dp(xBC, torch.int8, (b, L, Ct), "xBC"), _dp(weight, torch.int8, (Ct, 4), "weight"),
+        _dp(bias, torch.float32, (Ct,), "bias"), float(in_w_scale),
+        _dp(conv_state_in, torch.int8, (b, 3, Ct), "conv_state_in"), _dp(x_out, torch.int8, (b, L, H, P), "x_out"),
+        _dp(B_out, torch.int8, (b, L, G, N), "B_out"), _dp(C_out, torch.int8, (b, L, G, N), "C_out"),
+        _dp(conv_state_out, torch.int8, (b, 3, Ct), "conv_state_out"), _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_conv1d_q8")
 
 
 def quamba_hadamard_quantize(y, s_y: float, out, stream=None) -> None:

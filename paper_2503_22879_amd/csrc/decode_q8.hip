@@ -28,27 +28,6 @@ constexpr size_t kLdsLimit = 160 * 1024;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ float from_bits(uint32_t u) { return __builtin_bit_cast(float, u); }
-
-// exp(z) for z <= 0 as separately rounded fp32 steps: t = z log2(e), k = rint(t), f = t - k in [-1/2, 1/2],
-// 2^f = sum_i ((ln 2)^i / i!) f^i (i = 7..0, Horner, multiply then add), result 2^f 2^k; t < -125 gives 0 so that
-// no result is subnormal.  Constants are the fp32 roundings of log2(e) and of the Taylor coefficients.
-__device__ __forceinline__ float exp_steps(float z)
-{
-    const float t = z * from_bits(0x3FB8AA3Bu);
-    const float k = __builtin_rintf(t);
-    const float f = t - k;
-    float p = from_bits(0x377FE5FEu);
-    p = p * f; p = p + from_bits(0x39218489u);
-    p = p * f; p = p + from_bits(0x3AAEC3FFu);
-    p = p * f; p = p + from_bits(0x3C1D955Bu);
-    p = p * f; p = p + from_bits(0x3D635847u);
-    p = p * f; p = p + from_bits(0x3E75FDF0u);
-    p = p * f; p = p + from_bits(0x3F317218u);
-    p = p * f; p = p + 1.0f;
-    return t < -125.0f ? 0.0f : __builtin_ldexpf(p, (int)k);
-}
-
 // Eq. 1: clamp to [-127, 127], then round to nearest even by adding 1.5 * 2^23 (the sum's unit in the last place is
 // 1): the code is the low byte of the sum's bit pattern, in two's complement.  Clamping first gives the same code as
 // clamping after rounding because the bounds are integers.

@@ -78,6 +78,29 @@ __device__ __forceinline__ uint16_t f32_to_f16_bits(float v)
     return __builtin_bit_cast(uint16_t, h);
 }
 
+__device__ __forceinline__ float from_bits(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// exp(z) for z <= 0 as separately rounded fp32 steps: t = z log2(e), k = rint(t), f = t - k in [-1/2, 1/2],
+// 2^f = sum_i ((ln 2)^i / i!) f^i (i = 7..0, Horner, multiply then add), result 2^f 2^k; t < -125 gives 0 so that
+// no result is subnormal.  Constants are the fp32 roundings of log2(e) and of the Taylor coefficients.  Used where an
+// integer code depends on the result, so that it is the same fixed sequence of roundings on every machine.
+__device__ __forceinline__ float exp_steps(float z)
+{
+#pragma clang fp contract(off)
+    const float t = z * from_bits(0x3FB8AA3Bu);
+    const float k = __builtin_rintf(t);
+    const float f = t - k;
+    float p = from_bits(0x377FE5FEu);
+    p = p * f; p = p + from_bits(0x39218489u);
+    p = p * f; p = p + from_bits(0x3AAEC3FFu);
+    p = p * f; p = p + from_bits(0x3C1D955Bu);
+    p = p * f; p = p + from_bits(0x3D635847u);
+    p = p * f; p = p + from_bits(0x3E75FDF0u);
+    p = p * f; p = p + from_bits(0x3F317218u);
+    p = p * f; p = p + 1.0f;
+    return t < -125.0f ? 0.0f : __builtin_ldexpf(p, (int)k);
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v)
 {
@@ -107,6 +130,24 @@ hipError_t launch_quantize_state(const SsdArgs &a, const float *state_scales, in
 size_t decode_q8_lds_bytes(const quamba_ssd_shape_t &s);
 // Quantized Hadamard transform of rows of n = 2^k fp16 values (Section 4.2)
 hipError_t launch_hadamard_quantize(const uint16_t *y, int64_t rows, int n, float s_y, int8_t *out, hipStream_t stream);
+// W8A8 causal convolution in front of the scan (4 taps, SiLU, Eq. 1 to the scan's operands)
+struct ConvArgs {
+    quamba_ssd_shape_t s;
+    const float *x_scales;
+    const int32_t *head_cluster_end;
+    const int32_t *chan_cluster_end;
+    const float *B_scales;
+    const float *C_scales;
+    const int8_t *in;         // [b, L, HP + 2 GN]
+    const int8_t *weight;     // [HP + 2 GN, 4]
+    const float *bias;        // [HP + 2 GN] or null
+    float in_w_scale;
+    const int8_t *state_in;   // [b, 3, HP + 2 GN] or null
+    int8_t *state_out;        // same shape, or null
+    int8_t *x_out, *B_out, *C_out;
+};
+hipError_t launch_conv1d_q8(const ConvArgs &a, hipStream_t stream);
+int conv1d_segments(const quamba_ssd_shape_t &s);  // workgroups along one sequence (1: state_in may equal state_out)
 hipError_t launch_prefill_generic(const SsdArgs &a, hipStream_t stream);
 bool prefill_mfma_supports(const quamba_ssd_shape_t &s);
 hipError_t launch_prefill_mfma(const SsdArgs &a, hipStream_t stream);

@@ -70,3 +70,14 @@ def make_gate_inputs(s: W.LayerShape, r, seed: int, decode: bool = False, step: 
     ds = np.float32(np.abs(raw["dt_pre"]).max() / 127.0)
     return {"z": oracle.quantize(z, zs), "z_scale": float(zs), "dt_q": oracle.quantize(pre, ds),
             "dt_scale": float(ds), "dt_bias": np.ascontiguousarray(bias, np.float32)}
+
+
+def make_conv_inputs(s: W.LayerShape, seed: int, batch=None, seqlen=None, stream: int = 50):
+    """int8 codes of the convolution's input and filter, quantized with the oracle's Eq. 1 and one static scale per
+    tensor (absolute maximum / 127; the input scale is fixed at 4.5 / 127 so that pieces of one sequence share it).
+    Returns dict(xBC, weight, bias, in_w_scale)."""
+    raw = W.draw_conv(s, seed, batch=batch, seqlen=seqlen, stream=stream)
+    s_in = np.float32(4.5 / 127.0)
+    s_w = np.float32(np.abs(raw["weight"]).max() / 127.0)
+    return {"xBC": oracle.quantize(raw["xBC"], s_in), "weight": oracle.quantize(raw["weight"], s_w),
+            "bias": raw["bias"], "in_w_scale": float(np.float32(s_in * s_w))}

@@ -151,3 +151,26 @@ def test_hadamard_rejects_bad_arguments_without_a_device():
     for s in (0.0, -2.0, float("inf"), float("nan")):
         assert f(p, 1, 64, s, p, None) == -5
     assert f(p, 0, 64, 1.0, p, None) == 0          # no rows: nothing is launched
+
+
+def test_conv1d_rejects_bad_arguments_without_a_device():
+    lib = q.load_library()
+    dummy = C.create_string_buffer(64)
+    p = C.addressof(dummy)
+    from paper_2503_22879_amd.binding import _ScalesStruct
+    sc = _ScalesStruct(p, p, p, p, p)
+
+    def call(shape, scale=1e-3, null=None, st_in=None, st_out=None, scales=sc):
+        args = [p, p, p]                      # in weight bias
+        outs = [p, p, p]                      # x_out B_out C_out
+        if null is not None:
+            (args if null < 3 else outs)[null % 3] = None
+        return lib.quamba_conv1d_q8(C.byref(shape), C.byref(scales), args[0], args[1], args[2], scale, st_in, outs[0],
+                                    outs[1], outs[2], st_out, None)
+    for i in (0, 1, 3, 4, 5):                 # bias (2) may be NULL
+        assert call(_shape(), null=i) == -1
+    assert call(_shape(), scales=_ScalesStruct(p, None, p, p, p)) == -1
+    assert call(_shape(seqlen=0)) == -2 and call(_shape(nheads=5)) == -2
+    for s in (0.0, -1.0, float("inf"), float("nan")):
+        assert call(_shape(), scale=s) == -5
+    assert call(_shape(seqlen=33), st_in=p, st_out=p) == -5      # one buffer for both states only on short pieces

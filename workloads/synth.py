@@ -182,6 +182,24 @@ def draw_ssd_output(rows: int, n: int, seed: int = 0, outlier_frac: float = 0.00
     return y.astype(np.float16), sigma
 
 
+def draw_conv(s: LayerShape, seed: int = 0, batch: int | None = None, seqlen: int | None = None, stream: int = 50):
+    """Raw floats of the causal convolution in front of the scan, channels [x | B | C] (H*P + 2*G*N of them) already in
+    the sorted order the offline reordering gives them: the block's pre-convolution activations xBC [b,L,Ct] (standard
+    normal times a log-normal per-channel magnitude), the depthwise filter [Ct,4] (normal, a log-normal per-channel
+    gain, scaled so that the convolution's output has a standard deviation of about 1.5 per unit gain) and the bias
+    [Ct] (N(0, 0.3)).  `stream` separates draws (a later piece of a sequence, a decode step)."""
+    b = s.batch if batch is None else batch
+    L = s.seqlen if seqlen is None else seqlen
+    Ct = s.nheads * s.headdim + 2 * s.ngroups * s.d_state
+    gp = _rng(seed, 51)
+    in_sigma = np.exp(0.3 * gp.standard_normal(Ct)).astype(np.float32)
+    gain = np.exp(0.5 * gp.standard_normal(Ct)).astype(np.float32)
+    w = gp.standard_normal((Ct, 4)).astype(np.float32) * (gain / in_sigma * np.float32(0.75))[:, None]
+    bias = (0.3 * gp.standard_normal(Ct)).astype(np.float32)
+    x = _rng(seed, stream).standard_normal((b, L, Ct), dtype=np.float32) * in_sigma
+    return {"xBC": x, "weight": w, "bias": bias}
+
+
 def draw_cached_state(s: LayerShape, seed: int = 0, batch: int | None = None, stream: int = 21) -> np.ndarray:
     """Cached SSM state [b,H,P,N] float32 with the structure a state built from x and B has: the magnitude of
     element (h,p,n) follows the channel profile of x (rows, in the model's ORIGINAL head/channel order, like x) times
