@@ -52,6 +52,9 @@ Q8_OPS_PER_ELEMENT = 8
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3: fp32 vector instructions per second x 64 lanes, unpacked, unfused
 
 
+CONV_OPS_PER_ELEMENT = 45   # vector instructions per output element in conv1d_q8_vec_kernel's main loop
+
+
 def HADAMARD_OPS_PER_VALUE(n: int) -> int:
     """fp32 vector operations per value of the quantized Hadamard transform: one add or subtract per butterfly stage,
     then the scale, the clamp and the rounding add of Eq. 1."""
@@ -106,6 +109,7 @@ def main() -> int:
     ap.add_argument("--workload", default="m2_8b_b4", choices=["m2_8b_b4", "m2_8b_b1", "m2_2p7b", "m2_130m"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode leg")
+    ap.add_argument("--no-conv", action="store_true", help="skip the W8A8 causal convolution in front of the scan")
     ap.add_argument("--no-hadamard", action="store_true",
                     help="skip the quantized Hadamard transform of the prefill output")
     ap.add_argument("--precise-state", action="store_true", help="also return the final fp32 state (two-term state path)")
@@ -251,6 +255,58 @@ def main() -> int:
             out["hadamard"]["parity_spot_check"] = {
                 "rows": int(pick.numel()), "codes_differing": int((yq.view(rows, n_had)[pick].cpu().numpy() != ref).sum())}
         del yq, yflat
+
+    # ------------------------------------------------ W8A8 causal convolution in front of the scan (Section 4.2)
+    if not args.no_conv:
+        Ct = s.nheads * s.headdim + 2 * s.ngroups * s.d_state
+        rawc = W.draw_conv(s, seed)
+        s_in = np.float32(4.5 / 127.0)
+        s_w = np.float32(np.abs(rawc["weight"]).max() / 127.0)
+        cin = torch.from_numpy(q.quamba_quantize_groups(rawc["xBC"].reshape(-1, 1, Ct), np.array([s_in], np.float32))
+                               .reshape(s.batch, s.seqlen, Ct)).to(dev)
+        cw_np = q.quamba_quantize_groups(rawc["weight"].reshape(1, 1, -1), np.array([s_w], np.float32)).reshape(Ct, 4)
+        cw = torch.from_numpy(cw_np).to(dev)
+        cbias = torch.from_numpy(rawc["bias"]).to(dev)
+        in_w_scale = float(np.float32(s_in * s_w))
+        cx = torch.empty((s.batch, s.seqlen, s.nheads, s.headdim), dtype=torch.int8, device=dev)
+        cB = torch.empty((s.batch, s.seqlen, s.ngroups, s.d_state), dtype=torch.int8, device=dev)
+        cC = torch.empty_like(cB)
+        cst = torch.empty((s.batch, 3, Ct), dtype=torch.int8, device=dev)
+
+        def conv():
+            q.quamba_conv1d_q8(shape, dsc, cin, cw, cbias, in_w_scale, cx, cB, cC, conv_state_out=cst)
+
+        cms, cwall = time_region(torch, conv, args.steps, max(args.warmup, 4))
+        celems = float(s.batch) * s.seqlen * Ct
+        cgbs = 2.0 * celems / (cms * 1e-3) / 1e9
+        cops = CONV_OPS_PER_ELEMENT * celems
+        out["conv1d"] = {
+            "metric": "W8A8 causal conv1d + SiLU + Eq. 1 us/call", "value": cms * 1e3, "unit": "us/call",
+            "steps": args.steps, "higher_is_better": False, "wall_us_per_call": cwall * 1e3,
+            "config": {"workload": "%s: %d tokens x %d channels [x|B|C], 4 taps, int8 in, int8 x/B/C out with the "
+                                   "scan's cell and group scales" % (s.name, s.batch * s.seqlen, Ct)},
+            "roofline": {"kernel": "conv1d_q8_vec_kernel", "bound": "alu", "achieved": cops / (cms * 1e-3) / 1e12,
+                         "peak": ALU_PEAK_TOPS, "unit": "Top/s (fp32 vector instructions x 64 lanes)",
+                         "frac": cops / (cms * 1e-3) / 1e12 / ALU_PEAK_TOPS, "traffic": None,
+                         "note": "%d vector instructions per output element (counted in the kernel's main loop): "
+                                 "the fp32 decision sequence of the code with a polynomial exp and a correctly "
+                                 "rounded division" % CONV_OPS_PER_ELEMENT},
+            "roofline_hbm": {"kernel": "conv1d_q8_vec_kernel", "bound": "hbm", "achieved": cgbs,
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": cgbs / HBM_PEAK_GBS,
+                             "traffic": MEASURED_TRAFFIC_BYTES.get(s.name + "_conv1d")},
+            "saturated_fraction": float((cx == 127).float().mean().item()),
+        }
+        if not args.no_cpu:   # spot check against the oracle: the last 8 tokens of sequence 0, codes bit for bit
+            import oracle
+            sc = oracle.Scales(s.m, s.n, hs.x_scales, hs.head_cluster_end, hs.chan_cluster_end, hs.B_scales,
+                               hs.C_scales)
+            os_ = oracle.output_scales(sc, s.nheads, s.headdim, s.ngroups, s.d_state)
+            win = cin[:1, -11:].cpu().numpy()
+            ref, _ = oracle.ref_conv1d_q8(win, cw_np, in_w_scale, rawc["bias"], os_)
+            got = torch.cat([cx[:1, -8:].reshape(1, 8, -1), cB[:1, -8:].reshape(1, 8, -1),
+                             cC[:1, -8:].reshape(1, 8, -1)], dim=2).cpu().numpy()
+            out["conv1d"]["parity_spot_check"] = {"tokens": 8, "codes_differing": int((got != ref[:, -8:]).sum())}
+        del cin, cw, cx, cB, cC, cst, rawc
 
     # ------------------------------------------------------------------ decode
     if not args.no_decode:
