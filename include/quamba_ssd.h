@@ -217,6 +217,36 @@ int quamba_state_scales(int32_t nheads, int32_t headdim, int32_t ngroups, int32_
 int quamba_hadamard_quantize(const uint16_t *y, int64_t rows, int32_t n, float s_y, int8_t *out, void *hip_stream);
 
 /*
+ * The 8-bit Mamba1 selective scan (Section 3.2, Eq. 2 with the Mamba1 parameterisation: per-channel step size, A a
+ * [channels, states] matrix, B_t and C_t shared by all channels; Section 4.2 lists the 8-bit selective-scan kernel):
+ *   h_t[d,n] = exp(dt_t[d] A[d,n]) h_{t-1}[d,n] + dt_t[d] B_t[n] x_t[d],    y_t[d] = sum_n C_t[n] h_t[d,n] + D[d] x_t[d]
+ * with x = s_x(d) x_code, one scale per channel range (sort-and-cluster of Section 4.1 for a block without heads),
+ * B = s_B B_code, C = s_C C_code (one state group).  Tensors are channel-major with time last, as in the Mamba1 block.
+ * shape: nheads = 1, ngroups = 1, n_head_clusters = 1; headdim = number of channels D; d_state = N; n_chan_clusters =
+ * number of channel ranges; scales: x_scales [n_chan_clusters], chan_cluster_end [n_chan_clusters] (exclusive ends on
+ * the sorted channel positions), head_cluster_end [1] = {1}, B_scales [1], C_scales [1]  (all device).
+ *   x  device int8 [batch, D, seqlen]        B, C  device int8 [batch, N, seqlen]       dt  device fp32 [batch, D, seqlen]
+ *   A  device fp32 [D, N] (<= 0)             D     device fp32 [D] or NULL
+ *   init_state  device fp32 [batch, D, N] or NULL (zero)      final_state  device fp32 [batch, D, N] or NULL
+ *   y  device fp16 [batch, D, seqlen]
+ * d_state = 16, seqlen a multiple of 16 and 16-byte aligned tensors take the wave-scan kernel; other shapes (d_state
+ * <= 64) or QUAMBA_FLAG_GENERIC_KERNEL a one-thread-per-channel kernel.  fp32 throughout; y rounded to fp16.
+ * Errors: ENULL, ESHAPE, EINVAL, EHIP.
+ */
+int quamba_mamba1_scan(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales, const int8_t *x,
+                       const int8_t *B, const int8_t *C, const float *dt, const float *A, const float *D,
+                       const float *init_state, uint16_t *y, float *final_state, void *hip_stream);
+
+/*
+ * One generation step of the same recurrence on a persistent fp32 state, in place.
+ *   x device int8 [batch, D];  B, C device int8 [batch, N];  dt device fp32 [batch, D];  state device fp32 [batch, D, N]
+ *   (in/out);  y device fp16 [batch, D];  A, D, shape (seqlen ignored) and scales as above; any d_state.
+ */
+int quamba_mamba1_decode_step(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales, const int8_t *x,
+                              const int8_t *B, const int8_t *C, const float *dt, const float *A, const float *D,
+                              float *state, uint16_t *y, void *hip_stream);
+
+/*
  * W8A8 causal convolution in front of the scan (Section 4.2, "Efficient 4-bit/8-bit Mamba blocks": the W8A8 causal
  * convolution kernel; "Offline Hadamard matrix fusion" / reordering: its channels come in the sorted order, so its
  * outputs are the SSD kernel's operands as they are).  Depthwise over time, 4 taps, over the concatenated channels

@@ -191,6 +191,50 @@ extern "C" int quamba_ssd_quantize_state(const quamba_ssd_shape_t *shape, const 
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }
 
+namespace {
+int check_mamba1(const quamba_ssd_shape_t *s, bool scan)
+{
+    const int rc = check_shape(s, scan);
+    if (rc != QUAMBA_OK) return rc;
+    if (s->nheads != 1 || s->ngroups != 1 || s->n_head_clusters != 1) return QUAMBA_ESHAPE;
+    if ((int64_t)s->batch * s->headdim > 0x7fffffffLL || s->batch > 65535) return QUAMBA_ESHAPE;
+    return QUAMBA_OK;
+}
+}  // namespace
+
+extern "C" int quamba_mamba1_scan(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales, const int8_t *x,
+                                  const int8_t *B, const int8_t *C, const float *dt, const float *A, const float *D,
+                                  const float *init_state, uint16_t *y, float *final_state, void *hip_stream)
+{
+    if (!shape) return QUAMBA_ENULL;
+    int rc = check_scales(scales);
+    if (rc != QUAMBA_OK) return rc;
+    if (!x || !B || !C || !dt || !A || !y) return QUAMBA_ENULL;
+    rc = check_mamba1(shape, true);
+    if (rc != QUAMBA_OK) return rc;
+    if (shape->flags & ~QUAMBA_FLAG_GENERIC_KERNEL) return QUAMBA_EINVAL;
+    if (!quamba::mamba1_scan_supports_any(*shape)) return QUAMBA_ESHAPE;  // d_state <= 64
+    quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, nullptr, D, nullptr, nullptr, y);
+    const hipError_t e = quamba::launch_mamba1_scan(a, A, init_state, final_state, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
+extern "C" int quamba_mamba1_decode_step(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                         const int8_t *x, const int8_t *B, const int8_t *C, const float *dt,
+                                         const float *A, const float *D, float *state, uint16_t *y, void *hip_stream)
+{
+    if (!shape) return QUAMBA_ENULL;
+    int rc = check_scales(scales);
+    if (rc != QUAMBA_OK) return rc;
+    if (!x || !B || !C || !dt || !A || !state || !y) return QUAMBA_ENULL;
+    rc = check_mamba1(shape, false);
+    if (rc != QUAMBA_OK) return rc;
+    if (shape->flags) return QUAMBA_EINVAL;
+    quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, nullptr, D, nullptr, state, y);
+    const hipError_t e = quamba::launch_mamba1_decode(a, A, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
 extern "C" int quamba_conv1d_q8(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales, const int8_t *in,
                                 const int8_t *weight, const float *bias, float in_w_scale,
                                 const int8_t *conv_state_in, int8_t *x_out, int8_t *B_out, int8_t *C_out,

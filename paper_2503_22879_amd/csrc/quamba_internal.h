@@ -148,6 +148,10 @@ struct ConvArgs {
 };
 hipError_t launch_conv1d_q8(const ConvArgs &a, hipStream_t stream);
 int conv1d_segments(const quamba_ssd_shape_t &s);  // workgroups along one sequence (1: state_in may equal state_out)
+// Mamba1 selective scan: shape has nheads = ngroups = 1, headdim = channels; A is [channels, d_state]
+hipError_t launch_mamba1_scan(const SsdArgs &a, const float *A, const float *init, float *fin, hipStream_t stream);
+hipError_t launch_mamba1_decode(const SsdArgs &a, const float *A, hipStream_t stream);
+bool mamba1_scan_supports_any(const quamba_ssd_shape_t &s);
 hipError_t launch_prefill_generic(const SsdArgs &a, hipStream_t stream);
 bool prefill_mfma_supports(const quamba_ssd_shape_t &s);
 hipError_t launch_prefill_mfma(const SsdArgs &a, hipStream_t stream);

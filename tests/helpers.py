@@ -81,3 +81,30 @@ def make_conv_inputs(s: W.LayerShape, seed: int, batch=None, seqlen=None, stream
     s_w = np.float32(np.abs(raw["weight"]).max() / 127.0)
     return {"xBC": oracle.quantize(raw["xBC"], s_in), "weight": oracle.quantize(raw["weight"], s_w),
             "bias": raw["bias"], "in_w_scale": float(np.float32(s_in * s_w))}
+
+
+def make_mamba1_problem(batch: int, channels: int, d_state: int, seqlen: int, seed: int, nranges: int = 4):
+    """A Mamba1-shaped selective-scan problem: channels sorted by their calibrated maximum and clustered into n ranges
+    (Section 4.1 for a block without heads), raw tensors gathered into that order, Eq. 1 with the oracle's quantizer.  Returns (Scales, dict of numpy arrays: int8 x [b,D,L], B, C [b,N,L]; fp32 dt, A, D; scale vectors)."""
+    raw = W.draw_mamba1(batch, channels, d_state, seqlen, seed)
+    # channels sorted by their calibrated maximum; the ranges come from the oracle's clustering of an evenly thinned
+    # profile (at most 512 points: its exact 1-D clustering is quadratic in the number of points), scaled back
+    perm = np.argsort(raw["x_absmax"], kind="stable")
+    smax = raw["x_absmax"][perm]
+    step = max(1, channels // 512)
+    r = oracle.sort_and_cluster(smax[::step][None, :], 1, 1, nranges)
+    ends = np.minimum(r["chan_cluster_end"].astype(np.int64) * step, channels).astype(np.int32)
+    ends[-1] = channels
+    los = np.concatenate([[0], ends[:-1]])
+    xsc = oracle.group_scales(np.array([[smax[lo:hi].max() if hi > lo else 0.0] for lo, hi in zip(los, ends)], np.float32))
+    r = {"x_scales": xsc, "head_cluster_end": np.array([1], np.int32), "chan_cluster_end": ends}
+    bmax = np.abs(raw["B"]).max()
+    cmax = np.abs(raw["C"]).max()
+    sc = oracle.Scales(1, nranges, r["x_scales"], r["head_cluster_end"], r["chan_cluster_end"],
+                       oracle.group_scales(np.array([[bmax]], np.float32)), oracle.group_scales(np.array([[cmax]], np.float32)))
+    xs = oracle.channel_scales(sc.x_scales, sc.chan_cluster_end, channels).astype(np.float32)
+    x = raw["x"][:, perm]
+    prob = {"x": oracle.quantize(x, xs[None, :, None]), "B": oracle.quantize(raw["B"], sc.B_scales[0]),
+            "C": oracle.quantize(raw["C"], sc.C_scales[0]), "dt": np.ascontiguousarray(raw["dt"][:, perm]),
+            "A": np.ascontiguousarray(raw["A"][perm]), "D": np.ascontiguousarray(raw["D"][perm]), "xs": xs}
+    return sc, prob

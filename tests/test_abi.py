@@ -174,3 +174,32 @@ def test_conv1d_rejects_bad_arguments_without_a_device():
     for s in (0.0, -1.0, float("inf"), float("nan")):
         assert call(_shape(), scale=s) == -5
     assert call(_shape(seqlen=33), st_in=p, st_out=p) == -5      # one buffer for both states only on short pieces
+
+
+def test_mamba1_rejects_bad_arguments_without_a_device():
+    lib = q.load_library()
+    dummy = C.create_string_buffer(64)
+    p = C.addressof(dummy)
+    from paper_2503_22879_amd.binding import _ScalesStruct
+    sc = _ScalesStruct(p, p, p, p, p)
+    m1 = dict(nheads=1, ngroups=1, headdim=64, d_state=16, seqlen=32)
+
+    def scan(shape, null=None):
+        args = [p] * 9                        # x B C dt A D init y final
+        if null is not None:
+            args[null] = None
+        return lib.quamba_mamba1_scan(C.byref(shape), C.byref(sc), *args, None)
+
+    def step(shape, null=None):
+        args = [p] * 8                        # x B C dt A D state y
+        if null is not None:
+            args[null] = None
+        return lib.quamba_mamba1_decode_step(C.byref(shape), C.byref(sc), *args, None)
+    for i in (0, 1, 2, 3, 4, 7):
+        assert scan(_shape(**m1), null=i) == -1
+    for i in (0, 1, 2, 3, 4, 6, 7):
+        assert step(_shape(**m1), null=i) == -1
+    for bad in (dict(nheads=2, ngroups=1), dict(n_head_clusters=2), dict(seqlen=0), dict(d_state=65)):
+        assert scan(_shape(**dict(m1, **bad))) == -2
+    assert step(_shape(**dict(m1, nheads=4, ngroups=2))) == -2
+    assert scan(_shape(**dict(m1, flags=2))) == -5 and step(_shape(**dict(m1, flags=1))) == -5

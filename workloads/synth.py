@@ -182,6 +182,32 @@ def draw_ssd_output(rows: int, n: int, seed: int = 0, outlier_frac: float = 0.00
     return y.astype(np.float16), sigma
 
 
+def draw_mamba1(batch: int, channels: int, d_state: int, seqlen: int, seed: int = 0, stream: int = 70) -> dict:
+    """Raw floats of a Mamba1-shaped selective-scan layer, channel-major with time last, channels already in sorted
+    order: x [b,D,L] = N(0,1) times a per-channel magnitude that rises with the channel index (log-normal values,
+    sorted; 1 % of the channels 10x larger), B, C [b,N,L] = N(0,1) times a per-state gain exp(N(0,0.5)), dt [b,D,L] =
+    softplus(N(-3,1) + a per-channel offset N(0,0.5)), A [D,N] = -(n+1) exp(N(0,0.2)) (the S4D-real start the Mamba1
+    block trains from, perturbed), D [D] ~ N(0,1), and the per-channel maxima of |x| over a separate draw of 256 tokens
+    for calibration."""
+    g = _rng(seed, stream)
+    gp = _rng(seed, 71)
+    sigma = np.exp(gp.standard_normal(channels))
+    k = max(1, channels // 100)
+    sigma[gp.choice(channels, size=k, replace=False)] *= 10.0
+    sigma = np.sort(sigma).astype(np.float32)
+    gainB = np.exp(0.5 * gp.standard_normal(d_state)).astype(np.float32)
+    gainC = np.exp(0.5 * gp.standard_normal(d_state)).astype(np.float32)
+    off = (0.5 * gp.standard_normal(channels)).astype(np.float32)
+    A = (-(np.arange(1, d_state + 1, dtype=np.float32))[None, :] * np.exp(0.2 * gp.standard_normal((channels, d_state)))).astype(np.float32)
+    Dk = gp.standard_normal(channels).astype(np.float32)
+    xcal = np.abs(gp.standard_normal((256, channels), dtype=np.float32)).max(0) * sigma
+    x = g.standard_normal((batch, channels, seqlen), dtype=np.float32) * sigma[None, :, None]
+    B = g.standard_normal((batch, d_state, seqlen), dtype=np.float32) * gainB[None, :, None]
+    C = g.standard_normal((batch, d_state, seqlen), dtype=np.float32) * gainC[None, :, None]
+    dt = _softplus(g.standard_normal((batch, channels, seqlen), dtype=np.float32) - np.float32(3.0) + off[None, :, None])
+    return {"x": x, "B": B, "C": C, "dt": dt.astype(np.float32), "A": A, "D": Dk, "x_absmax": xcal.astype(np.float32)}
+
+
 def draw_conv(s: LayerShape, seed: int = 0, batch: int | None = None, seqlen: int | None = None, stream: int = 50):
     """Raw floats of the causal convolution in front of the scan, channels [x | B | C] (H*P + 2*G*N of them) already in
     the sorted order the offline reordering gives them: the block's pre-convolution activations xBC [b,L,Ct] (standard
