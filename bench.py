@@ -52,6 +52,7 @@ Q8_OPS_PER_ELEMENT = 8
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3: fp32 vector instructions per second x 64 lanes, unpacked, unfused
 
 
+MAMBA1_SLOTS_PER_ELEMENT = 10.7   # issue slots per (token, channel, state) element in mamba1_scan_kernel's state loop
 CONV_OPS_PER_ELEMENT = 45   # vector instructions per output element in conv1d_q8_vec_kernel's main loop
 
 
@@ -109,6 +110,7 @@ def main() -> int:
     ap.add_argument("--workload", default="m2_8b_b4", choices=["m2_8b_b4", "m2_8b_b1", "m2_2p7b", "m2_130m"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode leg")
+    ap.add_argument("--no-mamba1", action="store_true", help="skip the Mamba1 selective scan and its decode step")
     ap.add_argument("--no-conv", action="store_true", help="skip the W8A8 causal convolution in front of the scan")
     ap.add_argument("--no-hadamard", action="store_true",
                     help="skip the quantized Hadamard transform of the prefill output")
@@ -307,6 +309,90 @@ def main() -> int:
                              cC[:1, -8:].reshape(1, 8, -1)], dim=2).cpu().numpy()
             out["conv1d"]["parity_spot_check"] = {"tokens": 8, "codes_differing": int((got != ref[:, -8:]).sum())}
         del cin, cw, cx, cB, cC, cst, rawc
+
+    # ------------------------------------------------ 8-bit Mamba1 selective scan (Eq. 2, Mamba1 parameterisation)
+    if not args.no_mamba1:
+        mb, mD, mN, mL = 4, 5120, 16, 4096          # the Mamba1-2.8B-shaped layer: d_inner 5120, 16 states
+        rawm = W.draw_mamba1(mb, mD, mN, mL, seed)
+        _, mperm, mhs = q.quamba_reorder_params(1, mD, 1, 1, 4, mN, rawm["x_absmax"], np.abs(rawm["B"]).max((0, 2)),
+                                                np.abs(rawm["C"]).max((0, 2)))
+        mperm = mperm[0]
+        mshape = q.Shape(batch=mb, seqlen=mL, nheads=1, headdim=mD, d_state=mN, ngroups=1, chunk=1,
+                         n_head_clusters=1, n_chan_clusters=4, flags=0)
+        mdsc = q.DeviceScales(mhs, dev)
+        # per-channel scale of the sorted positions, then Eq. 1 by the library's host quantizer (one "group" per channel)
+        ends = mhs.chan_cluster_end
+        xs_c = np.repeat(mhs.x_scales, np.diff(np.concatenate([[0], ends])))
+        mx = torch.from_numpy(q.quamba_quantize_groups(np.ascontiguousarray(rawm["x"][:, mperm]), xs_c)).to(dev)
+        mB = torch.from_numpy(q.quamba_quantize_groups(rawm["B"].reshape(mb, 1, -1), mhs.B_scales)
+                              .reshape(mb, mN, mL)).to(dev)
+        mC = torch.from_numpy(q.quamba_quantize_groups(rawm["C"].reshape(mb, 1, -1), mhs.C_scales)
+                              .reshape(mb, mN, mL)).to(dev)
+        mdt = torch.from_numpy(np.ascontiguousarray(rawm["dt"][:, mperm])).to(dev)
+        mA = torch.from_numpy(np.ascontiguousarray(rawm["A"][mperm])).to(dev)
+        mDk = torch.from_numpy(np.ascontiguousarray(rawm["D"][mperm])).to(dev)
+        my = torch.empty((mb, mD, mL), dtype=torch.float16, device=dev)
+        mfin = torch.empty((mb, mD, mN), device=dev)
+
+        def mamba1():
+            q.quamba_mamba1_scan(mshape, mdsc, mx, mB, mC, mdt, mA, mDk, my, final_state=mfin)
+
+        mms, mwall = time_region(torch, mamba1, max(20, args.steps // 2), max(args.warmup // 2, 3))
+        melems = float(mb) * mD * mL * mN
+        mbytes = float(mb) * mD * mL * 7 + 2.0 * mb * mN * mL
+        out["mamba1_scan"] = {
+            "metric": "int8 Mamba1 selective scan tokens/s/layer", "value": mb * mL / (mms * 1e-3), "unit": "tokens/s",
+            "us_per_call": mms * 1e3, "wall_us_per_call": mwall * 1e3, "higher_is_better": True,
+            "config": {"workload": "Mamba1-2.8B-shaped layer: batch 4 x 4096 tokens, 5120 channels, 16 states, "
+                                   "4 channel ranges; int8 x/B/C, fp32 dt, fp16 y, final state returned"},
+            "roofline": {"kernel": "mamba1_scan_kernel", "bound": "alu",
+                         "achieved": MAMBA1_SLOTS_PER_ELEMENT * melems / (mms * 1e-3) / 1e12, "peak": ALU_PEAK_TOPS,
+                         "unit": "Top/s (fp32 vector instruction slots x 64 lanes)",
+                         "frac": MAMBA1_SLOTS_PER_ELEMENT * melems / (mms * 1e-3) / 1e12 / ALU_PEAK_TOPS, "traffic": None,
+                         "note": "%.2f issue slots per (token, channel, state) element counted in the kernel's state "
+                                 "loop: 6.4 full-rate instructions (2 multiplies, 2 multiply-adds, 2 mixed-precision multiply-adds "
+                                 "on the fp16 B/C codes, 0.4 for the lane scan) and 1.06 quarter-rate exponentials"
+                                 % MAMBA1_SLOTS_PER_ELEMENT},
+            "roofline_hbm": {"kernel": "mamba1_scan_kernel", "bound": "hbm", "achieved": mbytes / (mms * 1e-3) / 1e9,
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mbytes / (mms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "traffic": None},
+            "finite": bool(torch.isfinite(my).all().item()),
+        }
+        if not args.no_cpu:   # spot check against the oracle: 6 channels of sequence 0, all tokens
+            import oracle
+            pick = np.array([0, 1, mD // 3, mD // 2, mD - 2, mD - 1])
+            yref, sref = oracle.ref_mamba1_scan(xs_c[pick], mhs.B_scales[0], mhs.C_scales[0], mx[:1, pick].cpu().numpy(),
+                                                mB[:1].cpu().numpy(), mC[:1].cpu().numpy(), mdt[:1, pick].cpu().numpy(),
+                                                mA[pick].cpu().numpy(), mDk[pick].cpu().numpy())
+            err = float(np.abs(my[:1, pick].float().cpu().numpy() - yref).max() / np.abs(yref).max())
+            out["mamba1_scan"]["parity_spot_check"] = {"max_abs_err_over_max_abs_ref": err, "bar": 2e-3,
+                                                       "channels": int(pick.size)}
+        # one generation step of the same layer at batch 256 on the fp32 state
+        db = 256
+        dshape1 = q.Shape(batch=db, seqlen=1, nheads=1, headdim=mD, d_state=mN, ngroups=1, chunk=1, n_head_clusters=1,
+                          n_chan_clusters=4, flags=0)
+        sx1 = mx[0, :, :64].t().contiguous().repeat(4, 1)       # 256 token columns of the prefill inputs as the batch
+        sdt1 = mdt[0, :, :64].t().contiguous().repeat(4, 1)
+        sB1 = mB[0, :, :64].t().contiguous().repeat(4, 1)
+        sC1 = mC[0, :, :64].t().contiguous().repeat(4, 1)
+        mstate = mfin[:1].repeat(db, 1, 1).contiguous()
+        y1 = torch.empty((db, mD), dtype=torch.float16, device=dev)
+
+        def mamba1_step():
+            q.quamba_mamba1_decode_step(dshape1, mdsc, sx1, sB1, sC1, sdt1, mA, mDk, mstate, y1)
+
+        sms, swall = time_region(torch, mamba1_step, args.steps, max(args.warmup, 4))
+        sbytes = 8.0 * db * mD * mN + 7.0 * db * mD + 2.0 * db * mN + 4.0 * mD * mN
+        out["mamba1_decode"] = {
+            "metric": "Mamba1 decode state update us/step", "value": sms * 1e3, "unit": "us/step",
+            "higher_is_better": False, "wall_us_per_step": swall * 1e3,
+            "config": {"workload": "Mamba1-2.8B-shaped layer, batch 256: fp32 state [256, 5120, 16] (84 MB) in place"},
+            "roofline": {"kernel": "mamba1_decode16_kernel", "bound": "hbm", "achieved": sbytes / (sms * 1e-3) / 1e9,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sbytes / (sms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": None},
+            "finite": bool(torch.isfinite(mstate).all().item()),
+        }
+        del mx, mB, mC, mdt, my, rawm, mstate
 
     # ------------------------------------------------------------------ decode
     if not args.no_decode:

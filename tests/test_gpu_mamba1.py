@@ -46,15 +46,15 @@ def _check(q, b, D, N, L, seed, nranges=4, flags=0, with_init=False, with_D=True
 
 
 def test_wave_scan_kernel_several_tiles_and_a_ragged_one(gpu_lib):
-    """2608 tokens = two full tiles of 1024 and one of 560 (35 live lanes); channels not a multiple of the 16 a
-    workgroup owns at batch*channels >= 16384, nor of 4."""
+    """2608 tokens = two full tiles of 1024 and one of 560 (35 live lanes); channels not a multiple of the 8 a
+    workgroup owns (the last workgroup has waves without a channel)."""
     ey, es = _check(gpu_lib, b=2, D=8198, N=16, L=2608, seed=1, with_init=True)
-    print(f"mamba1 scan, 4 channels per wave: y {ey:.2e} state {es:.2e}")
+    print(f"mamba1 scan, 8198 channels x 2608 tokens: y {ey:.2e} state {es:.2e}")
 
 
-def test_wave_scan_kernel_one_channel_per_wave(gpu_lib):
+def test_wave_scan_kernel_small_shapes(gpu_lib):
     ey, es = _check(gpu_lib, b=1, D=203, N=16, L=1040, seed=2)
-    print(f"mamba1 scan, 1 channel per wave: y {ey:.2e} state {es:.2e}")
+    print(f"mamba1 scan, 203 channels x 1040 tokens: y {ey:.2e} state {es:.2e}")
     _check(gpu_lib, b=3, D=64, N=16, L=16, seed=3, with_init=True, with_D=False)       # one lane of tokens
 
 
