@@ -32,11 +32,31 @@ __device__ __forceinline__ float activation_over_scale(int acc, float s_cw, floa
     return a * inv;
 }
 
-// Eq. 1 for four values into one dword: clamp, then the rounding add (1.5 * 2^23) writes its low byte into byte k.
-__device__ __forceinline__ uint32_t codes4(float r0, float r1, float r2, float r3)
+// The same value through the hardware's approximate base-2 exponential and reciprocal (1 unit in the last place
+// each): v / (1 + 2^(-v log2 e)) * inv.  It shares v and the rounded exponent argument with the exact sequence above
+// (whose e is 2^-|t| for the same t), so the two differ only by the roundings after that point: by less than
+// 1e-6 of the value (derivation in the design notes).  Deeply negative v gives 2^t = inf and the result -0.
+__device__ __forceinline__ float activation_over_scale_fast(int acc, float s_cw, float bias, float inv)
 {
-    const float c0 = __builtin_amdgcn_fmed3f(r0, -128.0f, 127.0f), c1 = __builtin_amdgcn_fmed3f(r1, -128.0f, 127.0f);
-    const float c2 = __builtin_amdgcn_fmed3f(r2, -128.0f, 127.0f), c3 = __builtin_amdgcn_fmed3f(r3, -128.0f, 127.0f);
+    float v = (float)acc * s_cw;
+    v = v + bias;
+    const float E = __builtin_amdgcn_exp2f(-v * from_bits(0x3FB8AA3Bu));
+    const float w = __builtin_amdgcn_rcpf(1.0f + E);
+    const float a = v * w;
+    return a * inv;
+}
+
+// True when a clamped pre-rounding value c from the fast evaluation might round to another integer than the exact
+// sequence's value: when it lies within 2e-6 |c| + 1e-6 (twice the bound on their difference) of a half-integer.
+__device__ __forceinline__ bool near_rounding_boundary(float c)
+{
+    const float d = c - __builtin_rintf(c);
+    return __builtin_fabsf(d) >= __builtin_fmaf(-2e-6f, __builtin_fabsf(c), 0.499999f);
+}
+
+// Eq. 1 for four clamped values into one dword: the rounding add (1.5 * 2^23) writes its low byte into byte k.
+__device__ __forceinline__ uint32_t codes4(float c0, float c1, float c2, float c3)  // values already clamped
+{
     const float magic = 12582912.0f;
     uint32_t out;
     asm("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD"
@@ -143,7 +163,11 @@ __global__ __launch_bounds__(64) void conv1d_q8_vec_kernel(ConvArgs a)
             const u32x4 cur = nx[u];
             if (t + u + kAhead < t1)
                 nx[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ip + (size_t)(t - t0 + u + kAhead) * Ct));
+            // Codes from the fast evaluation wherever it provably rounds like the exact sequence; channels in which any
+            // lane sits too close to a rounding boundary (about 1 % of the channel-tokens of a wave) are redone with
+            // the exact sequence below, so every code is the exact sequence's code.
             u32x4 o;
+            uint32_t redo = 0;  // wave-uniform: bit j = channel j needs the exact sequence
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 float r[4];
@@ -152,9 +176,20 @@ __global__ __launch_bounds__(64) void conv1d_q8_vec_kernel(ConvArgs a)
                     const int j = 4 * q + i;
                     win[j] = __builtin_amdgcn_perm(cur[q], win[j], 0x04030201u + ((uint32_t)i << 24));
                     const int acc = __builtin_amdgcn_sdot4((int)win[j], (int)w[j], 0, false);
-                    r[i] = activation_over_scale(acc, a.in_w_scale, bias[j], inv[j]);
+                    r[i] = __builtin_amdgcn_fmed3f(activation_over_scale_fast(acc, a.in_w_scale, bias[j], inv[j]),
+                                                   -128.0f, 127.0f);
+                    redo |= (__builtin_amdgcn_ballot_w64(near_rounding_boundary(r[i])) != 0 ? 1u : 0u) << j;
                 }
                 o[q] = codes4(r[0], r[1], r[2], r[3]);
+            }
+            if (redo) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (redo & (1u << j)) {
+                        const int acc = __builtin_amdgcn_sdot4((int)win[j], (int)w[j], 0, false);
+                        const uint32_t code = code1(activation_over_scale(acc, a.in_w_scale, bias[j], inv[j]));
+                        o[j >> 2] = (o[j >> 2] & ~(0xffu << (8 * (j & 3)))) | (code << (8 * (j & 3)));
+                    }
             }
             __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(op + (size_t)(t - t0 + u) * row));
         }

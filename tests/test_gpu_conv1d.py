@@ -79,6 +79,17 @@ def test_8b_shape_with_carried_state_in_pieces(gpu_lib):
     assert np.array_equal(state, ref_state)
 
 
+def test_many_elements_against_the_exact_sequence(gpu_lib):
+    """21 million outputs compared one by one.  The kernel takes most codes from the hardware's approximate exponential
+    and reciprocal and falls back to the stated exact sequence wherever the two could round differently; a bound that
+    was too optimistic would show here as single codes off by one."""
+    s = W.CONFIGS["m2_8b_b1"].with_(batch=2, seqlen=1024)
+    sc, _, _ = make_problem(s.with_(batch=1, seqlen=8), seed=12, calib_tokens=256)
+    inp = make_conv_inputs(s, seed=12)
+    ref, _ = _check(gpu_lib, s, sc, inp)
+    assert len(np.unique(ref)) > 200
+
+
 def test_decode_step_updates_state_in_place(gpu_lib):
     s = W.CONFIGS["m2_8b_decode"].with_(batch=5, seqlen=1)
     sc, _, _ = make_problem(s.with_(batch=1, seqlen=8), seed=3, calib_tokens=256)
