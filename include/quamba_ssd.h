@@ -265,12 +265,12 @@ int quamba_mamba1_decode_step(const quamba_ssd_shape_t *shape, const quamba_ssd_
  *   bias           device fp32 [Ct] or NULL                 in_w_scale = (input scale) * (weight scale) > 0
  *   conv_state_in  device int8 [batch, 3, Ct] or NULL (the 3 input tokens before the sequence, oldest first)
  *   conv_state_out device int8 [batch, 3, Ct] or NULL: the last 3 input tokens after this call (for seqlen < 3 the tail
- *                  of the old state moves up); may be the same buffer as conv_state_in only when seqlen <= 32
+ *                  of the old state moves up); may be the same buffer as conv_state_in only when seqlen <= 16
  *   x_out device int8 [batch, seqlen, nheads, headdim];  B_out, C_out device int8 [batch, seqlen, ngroups, d_state]
  * shape: batch, seqlen, nheads, headdim, d_state, ngroups and the cluster counts are used; scales as for the prefill.
  * Shapes with headdim and d_state multiples of 16 and 16-byte aligned tensors take the vector kernel, others a
  * one-thread-per-channel kernel with the same results.
- * Errors: ENULL, ESHAPE, EINVAL (in_w_scale; aliased states with seqlen > 32), EHIP.
+ * Errors: ENULL, ESHAPE, EINVAL (in_w_scale; aliased states with seqlen > 16), EHIP.
  */
 int quamba_conv1d_q8(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales, const int8_t *in,
                      const int8_t *weight, const float *bias, float in_w_scale, const int8_t *conv_state_in,

@@ -249,14 +249,14 @@ extern "C" int quamba_conv1d_q8(const quamba_ssd_shape_t *shape, const quamba_ss
     const int64_t Ct = (int64_t)shape->nheads * shape->headdim + 2LL * shape->ngroups * shape->d_state;
     if (Ct > 0x7fffffffLL / 4 || shape->batch > 65535 || quamba::conv1d_segments(*shape) > 65535) return QUAMBA_ESHAPE;
     if (!(in_w_scale > 0.0f) || !std::isfinite(in_w_scale)) return QUAMBA_EINVAL;
-    if (conv_state_in && conv_state_in == conv_state_out && quamba::conv1d_segments(*shape) > 1) return QUAMBA_EINVAL;
+    if (conv_state_in && conv_state_in == conv_state_out && shape->seqlen > 16) return QUAMBA_EINVAL;
     quamba::ConvArgs a;
     a.s = *shape;
     a.x_scales = scales->x_scales; a.head_cluster_end = scales->head_cluster_end;
     a.chan_cluster_end = scales->chan_cluster_end; a.B_scales = scales->B_scales; a.C_scales = scales->C_scales;
     a.in = in; a.weight = weight; a.bias = bias; a.in_w_scale = in_w_scale;
     a.state_in = conv_state_in; a.state_out = conv_state_out;
-    a.x_out = x_out; a.B_out = B_out; a.C_out = C_out;
+    a.x_out = x_out; a.B_out = B_out; a.C_out = C_out; a.seg = 0;
     const hipError_t e = quamba::launch_conv1d_q8(a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }

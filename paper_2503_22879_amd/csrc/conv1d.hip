@@ -4,7 +4,7 @@
 // (Section 4.1) -- written straight into the scan's three input tensors.  The channel order is the sorted order
 // the offline reordering gives the convolution's weights (Section 4.2), so nothing is permuted here.
 //
-// A thread owns 16 consecutive channels (one 16-byte load per token) and walks a segment of tokens.  Per channel it
+// A thread owns 16 consecutive channels (one 16-byte load per token) and walks a segment of 16 or 32 tokens.  Per channel it
 // keeps the last four input codes in one dword (byte k = tap k, the newest in byte 3): a byte permute shifts the new
 // code in, one 4-way int8 dot product with the channel's packed taps gives the exact integer sum.  The code is an
 // integer decided by fp32 arithmetic; the decision sequence (stated in the header) is evaluated with every operation
@@ -16,9 +16,12 @@
 namespace quamba {
 namespace {
 
-constexpr int kSeg = 32;       // tokens per workgroup of the vector kernel
+constexpr int kSegLong = 32;   // tokens per workgroup of the vector kernel when that still gives the device enough waves,
+constexpr int kSegShort = 16;  // else this many
+constexpr int kWaveSlots = 4096;  // resident waves at this kernel's register budget (1024 SIMDs x 4)
 constexpr int kAhead = 4;      // tokens whose loads are in flight
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // r = SiLU(acc * s_cw + bias) * inv in the stated order: the value Eq. 1 rounds.
 __device__ __forceinline__ float activation_over_scale(int acc, float s_cw, float bias, float inv)
@@ -112,7 +115,7 @@ __global__ __launch_bounds__(64) void conv1d_q8_vec_kernel(ConvArgs a)
     const int c0 = 16 * (blockIdx.x * 64 + threadIdx.x);
     if (c0 >= Ct) return;
     const int b = blockIdx.z, L = a.s.seqlen;
-    const int t0 = blockIdx.y * kSeg, t1 = min(t0 + kSeg, L);
+    const int t0 = blockIdx.y * a.seg, t1 = min(t0 + a.seg, L);
 
     // per-channel constants: packed taps, bias, reciprocal output scale (one correctly rounded division each)
     uint32_t w[16];
@@ -125,13 +128,48 @@ __global__ __launch_bounds__(64) void conv1d_q8_vec_kernel(ConvArgs a)
             const u32x4 v = wp[q];
             w[4 * q] = v[0]; w[4 * q + 1] = v[1]; w[4 * q + 2] = v[2]; w[4 * q + 3] = v[3];
         }
-        int8_t *d; int rw, cl;
+        if (a.bias) {
+            const f32x4 *bp = reinterpret_cast<const f32x4 *>(a.bias + c0);  // c0 is a multiple of 16: 64-byte aligned
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            bias[j] = a.bias ? a.bias[c0 + j] : 0.0f;
-            inv[j] = __fdiv_rn(1.0f, channel_scale(a, c0 + j, &d, &rw, &cl));
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 v = bp[q];
+                bias[4 * q] = v[0]; bias[4 * q + 1] = v[1]; bias[4 * q + 2] = v[2]; bias[4 * q + 3] = v[3];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) bias[j] = 0.0f;
         }
-        channel_scale(a, c0, &dst, &row, &col);  // the 16 channels share one output tensor (16 divides HP and GN)
+        // The 16 channels share one output tensor and one head or state group (16 divides headdim and d_state), so
+        // one lookup finds the first channel's cell; the channel ranges of a head are ascending, so the following
+        // channels only step to the next range when they pass its end.
+        if (c0 < HP) {
+            SsdArgs t;
+            t.s = a.s; t.x_scales = a.x_scales; t.head_cluster_end = a.head_cluster_end;
+            t.chan_cluster_end = a.chan_cluster_end;
+            const int h = c0 / a.s.headdim, p0 = c0 - h * a.s.headdim;
+            int base;
+            int cell = cell_lookup(t, h, p0, &base);
+            const int last = base + a.s.n_chan_clusters - 1;
+            int end = cell < last ? a.chan_cluster_end[cell] : a.s.headdim;
+            float iv = __fdiv_rn(1.0f, a.x_scales[cell]);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                while (p0 + j >= end) {  // at most n - 1 steps over the 16 channels together
+                    ++cell;
+                    end = cell < last ? a.chan_cluster_end[cell] : a.s.headdim;
+                    iv = __fdiv_rn(1.0f, a.x_scales[cell]);
+                }
+                inv[j] = iv;
+            }
+            dst = a.x_out; row = HP; col = c0;
+        } else {
+            const bool isB = c0 < HP + GN;
+            const int cg = c0 - HP - (isB ? 0 : GN);
+            const float iv = __fdiv_rn(1.0f, (isB ? a.B_scales : a.C_scales)[cg / a.s.d_state]);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) inv[j] = iv;
+            dst = isB ? a.B_out : a.C_out; row = GN; col = cg;
+        }
     }
 
     // the window before the segment: tokens t0-3 .. t0-1 in bytes 1..3 (byte 0 is shifted out by the first token)
@@ -245,20 +283,35 @@ __global__ __launch_bounds__(256) void conv1d_q8_any_kernel(ConvArgs a)
 bool vec_ok(const ConvArgs &a)
 {
     auto al = [](const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
-    return a.s.headdim % 16 == 0 && a.s.d_state % 16 == 0 && al(a.in) && al(a.weight) && al(a.state_in) &&
+    return a.s.headdim % 16 == 0 && a.s.d_state % 16 == 0 && al(a.in) && al(a.weight) && al(a.bias) && al(a.state_in) &&
            al(a.state_out) && al(a.x_out) && al(a.B_out) && al(a.C_out);
 }
 
 }  // namespace
 
-int conv1d_segments(const quamba_ssd_shape_t &s) { return (s.seqlen + kSeg - 1) / kSeg; }
+// Tokens per workgroup: the long segment amortises the per-segment set-up and the 3-token halo better, the short one
+// is taken when the long one would leave wave slots empty.
+int conv1d_segment_tokens(const quamba_ssd_shape_t &s)
+{
+    const int64_t Ct = (int64_t)s.nheads * s.headdim + 2LL * s.ngroups * s.d_state;
+    const int64_t waves = ((Ct / 16 + 63) / 64) * s.batch * ((s.seqlen + kSegLong - 1) / kSegLong);
+    return waves >= kWaveSlots ? kSegLong : kSegShort;
+}
+
+int conv1d_segments(const quamba_ssd_shape_t &s)
+{
+    const int seg = conv1d_segment_tokens(s);
+    return (s.seqlen + seg - 1) / seg;
+}
 
 hipError_t launch_conv1d_q8(const ConvArgs &a, hipStream_t stream)
 {
     const int Ct = a.s.nheads * a.s.headdim + 2 * a.s.ngroups * a.s.d_state;
     if (vec_ok(a)) {
+        ConvArgs v = a;
+        v.seg = conv1d_segment_tokens(a.s);
         const dim3 grid((unsigned)((Ct / 16 + 63) / 64), (unsigned)conv1d_segments(a.s), (unsigned)a.s.batch);
-        hipLaunchKernelGGL(conv1d_q8_vec_kernel, grid, dim3(64), 0, stream, a);
+        hipLaunchKernelGGL(conv1d_q8_vec_kernel, grid, dim3(64), 0, stream, v);
     } else {
         const dim3 grid((unsigned)((Ct + 255) / 256), (unsigned)a.s.batch);
         hipLaunchKernelGGL(conv1d_q8_any_kernel, grid, dim3(256), 0, stream, a);

@@ -145,6 +145,7 @@ struct ConvArgs {
     const int8_t *state_in;   // [b, 3, HP + 2 GN] or null
     int8_t *state_out;        // same shape, or null
     int8_t *x_out, *B_out, *C_out;
+    int seg;                  // tokens per workgroup (set by the launcher)
 };
 hipError_t launch_conv1d_q8(const ConvArgs &a, hipStream_t stream);
 int conv1d_segments(const quamba_ssd_shape_t &s);  // workgroups along one sequence (1: state_in may equal state_out)
