@@ -9,9 +9,8 @@
 // phase B on values 32 apart (strides 32..512), phase C on values 1024 apart (strides 1024..n/2) for groups of
 // consecutive values, so that the codes leave as dwords.  The row is read once (fp16, 64 contiguous bytes per thread)
 // and written once (int8): 3 bytes of HBM traffic and 17 vector instructions (13 butterflies, a scale, a clamp, a
-// rounding add; no packed fp32) per value.  What bounds the kernel at n = 8192 is neither alone: a row's fp32 image
-// (33 KB of LDS) limits a compute unit to 4 rows in flight, and each row is a serial chain of three arithmetic
-// phases, two LDS exchanges (LDS writes run at about 80 bytes per clock per compute unit) and three barriers.
+// rounding add; no packed fp32) per value.  At n = 8192 the vector ALU, the LDS exchanges and HBM each take 40-60 us
+// when alone; a row's fp32 image (37 KB of LDS) limits a compute unit to 4 rows in flight, so they overlap only partly.
 #include "quamba_internal.h"
 
 #pragma clang fp contract(off)
@@ -71,7 +70,10 @@ __device__ __forceinline__ void butterflies(float (&v)[32])
 
 // n = 2^LOGN, 10 <= LOGN <= 14, n/32 threads, as many workgroups as stay resident; each loops over rows
 // blockIdx.x, blockIdx.x + gridDim.x, ... and loads its next row (16 registers of packed fp16) while it works on the
-// current one, so the HBM latency of a row is hidden behind the arithmetic of the row before.
+// current one, so the HBM latency of a row is hidden behind the arithmetic of the row before.  The loads are plain,
+// not non-temporal: a lane's four 16-byte loads walk through one 64-byte sector, which has to stay in the vector cache
+// between them (with non-temporal loads every one of the four fetched the sector again and the loads alone took 69 us
+// instead of 39 at the 8B layer's size).
 template <int LOGN>
 __global__ __launch_bounds__(1 << (LOGN - 5)) void hadamard_quantize_kernel(const uint16_t *y, int8_t *out, int rows,
                                                                             float inv_s)
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(1 << (LOGN - 5)) void hadamard_quantize_kernel(cons
     constexpr int CB = LOGN - 10;       // strides of phase C
     constexpr int NE = 1 << CB;         // values 1024 apart a thread holds in phase C
     constexpr int CONSEC = 32 / NE;     // consecutive values per such position (2..32)
-    extern __shared__ float lds[];      // N + N/32 floats
+    extern __shared__ float lds[];      // 1152 floats per block of 1024 values
     const int t = threadIdx.x;
     const int t_lo = t & 31, t_hi = t >> 5;
     float v[32];
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(1 << (LOGN - 5)) void hadamard_quantize_kernel(cons
     {
         const u32x4 *src = reinterpret_cast<const u32x4 *>(y + (size_t)r * N + 32 * t);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) nx[q] = __builtin_nontemporal_load(src + q);
+        for (int q = 0; q < 4; ++q) nx[q] = src[q];
     }
     for (; r < rows; r += gridDim.x) {
         // phase A: values 32 t + e;
@@ -109,23 +111,28 @@ __global__ __launch_bounds__(1 << (LOGN - 5)) void hadamard_quantize_kernel(cons
         if (r + (int)gridDim.x < rows) {
             const u32x4 *src = reinterpret_cast<const u32x4 *>(y + (size_t)(r + gridDim.x) * N + 32 * t);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) nx[q] = __builtin_nontemporal_load(src + q);
+            for (int q = 0; q < 4; ++q) nx[q] = src[q];
         }
         butterflies<5, 2>(v);
-        // through LDS with one float of padding per 32 (value i at i + (i >> 5)): both the writes of 32 consecutive
-        // values per thread and the reads 32 apart then fall on distinct banks
+        // Through LDS, transposed inside every block of 1024 values: value 32 a + k of the block (thread a's k-th
+        // value) goes to 36 k + a, so that the 32 values the next phase needs in one thread (k fixed, a = 0..31) are
+        // 32 consecutive floats, read 16 bytes at a time; the pitch of 36 floats keeps 16 lanes' 16-byte reads on
+        // distinct banks, and the writes of consecutive threads are consecutive floats.
         {
-            float *pa = lds + 33 * t;
+            float *pa = lds + t_lo + 1152 * t_hi;
 #pragma unroll
-            for (int e = 0; e < 32; ++e) pa[e] = v[e];
+            for (int k = 0; k < 32; ++k) pa[36 * k] = v[k];
             __syncthreads();
-            // phase B: values i = t_lo + 32 e + 1024 t_hi
-            const float *pb = lds + t_lo + 1056 * t_hi;
+            // phase B: values i = t_lo + 32 e + 1024 t_hi, e = 0..31
+            const f32x4 *pb = reinterpret_cast<const f32x4 *>(lds + 36 * t_lo + 1152 * t_hi);
 #pragma unroll
-            for (int e = 0; e < 32; ++e) v[e] = pb[33 * e];
+            for (int q = 0; q < 8; ++q) {
+                const f32x4 w = pb[q];
+                v[4 * q] = w[0]; v[4 * q + 1] = w[1]; v[4 * q + 2] = w[2]; v[4 * q + 3] = w[3];
+            }
         }
         butterflies<5>(v);
-        __syncthreads();  // all reads of the padded layout are done before the plain one overwrites it
+        __syncthreads();  // all reads of the transposed layout are done before the plain one overwrites it
         {
             float *pb = lds + t_lo + 1024 * t_hi;
 #pragma unroll
@@ -188,7 +195,7 @@ template <int LOGN>
 hipError_t launch_fast(const uint16_t *y, int64_t rows, float inv_s, int8_t *out, hipStream_t stream)
 {
     constexpr int N = 1 << LOGN;
-    constexpr int lds = (N + N / 32) * (int)sizeof(float);
+    constexpr int lds = (N / 1024) * 1152 * (int)sizeof(float);
     // twice the workgroups that fit the device at once (measured best; one round of exactly resident workgroups
     // is 10% slower), asked of the runtime once per order and device
     static int resident[16] = {0};

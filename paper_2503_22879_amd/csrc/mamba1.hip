@@ -129,7 +129,7 @@ __global__ __launch_bounds__(kThreads, 4) void mamba1_scan_kernel(SsdArgs a, con
             xq = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.x + row));
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.dt + row) + q);
+                const f32x4 v = reinterpret_cast<const f32x4 *>(a.dt + row)[q];  // plain: four loads share a sector
                 dt[4 * q] = v[0]; dt[4 * q + 1] = v[1]; dt[4 * q + 2] = v[2]; dt[4 * q + 3] = v[3];
             }
         } else {
