@@ -32,9 +32,12 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16/bf16
 MFMA_I8_PEAK_TOPS = 5000.0     # dense int8
 
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, each scaled by its reading for a plain
-# 256 MiB device copy in the same run: factors 1.9998 and 1.0000); profiles/hbm_traffic_prefill_m2_8b_b4_and_decode_m2_8b.txt.
+# 256 MiB device copy in the same run: factors 1.9998 and 1.0000); profiles/hbm_traffic_prefill_m2_8b_b4_and_decode_m2_8b.txt
+# and profiles/hbm_traffic_hadamard_conv1d_m2_8b_b4_and_mamba1_2p8b.txt.
 # None for workloads that were not profiled.
-MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 494.2e6, "m2_8b_decode": 2162.2e6, "m2_8b_decode_q8": 550.8e6}
+MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 495.3e6, "m2_8b_decode": 2162.2e6, "m2_8b_decode_q8": 550.9e6,
+                          "m2_8b_b4_hadamard": 402.7e6, "m2_8b_b4_conv1d": 352.1e6,
+                          "mamba1_2p8b_scan": 598.8e6, "mamba1_2p8b_decode": 178.7e6}
 
 
 def prefill_algorithmic(s: W.LayerShape):
@@ -289,7 +292,8 @@ def main() -> int:
                                    "scan's cell and group scales" % (s.name, s.batch * s.seqlen, Ct)},
             "roofline": {"kernel": "conv1d_q8_vec_kernel", "bound": "alu", "achieved": cops / (cms * 1e-3) / 1e12,
                          "peak": ALU_PEAK_TOPS, "unit": "Top/s (fp32 vector instructions x 64 lanes)",
-                         "frac": cops / (cms * 1e-3) / 1e12 / ALU_PEAK_TOPS, "traffic": None,
+                         "frac": cops / (cms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get(s.name + "_conv1d"),
                          "note": "%.1f issue slots per output element counted in the kernel's main loop (18.3 full-rate "
                                  "instructions, a quarter-rate exponential and a quarter-rate reciprocal), not "
                                  "counting the ~1 %% of channel-tokens redone with the exact 45-instruction sequence"
@@ -349,14 +353,15 @@ def main() -> int:
             "roofline": {"kernel": "mamba1_scan_kernel", "bound": "alu",
                          "achieved": MAMBA1_SLOTS_PER_ELEMENT * melems / (mms * 1e-3) / 1e12, "peak": ALU_PEAK_TOPS,
                          "unit": "Top/s (fp32 vector instruction slots x 64 lanes)",
-                         "frac": MAMBA1_SLOTS_PER_ELEMENT * melems / (mms * 1e-3) / 1e12 / ALU_PEAK_TOPS, "traffic": None,
+                         "frac": MAMBA1_SLOTS_PER_ELEMENT * melems / (mms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get("mamba1_2p8b_scan"),
                          "note": "%.2f issue slots per (token, channel, state) element counted in the kernel's state "
                                  "loop: 6.4 full-rate instructions (2 multiplies, 2 multiply-adds, 2 mixed-precision multiply-adds "
                                  "on the fp16 B/C codes, 0.4 for the lane scan) and 1.06 quarter-rate exponentials"
                                  % MAMBA1_SLOTS_PER_ELEMENT},
             "roofline_hbm": {"kernel": "mamba1_scan_kernel", "bound": "hbm", "achieved": mbytes / (mms * 1e-3) / 1e9,
                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mbytes / (mms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                             "traffic": None},
+                             "traffic": MEASURED_TRAFFIC_BYTES.get("mamba1_2p8b_scan")},
             "finite": bool(torch.isfinite(my).all().item()),
         }
         if not args.no_cpu:   # spot check against the oracle: 6 channels of sequence 0, all tokens
@@ -390,7 +395,7 @@ def main() -> int:
             "config": {"workload": "Mamba1-2.8B-shaped layer, batch 256: fp32 state [256, 5120, 16] (84 MB) in place"},
             "roofline": {"kernel": "mamba1_decode16_kernel", "bound": "hbm", "achieved": sbytes / (sms * 1e-3) / 1e9,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sbytes / (sms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "traffic": None},
+                         "traffic": MEASURED_TRAFFIC_BYTES.get("mamba1_2p8b_decode")},
             "finite": bool(torch.isfinite(mstate).all().item()),
         }
         del mx, mB, mC, mdt, my, rawm, mstate
