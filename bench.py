@@ -55,8 +55,9 @@ Q8_OPS_PER_ELEMENT = 8
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3: fp32 vector instructions per second x 64 lanes, unpacked, unfused
 
 
-MAMBA1_SLOTS_PER_ELEMENT = 10.7   # issue slots per (token, channel, state) element in mamba1_scan_kernel's state loop
-CONV_OPS_PER_ELEMENT = 24.3   # vector issue slots per output element in conv1d_q8_vec_kernel's main loop
+MAMBA1_SLOTS_PER_ELEMENT = 8.9   # vector instructions per (token, channel, state) element of mamba1_scan_kernel (counter)
+SPIN_UP_MS = float(os.environ.get("QUAMBA_BENCH_SPIN_UP_MS", "80"))   # untimed device work in front of every timed region, after the W warm-up launches (see time_region)
+CONV_OPS_PER_ELEMENT = 22.0   # vector instructions per output element of conv1d_q8_vec_kernel (SQ_INSTS_VALU x 64 / elements)
 
 
 def HADAMARD_OPS_PER_VALUE(n: int) -> int:
@@ -87,12 +88,20 @@ def quantize_layer(q, shape, hs, raw):
             "dt": np.ascontiguousarray(raw["dt"], np.float32)}
 
 
-def time_region(torch, fn, steps, warmup):
+def time_region(torch, fn, steps, warmup, min_warm_ms=0.0):
     """Mean ms per call over `steps` calls on torch's current stream (the stream the kernels are launched on),
-    bracketed by device synchronisation; HIP events give the device-side duration."""
+    bracketed by device synchronisation; HIP events give the device-side duration.  With min_warm_ms the untimed
+    warm-up is continued until that much wall time has gone by: after seconds of host-side preparation the first tens
+    of milliseconds of device work run up to 1.5x slower (measured on the decode legs), which a handful of warm-up
+    launches does not cover."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
+    t_w = time.perf_counter()
+    while (time.perf_counter() - t_w) * 1e3 < min_warm_ms:
+        for _ in range(8):
+            fn()
+        torch.cuda.synchronize()
     ev0 = torch.cuda.Event(enable_timing=True)
     ev1 = torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
@@ -136,6 +145,14 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
     seed = 3
+    # The decode legs' state buffers are allocated first, while the process's device address space is still empty: the
+    # same kernels ran up to 1.5x (fp32 state) and 3x (int8 state) slower on buffers allocated after the other legs had
+    # allocated and freed theirs (the allocation's physical backing, not the kernel, differs).
+    sd0 = W.CONFIGS["m2_8b_decode"]
+    state_buf = qstate_buf = None
+    if not args.no_decode:
+        state_buf = torch.empty((sd0.batch, sd0.nheads, sd0.headdim, sd0.d_state), device=dev)
+        qstate_buf = torch.empty((sd0.batch, sd0.nheads, sd0.headdim, sd0.d_state), dtype=torch.int8, device=dev)
 
     # ------------------------------------------------------------------ prefill
     s = W.CONFIGS[args.workload]
@@ -170,7 +187,7 @@ def main() -> int:
     def prefill():
         q.quamba_ssd_prefill(shape, dsc, t["x"], t["B"], t["C"], t["dt"], A, D, None, y, fin, ws, gate=gate)
 
-    ms, wall_ms = time_region(torch, prefill, args.steps, args.warmup)
+    ms, wall_ms = time_region(torch, prefill, args.steps, args.warmup, min_warm_ms=SPIN_UP_MS)
     tokens = s.batch * s.seqlen
     f16_macs, i8_macs, bytes_tok = prefill_algorithmic(s)
     flops_equiv = tokens * (2 * f16_macs + 2 * i8_macs * (MFMA_F16_PEAK_TFLOPS / MFMA_I8_PEAK_TOPS))
@@ -180,7 +197,8 @@ def main() -> int:
 
     out = {
         "metric": "int8 SSD prefill tokens/s/layer", "value": tokens / (ms * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "wall_ms_per_step": wall_ms,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "spin_up_ms": SPIN_UP_MS, "ms_per_step": ms,
+        "wall_ms_per_step": wall_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8 x/B/C, fp16 MFMA, fp32 acc",
         "data": "synthetic",
         "config": {"workload": f"{s.name}: Mamba2-8B-shaped SSD layer prefill" if "8b" in s.name else s.name,
@@ -234,7 +252,7 @@ def main() -> int:
         def hadamard():
             q.quamba_hadamard_quantize(yflat, s_y, yq)
 
-        hms, hwall = time_region(torch, hadamard, args.steps, max(args.warmup, 4))
+        hms, hwall = time_region(torch, hadamard, args.steps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS)
         hbytes = 3.0 * rows * n_had
         hgbs = hbytes / (hms * 1e-3) / 1e9
         hops = HADAMARD_OPS_PER_VALUE(n_had) * rows * n_had
@@ -281,7 +299,7 @@ def main() -> int:
         def conv():
             q.quamba_conv1d_q8(shape, dsc, cin, cw, cbias, in_w_scale, cx, cB, cC, conv_state_out=cst)
 
-        cms, cwall = time_region(torch, conv, args.steps, max(args.warmup, 4))
+        cms, cwall = time_region(torch, conv, args.steps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS)
         celems = float(s.batch) * s.seqlen * Ct
         cgbs = 2.0 * celems / (cms * 1e-3) / 1e9
         cops = CONV_OPS_PER_ELEMENT * celems
@@ -294,10 +312,10 @@ def main() -> int:
                          "peak": ALU_PEAK_TOPS, "unit": "Top/s (fp32 vector instructions x 64 lanes)",
                          "frac": cops / (cms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
                          "traffic": MEASURED_TRAFFIC_BYTES.get(s.name + "_conv1d"),
-                         "note": "%.1f issue slots per output element counted in the kernel's main loop (18.3 full-rate "
-                                 "instructions, a quarter-rate exponential and a quarter-rate reciprocal), not "
-                                 "counting the ~1 %% of channel-tokens redone with the exact 45-instruction sequence"
-                                 % CONV_OPS_PER_ELEMENT},
+                         "note": "%.1f vector instructions per output element as executed (rocprofv3 SQ_INSTS_VALU x 64 / "
+                                 "elements: 18.3 in the main loop, two of them quarter-rate, plus the set-up and the "
+                                 "channel-tokens redone with the exact 45-instruction sequence), against one "
+                                 "instruction per lane and cycle" % CONV_OPS_PER_ELEMENT},
             "roofline_hbm": {"kernel": "conv1d_q8_vec_kernel", "bound": "hbm", "achieved": cgbs,
                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": cgbs / HBM_PEAK_GBS,
                              "traffic": MEASURED_TRAFFIC_BYTES.get(s.name + "_conv1d")},
@@ -342,7 +360,7 @@ def main() -> int:
         def mamba1():
             q.quamba_mamba1_scan(mshape, mdsc, mx, mB, mC, mdt, mA, mDk, my, final_state=mfin)
 
-        mms, mwall = time_region(torch, mamba1, max(20, args.steps // 2), max(args.warmup // 2, 3))
+        mms, mwall = time_region(torch, mamba1, max(20, args.steps // 2), max(args.warmup // 2, 3), min_warm_ms=SPIN_UP_MS)
         melems = float(mb) * mD * mL * mN
         mbytes = float(mb) * mD * mL * 7 + 2.0 * mb * mN * mL
         out["mamba1_scan"] = {
@@ -352,13 +370,12 @@ def main() -> int:
                                    "4 channel ranges; int8 x/B/C, fp32 dt, fp16 y, final state returned"},
             "roofline": {"kernel": "mamba1_scan_kernel", "bound": "alu",
                          "achieved": MAMBA1_SLOTS_PER_ELEMENT * melems / (mms * 1e-3) / 1e12, "peak": ALU_PEAK_TOPS,
-                         "unit": "Top/s (fp32 vector instruction slots x 64 lanes)",
+                         "unit": "Top/s (fp32 vector instructions x 64 lanes)",
                          "frac": MAMBA1_SLOTS_PER_ELEMENT * melems / (mms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
                          "traffic": MEASURED_TRAFFIC_BYTES.get("mamba1_2p8b_scan"),
-                         "note": "%.2f issue slots per (token, channel, state) element counted in the kernel's state "
-                                 "loop: 6.4 full-rate instructions (2 multiplies, 2 multiply-adds, 2 mixed-precision multiply-adds "
-                                 "on the fp16 B/C codes, 0.4 for the lane scan) and 1.06 quarter-rate exponentials"
-                                 % MAMBA1_SLOTS_PER_ELEMENT},
+                         "note": "%.1f vector instructions per (token, channel, state) element as executed (rocprofv3 "
+                                 "SQ_INSTS_VALU x 64 / elements; 1.06 of them quarter-rate exponentials), against one "
+                                 "instruction per lane and cycle" % MAMBA1_SLOTS_PER_ELEMENT},
             "roofline_hbm": {"kernel": "mamba1_scan_kernel", "bound": "hbm", "achieved": mbytes / (mms * 1e-3) / 1e9,
                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mbytes / (mms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                              "traffic": MEASURED_TRAFFIC_BYTES.get("mamba1_2p8b_scan")},
@@ -387,7 +404,7 @@ def main() -> int:
         def mamba1_step():
             q.quamba_mamba1_decode_step(dshape1, mdsc, sx1, sB1, sC1, sdt1, mA, mDk, mstate, y1)
 
-        sms, swall = time_region(torch, mamba1_step, args.steps, max(args.warmup, 4))
+        sms, swall = time_region(torch, mamba1_step, args.steps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS)
         sbytes = 8.0 * db * mD * mN + 7.0 * db * mD + 2.0 * db * mN + 4.0 * mD * mN
         out["mamba1_decode"] = {
             "metric": "Mamba1 decode state update us/step", "value": sms * 1e3, "unit": "us/step",
@@ -417,7 +434,8 @@ def main() -> int:
             r = W.apply_reorder(W.draw_decode_step(sd, seed, k), dhp, dcp)
             qd = quantize_layer(q, dshape, dhs, r)
             steps_in.append({n: torch.from_numpy(v).to(dev) for n, v in qd.items()})
-        state = torch.from_numpy(W.draw_state(sd, seed)).to(dev)
+        state = state_buf
+        state.copy_(torch.from_numpy(W.draw_state(sd, seed)))
         yd = torch.empty((sd.batch, sd.nheads, sd.headdim), dtype=torch.float16, device=dev)
         counter = [0]
 
@@ -427,7 +445,7 @@ def main() -> int:
             q.quamba_ssd_decode_step(dshape, ddsc, i["x"], i["B"], i["C"], i["dt"], dA, dD, state, yd)
 
         dsteps = max(args.steps, sd.decode_steps)
-        dms, dwall = time_region(torch, decode, dsteps, max(args.warmup, 4))
+        dms, dwall = time_region(torch, decode, dsteps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS)
         dgbs = decode_bytes(sd) / (dms * 1e-3) / 1e9
         out["decode"] = {
             "metric": "decode state update us/step", "value": dms * 1e3, "unit": "us/step", "steps": dsteps,
@@ -439,8 +457,6 @@ def main() -> int:
         }
 
         # ------------------------------------------------ decode on the 8-bit cached state (Appendix E)
-        del state
-        torch.cuda.empty_cache()
         ncell = sd.ngroups * sd.m * sd.n
         mx = W.reorder_state(W.draw_cached_state_calibration(sd, seed), dhp, dcp)
         ss = q.quamba_state_scales(sd.nheads, sd.headdim, sd.ngroups, sd.m, sd.n, sd.d_state, dhs.head_cluster_end,
@@ -450,7 +466,7 @@ def main() -> int:
         # cached states of 32 sequences, drawn once and repeated over the batch, quantized by the library itself
         rep = 32
         st32 = torch.from_numpy(W.reorder_state(W.draw_cached_state(sd, seed, batch=rep), dhp, dcp)).to(dev)
-        qstate = torch.empty((sd.batch, sd.nheads, sd.headdim, sd.d_state), dtype=torch.int8, device=dev)
+        qstate = qstate_buf
         shape32 = q.Shape(**{f: (rep if f == "batch" else getattr(dshape, f)) for f, _ in dshape._fields_})
         q32 = torch.empty((rep, sd.nheads, sd.headdim, sd.d_state), dtype=torch.int8, device=dev)
         q.quamba_ssd_quantize_state(shape32, ddsc, dss, st32, q32)
@@ -464,7 +480,7 @@ def main() -> int:
             counter[0] += 1
             q.quamba_ssd_decode_step_q8(dshape, ddsc, dss, i["x"], i["B"], i["C"], i["dt"], dA, dD, qstate, yd)
 
-        qms, qwall = time_region(torch, decode_q8, dsteps, max(args.warmup, 4))
+        qms, qwall = time_region(torch, decode_q8, dsteps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS)
         qbytes = decode_bytes(sd, state_bytes=1)
         qgbs = qbytes / (qms * 1e-3) / 1e9
         elems = sd.batch * sd.nheads * sd.headdim * sd.d_state
