@@ -57,7 +57,7 @@ ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3: fp32 vector instructions p
 
 MAMBA1_SLOTS_PER_ELEMENT = 8.9   # vector instructions per (token, channel, state) element of mamba1_scan_kernel (counter)
 SPIN_UP_MS = float(os.environ.get("QUAMBA_BENCH_SPIN_UP_MS", "80"))   # untimed device work in front of every timed region, after the W warm-up launches (see time_region)
-CONV_OPS_PER_ELEMENT = 22.0   # vector instructions per output element of conv1d_q8_vec_kernel (SQ_INSTS_VALU x 64 / elements)
+CONV_OPS_PER_ELEMENT = 19.6   # vector instructions per output element of conv1d_q8_vec_kernel (SQ_INSTS_VALU x 64 / elements)
 
 
 def HADAMARD_OPS_PER_VALUE(n: int) -> int:
