@@ -204,15 +204,21 @@ int quamba_state_scales(int32_t nheads, int32_t headdim, int32_t ngroups, int32_
 
 /*
  * Quantized Hadamard transform of the SSD output (Section 4.2, "Offline Hadamard matrix fusion" and "Efficient
- * 4-bit/8-bit Mamba blocks"): out = Eq. 1 of (1/s_y) H_n y for every row, H_n the Sylvester-Hadamard matrix of order
- * n (entries +-1, no normalisation), the 8-bit input of an output projection whose weight carries H_n offline.
+ * 4-bit/8-bit Mamba blocks"): out = Eq. 1 of (1/s_y) H_n y for every row, H_n a Hadamard matrix of order n (entries +-1,
+ * no normalisation), the 8-bit input of an output projection whose weight carries H_n offline.
  *   y   device fp16 [rows, n] (the flattened [.., nheads*headdim] output of the scan, gated or not)
  *   out device int8 [rows, n]; must not overlap y
- *   n   a power of two, 2 <= n <= 16384;  s_y > 0 the static scale of the transformed output
- * The transform is evaluated in fp32 as the radix-2 butterfly network with strides 1, 2, 4, ..., n/2 in this order
- * (stage h replaces (v[i], v[i+h]), i & h == 0, by (v[i] + v[i+h], v[i] - v[i+h])), every operation rounded on its own;
- * then code = clamp(rint(v * (1/s_y)), -128, 127) with 1/s_y and the product rounded to fp32, ties to even.
- * Errors: ENULL, ESHAPE (n not a power of two or out of range, rows < 0 or > 2^31 - 1), EINVAL (s_y), EHIP.
+ *   n   2^k (2 <= n <= 16384), or 12 * 2^k or 20 * 2^k with k >= 2 (48 <= n <= 16384: the widths 1536, 3072, 5120 of the
+ *       Mamba blocks);  s_y > 0 the static scale of the transformed output
+ * n = 2^k: H_n is the Sylvester matrix, evaluated in fp32 as the radix-2 butterfly network with strides 1, 2, 4, ..., n/2
+ * in this order (stage h replaces (v[i], v[i+h]), i & h == 0, by (v[i] + v[i+h], v[i] - v[i+h])), every operation
+ * rounded on its own.  n = m * 2^k, m = 12 or 20: H_n = H_m (x) H_{2^k} (Kronecker product, H_m on the slow index), H_m =
+ * I + S by Paley's first construction with q = m - 1: S[0][b] = 1, S[a][0] = -1, S[a][b] = chi(a - b mod q) for a, b >= 1
+ * (chi = +1 on the non-zero squares mod q, -1 on the others, 0 at 0); the butterfly network runs inside every block of
+ * 2^k consecutive values, then element (a, j) is the sum over the blocks b = 0, 1, ..., m-1 of H_m[a][b] * block_b[j],
+ * accumulated in this order with every addition rounded to fp32.
+ * Then code = clamp(rint(v * (1/s_y)), -128, 127) with 1/s_y and the product rounded to fp32, ties to even.
+ * Errors: ENULL, ESHAPE (unsupported n, rows < 0 or > 2^31 - 1), EINVAL (s_y), EHIP.
  */
 int quamba_hadamard_quantize(const uint16_t *y, int64_t rows, int32_t n, float s_y, int8_t *out, void *hip_stream);
 

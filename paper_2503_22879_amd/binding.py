@@ -376,7 +376,7 @@ def quamba_conv1d_q8(shape: Shape, scales: DeviceScales, xBC, weight, bias, in_w
 
 
 def quamba_hadamard_quantize(y, s_y: float, out, stream=None) -> None:
-    """Enqueue out = Eq.1((1/s_y) H_n y) over the last axis of the fp16 device tensor y (n a power of two)."""
+    """Enqueue out = Eq.1((1/s_y) H_n y) over the last axis of the fp16 device tensor y (n = 2^k, 12 * 2^k or 20 * 2^k)."""
     import torch
     n = y.shape[-1]
     rows = y.numel() // max(1, n)

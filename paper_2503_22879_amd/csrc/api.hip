@@ -265,7 +265,7 @@ extern "C" int quamba_hadamard_quantize(const uint16_t *y, int64_t rows, int32_t
                                         void *hip_stream)
 {
     if (!y || !out) return QUAMBA_ENULL;
-    if (n < 2 || n > 16384 || (n & (n - 1)) || rows < 0 || rows > 0x7fffffffLL) return QUAMBA_ESHAPE;
+    if (!quamba::hadamard_order_supported(n) || rows < 0 || rows > 0x7fffffffLL) return QUAMBA_ESHAPE;
     if (!(s_y > 0.0f) || !std::isfinite(s_y)) return QUAMBA_EINVAL;
     const hipError_t e = quamba::launch_hadamard_quantize(y, rows, n, s_y, out, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;

@@ -191,6 +191,71 @@ __global__ __launch_bounds__(256) void hadamard_quantize_small_kernel(const uint
     for (int i = threadIdx.x; i < n; i += 256) out[row + i] = (int8_t)code_byte(lds[i] * inv_s);
 }
 
+// Orders m * 2^k, m = 12 or 20: H_n = H_m (x) H_{2^k} with H_m from Paley's first construction (q = m - 1 prime, 3 mod 4):
+// H_m = I + S, S = [[0, 1^T], [-1, Q]], Q[i, j] = chi(i - j), chi the quadratic character mod q.  chi is a bit mask of
+// the non-zero squares mod q, built at compile time.
+constexpr uint32_t square_mask(int q)
+{
+    uint32_t mask = 0;
+    for (int v = 1; v < q; ++v) mask |= 1u << ((v * v) % q);
+    return mask;
+}
+template <int M>
+constexpr float paley_sign(int a, int b)  // H_M[a][b] as +-1.0f
+{
+    constexpr int q = M - 1;
+    if (a == 0 || a == b) return 1.0f;
+    if (b == 0) return -1.0f;
+    const int d = ((a - b) % q + q) % q;
+    return (square_mask(q) >> d) & 1u ? 1.0f : -1.0f;
+}
+
+// One workgroup per row: the butterfly network inside every block of p = 2^k values stage by stage in LDS, then for
+// every position j the M-point transform across the blocks, accumulated over the blocks in ascending order (the order
+// the header states), Eq. 1, and the codes of 4 consecutive positions per store.
+template <int M>
+__global__ __launch_bounds__(256) void hadamard_quantize_mixed_kernel(const uint16_t *y, int8_t *out, int p, float inv_s,
+                                                                     int out_aligned)
+{
+    extern __shared__ float lds[];
+    const int n = M * p;
+    const size_t row = (size_t)blockIdx.x * n;
+    for (int i = threadIdx.x; i < n; i += 256) {
+        const _Float16 hv = __builtin_bit_cast(_Float16, y[row + i]);
+        lds[i] = (float)hv;
+    }
+    __syncthreads();
+    for (int h = 1; h < p; h <<= 1) {
+        for (int k = threadIdx.x; k < n / 2; k += 256) {
+            const int i = ((k & ~(h - 1)) << 1) | (k & (h - 1));  // k-th index with bit h clear; h < p stays in a block
+            const float a = lds[i], b = lds[i + h];
+            lds[i] = a + b;
+            lds[i + h] = a - b;
+        }
+        __syncthreads();
+    }
+    for (int j4 = threadIdx.x; j4 < p / 4; j4 += 256) {
+        f32x4 t[M];
+#pragma unroll
+        for (int b = 0; b < M; ++b) t[b] = *reinterpret_cast<const f32x4 *>(lds + b * p + 4 * j4);
+#pragma unroll
+        for (int a = 0; a < M; ++a) {
+            f32x4 acc = t[0] * paley_sign<M>(a, 0);
+#pragma unroll
+            for (int b = 1; b < M; ++b) acc = acc + t[b] * paley_sign<M>(a, b);
+            const float sc[4] = {acc[0] * inv_s, acc[1] * inv_s, acc[2] * inv_s, acc[3] * inv_s};
+            int8_t *dst = out + row + (size_t)a * p + 4 * j4;
+            const uint32_t w = codes_packed<4>(sc);
+            if (out_aligned) {
+                *reinterpret_cast<uint32_t *>(dst) = w;
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) dst[k] = (int8_t)(w >> (8 * k));
+            }
+        }
+    }
+}
+
 template <int LOGN>
 hipError_t launch_fast(const uint16_t *y, int64_t rows, float inv_s, int8_t *out, hipStream_t stream)
 {
@@ -224,10 +289,42 @@ hipError_t launch_fast(const uint16_t *y, int64_t rows, float inv_s, int8_t *out
 
 }  // namespace
 
+bool hadamard_order_supported(int n)
+{
+    if (n < 2 || n > 16384) return false;
+    if ((n & (n - 1)) == 0) return true;
+    for (int m : {12, 20})
+        if (n % m == 0 && ((n / m) & (n / m - 1)) == 0 && n / m >= 4) return true;
+    return false;
+}
+
 hipError_t launch_hadamard_quantize(const uint16_t *y, int64_t rows, int n, float s_y, int8_t *out, hipStream_t stream)
 {
     if (rows == 0) return hipSuccess;
     const float inv_s = 1.0f / s_y;  // correctly rounded fp32 division on the host
+    if (n & (n - 1)) {
+        const int m = (n % 12 == 0 && ((n / 12) & (n / 12 - 1)) == 0) ? 12 : 20;
+        const int lds = n * (int)sizeof(float);
+        const int aligned = reinterpret_cast<uintptr_t>(out) % 4 == 0;
+        if (m == 12) {
+            if (lds > 48 * 1024) {
+                const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(hadamard_quantize_mixed_kernel<12>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+                if (e != hipSuccess) return e;
+            }
+            hipLaunchKernelGGL(hadamard_quantize_mixed_kernel<12>, dim3((unsigned)rows), dim3(256), lds, stream, y, out,
+                               n / 12, inv_s, aligned);
+        } else {
+            if (lds > 48 * 1024) {
+                const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(hadamard_quantize_mixed_kernel<20>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+                if (e != hipSuccess) return e;
+            }
+            hipLaunchKernelGGL(hadamard_quantize_mixed_kernel<20>, dim3((unsigned)rows), dim3(256), lds, stream, y, out,
+                               n / 20, inv_s, aligned);
+        }
+        return hipGetLastError();
+    }
     const bool al = reinterpret_cast<uintptr_t>(y) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 4 == 0;
     if (al) {
         switch (n) {

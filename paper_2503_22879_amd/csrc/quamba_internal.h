@@ -130,6 +130,7 @@ hipError_t launch_quantize_state(const SsdArgs &a, const float *state_scales, in
 size_t decode_q8_lds_bytes(const quamba_ssd_shape_t &s);
 // Quantized Hadamard transform of rows of n = 2^k fp16 values (Section 4.2)
 hipError_t launch_hadamard_quantize(const uint16_t *y, int64_t rows, int n, float s_y, int8_t *out, hipStream_t stream);
+bool hadamard_order_supported(int n);  // 2^k, or 12 * 2^k / 20 * 2^k with k >= 2, up to 16384
 // W8A8 causal convolution in front of the scan (4 taps, SiLU, Eq. 1 to the scan's operands)
 struct ConvArgs {
     quamba_ssd_shape_t s;

@@ -145,7 +145,7 @@ def test_hadamard_rejects_bad_arguments_without_a_device():
     p = C.addressof(dummy)
     f = lib.quamba_hadamard_quantize
     assert f(None, 1, 64, 1.0, p, None) == -1 and f(p, 1, 64, 1.0, None, None) == -1
-    for n in (0, 1, 48, 3, 32768, -64):
+    for n in (0, 1, 36, 3, 24, 40, 12 * 2048, 28 * 64, 32768, -64):     # 12 * 2^k and 20 * 2^k need k >= 2 and n <= 16384
         assert f(p, 1, n, 1.0, p, None) == -2
     assert f(p, -1, 64, 1.0, p, None) == -2 and f(p, 2 ** 31, 64, 1.0, p, None) == -2
     for s in (0.0, -2.0, float("inf"), float("nan")):

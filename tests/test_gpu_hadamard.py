@@ -39,6 +39,30 @@ def test_codes_bit_exact_every_order(gpu_lib, n):
         assert (np.abs(ref.astype(int)) >= 127).any() and len(np.unique(ref)) > 100     # saturation and spread
 
 
+@pytest.mark.parametrize("n", [48, 80, 1536, 3072, 5120, 12288, 10240])
+def test_codes_bit_exact_paley_orders(gpu_lib, n):
+    """Orders 12 * 2^k and 20 * 2^k: the block widths of the Mamba models that are no power of two."""
+    y16, sigma = W.draw_ssd_output(29, n, seed=n, outlier_frac=0.01 if n >= 256 else 0.0)
+    s_y = _scale(sigma, k=3.0)
+    ref = _check(_run(gpu_lib, y16, s_y), y16, s_y)
+    if n >= 1536:
+        assert (np.abs(ref.astype(int)) >= 127).any() and len(np.unique(ref)) > 100
+
+
+def test_paley_order_unaligned_output_and_2p7b_rows(gpu_lib):
+    import torch
+    n = 5120
+    y16, sigma = W.draw_ssd_output(2048, n, seed=77)
+    s_y = _scale(sigma)
+    got = _run(gpu_lib, y16, s_y)
+    pick = np.arange(0, 2048, 61)
+    assert np.array_equal(got[pick], oracle.hadamard_quantize(y16[pick], s_y))
+    buf = torch.zeros(7 * n + 1, dtype=torch.int8, device="cuda")
+    out = buf[1:].view(7, n)                                   # 1 byte off: byte stores
+    gpu_lib.quamba_hadamard_quantize(torch.from_numpy(y16[:7]).cuda(), s_y, out)
+    assert np.array_equal(out.cpu().numpy(), oracle.hadamard_quantize(y16[:7], s_y)) and int(buf[0]) == 0
+
+
 def test_saturation_and_ties(gpu_lib):
     """Rows built so that the transformed values hit exact half-integers and both clamps: a single non-zero input
     c at position j gives +-c in every output; with s_y = 1 the values c = k + 0.5 are ties of Eq. 1."""
@@ -89,9 +113,9 @@ def test_zero_rows_and_bad_arguments(gpu_lib):
     import torch
     y = torch.zeros((0, 1024), dtype=torch.float16, device="cuda")
     gpu_lib.quamba_hadamard_quantize(y, 1.0, torch.zeros((0, 1024), dtype=torch.int8, device="cuda"))
-    y = torch.zeros((2, 48), dtype=torch.float16, device="cuda")
+    y = torch.zeros((2, 36), dtype=torch.float16, device="cuda")
     with pytest.raises(gpu_lib.QuambaError):
-        gpu_lib.quamba_hadamard_quantize(y, 1.0, torch.zeros((2, 48), dtype=torch.int8, device="cuda"))
+        gpu_lib.quamba_hadamard_quantize(y, 1.0, torch.zeros((2, 36), dtype=torch.int8, device="cuda"))
     y = torch.zeros((2, 64), dtype=torch.float16, device="cuda")
     for bad in (0.0, -1.0, float("inf"), float("nan")):
         with pytest.raises(gpu_lib.QuambaError):
