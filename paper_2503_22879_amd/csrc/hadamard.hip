@@ -74,27 +74,43 @@ __device__ __forceinline__ void butterflies(float (&v)[32])
 // not non-temporal: a lane's four 16-byte loads walk through one 64-byte sector, which has to stay in the vector cache
 // between them (with non-temporal loads every one of the four fetched the sector again and the loads alone took 69 us
 // instead of 39 at the 8B layer's size).
+// Rows of fewer than 8192 values share a workgroup (8 rows of 1024, 4 of 2048, 2 of 4096), each with its own threads
+// and its own piece of LDS, so that a workgroup always has 256 or 512 threads; the rows of a workgroup move through
+// the phases together.
 template <int LOGN>
-__global__ __launch_bounds__(1 << (LOGN - 5)) void hadamard_quantize_kernel(const uint16_t *y, int8_t *out, int rows,
-                                                                            float inv_s)
+constexpr int rows_per_workgroup() { return LOGN >= 13 ? 1 : 1 << (13 - LOGN); }
+
+template <int LOGN>
+__global__ __launch_bounds__((1 << (LOGN - 5)) * rows_per_workgroup<LOGN>()) void hadamard_quantize_kernel(
+    const uint16_t *y, int8_t *out, int rows, float inv_s)
 {
     constexpr int N = 1 << LOGN;
-    constexpr int CB = LOGN - 10;       // strides of phase C
-    constexpr int NE = 1 << CB;         // values 1024 apart a thread holds in phase C
-    constexpr int CONSEC = 32 / NE;     // consecutive values per such position (2..32)
-    extern __shared__ float lds[];      // 1152 floats per block of 1024 values
-    const int t = threadIdx.x;
+    constexpr int RPW = rows_per_workgroup<LOGN>(), T = N / 32;
+    // phase C: a thread holds CONSEC consecutive values at NE places GS apart (4 x 8, n/8 apart; 2 x 16, 1024 apart for
+    // n = 16384); the places' index bits that are strides >= 1024 still have their butterflies to come
+    constexpr int NE = LOGN == 14 ? 16 : 8;
+    constexpr int CONSEC = 32 / NE;
+    constexpr int GS = N / NE;
+    constexpr int CFIRST = LOGN >= 13 ? 1 : 1 << (13 - LOGN);  // first register stride of phase C that is a stride >= 1024
+    extern __shared__ float lds_all[];  // per row 1152 floats per block of 1024 values
+    const int t = threadIdx.x % T, rw = threadIdx.x / T;
+    float *lds = lds_all + rw * (N / 1024) * 1152;
     const int t_lo = t & 31, t_hi = t >> 5;
     float v[32];
     u32x4 nx[4];
+    const long long stride = (long long)gridDim.x * RPW;  // rows between two rounds of a thread
 
-    int r = blockIdx.x;  // the launch has no more workgroups than rows
-    {
+    long long r = (long long)blockIdx.x * RPW + rw;  // the launch has no more workgroups than groups of RPW rows
+#pragma unroll
+    for (int q = 0; q < 4; ++q) nx[q] = (u32x4){0, 0, 0, 0};
+    if (r < rows) {
         const u32x4 *src = reinterpret_cast<const u32x4 *>(y + (size_t)r * N + 32 * t);
 #pragma unroll
         for (int q = 0; q < 4; ++q) nx[q] = src[q];
     }
-    for (; r < rows; r += gridDim.x) {
+    // every thread of the workgroup makes the same number of rounds (the barriers below are the workgroup's); a thread
+    // whose row lies past the end works on zeros and stores nothing
+    for (long long r0 = (long long)blockIdx.x * RPW; r0 < rows; r0 += stride, r += stride) {
         // phase A: values 32 t + e;
         // stride 1 straight from the packed fp16 pairs: the mixed-precision fused multiply-add takes both halves of a
         // dword as fp16 sources, lo * 1.0 +- hi in fp32 with one rounding (conversion of fp16 to fp32 is exact, so
@@ -108,8 +124,8 @@ __global__ __launch_bounds__(1 << (LOGN - 5)) void hadamard_quantize_kernel(cons
                 asm("v_fma_mix_f32 %0, %1, 1.0, -%1 op_sel:[0,0,1] op_sel_hi:[1,0,1]"
                     : "=v"(v[8 * q + 2 * i + 1]) : "v"(w));
             }
-        if (r + (int)gridDim.x < rows) {
-            const u32x4 *src = reinterpret_cast<const u32x4 *>(y + (size_t)(r + gridDim.x) * N + 32 * t);
+        if (r + stride < rows) {
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(y + (size_t)(r + stride) * N + 32 * t);
 #pragma unroll
             for (int q = 0; q < 4; ++q) nx[q] = src[q];
         }
@@ -140,29 +156,30 @@ __global__ __launch_bounds__(1 << (LOGN - 5)) void hadamard_quantize_kernel(cons
         }
         __syncthreads();
 
-        // phase C: CONSEC consecutive values at CONSEC t + 1024 e', e' = 0..NE-1; register index k * NE + e', so the
-        // strides 1024 .. n/2 are its low CB bits
+        // phase C: CONSEC consecutive values at CONSEC t + GS e', e' = 0..NE-1; register index k * NE + e', so the
+        // strides GS .. n/2 are its low bits, of which those below 1024 are already done
 #pragma unroll
         for (int ep = 0; ep < NE; ++ep)
 #pragma unroll
-            for (int k = 0; k < CONSEC; ++k) v[k * NE + ep] = (lds + CONSEC * t)[k + 1024 * ep];
-        butterflies<CB>(v);
+            for (int k = 0; k < CONSEC; ++k) v[k * NE + ep] = (lds + CONSEC * t)[k + GS * ep];
+        butterflies<(LOGN == 14 ? 4 : 3), CFIRST>(v);
 
         // Eq. 1 and the store: CONSEC consecutive codes per e'
         int8_t *orow = out + (size_t)r * N + CONSEC * t;
 #pragma unroll
         for (int ep = 0; ep < NE; ++ep) {
+            if (r >= rows) break;
             if (CONSEC >= 4) {
 #pragma unroll
                 for (int k = 0; k < CONSEC; k += 4) {
                     const float sc[4] = {v[k * NE + ep] * inv_s, v[(k + 1) * NE + ep] * inv_s,
                                          v[(k + 2) * NE + ep] * inv_s, v[(k + 3) * NE + ep] * inv_s};
                     __builtin_nontemporal_store(codes_packed<4>(sc),
-                                                reinterpret_cast<uint32_t *>(orow + 1024 * ep + k));
+                                                reinterpret_cast<uint32_t *>(orow + GS * ep + k));
                 }
             } else {
                 const float sc[4] = {v[ep] * inv_s, v[NE + ep] * inv_s, 0.0f, 0.0f};
-                *reinterpret_cast<uint16_t *>(orow + 1024 * ep) = (uint16_t)codes_packed<2>(sc);
+                *reinterpret_cast<uint16_t *>(orow + GS * ep) = (uint16_t)codes_packed<2>(sc);
             }
         }
         __syncthreads();  // phase C has read the row before the next row's phase A writes
@@ -256,11 +273,105 @@ __global__ __launch_bounds__(256) void hadamard_quantize_mixed_kernel(const uint
     }
 }
 
+// The same orders with the register-blocked phases of the power-of-two kernel (p = 2^LOGP values per block, 7 <= LOGP
+// <= 10, 16-byte aligned rows): phase A, strides 1..16 on the 32 consecutive values a thread loads; exchange through
+// LDS, transposed inside super-blocks of 1024 values like the power-of-two kernel's first exchange; phase B, strides
+// 32..p/2 on values 32 apart (a thread's 32 values span 1024 / p blocks, the butterflies stay inside each); exchange
+// in plain order; phase C, for 2 consecutive positions the M-point sum over the blocks in ascending order, Eq. 1, one
+// 2-byte store per block.  A row need not fill its last super-block: the missing part is never written, and what
+// phase B reads of it stays in register groups of its own that are not used.
+template <int M, int LOGP>
+__global__ void hadamard_quantize_mixed_fast_kernel(const uint16_t *y, int8_t *out, float inv_s)
+{
+    constexpr int P = 1 << LOGP, N = M * P, T = N / 32, NSB = (N + 1023) / 1024;
+    extern __shared__ float lds[];  // NSB * 1152 floats
+    const int t = threadIdx.x;
+    const size_t row = (size_t)blockIdx.x * N;
+    float v[32];
+    if (t < T) {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(y + row + 32 * t);
+        u32x4 nx[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) nx[q] = src[q];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t w = nx[q][i];
+                asm("v_fma_mix_f32 %0, %1, 1.0, %1 op_sel:[0,0,1] op_sel_hi:[1,0,1]" : "=v"(v[8 * q + 2 * i]) : "v"(w));
+                asm("v_fma_mix_f32 %0, %1, 1.0, -%1 op_sel:[0,0,1] op_sel_hi:[1,0,1]"
+                    : "=v"(v[8 * q + 2 * i + 1]) : "v"(w));
+            }
+        butterflies<5, 2>(v);
+        float *pa = lds + (t & 31) + 1152 * (t >> 5);
+#pragma unroll
+        for (int k = 0; k < 32; ++k) pa[36 * k] = v[k];
+    }
+    __syncthreads();
+    const int t_lo = t & 31, t_hi = t >> 5;
+    if (t_hi < NSB) {
+        // phase B: values i = t_lo + 32 e + 1024 t_hi, e = 0..31; e's low LOGP - 5 bits are the strides 32..p/2
+        const f32x4 *pb = reinterpret_cast<const f32x4 *>(lds + 36 * t_lo + 1152 * t_hi);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const f32x4 w = pb[q];
+            v[4 * q] = w[0]; v[4 * q + 1] = w[1]; v[4 * q + 2] = w[2]; v[4 * q + 3] = w[3];
+        }
+        butterflies<LOGP - 5>(v);
+    }
+    __syncthreads();  // all reads of the transposed layout are done before the plain one overwrites it
+    if (t_hi < NSB) {
+        float *pb = lds + t_lo + 1024 * t_hi;
+#pragma unroll
+        for (int e = 0; e < 32; ++e)
+            if (1024 * t_hi + 32 * e < N) pb[32 * e] = v[e];  // uniform per wave half: whole groups of 32 lanes
+    }
+    __syncthreads();
+    if (t < P / 2) {
+        // phase C: positions 2 t and 2 t + 1 of every block
+        float t0[M], t1[M];
+#pragma unroll
+        for (int b = 0; b < M; ++b) {
+            t0[b] = lds[b * P + 2 * t];
+            t1[b] = lds[b * P + 2 * t + 1];
+        }
+#pragma unroll
+        for (int a = 0; a < M; ++a) {
+            float a0 = t0[0] * paley_sign<M>(a, 0), a1 = t1[0] * paley_sign<M>(a, 0);
+#pragma unroll
+            for (int b = 1; b < M; ++b) {
+                a0 = a0 + t0[b] * paley_sign<M>(a, b);
+                a1 = a1 + t1[b] * paley_sign<M>(a, b);
+            }
+            const float sc[4] = {a0 * inv_s, a1 * inv_s, 0.0f, 0.0f};
+            *reinterpret_cast<uint16_t *>(out + row + (size_t)a * P + 2 * t) = (uint16_t)codes_packed<2>(sc);
+        }
+    }
+}
+
+template <int M, int LOGP>
+hipError_t launch_mixed_fast(const uint16_t *y, int64_t rows, float inv_s, int8_t *out, hipStream_t stream)
+{
+    constexpr int P = 1 << LOGP, N = M * P, NSB = (N + 1023) / 1024;
+    constexpr int need = N / 32 > 32 * NSB ? N / 32 : 32 * NSB;
+    constexpr int threads = ((need > P / 2 ? need : P / 2) + 63) / 64 * 64;
+    constexpr int lds = NSB * 1152 * (int)sizeof(float);
+    static_assert(threads <= 1024 && lds <= 160 * 1024, "launch shape");
+    if (lds > 48 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(hadamard_quantize_mixed_fast_kernel<M, LOGP>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((hadamard_quantize_mixed_fast_kernel<M, LOGP>), dim3((unsigned)rows), dim3(threads), lds, stream, y,
+                       out, inv_s);
+    return hipGetLastError();
+}
+
 template <int LOGN>
 hipError_t launch_fast(const uint16_t *y, int64_t rows, float inv_s, int8_t *out, hipStream_t stream)
 {
-    constexpr int N = 1 << LOGN;
-    constexpr int lds = (N / 1024) * 1152 * (int)sizeof(float);
+    constexpr int N = 1 << LOGN, RPW = rows_per_workgroup<LOGN>();
+    constexpr int lds = RPW * (N / 1024) * 1152 * (int)sizeof(float);
     // twice the workgroups that fit the device at once (measured best; one round of exactly resident workgroups
     // is 10% slower), asked of the runtime once per order and device
     static int resident[16] = {0};
@@ -275,14 +386,15 @@ hipError_t launch_fast(const uint16_t *y, int64_t rows, float inv_s, int8_t *out
             if (e != hipSuccess) return e;
         }
         int per_cu = 0, cus = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, hadamard_quantize_kernel<LOGN>, N / 32, lds);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, hadamard_quantize_kernel<LOGN>, RPW * N / 32, lds);
         if (e != hipSuccess) return e;
         e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
         resident[dev] = per_cu > 0 && cus > 0 ? 2 * per_cu * cus : 2048;
     }
-    const unsigned grid = (unsigned)(rows < resident[dev] ? rows : resident[dev]);
-    hipLaunchKernelGGL(hadamard_quantize_kernel<LOGN>, dim3(grid), dim3(N / 32), lds, stream, y, out, (int)rows,
+    const int64_t groups = (rows + RPW - 1) / RPW;
+    const unsigned grid = (unsigned)(groups < resident[dev] ? groups : resident[dev]);
+    hipLaunchKernelGGL(hadamard_quantize_kernel<LOGN>, dim3(grid), dim3(RPW * N / 32), lds, stream, y, out, (int)rows,
                        inv_s);
     return hipGetLastError();
 }
@@ -304,6 +416,18 @@ hipError_t launch_hadamard_quantize(const uint16_t *y, int64_t rows, int n, floa
     const float inv_s = 1.0f / s_y;  // correctly rounded fp32 division on the host
     if (n & (n - 1)) {
         const int m = (n % 12 == 0 && ((n / 12) & (n / 12 - 1)) == 0) ? 12 : 20;
+        if (reinterpret_cast<uintptr_t>(y) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 2 == 0) {
+            switch (n) {  // the register-blocked kernel for blocks of 128 .. 1024 values
+                case 12 * 128: return launch_mixed_fast<12, 7>(y, rows, inv_s, out, stream);
+                case 12 * 256: return launch_mixed_fast<12, 8>(y, rows, inv_s, out, stream);
+                case 12 * 512: return launch_mixed_fast<12, 9>(y, rows, inv_s, out, stream);
+                case 12 * 1024: return launch_mixed_fast<12, 10>(y, rows, inv_s, out, stream);
+                case 20 * 128: return launch_mixed_fast<20, 7>(y, rows, inv_s, out, stream);
+                case 20 * 256: return launch_mixed_fast<20, 8>(y, rows, inv_s, out, stream);
+                case 20 * 512: return launch_mixed_fast<20, 9>(y, rows, inv_s, out, stream);
+                default: break;
+            }
+        }
         const int lds = n * (int)sizeof(float);
         const int aligned = reinterpret_cast<uintptr_t>(out) % 4 == 0;
         if (m == 12) {
