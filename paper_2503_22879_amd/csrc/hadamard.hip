@@ -11,6 +11,8 @@
 // and written once (int8): 3 bytes of HBM traffic and 17 vector instructions (13 butterflies, a scale, a clamp, a
 // rounding add; no packed fp32) per value.  At n = 8192 the vector ALU, the LDS exchanges and HBM each take 40-60 us
 // when alone; a row's fp32 image (37 KB of LDS) limits a compute unit to 4 rows in flight, so they overlap only partly.
+#include <atomic>
+
 #include "quamba_internal.h"
 
 #pragma clang fp contract(off)
@@ -357,10 +359,17 @@ hipError_t launch_mixed_fast(const uint16_t *y, int64_t rows, float inv_s, int8_
     constexpr int threads = ((need > P / 2 ? need : P / 2) + 63) / 64 * 64;
     constexpr int lds = NSB * 1152 * (int)sizeof(float);
     static_assert(threads <= 1024 && lds <= 160 * 1024, "launch shape");
-    if (lds > 48 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(hadamard_quantize_mixed_fast_kernel<M, LOGP>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (lds > 48 * 1024) {  // raise the kernel's LDS limit once per device
+        static std::atomic<uint32_t> done{0};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 32 || !(done.load() >> dev & 1u)) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(hadamard_quantize_mixed_fast_kernel<M, LOGP>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return e;
+            if (dev >= 0 && dev < 32) done.fetch_or(1u << dev);
+        }
     }
     hipLaunchKernelGGL((hadamard_quantize_mixed_fast_kernel<M, LOGP>), dim3((unsigned)rows), dim3(threads), lds, stream, y,
                        out, inv_s);
@@ -374,12 +383,12 @@ hipError_t launch_fast(const uint16_t *y, int64_t rows, float inv_s, int8_t *out
     constexpr int lds = RPW * (N / 1024) * 1152 * (int)sizeof(float);
     // twice the workgroups that fit the device at once (measured best; one round of exactly resident workgroups
     // is 10% slower), asked of the runtime once per order and device
-    static int resident[16] = {0};
+    static std::atomic<int> resident[16];  // zero-initialised; concurrent first calls compute the same value
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
-    if (!resident[dev]) {
+    if (!resident[dev].load()) {
         if (lds > 48 * 1024) {
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(hadamard_quantize_kernel<LOGN>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -390,10 +399,11 @@ hipError_t launch_fast(const uint16_t *y, int64_t rows, float inv_s, int8_t *out
         if (e != hipSuccess) return e;
         e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
-        resident[dev] = per_cu > 0 && cus > 0 ? 2 * per_cu * cus : 2048;
+        resident[dev].store(per_cu > 0 && cus > 0 ? 2 * per_cu * cus : 2048);
     }
+    const int res = resident[dev].load();
     const int64_t groups = (rows + RPW - 1) / RPW;
-    const unsigned grid = (unsigned)(groups < resident[dev] ? groups : resident[dev]);
+    const unsigned grid = (unsigned)(groups < res ? groups : res);
     hipLaunchKernelGGL(hadamard_quantize_kernel<LOGN>, dim3(grid), dim3(RPW * N / 32), lds, stream, y, out, (int)rows,
                        inv_s);
     return hipGetLastError();
