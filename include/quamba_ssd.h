@@ -253,6 +253,25 @@ int quamba_mamba1_decode_step(const quamba_ssd_shape_t *shape, const quamba_ssd_
                               float *state, uint16_t *y, void *hip_stream);
 
 /*
+ * quamba_mamba1_scan / quamba_mamba1_decode_step with the 8-bit side inputs of quamba_ssd_gate_t (Section 3.2: the step
+ * size is softplus of a quantized projection plus a bias, and the branch z gates the output); `gate` may be NULL.
+ *   gate->z        int8, laid out like x ([batch, D, seqlen] / [batch, D]): y becomes y * SiLU(z_scale * z)
+ *   gate->dt_q     int8, laid out like dt: the step size becomes softplus(dt_scale * dt_q + dt_bias[d]); `dt` is then
+ *                  ignored and may be NULL
+ *   gate->dt_bias  fp32 [D] (one per channel) or NULL
+ * The wave-scan kernel additionally needs z and dt_q 16-byte aligned.  Errors as the plain entry points, plus EINVAL for
+ * non-finite or non-positive scales.
+ */
+int quamba_mamba1_scan_gated(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                             const quamba_ssd_gate_t *gate, const int8_t *x, const int8_t *B, const int8_t *C,
+                             const float *dt, const float *A, const float *D, const float *init_state, uint16_t *y,
+                             float *final_state, void *hip_stream);
+int quamba_mamba1_decode_step_gated(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                    const quamba_ssd_gate_t *gate, const int8_t *x, const int8_t *B, const int8_t *C,
+                                    const float *dt, const float *A, const float *D, float *state, uint16_t *y,
+                                    void *hip_stream);
+
+/*
  * W8A8 causal convolution in front of the scan (Section 4.2, "Efficient 4-bit/8-bit Mamba blocks": the W8A8 causal
  * convolution kernel; "Offline Hadamard matrix fusion" / reordering: its channels come in the sorted order, so its
  * outputs are the SSD kernel's operands as they are).  Depthwise over time, 4 taps, over the concatenated channels

@@ -18,7 +18,8 @@ FLAG_NO_CHANNEL_SPLIT = 0x4
 EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "quamba_ssd_decode_step",
                     "quamba_ssd_decode_step_q8", "quamba_ssd_quantize_state", "quamba_state_scales",
                     "quamba_hadamard_quantize", "quamba_conv1d_q8", "quamba_mamba1_scan",
-                    "quamba_mamba1_decode_step", "quamba_ssd_prefill_gated", "quamba_ssd_decode_step_gated", "quamba_ssd_decode_step_q8_gated",
+                    "quamba_mamba1_decode_step", "quamba_mamba1_scan_gated", "quamba_mamba1_decode_step_gated",
+                    "quamba_ssd_prefill_gated", "quamba_ssd_decode_step_gated", "quamba_ssd_decode_step_q8_gated",
                     "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x",
                     "quamba_quantize_groups", "quamba_strerror")
 
@@ -89,6 +90,12 @@ def load_library():
         lib.quamba_mamba1_scan.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 10
         lib.quamba_mamba1_decode_step.restype = C.c_int
         lib.quamba_mamba1_decode_step.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 9
+        lib.quamba_mamba1_scan_gated.restype = C.c_int
+        lib.quamba_mamba1_scan_gated.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct), C.POINTER(_GateStruct)] + \
+            [C.c_void_p] * 10
+        lib.quamba_mamba1_decode_step_gated.restype = C.c_int
+        lib.quamba_mamba1_decode_step_gated.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct),
+                                                        C.POINTER(_GateStruct)] + [C.c_void_p] * 9
         lib.quamba_conv1d_q8.restype = C.c_int
         lib.quamba_conv1d_q8.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct), C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_float] + [C.c_void_p] * 6
@@ -329,33 +336,46 @@ def quamba_state_scales(nheads, headdim, ngroups, m, n, d_state, head_cluster_en
 
 
 def quamba_mamba1_scan(shape: Shape, scales: DeviceScales, x, B, Cm, dt, A, D, y, init_state=None, final_state=None,
-                       stream=None) -> None:
-    """Enqueue the 8-bit Mamba1 selective scan (channel-major device tensors, time last)."""
+                       stream=None, gate: Gate | None = None) -> None:
+    """Enqueue the 8-bit Mamba1 selective scan (channel-major device tensors, time last).  With `gate`,
+    quamba_mamba1_scan_gated is called (dt may then be None if the gate carries the step-size codes)."""
     import torch
     b, L, Dn, N = shape.batch, shape.seqlen, shape.headdim, shape.d_state
     sc = scales.struct()
-    rc = load_library().quamba_mamba1_scan(
-        C.byref(shape), C.byref(sc), _dp(x, torch.int8, (b, Dn, L), "x"), _dp(B, torch.int8, (b, N, L), "B"),
-        _dp(Cm, torch.int8, (b, N, L), "C"), _dp(dt, torch.float32, (b, Dn, L), "dt"),
-        _dp(A, torch.float32, (Dn, N), "A"), _dp(D, torch.float32, (Dn,), "D"),
-        _dp(init_state, torch.float32, (b, Dn, N), "init_state"), _dp(y, torch.float16, (b, Dn, L), "y"),
-        _dp(final_state, torch.float32, (b, Dn, N), "final_state"), _stream_ptr(stream))
+    args = (_dp(x, torch.int8, (b, Dn, L), "x"), _dp(B, torch.int8, (b, N, L), "B"),
+            _dp(Cm, torch.int8, (b, N, L), "C"), _dp(dt, torch.float32, (b, Dn, L), "dt"),
+            _dp(A, torch.float32, (Dn, N), "A"), _dp(D, torch.float32, (Dn,), "D"),
+            _dp(init_state, torch.float32, (b, Dn, N), "init_state"), _dp(y, torch.float16, (b, Dn, L), "y"),
+            _dp(final_state, torch.float32, (b, Dn, N), "final_state"), _stream_ptr(stream))
+    if gate is None:
+        rc, name = load_library().quamba_mamba1_scan(C.byref(shape), C.byref(sc), *args), "quamba_mamba1_scan"
+    else:
+        g = gate.struct((b, Dn, L), (b, Dn, L), Dn)
+        rc = load_library().quamba_mamba1_scan_gated(C.byref(shape), C.byref(sc), C.byref(g), *args)
+        name = "quamba_mamba1_scan_gated"
     if rc != 0:
-        raise QuambaError(rc, "quamba_mamba1_scan")
+        raise QuambaError(rc, name)
 
 
-def quamba_mamba1_decode_step(shape: Shape, scales: DeviceScales, x, B, Cm, dt, A, D, state, y, stream=None) -> None:
-    """Enqueue one generation step of the Mamba1 recurrence on the fp32 state [b, D, N], in place."""
+def quamba_mamba1_decode_step(shape: Shape, scales: DeviceScales, x, B, Cm, dt, A, D, state, y, stream=None,
+                              gate: Gate | None = None) -> None:
+    """Enqueue one generation step of the Mamba1 recurrence on the fp32 state [b, D, N], in place.  With `gate`,
+    quamba_mamba1_decode_step_gated is called."""
     import torch
     b, Dn, N = shape.batch, shape.headdim, shape.d_state
     sc = scales.struct()
-    rc = load_library().quamba_mamba1_decode_step(
-        C.byref(shape), C.byref(sc), _dp(x, torch.int8, (b, Dn), "x"), _dp(B, torch.int8, (b, N), "B"),
-        _dp(Cm, torch.int8, (b, N), "C"), _dp(dt, torch.float32, (b, Dn), "dt"),
-        _dp(A, torch.float32, (Dn, N), "A"), _dp(D, torch.float32, (Dn,), "D"),
-        _dp(state, torch.float32, (b, Dn, N), "state"), _dp(y, torch.float16, (b, Dn), "y"), _stream_ptr(stream))
+    args = (_dp(x, torch.int8, (b, Dn), "x"), _dp(B, torch.int8, (b, N), "B"),
+            _dp(Cm, torch.int8, (b, N), "C"), _dp(dt, torch.float32, (b, Dn), "dt"),
+            _dp(A, torch.float32, (Dn, N), "A"), _dp(D, torch.float32, (Dn,), "D"),
+            _dp(state, torch.float32, (b, Dn, N), "state"), _dp(y, torch.float16, (b, Dn), "y"), _stream_ptr(stream))
+    if gate is None:
+        rc, name = load_library().quamba_mamba1_decode_step(C.byref(shape), C.byref(sc), *args), "quamba_mamba1_decode_step"
+    else:
+        g = gate.struct((b, Dn), (b, Dn), Dn)
+        rc = load_library().quamba_mamba1_decode_step_gated(C.byref(shape), C.byref(sc), C.byref(g), *args)
+        name = "quamba_mamba1_decode_step_gated"
     if rc != 0:
-        raise QuambaError(rc, "quamba_mamba1_decode_step")
+        raise QuambaError(rc, name)
 
 
 def quamba_conv1d_q8(shape: Shape, scales: DeviceScales, xBC, weight, bias, in_w_scale: float, x_out, B_out, C_out,

@@ -206,15 +206,25 @@ extern "C" int quamba_mamba1_scan(const quamba_ssd_shape_t *shape, const quamba_
                                   const int8_t *B, const int8_t *C, const float *dt, const float *A, const float *D,
                                   const float *init_state, uint16_t *y, float *final_state, void *hip_stream)
 {
+    return quamba_mamba1_scan_gated(shape, scales, nullptr, x, B, C, dt, A, D, init_state, y, final_state, hip_stream);
+}
+
+extern "C" int quamba_mamba1_scan_gated(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                        const quamba_ssd_gate_t *gate, const int8_t *x, const int8_t *B,
+                                        const int8_t *C, const float *dt, const float *A, const float *D,
+                                        const float *init_state, uint16_t *y, float *final_state, void *hip_stream)
+{
     if (!shape) return QUAMBA_ENULL;
     int rc = check_scales(scales);
     if (rc != QUAMBA_OK) return rc;
-    if (!x || !B || !C || !dt || !A || !y) return QUAMBA_ENULL;
+    if (!x || !B || !C || !A || !y) return QUAMBA_ENULL;
     rc = check_mamba1(shape, true);
     if (rc != QUAMBA_OK) return rc;
     if (shape->flags & ~QUAMBA_FLAG_GENERIC_KERNEL) return QUAMBA_EINVAL;
     if (!quamba::mamba1_scan_supports_any(*shape)) return QUAMBA_ESHAPE;  // d_state <= 64
     quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, nullptr, D, nullptr, nullptr, y);
+    rc = apply_gate(gate, dt, &a);
+    if (rc != QUAMBA_OK) return rc;
     const hipError_t e = quamba::launch_mamba1_scan(a, A, init_state, final_state, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }
@@ -223,14 +233,24 @@ extern "C" int quamba_mamba1_decode_step(const quamba_ssd_shape_t *shape, const 
                                          const int8_t *x, const int8_t *B, const int8_t *C, const float *dt,
                                          const float *A, const float *D, float *state, uint16_t *y, void *hip_stream)
 {
+    return quamba_mamba1_decode_step_gated(shape, scales, nullptr, x, B, C, dt, A, D, state, y, hip_stream);
+}
+
+extern "C" int quamba_mamba1_decode_step_gated(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                               const quamba_ssd_gate_t *gate, const int8_t *x, const int8_t *B,
+                                               const int8_t *C, const float *dt, const float *A, const float *D,
+                                               float *state, uint16_t *y, void *hip_stream)
+{
     if (!shape) return QUAMBA_ENULL;
     int rc = check_scales(scales);
     if (rc != QUAMBA_OK) return rc;
-    if (!x || !B || !C || !dt || !A || !state || !y) return QUAMBA_ENULL;
+    if (!x || !B || !C || !A || !state || !y) return QUAMBA_ENULL;
     rc = check_mamba1(shape, false);
     if (rc != QUAMBA_OK) return rc;
     if (shape->flags) return QUAMBA_EINVAL;
     quamba::SsdArgs a = pack(shape, scales, x, B, C, dt, nullptr, D, nullptr, state, y);
+    rc = apply_gate(gate, dt, &a);
+    if (rc != QUAMBA_OK) return rc;
     const hipError_t e = quamba::launch_mamba1_decode(a, A, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }

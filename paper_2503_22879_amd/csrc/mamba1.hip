@@ -52,6 +52,16 @@ __device__ __forceinline__ void wave_scan(float &P, float &h)
 }
 #undef QUAMBA_SCAN_STEP
 
+// log(1 + exp(v)) = max(v, 0) + log(1 + e), e = 2^(-|v| log2 e), on the hardware's base-2 exponential and logarithm.
+__device__ __forceinline__ float softplus_fast(float v)
+{
+    const float e = __builtin_amdgcn_exp2f(-__builtin_fabsf(v) * kLog2e);
+    // below 1/32 the rounding of 1 + e would cost more than the series' fifth-order remainder
+    const float series = e * fmaf(e, fmaf(e, fmaf(e, -0.25f, 0.33333334f), -0.5f), 1.0f);
+    const float viaLog = __builtin_amdgcn_logf(1.0f + e) * 0.69314718055994530942f;
+    return fmaxf(v, 0.0f) + (e < 0.03125f ? series : viaLog);
+}
+
 __device__ __forceinline__ float byte_to_float(uint32_t w, int k) { return (float)(int)(int8_t)(w >> (8 * k)); }
 
 // u * (fp16 half HI of w) and (fp16 half HI of w) * g + acc as one mixed-precision multiply-add each: the fp16 operand
@@ -85,6 +95,7 @@ __global__ __launch_bounds__(kThreads, 4) void mamba1_scan_kernel(SsdArgs a, con
     __shared__ u32x4 s_B[N][64][2];  // [state][lane]: the lane's 16 token codes of the tile as fp16 pairs
     __shared__ u32x4 s_C[N][64][2];
     __shared__ float s_carry[kWaves][N];  // per wave: the state in front of the current tile
+    __shared__ float s_silu[256];         // SiLU(z_scale * code), indexed by the gate code's byte
     const int D = a.s.headdim, L = a.s.seqlen;
     const int b = blockIdx.y;
     const int lane = threadIdx.x & 63;
@@ -98,6 +109,7 @@ __global__ __launch_bounds__(kThreads, 4) void mamba1_scan_kernel(SsdArgs a, con
     const float *Ad = A + (size_t)dd * N;
 
     if (lane < N) s_carry[wave][lane] = (init && own) ? init[((size_t)b * D + d) * N + lane] : 0.0f;
+    if (a.z && threadIdx.x < 256) s_silu[threadIdx.x] = silu_of_code(a.z_scale, (int8_t)threadIdx.x);
 
     for (int t0 = 0; t0 < L; t0 += kTile) {
         // the tile's B and C codes: 2 * 16 rows of 1024 codes, 16 codes per thread and trip
@@ -123,14 +135,22 @@ __global__ __launch_bounds__(kThreads, 4) void mamba1_scan_kernel(SsdArgs a, con
         const int t = t0 + kE * lane;
         const bool live = t < L;  // whole groups of 16 tokens: seqlen is a multiple of 16
         const size_t row = ((size_t)b * D + d) * L + t;
-        u32x4 xq = {0, 0, 0, 0};
+        u32x4 xq = {0, 0, 0, 0}, zq = {0, 0, 0, 0};
         float dt[kE];
         if (live) {
             xq = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.x + row));
+            if (a.z) zq = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.z + row));  // used after the scan
+            if (a.dt_q) {  // step size = softplus(s_dt code + bias[d]) (Section 3.2), 16 codes in one load
+                const u32x4 dq = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.dt_q + row));
+                const float bias = a.dt_bias ? a.dt_bias[d] : 0.0f;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x4 v = reinterpret_cast<const f32x4 *>(a.dt + row)[q];  // plain: four loads share a sector
-                dt[4 * q] = v[0]; dt[4 * q + 1] = v[1]; dt[4 * q + 2] = v[2]; dt[4 * q + 3] = v[3];
+                for (int i = 0; i < kE; ++i) dt[i] = softplus_fast(fmaf(a.dt_scale, byte_to_float(dq[i >> 2], i & 3), bias));
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 v = reinterpret_cast<const f32x4 *>(a.dt + row)[q];  // plain: four loads share a sector
+                    dt[4 * q] = v[0]; dt[4 * q + 1] = v[1]; dt[4 * q + 2] = v[2]; dt[4 * q + 3] = v[3];
+                }
             }
         } else {
 #pragma unroll
@@ -173,13 +193,16 @@ __global__ __launch_bounds__(kThreads, 4) void mamba1_scan_kernel(SsdArgs a, con
         }
         if (live) {
             const float Dx = (a.D ? a.D[d] : 0.0f) * sx;
+#pragma unroll
+            for (int i = 0; i < kE; ++i) y[i] = fmaf(Dx, byte_to_float(xq[i >> 2], i & 3), sC * y[i]);
+            if (a.z) {  // y * SiLU(z) on the gate codes of the lane's 16 tokens (Section 3.2), from the table
+#pragma unroll
+                for (int i = 0; i < kE; ++i) y[i] *= s_silu[(zq[i >> 2] >> (8 * (i & 3))) & 255u];
+            }
             u32x4 o[2];
 #pragma unroll
-            for (int i = 0; i < kE; i += 2) {
-                const uint32_t lo = f32_to_f16_bits(fmaf(Dx, byte_to_float(xq[i >> 2], i & 3), sC * y[i]));
-                const uint32_t hi = f32_to_f16_bits(fmaf(Dx, byte_to_float(xq[(i + 1) >> 2], (i + 1) & 3), sC * y[i + 1]));
-                o[i >> 3][(i >> 1) & 3] = lo | (hi << 16);
-            }
+            for (int i = 0; i < kE; i += 2)
+                o[i >> 3][(i >> 1) & 3] = (uint32_t)f32_to_f16_bits(y[i]) | ((uint32_t)f32_to_f16_bits(y[i + 1]) << 16);
             u32x4 *yp = reinterpret_cast<u32x4 *>(a.y + row);
             __builtin_nontemporal_store(o[0], yp);
             __builtin_nontemporal_store(o[1], yp + 1);
@@ -204,7 +227,7 @@ __global__ __launch_bounds__(64) void mamba1_scan_any_kernel(SsdArgs a, const fl
     const float Dk = a.D ? a.D[d] : 0.0f;
     for (int t = 0; t < L; ++t) {
         const size_t row = ((size_t)b * D + d) * L + t;
-        const float dt = a.dt[row], xv = sx * (float)a.x[row];
+        const float dt = step_size(a, row, d), xv = sx * (float)a.x[row];
         const float u = dt * xv * sB;
         float y = 0.0f;
         for (int n = 0; n < N; ++n) {
@@ -212,7 +235,8 @@ __global__ __launch_bounds__(64) void mamba1_scan_any_kernel(SsdArgs a, const fl
             h[n] = fmaf(__builtin_amdgcn_exp2f(dt * A2[n]), h[n], u * (float)a.B[bc]);
             y = fmaf((float)a.C[bc], h[n], y);
         }
-        a.y[row] = f32_to_f16_bits(fmaf(Dk, xv, sC * y));
+        const float gate = a.z ? silu_of_code(a.z_scale, a.z[row]) : 1.0f;
+        a.y[row] = f32_to_f16_bits(fmaf(Dk, xv, sC * y) * gate);
     }
     if (fin)
         for (int n = 0; n < N; ++n) fin[((size_t)b * D + d) * N + n] = h[n];
@@ -229,7 +253,7 @@ __global__ __launch_bounds__(256) void mamba1_decode16_kernel(SsdArgs a, const f
     const size_t idx = gid >> 2 < total ? gid >> 2 : total - 1;  // lanes past the end redo the last row, store nothing
     const int j = (int)(gid & 3);
     const int b = (int)(idx / D), d = (int)(idx - (size_t)b * D);
-    const float dt = a.dt[idx], xv = x_scale_lookup(a, 0, d) * (float)a.x[idx];
+    const float dt = step_size(a, idx, d), xv = x_scale_lookup(a, 0, d) * (float)a.x[idx];
     const float u = dt * xv * a.B_scales[0];
     f32x4 *st = reinterpret_cast<f32x4 *>(a.state + idx * 16) + j;
     f32x4 h = __builtin_nontemporal_load(st);
@@ -244,7 +268,10 @@ __global__ __launch_bounds__(256) void mamba1_decode16_kernel(SsdArgs a, const f
     }
     if (gid >> 2 < total) __builtin_nontemporal_store(h, st);
     y = group_sum<4>(y);
-    if (j == 0 && gid >> 2 < total) a.y[idx] = f32_to_f16_bits(fmaf(a.D ? a.D[d] : 0.0f, xv, a.C_scales[0] * y));
+    if (j == 0 && gid >> 2 < total) {
+        const float gate = a.z ? silu_of_code(a.z_scale, a.z[idx]) : 1.0f;
+        a.y[idx] = f32_to_f16_bits(fmaf(a.D ? a.D[d] : 0.0f, xv, a.C_scales[0] * y) * gate);
+    }
 }
 
 // Any d_state: one thread per (sequence, channel).
@@ -254,7 +281,7 @@ __global__ __launch_bounds__(256) void mamba1_decode_any_kernel(SsdArgs a, const
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (size_t)a.s.batch * D) return;
     const int b = (int)(idx / D), d = (int)(idx - (size_t)b * D);
-    const float dt = a.dt[idx], xv = x_scale_lookup(a, 0, d) * (float)a.x[idx];
+    const float dt = step_size(a, idx, d), xv = x_scale_lookup(a, 0, d) * (float)a.x[idx];
     const float u = dt * xv * a.B_scales[0];
     float *st = a.state + idx * N;
     const float *Ar = A + (size_t)d * N;
@@ -265,7 +292,8 @@ __global__ __launch_bounds__(256) void mamba1_decode_any_kernel(SsdArgs a, const
         st[n] = hn;
         y = fmaf((float)Cq[n], hn, y);
     }
-    a.y[idx] = f32_to_f16_bits(fmaf(a.D ? a.D[d] : 0.0f, xv, a.C_scales[0] * y));
+    const float gate = a.z ? silu_of_code(a.z_scale, a.z[idx]) : 1.0f;
+    a.y[idx] = f32_to_f16_bits(fmaf(a.D ? a.D[d] : 0.0f, xv, a.C_scales[0] * y) * gate);
 }
 
 bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
@@ -278,7 +306,8 @@ hipError_t launch_mamba1_scan(const SsdArgs &a, const float *A, const float *ini
 {
     const int D = a.s.headdim;
     const bool fast = !(a.s.flags & QUAMBA_FLAG_GENERIC_KERNEL) && a.s.d_state == 16 && a.s.seqlen % 16 == 0 &&
-                      aligned16(a.x) && aligned16(a.B) && aligned16(a.C) && aligned16(a.dt) && aligned16(a.y);
+                      aligned16(a.x) && aligned16(a.B) && aligned16(a.C) && aligned16(a.dt) && aligned16(a.y) &&
+                      aligned16(a.z) && aligned16(a.dt_q);
     if (fast) {
         const dim3 grid((unsigned)((D + kWaves - 1) / kWaves), (unsigned)a.s.batch);
         hipLaunchKernelGGL(mamba1_scan_kernel, grid, dim3(kThreads), 0, stream, a, A, init, fin);

@@ -108,3 +108,14 @@ def make_mamba1_problem(batch: int, channels: int, d_state: int, seqlen: int, se
             "C": oracle.quantize(raw["C"], sc.C_scales[0]), "dt": np.ascontiguousarray(raw["dt"][:, perm]),
             "A": np.ascontiguousarray(raw["A"][perm]), "D": np.ascontiguousarray(raw["D"][perm]), "xs": xs}
     return sc, prob
+
+
+def make_mamba1_gate(batch: int, channels: int, seqlen: int, seed: int):
+    """int8 codes of the Mamba1 scan's side inputs [b,D,L] (drawn in the sorted channel order), quantized with the
+    oracle's Eq. 1 and one static scale per tensor (absolute maximum / 127).  Returns dict(z, z_scale, dt_q, dt_scale,
+    dt_bias [D])."""
+    raw = W.draw_mamba1_gate(batch, channels, seqlen, seed)
+    zs = np.float32(np.abs(raw["z"]).max() / 127.0)
+    ds = np.float32(np.abs(raw["dt_pre"]).max() / 127.0)
+    return {"z": oracle.quantize(raw["z"], zs), "z_scale": float(zs), "dt_q": oracle.quantize(raw["dt_pre"], ds),
+            "dt_scale": float(ds), "dt_bias": raw["dt_bias"]}

@@ -203,3 +203,16 @@ def test_mamba1_rejects_bad_arguments_without_a_device():
         assert scan(_shape(**dict(m1, **bad))) == -2
     assert step(_shape(**dict(m1, nheads=4, ngroups=2))) == -2
     assert scan(_shape(**dict(m1, flags=2))) == -5 and step(_shape(**dict(m1, flags=1))) == -5
+    # the variants with the 8-bit side inputs: dt may be absent only when the gate carries its codes; bad scales
+    from paper_2503_22879_amd.binding import _GateStruct
+
+    def gated(fn, n, g, dt):
+        args = [p] * n
+        args[3] = dt
+        return fn(C.byref(_shape(**m1)), C.byref(sc), None if g is None else C.byref(g), *args, None)
+    for fn, n in ((lib.quamba_mamba1_scan_gated, 9), (lib.quamba_mamba1_decode_step_gated, 8)):
+        assert gated(fn, n, None, None) == -1
+        assert gated(fn, n, _GateStruct(p, 1.0, None, 0.0, None), None) == -1
+        assert gated(fn, n, _GateStruct(None, 0.0, p, 0.0, None), None) == -5
+        assert gated(fn, n, _GateStruct(p, float("inf"), None, 0.0, None), p) == -5
+        assert gated(fn, n, _GateStruct(p, 0.0, p, 0.1, None), None) == -5

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 import workloads as W
-from helpers import make_mamba1_problem, host_scales
+from helpers import make_mamba1_problem, make_mamba1_gate, host_scales
 
 pytestmark = pytest.mark.gpu
 
@@ -131,5 +131,76 @@ def test_decode_steps(gpu_lib):
                                                   sl["B"][:, :, None], sl["C"][:, :, None], sl["dt"][:, :, None], p["A"],
                                                   p["D"], st_ref)
             ey = np.abs(y.cpu().numpy().astype(np.float64) - yref[:, :, 0]).max() / np.abs(yref).max()
+            es = np.abs(st.cpu().numpy().astype(np.float64) - st_ref).max() / np.abs(st_ref).max()
+            assert ey <= Y_TOL and es <= S_TOL, (t, ey, es)
+
+
+def _gate(q, g, use_z, use_dt, sl=None):
+    import torch
+    pick = (lambda v: torch.from_numpy(np.ascontiguousarray(v if sl is None else v[:, :, sl])).cuda())
+    return q.Gate(z=pick(g["z"]) if use_z else None, z_scale=g["z_scale"] if use_z else 0.0,
+                  dt_q=pick(g["dt_q"]) if use_dt else None, dt_scale=g["dt_scale"] if use_dt else 0.0,
+                  dt_bias=torch.from_numpy(g["dt_bias"]).cuda() if use_dt else None)
+
+
+def _dt_of_codes(g):
+    """The oracle's softplus takes the bias along the last axis: channels last, then back to time last."""
+    return np.moveaxis(oracle.dt_from_codes(np.moveaxis(g["dt_q"], 1, -1), g["dt_scale"], g["dt_bias"]), -1, 1)
+
+
+@pytest.mark.parametrize("use_z,use_dt", [(True, False), (False, True), (True, True)])
+@pytest.mark.parametrize("b,D,N,L,flags", [(2, 203, 16, 2608, 0), (2, 70, 16, 45, 0), (1, 33, 24, 64, 0),
+                                           (1, 130, 16, 256, 1)])
+def test_scan_with_side_inputs(gpu_lib, b, D, N, L, flags, use_z, use_dt):
+    """Step size from int8 codes of its pre-activation plus a per-channel bias, and / or the output gate on int8 z
+    (Section 3.2), on the wave-scan kernel (several tiles and a ragged one) and the any-shape kernel: the oracle's
+    scan on the oracle's own step size, followed by the oracle's gate."""
+    import torch
+    q = gpu_lib
+    sc, p = make_mamba1_problem(b, D, N, L, seed=11)
+    g = make_mamba1_gate(b, D, L, seed=11)
+    dt_ref = _dt_of_codes(g).astype(np.float32) if use_dt else p["dt"]
+    init = np.random.default_rng(11).normal(0, 0.05, size=(b, D, N)).astype(np.float32)
+    yref, sref = oracle.ref_mamba1_scan(p["xs"], sc.B_scales[0], sc.C_scales[0], p["x"], p["B"], p["C"], dt_ref, p["A"],
+                                        p["D"], init)
+    if use_z:
+        yref = oracle.silu_gate(yref, g["z"], g["z_scale"])
+    t = {k: torch.from_numpy(np.ascontiguousarray(p[k])).cuda() for k in ("x", "B", "C", "dt", "A", "D")}
+    y = torch.full((b, D, L), float("nan"), dtype=torch.float16, device="cuda")
+    fin = torch.full((b, D, N), float("nan"), device="cuda")
+    q.quamba_mamba1_scan(_shape(q, b, D, N, L, 4, flags), q.DeviceScales(host_scales(q, sc)), t["x"], t["B"], t["C"],
+                         None if use_dt else t["dt"], t["A"], t["D"], y, init_state=torch.from_numpy(init).cuda(),
+                         final_state=fin, gate=_gate(q, g, use_z, use_dt))
+    yg, sg = y.cpu().numpy().astype(np.float64), fin.cpu().numpy().astype(np.float64)
+    assert np.isfinite(yg).all() and np.isfinite(sg).all()
+    ey = np.abs(yg - yref).max() / np.abs(yref).max()
+    es = np.abs(sg - sref).max() / np.abs(sref).max()
+    print(f"mamba1 scan D={D} L={L} flags={flags} z={use_z} dt_q={use_dt}: y {ey:.2e} state {es:.2e}")
+    assert ey <= Y_TOL and es <= S_TOL
+
+
+def test_decode_steps_with_side_inputs(gpu_lib):
+    import torch
+    q = gpu_lib
+    for (b, D, N) in [(5, 5120, 16), (3, 77, 24)]:
+        sc, p = make_mamba1_problem(b, D, N, 4, seed=12)
+        g = make_mamba1_gate(b, D, 4, seed=12)
+        dt_all = _dt_of_codes(g).astype(np.float32)
+        shape = _shape(q, b, D, N, 1, 4)
+        dsc = q.DeviceScales(host_scales(q, sc))
+        st_ref = np.random.default_rng(12).normal(0, 0.1, size=(b, D, N)).astype(np.float32)
+        st = torch.from_numpy(st_ref).cuda()
+        st_ref = st_ref.astype(np.float64)
+        A, Dk = torch.from_numpy(p["A"]).cuda(), torch.from_numpy(p["D"]).cuda()
+        y = torch.empty((b, D), dtype=torch.float16, device="cuda")
+        for t in range(4):
+            sl = {k: np.ascontiguousarray(p[k][:, :, t]) for k in ("x", "B", "C")}
+            q.quamba_mamba1_decode_step(shape, dsc, *(torch.from_numpy(sl[k]).cuda() for k in ("x", "B", "C")), None,
+                                        A, Dk, st, y, gate=_gate(q, g, True, True, sl=t))
+            yref, st_ref = oracle.ref_mamba1_scan(p["xs"], sc.B_scales[0], sc.C_scales[0], sl["x"][:, :, None],
+                                                  sl["B"][:, :, None], sl["C"][:, :, None], dt_all[:, :, t:t + 1],
+                                                  p["A"], p["D"], st_ref)
+            yref = oracle.silu_gate(yref[:, :, 0], g["z"][:, :, t], g["z_scale"])
+            ey = np.abs(y.cpu().numpy().astype(np.float64) - yref).max() / np.abs(yref).max()
             es = np.abs(st.cpu().numpy().astype(np.float64) - st_ref).max() / np.abs(st_ref).max()
             assert ey <= Y_TOL and es <= S_TOL, (t, ey, es)

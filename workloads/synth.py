@@ -208,6 +208,20 @@ def draw_mamba1(batch: int, channels: int, d_state: int, seqlen: int, seed: int 
     return {"x": x, "B": B, "C": C, "dt": dt.astype(np.float32), "A": A, "D": Dk, "x_absmax": xcal.astype(np.float32)}
 
 
+def draw_mamba1_gate(batch: int, channels: int, seqlen: int, seed: int = 0, stream: int = 75) -> dict:
+    """Raw floats of the Mamba1 scan's optional side inputs, channel-major with time last like draw_mamba1's tensors
+    and in the same sorted channel order: the gate branch z [b,D,L] (standard normal times a log-normal per-channel
+    magnitude), the step size's pre-activation without its bias [b,D,L] (N(-3, 1) minus the bias) and the per-channel
+    bias [D] (N(0, 0.5))."""
+    g = _rng(seed, stream)
+    gp = _rng(seed, 76)
+    zsig = np.exp(0.5 * gp.standard_normal(channels)).astype(np.float32)
+    bias = (0.5 * gp.standard_normal(channels)).astype(np.float32)
+    z = g.standard_normal((batch, channels, seqlen), dtype=np.float32) * zsig[None, :, None]
+    pre = (g.standard_normal((batch, channels, seqlen), dtype=np.float32) - np.float32(3.0)) - bias[None, :, None]
+    return {"z": z, "dt_pre": pre.astype(np.float32), "dt_bias": bias}
+
+
 def draw_conv(s: LayerShape, seed: int = 0, batch: int | None = None, seqlen: int | None = None, stream: int = 50):
     """Raw floats of the causal convolution in front of the scan, channels [x | B | C] (H*P + 2*G*N of them) already in
     the sorted order the offline reordering gives them: the block's pre-convolution activations xBC [b,L,Ct] (standard
