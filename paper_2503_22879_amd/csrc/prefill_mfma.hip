@@ -497,6 +497,9 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                                 *reinterpret_cast<const uint32_t *>(s_zs + tl * kZsStride + pt * 32 + 8 * rg + 4 * hb);
                 }
                 if (d_by_mfma) {
+                    // the chunk's LDS arrays are not read past this point (the scale and SiLU tables stay as they are):
+                    // the state waves restage them for the next chunk while this wave scales and stores its outputs
+                    __syncthreads();
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt) {
                         f32x4 k4[4];  // s_x(h,p) * y_scale of the lane's 16 channels of this p tile
@@ -557,11 +560,12 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                             const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
                             if (tl < nv) *reinterpret_cast<u32x4 *>(yrow + pt * 32 + 16 * j + 8 * hb) = v;
                         }
+                    __syncthreads();  // this epilogue reads the staged x: the chunk's LDS arrays are free only now
                 }
+            } else {
+                if (c + 1 < nchunks) issue_c_rows(c + 1);
+                __syncthreads();  // both roles are done with the chunk's LDS arrays
             }
-
-            else if (c + 1 < nchunks) issue_c_rows(c + 1);
-            __syncthreads();  // both roles are done with the chunk's LDS arrays
         }
     } else {
         // ================= state waves: staging, token weights, state update ================= Carried state in x-code
