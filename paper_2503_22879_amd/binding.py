@@ -78,6 +78,13 @@ def load_library():
             raise FileNotFoundError(
                 f"{_LIB_PATH} is missing: build it with `python -m paper_2503_22879_amd.build` "
                 "(or __graft_entry__.build()); this package has no CPU fallback")
+        # PyTorch ships its own HIP runtime.  Import it before the library is opened, so that the library's dependency
+        # on libamdhip64 resolves to the runtime that owns the tensors and streams the callers pass in; opened the other
+        # way round, the process holds two runtimes and launches on torch's streams are refused.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = C.CDLL(_LIB_PATH)
         lib.quamba_ssd_prefill_workspace_size.restype = C.c_size_t
         lib.quamba_ssd_prefill_workspace_size.argtypes = [C.POINTER(Shape)]

@@ -12,6 +12,7 @@
 // a fixed order (the header states it); the compiler must not contract multiplies and adds, and the exponential of
 // the decay is a fixed sequence of such operations instead of a library call.
 #include <algorithm>
+#include <atomic>
 
 #include "quamba_internal.h"
 
@@ -328,15 +329,15 @@ hipError_t launch(K kernel, dim3 grid, const SsdArgs &a, const float *ss, int8_t
 // Compute units of the current device (cached per device id).
 int compute_units()
 {
-    static int cached[64];
+    static std::atomic<int> cached[64];  // zero-initialised; concurrent first calls store the same value
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 // Sequences per workgroup of the vector kernel: enough workgroups to fill the chip several times over (>= 4096 when

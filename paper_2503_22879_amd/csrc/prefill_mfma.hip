@@ -35,6 +35,8 @@
 // operands that need the token index as k (x^T, B^T) are fetched with the transposing LDS loads
 // (ds_read_b64_tr_b8 / _tr_b16), whose source lanes address whole token rows; the rows are stored with bits 2 and 3
 // of the token index swapped so that the 8 tokens of one k group are 8 consecutive rows.
+#include <atomic>
+
 #include "quamba_internal.h"
 
 namespace quamba {
@@ -863,15 +865,15 @@ hipError_t launch_scan(const SsdArgs &a, hipStream_t stream)
 // Compute units of the current device (cached per device id).
 int compute_units()
 {
-    static int cached[64];
+    static std::atomic<int> cached[64];  // zero-initialised; concurrent first calls store the same value
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 }  // namespace
