@@ -12,6 +12,8 @@
 // and broadcasts (the operator of a first-order linear recurrence), and replays its 16 tokens from the scanned-in state
 // while accumulating y.  The tile's B and C codes sit in LDS, shared by the workgroup's eight channels; the state at the
 // end of a tile is carried to the next tile through LDS.
+#include <algorithm>
+
 #include "quamba_internal.h"
 
 namespace quamba {
@@ -22,6 +24,7 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kE = 16;              // tokens per lane
 constexpr int kTile = 64 * kE;      // tokens per tile
 constexpr float kLog2e = 1.44269504088896340736f;
+constexpr int kDecodeSeqs = 4;      // sequences per thread and trip of the decode step
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -247,30 +250,49 @@ __global__ __launch_bounds__(64) void mamba1_scan_any_kernel(SsdArgs a, const fl
 // by data-parallel-primitive moves inside the quad.
 __global__ __launch_bounds__(256) void mamba1_decode16_kernel(SsdArgs a, const float *A)
 {
-    const int D = a.s.headdim;
-    const size_t gid = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t total = (size_t)a.s.batch * D;
-    const size_t idx = gid >> 2 < total ? gid >> 2 : total - 1;  // lanes past the end redo the last row, store nothing
-    const int j = (int)(gid & 3);
-    const int b = (int)(idx / D), d = (int)(idx - (size_t)b * D);
-    const float dt = step_size(a, idx, d), xv = x_scale_lookup(a, 0, d) * (float)a.x[idx];
-    const float u = dt * xv * a.B_scales[0];
-    f32x4 *st = reinterpret_cast<f32x4 *>(a.state + idx * 16) + j;
-    f32x4 h = __builtin_nontemporal_load(st);
-    const f32x4 Ar = *(reinterpret_cast<const f32x4 *>(A + (size_t)d * 16) + j);
-    const uint32_t bq = *reinterpret_cast<const uint32_t *>(a.B + (size_t)b * 16 + 4 * j);
-    const uint32_t cq = *reinterpret_cast<const uint32_t *>(a.C + (size_t)b * 16 + 4 * j);
-    float y = 0.0f;
+    constexpr int kSeq = kDecodeSeqs;  // sequences per thread and trip: the loads of a trip are in flight together
+    const int D = a.s.headdim, nb = a.s.batch;
+    const int q = blockIdx.x * 256 + threadIdx.x;  // (channel, quarter of its 16 states)
+    const int j = q & 3;
+    const bool live = (q >> 2) < D;
+    const int d = live ? q >> 2 : D - 1;  // lanes past the end redo the last channel and store nothing
+    // per channel, once for all sequences of the thread: scale, skip coefficient, the quarter's row of A
+    const float sx = x_scale_lookup(a, 0, d);
+    const float sxB = sx * a.B_scales[0], sC = a.C_scales[0];
+    const float Dx = (a.D ? a.D[d] : 0.0f) * sx;
+    const f32x4 A2 = *(reinterpret_cast<const f32x4 *>(A + (size_t)d * 16) + j) * kLog2e;
+    for (int b0 = blockIdx.y * kSeq; b0 < nb; b0 += gridDim.y * kSeq) {
+        f32x4 h[kSeq];
+        float dt[kSeq], xc[kSeq];
+        uint32_t bq[kSeq], cq[kSeq];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        h[k] = fmaf(__builtin_amdgcn_exp2f(dt * Ar[k] * kLog2e), h[k], u * byte_to_float(bq, k));
-        y = fmaf(byte_to_float(cq, k), h[k], y);
-    }
-    if (gid >> 2 < total) __builtin_nontemporal_store(h, st);
-    y = group_sum<4>(y);
-    if (j == 0 && gid >> 2 < total) {
-        const float gate = a.z ? silu_of_code(a.z_scale, a.z[idx]) : 1.0f;
-        a.y[idx] = f32_to_f16_bits(fmaf(a.D ? a.D[d] : 0.0f, xv, a.C_scales[0] * y) * gate);
+        for (int s = 0; s < kSeq; ++s) {
+            const int b = min(b0 + s, nb - 1);  // sequences past the end redo the last one and store nothing
+            const size_t idx = (size_t)b * D + d;
+            h[s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.state + idx * 16) + j);
+            dt[s] = step_size(a, idx, d);
+            xc[s] = (float)a.x[idx];
+            bq[s] = *reinterpret_cast<const uint32_t *>(a.B + (size_t)b * 16 + 4 * j);
+            cq[s] = *reinterpret_cast<const uint32_t *>(a.C + (size_t)b * 16 + 4 * j);
+        }
+#pragma unroll
+        for (int s = 0; s < kSeq; ++s) {
+            const bool store = live && b0 + s < nb;
+            const size_t idx = (size_t)min(b0 + s, nb - 1) * D + d;
+            const float u = dt[s] * (sxB * xc[s]);
+            float y = 0.0f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                h[s][k] = fmaf(__builtin_amdgcn_exp2f(dt[s] * A2[k]), h[s][k], u * byte_to_float(bq[s], k));
+                y = fmaf(byte_to_float(cq[s], k), h[s][k], y);
+            }
+            if (store) __builtin_nontemporal_store(h[s], reinterpret_cast<f32x4 *>(a.state + idx * 16) + j);
+            y = group_sum<4>(y);
+            if (j == 0 && store) {
+                const float gate = a.z ? silu_of_code(a.z_scale, a.z[idx]) : 1.0f;
+                a.y[idx] = f32_to_f16_bits(fmaf(Dx, xc[s], sC * y) * gate);
+            }
+        }
     }
 }
 
@@ -322,10 +344,15 @@ hipError_t launch_mamba1_decode(const SsdArgs &a, const float *A, hipStream_t st
 {
     const size_t total = (size_t)a.s.batch * a.s.headdim;
     if (a.s.d_state == 16 && aligned16(a.state) && aligned16(A) && reinterpret_cast<uintptr_t>(a.B) % 4 == 0 &&
-        reinterpret_cast<uintptr_t>(a.C) % 4 == 0)
-        hipLaunchKernelGGL(mamba1_decode16_kernel, dim3((unsigned)((4 * total + 255) / 256)), dim3(256), 0, stream, a, A);
-    else
+        reinterpret_cast<uintptr_t>(a.C) % 4 == 0) {
+        // x: the (channel, quarter) pairs; y: groups of kDecodeSeqs sequences (a thread loops if the batch has more
+        // groups than the grid's y dimension may hold)
+        const dim3 grid((unsigned)((4 * (size_t)a.s.headdim + 255) / 256),
+                        (unsigned)std::min((a.s.batch + kDecodeSeqs - 1) / kDecodeSeqs, 65535));
+        hipLaunchKernelGGL(mamba1_decode16_kernel, grid, dim3(256), 0, stream, a, A);
+    } else {
         hipLaunchKernelGGL(mamba1_decode_any_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, a, A);
+    }
     return hipGetLastError();
 }
 
