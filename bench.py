@@ -88,7 +88,41 @@ def quantize_layer(q, shape, hs, raw):
             "dt": np.ascontiguousarray(raw["dt"], np.float32)}
 
 
-def time_region(torch, fn, steps, warmup, min_warm_ms=0.0):
+# --power: after a leg's timed region the same call is repeated for POWER_SECONDS and the board power sensor
+# (hwmon power1_input, microwatts; a slow average, hence the long run) is sampled over the second half.
+POWER_SECONDS = 0.0
+BOARD_POWER_W = {}
+
+
+def _hwmon(name):
+    import glob
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/" + name)):
+        try:
+            with open(path) as f:
+                return float(f.read().strip()) * 1e-6
+        except (OSError, ValueError):
+            continue
+    return None
+
+
+def sample_board_power(torch, fn, key):
+    """Mean and maximum board power (W) while fn runs back to back, or None when the sensor cannot be read."""
+    if _hwmon("power1_input") is None:
+        BOARD_POWER_W[key] = None
+        return
+    t0 = time.perf_counter()
+    vals = []
+    while time.perf_counter() - t0 < POWER_SECONDS:
+        for _ in range(50):
+            fn()
+        torch.cuda.synchronize()
+        if time.perf_counter() - t0 > 0.5 * POWER_SECONDS:
+            vals.append(_hwmon("power1_input"))
+    vals = [v for v in vals if v is not None]
+    BOARD_POWER_W[key] = {"mean": sum(vals) / len(vals), "max": max(vals)} if vals else None
+
+
+def time_region(torch, fn, steps, warmup, min_warm_ms=0.0, power_key=None):
     """Mean ms per call over `steps` calls on torch's current stream (the stream the kernels are launched on),
     bracketed by device synchronisation; HIP events give the device-side duration.  With min_warm_ms the untimed
     warm-up is continued until that much wall time has gone by: after seconds of host-side preparation the first tens
@@ -111,6 +145,8 @@ def time_region(torch, fn, steps, warmup, min_warm_ms=0.0):
     ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
+    if POWER_SECONDS > 0 and power_key:
+        sample_board_power(torch, fn, power_key)
     return ev0.elapsed_time(ev1) / steps, wall_ms / steps
 
 
@@ -126,6 +162,8 @@ def main() -> int:
     ap.add_argument("--no-conv", action="store_true", help="skip the W8A8 causal convolution in front of the scan")
     ap.add_argument("--no-hadamard", action="store_true",
                     help="skip the quantized Hadamard transform of the prefill output")
+    ap.add_argument("--power", action="store_true",
+                    help="after each leg run it for 2 more seconds and report the board power from the hwmon sensor")
     ap.add_argument("--precise-state", action="store_true", help="also return the final fp32 state (two-term state path)")
     ap.add_argument("--gated", action="store_true",
                     help="prefill through quamba_ssd_prefill_gated: int8 gate z and int8 step-size codes (not the "
@@ -139,6 +177,9 @@ def main() -> int:
               "state group with no exchange, see DESIGN.md)" % args.gpus, file=sys.stderr)
         return 2
 
+    if args.power:
+        global POWER_SECONDS
+        POWER_SECONDS = 2.0
     import torch
     import paper_2503_22879_amd as q
     q.load_library()
@@ -187,7 +228,7 @@ def main() -> int:
     def prefill():
         q.quamba_ssd_prefill(shape, dsc, t["x"], t["B"], t["C"], t["dt"], A, D, None, y, fin, ws, gate=gate)
 
-    ms, wall_ms = time_region(torch, prefill, args.steps, args.warmup, min_warm_ms=SPIN_UP_MS)
+    ms, wall_ms = time_region(torch, prefill, args.steps, args.warmup, min_warm_ms=SPIN_UP_MS, power_key="prefill")
     tokens = s.batch * s.seqlen
     f16_macs, i8_macs, bytes_tok = prefill_algorithmic(s)
     flops_equiv = tokens * (2 * f16_macs + 2 * i8_macs * (MFMA_F16_PEAK_TFLOPS / MFMA_I8_PEAK_TOPS))
@@ -252,7 +293,7 @@ def main() -> int:
         def hadamard():
             q.quamba_hadamard_quantize(yflat, s_y, yq)
 
-        hms, hwall = time_region(torch, hadamard, args.steps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS)
+        hms, hwall = time_region(torch, hadamard, args.steps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS, power_key="hadamard")
         hbytes = 3.0 * rows * n_had
         hgbs = hbytes / (hms * 1e-3) / 1e9
         hops = HADAMARD_OPS_PER_VALUE(n_had) * rows * n_had
@@ -299,7 +340,7 @@ def main() -> int:
         def conv():
             q.quamba_conv1d_q8(shape, dsc, cin, cw, cbias, in_w_scale, cx, cB, cC, conv_state_out=cst)
 
-        cms, cwall = time_region(torch, conv, args.steps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS)
+        cms, cwall = time_region(torch, conv, args.steps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS, power_key="conv1d")
         celems = float(s.batch) * s.seqlen * Ct
         cgbs = 2.0 * celems / (cms * 1e-3) / 1e9
         cops = CONV_OPS_PER_ELEMENT * celems
@@ -360,7 +401,7 @@ def main() -> int:
         def mamba1():
             q.quamba_mamba1_scan(mshape, mdsc, mx, mB, mC, mdt, mA, mDk, my, final_state=mfin)
 
-        mms, mwall = time_region(torch, mamba1, max(20, args.steps // 2), max(args.warmup // 2, 3), min_warm_ms=SPIN_UP_MS)
+        mms, mwall = time_region(torch, mamba1, max(20, args.steps // 2), max(args.warmup // 2, 3), min_warm_ms=SPIN_UP_MS, power_key="mamba1_scan")
         melems = float(mb) * mD * mL * mN
         mbytes = float(mb) * mD * mL * 7 + 2.0 * mb * mN * mL
         out["mamba1_scan"] = {
@@ -404,7 +445,7 @@ def main() -> int:
         def mamba1_step():
             q.quamba_mamba1_decode_step(dshape1, mdsc, sx1, sB1, sC1, sdt1, mA, mDk, mstate, y1)
 
-        sms, swall = time_region(torch, mamba1_step, args.steps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS)
+        sms, swall = time_region(torch, mamba1_step, args.steps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS, power_key="mamba1_decode")
         sbytes = 8.0 * db * mD * mN + 7.0 * db * mD + 2.0 * db * mN + 4.0 * mD * mN
         out["mamba1_decode"] = {
             "metric": "Mamba1 decode state update us/step", "value": sms * 1e3, "unit": "us/step",
@@ -445,7 +486,7 @@ def main() -> int:
             q.quamba_ssd_decode_step(dshape, ddsc, i["x"], i["B"], i["C"], i["dt"], dA, dD, state, yd)
 
         dsteps = max(args.steps, sd.decode_steps)
-        dms, dwall = time_region(torch, decode, dsteps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS)
+        dms, dwall = time_region(torch, decode, dsteps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS, power_key="decode")
         dgbs = decode_bytes(sd) / (dms * 1e-3) / 1e9
         out["decode"] = {
             "metric": "decode state update us/step", "value": dms * 1e3, "unit": "us/step", "steps": dsteps,
@@ -480,7 +521,7 @@ def main() -> int:
             counter[0] += 1
             q.quamba_ssd_decode_step_q8(dshape, ddsc, dss, i["x"], i["B"], i["C"], i["dt"], dA, dD, qstate, yd)
 
-        qms, qwall = time_region(torch, decode_q8, dsteps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS)
+        qms, qwall = time_region(torch, decode_q8, dsteps, max(args.warmup, 4), min_warm_ms=SPIN_UP_MS, power_key="decode_q8")
         qbytes = decode_bytes(sd, state_bytes=1)
         qgbs = qbytes / (qms * 1e-3) / 1e9
         elems = sd.batch * sd.nheads * sd.headdim * sd.d_state
@@ -511,6 +552,8 @@ def main() -> int:
         torch.cuda.synchronize()
         out["copy_calibration"] = {"bytes_read": 256 << 20, "bytes_written": 256 << 20, "launches": 3}
 
+    if args.power:
+        out["board_power_w"] = dict(BOARD_POWER_W, cap=_hwmon("power1_cap"), seconds_per_leg=POWER_SECONDS)
     print(json.dumps(out))
     return 0
 

@@ -66,12 +66,14 @@ constexpr float kXs = 1.0f / 16.0f;
 constexpr float kAcc = 1.0f / 64.0f;
 
 // LDS map (bytes) for PT 32-channel tiles per workgroup.  Row pitches: with 4-byte banks, the 8 token rows x 16 bytes
-// a group of 16 lanes fetches from Bq, and the 4 token rows x 32 bytes it fetches from x, fall into distinct
-// banks (pitches of 36 and 40 / 24 banks).
+// a group of 16 lanes fetches from Bq fall into distinct banks (pitch of 36 banks), and so do the 4 token rows x 32
+// bytes that each of the two 16-lane groups of a half-wave fetches from x in the same cycle (pitch of 48 banks: rows
+// at banks 0, 48, 32, 16, the second group 8 banks further; the pitch of 40 banks used before put the second group's
+// last row on the first group's first and showed as a third of the LDS time in the bank-conflict counter).
 template <int PT>
 struct Lds {
     static constexpr int kPw = 32 * PT;                      // channels of the workgroup
-    static constexpr int kXsStride = PT == 2 ? 80 : 48;      // halves per row of x [token][p]
+    static constexpr int kXsStride = PT == 2 ? 96 : 48;      // halves per row of x [token][p]
     static constexpr int kOffCum = 0;                        // float[128]  prefix sums (log2 units)
     static constexpr int kOffDt = kOffCum + 4 * kQ;          // float[128]  dt 2^-7 / kXs
     static constexpr int kOffW2 = kOffDt + 4 * kQ;           // float[128]  column weights of the diagonal blocks
