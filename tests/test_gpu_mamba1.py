@@ -114,7 +114,7 @@ def test_2p8b_shape_sampled(gpu_lib):
 def test_decode_steps(gpu_lib):
     import torch
     q = gpu_lib
-    for (b, D, N) in [(5, 5120, 16), (3, 77, 24)]:
+    for (b, D, N) in [(5, 5120, 16), (7, 203, 16), (3, 77, 24)]:  # 203: a last workgroup with idle lanes
         sc, p = make_mamba1_problem(b, D, N, 6, seed=10)
         shape = _shape(q, b, D, N, 1, 4)
         dsc = q.DeviceScales(host_scales(q, sc))
@@ -182,7 +182,7 @@ def test_scan_with_side_inputs(gpu_lib, b, D, N, L, flags, use_z, use_dt):
 def test_decode_steps_with_side_inputs(gpu_lib):
     import torch
     q = gpu_lib
-    for (b, D, N) in [(5, 5120, 16), (3, 77, 24)]:
+    for (b, D, N) in [(5, 5120, 16), (7, 203, 16), (3, 77, 24)]:  # 203: a last workgroup with idle lanes
         sc, p = make_mamba1_problem(b, D, N, 4, seed=12)
         g = make_mamba1_gate(b, D, 4, seed=12)
         dt_all = _dt_of_codes(g).astype(np.float32)
