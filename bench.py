@@ -35,9 +35,9 @@ MFMA_I8_PEAK_TOPS = 5000.0     # dense int8
 # 256 MiB device copy in the same run: factors 1.9998 and 1.0000); profiles/hbm_traffic_prefill_m2_8b_b4_and_decode_m2_8b.txt
 # and profiles/hbm_traffic_hadamard_conv1d_m2_8b_b4_and_mamba1_2p8b.txt.
 # None for workloads that were not profiled.
-MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 525.4e6, "m2_8b_decode": 2162.3e6, "m2_8b_decode_q8": 550.9e6,
+MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 527.6e6, "m2_8b_decode": 2162.3e6, "m2_8b_decode_q8": 550.9e6,
                           "m2_8b_b4_hadamard": 402.7e6, "m2_8b_b4_conv1d": 352.1e6,
-                          "mamba1_2p8b_scan": 599.0e6, "mamba1_2p8b_decode": 178.8e6}
+                          "mamba1_2p8b_scan": 599.2e6, "mamba1_2p8b_decode": 178.8e6}
 
 
 def prefill_algorithmic(s: W.LayerShape):
@@ -88,9 +88,11 @@ def quantize_layer(q, shape, hs, raw):
             "dt": np.ascontiguousarray(raw["dt"], np.float32)}
 
 
-# --power: after a leg's timed region the same call is repeated for POWER_SECONDS and the board power sensor
-# (hwmon power1_input, microwatts; a slow average, hence the long run) is sampled over the second half.
-POWER_SECONDS = 0.0
+# After the prefill leg's timed region (with --power: after every leg's) the same call is repeated for POWER_SECONDS
+# and the board power sensor (hwmon power1_input, microwatts; a slow average, hence the long run) is sampled over the
+# second half; --no-power skips it.  A kernel that sits on the board's power cap runs as fast as its energy allows.
+POWER_SECONDS = 2.0
+POWER_ALL_LEGS = False   # by default only the prefill leg (the headline kernel) is sampled
 BOARD_POWER_W = {}
 
 
@@ -145,7 +147,7 @@ def time_region(torch, fn, steps, warmup, min_warm_ms=0.0, power_key=None):
     ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    if POWER_SECONDS > 0 and power_key:
+    if POWER_SECONDS > 0 and power_key and (POWER_ALL_LEGS or power_key == "prefill"):
         sample_board_power(torch, fn, power_key)
     return ev0.elapsed_time(ev1) / steps, wall_ms / steps
 
@@ -163,7 +165,9 @@ def main() -> int:
     ap.add_argument("--no-hadamard", action="store_true",
                     help="skip the quantized Hadamard transform of the prefill output")
     ap.add_argument("--power", action="store_true",
-                    help="after each leg run it for 2 more seconds and report the board power from the hwmon sensor")
+                    help="report the board power (hwmon sensor, 2 more seconds of launches) of every leg, not only of "
+                         "the prefill")
+    ap.add_argument("--no-power", action="store_true", help="do not sample the board power at all")
     ap.add_argument("--precise-state", action="store_true", help="also return the final fp32 state (two-term state path)")
     ap.add_argument("--gated", action="store_true",
                     help="prefill through quamba_ssd_prefill_gated: int8 gate z and int8 step-size codes (not the "
@@ -177,9 +181,10 @@ def main() -> int:
               "state group with no exchange, see DESIGN.md)" % args.gpus, file=sys.stderr)
         return 2
 
-    if args.power:
-        global POWER_SECONDS
-        POWER_SECONDS = 2.0
+    global POWER_SECONDS, POWER_ALL_LEGS
+    POWER_ALL_LEGS = args.power
+    if args.no_power:
+        POWER_SECONDS = 0.0
     import torch
     import paper_2503_22879_amd as q
     q.load_library()
@@ -552,7 +557,7 @@ def main() -> int:
         torch.cuda.synchronize()
         out["copy_calibration"] = {"bytes_read": 256 << 20, "bytes_written": 256 << 20, "launches": 3}
 
-    if args.power:
+    if POWER_SECONDS > 0:
         out["board_power_w"] = dict(BOARD_POWER_W, cap=_hwmon("power1_cap"), seconds_per_leg=POWER_SECONDS)
     print(json.dumps(out))
     return 0
