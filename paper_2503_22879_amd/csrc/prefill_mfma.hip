@@ -272,10 +272,15 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
     const bool d_by_mfma = fabsf(d_acc) < 3.0e4f;
     const float d_sel = d_by_mfma ? d_acc : 0.0f;
 
-    if (tid < kPw) s_sx[tid] = x_scale_lookup(a, h, p_base + tid) * (d_by_mfma ? y_scale : 1.0f);
-    // a gate code has 256 values: their SiLU is tabulated once (exp and reciprocal are quarter-rate instructions)
-    if (GATED && tid < 256) s_silu[tid] = silu_of_code(a.z_scale, (int8_t)tid);
-    __syncthreads();
+    // The channel scales (three dependent look-ups in global memory) and the SiLU table are written by the output waves
+    // after they have requested their first C rows, so that the look-ups do not stand in front of the first chunk's
+    // loads; their first readers sit behind the first chunk's staging barrier.  Only an initial state needs the scales
+    // earlier (the state waves convert it with them), which costs one more barrier.
+    auto fill_tables = [&]() {
+        if (tid < kPw) s_sx[tid] = x_scale_lookup(a, h, p_base + tid) * (d_by_mfma ? y_scale : 1.0f);
+        // a gate code has 256 values: their SiLU is tabulated once (exp and reciprocal are quarter-rate instructions)
+        if (GATED && tid < 256) s_silu[tid] = silu_of_code(a.z_scale, (int8_t)tid);
+    };
     const int nchunks = (L + kQ - 1) / kQ;
     constexpr float kStScale = kNarrow;
     const uint32_t x_row = (uint32_t)H * kP, b_row = (uint32_t)G * kN, dt_row = (uint32_t)H * 4u;
@@ -299,6 +304,8 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 ct[kk] = *reinterpret_cast<const i32x4 *>(cbase + (row * b_row + 16u * (ln >> 5)) + 32 * kk);
         };
         issue_c_rows(0);
+        fill_tables();
+        if (a.init_state) __syncthreads();  // the state waves wait for the scales
         for (int c = 0; c < nchunks; ++c) {
             const int t0 = c * kQ;
             const int nv = min(kQ, L - t0);
@@ -582,23 +589,6 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
         for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) st[pt][r] = 0.0f;
-        if (a.init_state) {
-#pragma unroll
-            for (int pt = 0; pt < PT; ++pt) {
-                const int p = pt * 32 + l32;
-                const float inv = kStScale * (d_by_mfma ? y_scale : 1.0f) / (s_sx[p] * sB);
-#pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    const int n0 = 32 * wave + 8 * rg + 4 * hb;
-                    const f32x4 v =
-                        *reinterpret_cast<const f32x4 *>(a.init_state + ((size_t)bh * kP + p_base + p) * kN + n0);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) st[pt][4 * rg + i] = v[i] * inv;
-                }
-            }
-        }
-
-
         // Registers that carry one chunk's global loads from the point of issue (the start of the previous chunk's
         // state update) to the staging phase: x codes (4 tokens x 4 PT channels), B codes (4 tokens x 16 states), and
         // dt of tokens 2 lane, 2 lane + 1 (first wave only: it computes every weight of the chunk).  Rows past the end
@@ -644,6 +634,22 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
             }
         };
         issue_loads(0);
+        if (a.init_state) {
+            __syncthreads();  // the scales are in LDS
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) {
+                const int p = pt * 32 + l32;
+                const float inv = kStScale * (d_by_mfma ? y_scale : 1.0f) / (s_sx[p] * sB);
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int n0 = 32 * wave + 8 * rg + 4 * hb;
+                    const f32x4 v =
+                        *reinterpret_cast<const f32x4 *>(a.init_state + ((size_t)bh * kP + p_base + p) * kN + n0);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) st[pt][4 * rg + i] = v[i] * inv;
+                }
+            }
+        }
         for (int c = 0; c < nchunks; ++c) {
             const int t0 = c * kQ;
             const int nv = min(kQ, L - t0);
