@@ -132,19 +132,26 @@ __device__ __forceinline__ f16x8 lds_read_tr16x8(const unsigned char *p)
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-// 8 int8 codes (two dwords, lowest address first) -> 8 exact fp16 values: byte^0x80 placed under the fp16
-// pattern of 1024 gives 1024 + (code + 128); subtract 1152.
+// 8 int8 codes (two dwords, lowest address first) -> 8 exact fp16 values, one conversion per code: the source byte is
+// picked and sign-extended by the instruction's sub-dword source select, the result written to the low or high half of
+// the destination by its destination select (the high half keeps the low one).
+__device__ __forceinline__ uint32_t i8x2_to_f16_lo_hi(uint32_t w, int first_byte)
+{
+    uint32_t r;
+    if (first_byte == 0) {
+        asm("v_cvt_f16_i16_sdwa %0, sext(%1) dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:BYTE_0" : "=v"(r) : "v"(w));
+        asm("v_cvt_f16_i16_sdwa %0, sext(%1) dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_1" : "+v"(r) : "v"(w));
+    } else {
+        asm("v_cvt_f16_i16_sdwa %0, sext(%1) dst_sel:WORD_0 dst_unused:UNUSED_PAD src0_sel:BYTE_2" : "=v"(r) : "v"(w));
+        asm("v_cvt_f16_i16_sdwa %0, sext(%1) dst_sel:WORD_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_3" : "+v"(r) : "v"(w));
+    }
+    return r;
+}
 __device__ __forceinline__ f16x8 i8x8_to_f16(uint32_t w0, uint32_t w1)
 {
-    const f16x2 bias = {(_Float16)1152.0f, (_Float16)1152.0f};
-    w0 ^= 0x80808080u;
-    w1 ^= 0x80808080u;
-    union { f16x8 v; f16x2 h[4]; } r;
-    r.h[0] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x64646464u, w0, 0x04010400u)) - bias;
-    r.h[1] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x64646464u, w0, 0x04030402u)) - bias;
-    r.h[2] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x64646464u, w1, 0x04010400u)) - bias;
-    r.h[3] = __builtin_bit_cast(f16x2, __builtin_amdgcn_perm(0x64646464u, w1, 0x04030402u)) - bias;
-    return r.v;
+    const u32x4 r = {i8x2_to_f16_lo_hi(w0, 0), i8x2_to_f16_lo_hi(w0, 2), i8x2_to_f16_lo_hi(w1, 0),
+                     i8x2_to_f16_lo_hi(w1, 2)};
+    return __builtin_bit_cast(f16x8, r);
 }
 
 // 4 int8 codes (one dword) -> fp16 values kXs * code, exact: byte^0x80 placed under the fp16 pattern of 64 (whose
