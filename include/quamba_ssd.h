@@ -55,6 +55,13 @@ typedef enum quamba_status {
                                            batches give every head two workgroups of 32 channels each); the
                                            results of the two launch shapes agree to rounding                  */
 
+#define QUAMBA_FLAG_NO_DECAY_SKIP 0x8u  /* prefill: also compute the products whose decay factor exp(sum of dt*A)
+                                           over the tokens between their operands is below 2^-32 (by default the
+                                           chunked kernel leaves such 32-token blocks out: the carried-state term of
+                                           an output block, score blocks far below the diagonal, a block's share of
+                                           the chunk state; what is left out is below 2.4e-10 of the term's own
+                                           undecayed size, five orders under the tightest tolerance)          */
+
 typedef struct quamba_ssd_shape_t {
     int32_t batch;           /* sequences                                                             */
     int32_t seqlen;          /* tokens per sequence (ignored by decode)                               */

@@ -9,12 +9,13 @@ from .binding import (QuambaError, Shape, HostScales, DeviceScales, Gate, load_l
                       quamba_ssd_decode_step_q8, quamba_ssd_quantize_state, quamba_state_scales,
                       quamba_hadamard_quantize, quamba_conv1d_q8, quamba_mamba1_scan, quamba_mamba1_decode_step,
                       quamba_reorder_params, quamba_gather_rows, quamba_quantize_x, quamba_quantize_groups,
-                      quamba_strerror, FLAG_GENERIC_KERNEL, FLAG_PRECISE_STATE, FLAG_NO_CHANNEL_SPLIT, EXPORTED_SYMBOLS)
+                      quamba_strerror, FLAG_GENERIC_KERNEL, FLAG_PRECISE_STATE, FLAG_NO_CHANNEL_SPLIT, FLAG_NO_DECAY_SKIP,
+                      EXPORTED_SYMBOLS)
 
 __all__ = ["QuambaError", "Shape", "HostScales", "DeviceScales", "Gate", "load_library", "library_path",
            "quamba_ssd_prefill", "quamba_ssd_prefill_workspace_size", "quamba_ssd_decode_step",
            "quamba_ssd_decode_step_q8", "quamba_ssd_quantize_state", "quamba_state_scales",
            "quamba_hadamard_quantize", "quamba_conv1d_q8", "quamba_mamba1_scan", "quamba_mamba1_decode_step",
            "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x", "quamba_quantize_groups",
-           "quamba_strerror", "FLAG_GENERIC_KERNEL", "FLAG_PRECISE_STATE", "FLAG_NO_CHANNEL_SPLIT",
+           "quamba_strerror", "FLAG_GENERIC_KERNEL", "FLAG_PRECISE_STATE", "FLAG_NO_CHANNEL_SPLIT", "FLAG_NO_DECAY_SKIP",
            "EXPORTED_SYMBOLS"]

@@ -13,7 +13,8 @@ int check_shape(const quamba_ssd_shape_t *s, bool prefill)
         s->n_head_clusters <= 0 || s->n_chan_clusters <= 0)
         return QUAMBA_ESHAPE;
     if (s->nheads % s->ngroups) return QUAMBA_ESHAPE;
-    if (s->flags & ~(QUAMBA_FLAG_GENERIC_KERNEL | QUAMBA_FLAG_PRECISE_STATE | QUAMBA_FLAG_NO_CHANNEL_SPLIT))
+    if (s->flags & ~(QUAMBA_FLAG_GENERIC_KERNEL | QUAMBA_FLAG_PRECISE_STATE | QUAMBA_FLAG_NO_CHANNEL_SPLIT |
+                     QUAMBA_FLAG_NO_DECAY_SKIP))
         return QUAMBA_EINVAL;
     if ((int64_t)s->batch * s->nheads > 0x7fffffffLL) return QUAMBA_ESHAPE;
     if (prefill) {

@@ -64,6 +64,9 @@ constexpr float kNarrow = 1.0f / 128.0f;  // applied to G and H before narrowing
 // is far from the subnormals), and the C operand of the carried-state product carries kAcc.
 constexpr float kXs = 1.0f / 16.0f;
 constexpr float kAcc = 1.0f / 64.0f;
+// A product whose operands are separated by a decay factor below 2^-kDead (prefix sums are in log2 units) is left out
+// unless the caller asks for it: it is below 2.4e-10 of the term's own undecayed size.
+constexpr float kDead = 32.0f;
 
 // LDS map (bytes) for PT 32-channel tiles per workgroup.  Row pitches: with 4-byte banks, the 8 token rows x 16 bytes
 // a group of 16 lanes fetches from Bq fall into distinct banks (pitch of 36 banks), and so do the 4 token rows x 32
@@ -289,6 +292,8 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
         if (GATED && tid < 256) s_silu[tid] = silu_of_code(a.z_scale, (int8_t)tid);
     };
     const int nchunks = (L + kQ - 1) / kQ;
+    // decay below which a 32-token block's product is left out; +inf keeps everything
+    const float dead = (a.s.flags & QUAMBA_FLAG_NO_DECAY_SKIP) ? __builtin_inff() : kDead;
     constexpr float kStScale = kNarrow;
     const uint32_t x_row = (uint32_t)H * kP, b_row = (uint32_t)G * kN, dt_row = (uint32_t)H * 4u;
     typedef uint32_t xvec __attribute__((ext_vector_type(PT)));
@@ -359,8 +364,15 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                         gi = __builtin_amdgcn_mfma_i32_32x32x32_i8(bq[kk], ct[kk], gi, 0, 0, 0);
                     return gi;
                 };
+                // Prefix sums never rise (dt >= 0, A <= 0), so the blocks whose decay towards this block has died are
+                // the first ones: sb0 is the first block still alive (tb itself if none is), and the carried state is
+                // dead when the prefix sum in front of the block is.  Wave-uniform.
+                const float r_tb = tb > 0 ? s_cum[tb * kBlk - 1] : 0.0f;
+                int sb0 = 0;
+                while (sb0 < tb && __builtin_amdgcn_readfirstlane(r_tb - s_cum[sb0 * kBlk + kBlk - 1] < -dead)) ++sb0;
+                const bool carry_alive = !__builtin_amdgcn_readfirstlane(r_tb < -dead);
                 i32x4 bq[4];
-                load_bq(0, bq);
+                load_bq(sb0, bq);
                 i32x16 gi = gemm_g(bq);
 
                 // carried-state term: Y^T[p,t] = sum_n H[p,n] (exp(cum_t) Cq[t,n])
@@ -373,6 +385,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 const _Float16 e_t = (_Float16)(exp2_fast(cum_t) * kAcc);
 #pragma unroll
                 for (int k2 = 0; k2 < 4; ++k2) {  // batches of two k-steps: all LDS reads of a batch are issued first
+                    if (!carry_alive) break;
                     f16x8 hf[2][PT];
 #pragma unroll
                     for (int kk = 0; kk < 2; ++kk)
@@ -396,7 +409,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
 
                 // intra-chunk term, block pairs (sb <= tb); the G^T tile of the next pair is issued before this one is
                 // scaled and narrowed so that the matrix core and the vector ALU overlap inside the wave
-                for (int sb = 0; sb < tb; ++sb) {  // strictly lower block pairs
+                for (int sb = sb0; sb < tb; ++sb) {  // strictly lower block pairs that are alive
                     load_bq(sb + 1, bq);
                     f16x8 xa[2][PT];
 #pragma unroll
@@ -775,6 +788,8 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                     for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
+                    // what this block adds decays by exp2(cum_last - m) before the chunk ends: dead blocks only decay
+                    if (__builtin_amdgcn_readfirstlane(s_cum[kQ - 1] - m < -dead)) continue;
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks) {
                         const int row = sb * kBlk + 16 * ks;
@@ -807,6 +822,8 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                 // blocks past the end hold zero weights (dt = 0): they add nothing
                 for (int sb = 0; sb < kNBlk; ++sb) {
+                    // the block's largest weight is that of its last token, exp2(cum_last - m_sb) dt
+                    if (__builtin_amdgcn_readfirstlane(s_cum[kQ - 1] - s_cum[sb * kBlk + kBlk - 1] < -dead)) continue;
                     u32x2 bw[2];
                     f16x8 xb[2][PT], wv[2];
 #pragma unroll

@@ -221,6 +221,36 @@ def test_extreme_decay_takes_the_per_element_diagonal(gpu_lib):
         check(yg, hg, yref, href if want_state else None, f"extreme decay, state={want_state}, flags={flags}")
 
 
+NO_DECAY_SKIP = 0x8
+
+
+@pytest.mark.parametrize("want_state", [True, False])
+def test_blocks_with_dead_decay_are_left_out_without_a_trace(gpu_lib, want_state):
+    """By default 32-token blocks whose decay factor is below 2^-32 are not computed.  Heads range from no decay to
+    a decay that kills the carried state within a block (dt scaled per head), so every skip (carried state, far score
+    blocks, state blocks) is taken on some heads and none on others; the result must meet the oracle like the full
+    computation (QUAMBA_FLAG_NO_DECAY_SKIP) and agree with it up to a few flipped roundings."""
+    s = W.CONFIGS["m2_130m"].with_(batch=2, seqlen=700)
+    sc, prob, _ = make_problem(s, 14, calib_tokens=256)
+    p1 = dict(prob)
+    dt = prob["dt"].copy()
+    dt *= np.geomspace(0.05, 8.0, s.nheads).astype(np.float32)[None, None, :]
+    p1["dt"] = dt
+    per_block = -(dt * prob["A"][None, None, :]).astype(np.float64)[:, :672].reshape(2, 21, 32, s.nheads).sum(axis=2) * 1.4426950408889634
+    assert per_block.min() < 1.0 and per_block.max() > 64.0     # log2 units: both ends are there
+    init = (0.05 * np.random.default_rng(14).standard_normal((2, s.nheads, s.headdim, s.d_state))).astype(np.float32)
+    yref, href, _ = oracle.ref_prefill(sc, p1["x"], p1["B"], p1["C"], p1["dt"], p1["A"], p1["D"],
+                                       init_state=init.astype(np.float64), want_state=want_state)
+    y0, h0 = run_prefill(gpu_lib, s, sc, p1, flags=0, init_state=init, want_state=want_state)
+    y1, h1 = run_prefill(gpu_lib, s, sc, p1, flags=NO_DECAY_SKIP, init_state=init, want_state=want_state)
+    check(y0, h0, yref, href if want_state else None, "decay skip on")
+    check(y1, h1, yref, href if want_state else None, "decay skip off")
+    # what is left out is below 2^-32 of a term: it can flip the fp16 rounding of an output that sat on a tie, no more
+    assert (y0 != y1).sum() <= 16 and np.abs(y0 - y1).max() <= 2.0 ** -10 * np.abs(yref).max()
+    if want_state:
+        assert np.abs(h0 - h1).max() <= 1e-6 * np.abs(href).max()
+
+
 def test_precise_flag_without_final_state(gpu_lib):
     """QUAMBA_FLAG_PRECISE_STATE selects the two-term state path even when no final state is returned."""
     s = W.CONFIGS["m2_130m"].with_(seqlen=700)
