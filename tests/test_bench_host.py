@@ -1,0 +1,36 @@
+"""Host-side logic of bench.py (no GPU): the algorithmic work it prices, and that it refuses more than one GPU."""
+import os
+import subprocess
+import sys
+
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+import bench  # noqa: E402
+
+
+def test_algorithmic_work_of_the_8b_shape():
+    """Per token of the Mamba2-8B-shaped layer (H 128, P 64, N 128, G 8, priced chunk 256): the causal half of the
+    score products, the carried-state and state-update products, and the bytes of x, B, C, dt and y."""
+    s = W.CONFIGS["m2_8b_b4"]
+    f16, i8, nbytes = bench.prefill_algorithmic(s)
+    assert f16 == 128 * (257 / 2 * 64 + 2 * 128 * 64) == 3149824
+    assert i8 == 8 * 257 / 2 * 128 == 131584
+    assert nbytes == 128 * 64 + 2 * 8 * 128 + 4 * 128 + 2 * 128 * 64 == 27136
+    tokens = s.batch * s.seqlen
+    assert tokens == 16384 and abs(2 * f16 * tokens - 103.2e9) < 0.1e9 and abs(nbytes * tokens - 444.6e6) < 0.1e6
+
+
+def test_decode_bytes_of_the_8b_batch():
+    s = W.CONFIGS["m2_8b_decode"] if "m2_8b_decode" in W.CONFIGS else W.CONFIGS["m2_8b_b4"].with_(batch=256, seqlen=1)
+    b, H, P, N, G = s.batch, s.nheads, s.headdim, s.d_state, s.ngroups
+    assert bench.decode_bytes(s) == 2 * 4 * b * H * P * N + b * H * P + 2 * b * G * N + 4 * b * H + 2 * b * H * P
+    assert bench.decode_bytes(s, state_bytes=1) < bench.decode_bytes(s) / 3.9
+    assert bench.HADAMARD_OPS_PER_VALUE(8192) == 13 + 3
+
+
+def test_more_than_one_gpu_is_refused():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
