@@ -180,12 +180,14 @@ __device__ __forceinline__ float dpp_f32(float v)
 // Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves only (no LDS round trips):
 // shifts by 1, 2, 4, 8 inside each row of 16 lanes (zero fill), then the last lane of row 0/2 is added to row 1/3
 // and the last lane of row 1 to rows 2 and 3.
-__device__ __forceinline__ float wave_inclusive_scan(float v)
+// `row` receives the scan inside the lane's row of 16 lanes alone (the first four steps).
+__device__ __forceinline__ float wave_inclusive_scan(float v, float &row)
 {
     v += dpp_f32<0x111, 0xf, true>(v);   // row_shr:1
     v += dpp_f32<0x112, 0xf, true>(v);   // row_shr:2
     v += dpp_f32<0x114, 0xf, true>(v);   // row_shr:4
     v += dpp_f32<0x118, 0xf, true>(v);   // row_shr:8
+    row = v;
     v += dpp_f32<0x142, 0xa, false>(v);  // row_bcast:15 into rows 1 and 3
     v += dpp_f32<0x143, 0xc, false>(v);  // row_bcast:31 into rows 2 and 3
     return v;
@@ -695,20 +697,24 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 if (2 * lane >= nv) dt0 = 0.0f;  // padded steps: dt = 0
                 if (2 * lane + 1 >= nv) dt1 = 0.0f;
                 const float a0 = dt0 * Ah, a1 = dt1 * Ah;
-                const float cum1 = wave_inclusive_scan(a0 + a1), cum0 = cum1 - a1;
-                const float m = __shfl(cum1, lane | 15, 64);
-                const float rb = __shfl(cum1, (lane & ~15) - 1, 64);
-                const float R = lane >= 16 ? rb : 0.0f;
+                // A row of 16 lanes is one 32-token block: the weights inside a block are formed from the block's own
+                // prefix sums (loc), not from differences of the chunk's, which lose ulp(|prefix sum|) when the decay
+                // is extreme.  With m and R the chunk's prefix sums at the block's end and in front of it:
+                // m - cum_s = m_loc - loc_s and R - cum_s = -loc_s.
+                float loc1;
+                const float cum1 = wave_inclusive_scan(a0 + a1, loc1), cum0 = cum1 - a1;
+                const float loc0 = loc1 - a1;
+                const float m_loc = __shfl(loc1, lane | 15, 64);
                 // weights towards the output accumulators
                 const float d0 = dt0 * (kAcc / kXs), d1 = dt1 * (kAcc / kXs);
                 // weights towards the state accumulators
                 const float q0 = dt0 * (kNarrow / kXs), q1 = dt1 * (kNarrow / kXs);
-                const float e0 = exp2_fast(m - cum0), e1 = exp2_fast(m - cum1);
+                const float e0 = exp2_fast(m_loc - loc0), e1 = exp2_fast(m_loc - loc1);
                 const float we0 = e0 * d0, we1 = e1 * d1;
                 *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
                 *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(d0 * kNarrow, d1 * kNarrow);
                 *reinterpret_cast<float2 *>(s_w2 + 2 * lane) =
-                    make_float2(exp2_fast(R - cum0) * d0 * kNarrow, exp2_fast(R - cum1) * d1 * kNarrow);
+                    make_float2(exp2_fast(-loc0) * d0 * kNarrow, exp2_fast(-loc1) * d1 * kNarrow);
                 *reinterpret_cast<f16x2 *>(s_we + 2 * lane) = (f16x2){(_Float16)we0, (_Float16)we1};
                 if (!PRECISE) {
                     const float cum_last =
