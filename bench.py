@@ -35,9 +35,9 @@ MFMA_I8_PEAK_TOPS = 5000.0     # dense int8
 # 256 MiB device copy in the same run: factors 1.9998 and 1.0000); profiles/hbm_traffic_prefill_m2_8b_b4_and_decode_m2_8b.txt
 # and profiles/hbm_traffic_hadamard_conv1d_m2_8b_b4_and_mamba1_2p8b.txt.
 # None for workloads that were not profiled.
-MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 506.0e6, "m2_8b_decode": 2162.3e6, "m2_8b_decode_q8": 550.9e6,
+MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 505.0e6, "m2_8b_decode": 2162.3e6, "m2_8b_decode_q8": 550.9e6,
                           "m2_8b_b4_hadamard": 402.7e6, "m2_8b_b4_conv1d": 352.1e6,
-                          "mamba1_2p8b_scan": 599.1e6, "mamba1_2p8b_decode": 178.8e6}
+                          "mamba1_2p8b_scan": 599.0e6, "mamba1_2p8b_decode": 178.8e6}
 
 
 def prefill_algorithmic(s: W.LayerShape):
