@@ -25,6 +25,11 @@
 // so that Bq wq_s is exact in fp16 (7 + 4 bits); the update takes two products, xq^T (wq_s Bq) and xq^T (d_s wq_s Bq),
 // the first exact, the second (|d_s| <= 1/16) rounded at 2^-16 of the total.
 //
+// The token weights inside a 32-token block come from the block's own prefix sums (no cancellation against the
+// chunk's when the decay is extreme); a block pair, a carried-state product or a block's share of the chunk state
+// whose decay factor is below 2^-32 is left out unless QUAMBA_FLAG_NO_DECAY_SKIP is set.  The chunk's closing barrier
+// sits in front of the output epilogue, which reads registers and constant tables only.
+//
 // which is Eq. 2 with A-dot = exp(dt A), B-dot = dt B (Section 3.2) regrouped; the quantization scales of
 // Section 4.1 enter only in the epilogue because x enters linearly and channel-wise and B, C have one scale per
 // state group.  The result does not depend on the chunk length, so the caller's `chunk` is not used here.
