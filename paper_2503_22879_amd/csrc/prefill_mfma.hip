@@ -30,7 +30,7 @@
 // whose decay factor is below 2^-32 is left out unless QUAMBA_FLAG_NO_DECAY_SKIP is set.  The chunk's closing barrier
 // sits in front of the output epilogue, which reads registers and constant tables only.
 //
-// which is Eq. 2 with A-dot = exp(dt A), B-dot = dt B (Section 3.2) regrouped; the quantization scales of
+// All of this is Eq. 2 with A-dot = exp(dt A), B-dot = dt B (Section 3.2) regrouped; the quantization scales of
 // Section 4.1 enter only in the epilogue because x enters linearly and channel-wise and B, C have one scale per
 // state group.  The result does not depend on the chunk length, so the caller's `chunk` is not used here.
 // int8 codes are exact in fp16; G (|G| <= 2^21) is scaled by 2^-7 in fp32 before it is narrowed.
