@@ -1,0 +1,42 @@
+/*
+ * quamba_probe — measurement helpers of the benchmark harness (NOT part of the method): small kernels that measure what
+ * this machine attains for the two resources the rooflines are priced against, and the shader clock it runs at.
+ * The benchmark reports its kernels' fractions of these measured figures beside the fractions of the published peaks.
+ * They live in the same library so that the harness needs no second build product; nothing in the scan calls them.
+ *
+ * Conventions as in quamba_ssd.h: plain pointers and sizes, work is only ENQUEUED on the caller's stream (a
+ * hipStream_t passed as void*), nothing is allocated, nothing synchronises; returns QUAMBA_OK or a negative status.
+ */
+#ifndef QUAMBA_PROBE_H_
+#define QUAMBA_PROBE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Register-resident matrix-core loop: every wave of the launch issues `iters` rounds of 4 independent
+ * v_mfma_f32_32x32x16_f16 (kind 0) or v_mfma_i32_32x32x32_i8 (kind 1) on operands that never leave its registers
+ * (no memory traffic inside the loop), so the elapsed time of the launch gives the matrix-core rate the machine
+ * sustains.  *ops_out (host) receives the number of multiply-add operations x 2 the launch performs
+ * (32*32*16*2 per fp16 instruction, 32*32*32*2 per int8 instruction).  sink (device, >= 4 bytes) receives one word so
+ * that the loop cannot be removed.  Errors: QUAMBA_ENULL, QUAMBA_EINVAL (kind, iters <= 0), QUAMBA_EHIP. */
+int quamba_probe_mfma(int kind, int iters, double *ops_out, uint32_t *sink, void *stream);
+
+/* In-place streaming pass over buf (device, n_bytes a multiple of 16): every 16-byte piece is read, changed and
+ * written back once (non-temporal), the access pattern of the decode state update without its arithmetic.  The launch
+ * moves 2 * n_bytes.  Errors: QUAMBA_ENULL, QUAMBA_EINVAL (n_bytes == 0 or not a multiple of 16), QUAMBA_EHIP. */
+int quamba_probe_stream_rmw(void *buf, size_t n_bytes, void *stream);
+
+/* Shader clock: one wave reads the shader-clock counter and the constant 100 MHz counter, spins for about
+ * spin_iters dependent vector operations, reads both again and writes the two differences to out[0] (shader clocks)
+ * and out[1] (ticks of 10 ns) (device, 16 bytes).  Enqueued between launches of a kernel it shows the clock the
+ * power management holds the chip at while that kernel runs back to back.  Errors: QUAMBA_ENULL, QUAMBA_EINVAL, QUAMBA_EHIP. */
+int quamba_probe_clock(int64_t *out, int spin_iters, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUAMBA_PROBE_H_ */

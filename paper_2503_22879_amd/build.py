@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libquamba_ssd.so")
-SOURCES = ["api.hip", "conv1d.hip", "decode.hip", "decode_q8.hip", "hadamard.hip", "mamba1.hip", "prefill_generic.hip", "prefill_mfma.hip", "offline.cpp"]
+SOURCES = ["api.hip", "probe.hip", "conv1d.hip", "decode.hip", "decode_q8.hip", "hadamard.hip", "mamba1.hip", "prefill_generic.hip", "prefill_mfma.hip", "offline.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops is switched off: some packed fp32 forms have given wrong results on the test machines.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -1,0 +1,131 @@
+// Measurement helpers of the benchmark harness (not part of the method): what this machine attains for the matrix
+// cores and for an in-place HBM stream, and the shader clock it runs at.  See include/quamba_probe.h.
+#include <hip/hip_runtime.h>
+
+#include "quamba_probe.h"
+#include "quamba_ssd.h"
+
+namespace {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kProbeThreads = 256;     // 4 waves per workgroup
+constexpr int kProbeBlocksPerCu = 4;   // 4 waves per SIMD
+constexpr int kChains = 4;             // independent accumulators per wave
+
+template <int KIND>
+__global__ __launch_bounds__(kProbeThreads) void mfma_probe_kernel(int iters, uint32_t *sink)
+{
+    const int lane = threadIdx.x & 63;
+    uint32_t keep = 0;
+    if (KIND == 0) {
+        f16x8 a, b;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            a[i] = (_Float16)(0.001f * (float)(lane + i));
+            b[i] = (_Float16)(0.002f * (float)(lane - i));
+        }
+        f32x16 acc[kChains];
+#pragma unroll
+        for (int c = 0; c < kChains; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[c][r] = 0.0f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int c = 0; c < kChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[c], 0, 0, 0);
+        }
+#pragma unroll
+        for (int c = 0; c < kChains; ++c) keep += __builtin_bit_cast(uint32_t, acc[c][c]);
+    } else {
+        i32x4 a, b;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[i] = 0x01020304 * (lane + i);
+            b[i] = 0x04030201 * (lane - i);
+        }
+        i32x16 acc[kChains];
+#pragma unroll
+        for (int c = 0; c < kChains; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[c][r] = 0;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int c = 0; c < kChains; ++c) acc[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[c], 0, 0, 0);
+        }
+#pragma unroll
+        for (int c = 0; c < kChains; ++c) keep += (uint32_t)acc[c][c];
+    }
+    if (keep == 0x9e3779b9u) sink[0] = keep;  // practically never: keeps the loop alive
+}
+
+__global__ __launch_bounds__(256) void stream_rmw_kernel(u32x4 *buf, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        u32x4 v = __builtin_nontemporal_load(buf + i);
+        v[0] += 1u;
+        __builtin_nontemporal_store(v, buf + i);
+    }
+}
+
+__global__ __launch_bounds__(64) void clock_probe_kernel(int64_t *out, int spin_iters)
+{
+    const long long c0 = __builtin_amdgcn_s_memtime();
+    const long long r0 = __builtin_amdgcn_s_memrealtime();
+    float v = (float)threadIdx.x;
+    for (int i = 0; i < spin_iters; ++i) v = __builtin_fmaf(v, 1.0000001f, 1.0e-7f);
+    asm volatile("" : "+v"(v));
+    const long long c1 = __builtin_amdgcn_s_memtime();
+    const long long r1 = __builtin_amdgcn_s_memrealtime();
+    if (threadIdx.x == 0) {
+        out[0] = c1 - c0;
+        out[1] = r1 - r0;
+    }
+    if (v == 12345.678f) out[0] = 0;
+}
+
+int device_cus()
+{
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+    return n;
+}
+
+}  // namespace
+
+extern "C" int quamba_probe_mfma(int kind, int iters, double *ops_out, uint32_t *sink, void *stream)
+{
+    if (!ops_out || !sink) return QUAMBA_ENULL;
+    if ((kind != 0 && kind != 1) || iters <= 0) return QUAMBA_EINVAL;
+    const int blocks = device_cus() * kProbeBlocksPerCu;
+    const double per_inst = kind == 0 ? 32.0 * 32.0 * 16.0 * 2.0 : 32.0 * 32.0 * 32.0 * 2.0;
+    *ops_out = per_inst * kChains * (double)iters * (kProbeThreads / 64) * blocks;
+    if (kind == 0)
+        hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(blocks), dim3(kProbeThreads), 0, (hipStream_t)stream, iters, sink);
+    else
+        hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(blocks), dim3(kProbeThreads), 0, (hipStream_t)stream, iters, sink);
+    return hipGetLastError() == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
+extern "C" int quamba_probe_stream_rmw(void *buf, size_t n_bytes, void *stream)
+{
+    if (!buf) return QUAMBA_ENULL;
+    if (n_bytes == 0 || n_bytes % 16) return QUAMBA_EINVAL;
+    const int blocks = device_cus() * 8;
+    hipLaunchKernelGGL(stream_rmw_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, static_cast<u32x4 *>(buf),
+                       n_bytes / 16);
+    return hipGetLastError() == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
+extern "C" int quamba_probe_clock(int64_t *out, int spin_iters, void *stream)
+{
+    if (!out) return QUAMBA_ENULL;
+    if (spin_iters <= 0) return QUAMBA_EINVAL;
+    hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, out, spin_iters);
+    return hipGetLastError() == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}

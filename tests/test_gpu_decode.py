@@ -61,9 +61,9 @@ def test_decode_other_shapes(gpu_lib, P, N, H, G):
     _run_steps(gpu_lib, s, steps=3, seed=6, batch=2)
 
 
-def test_decode_full_batch_sampled(gpu_lib):
-    """configs[4] at full size (batch 256, 1 GiB state), 32 steps, checked on 6 sampled sequences every step:
-    sequences are independent, so the oracle runs the sampled ones alone."""
+def test_decode_full_batch(gpu_lib):
+    """configs[4] at full size (batch 256, 1 GiB state), 32 steps: y of every sequence against the fp64 oracle at every
+    step, the whole state at the end (the oracle's fp64 state is 2 GiB of host memory)."""
     import torch
     q = gpu_lib
     s = W.CONFIGS["m2_8b_decode"]
@@ -73,19 +73,24 @@ def test_decode_full_batch_sampled(gpu_lib):
     A = torch.from_numpy(prob["A"]).cuda(); D = torch.from_numpy(prob["D"]).cuda()
     gen = torch.Generator(device="cuda"); gen.manual_seed(1234)
     st = torch.randn((s.batch, s.nheads, s.headdim, s.d_state), device="cuda", generator=gen) * 0.1
-    sample = [0, 1, 77, 128, 254, 255]
-    st64 = st[sample].cpu().numpy().astype(np.float64)
+    st64 = st.cpu().numpy().astype(np.float64)
     y = torch.empty((s.batch, s.nheads, s.headdim), dtype=torch.float16, device="cuda")
+    worst = 0.0
     for k in range(s.decode_steps):
         inp = make_decode_inputs(s, sc, r, 4, k)
         t = {n: torch.from_numpy(v).cuda() for n, v in inp.items()}
         q.quamba_ssd_decode_step(shape, dsc, t["x"], t["B"], t["C"], t["dt"], A, D, st, y)
-        yref = oracle.ref_decode_step(sc, inp["x"][sample], inp["B"][sample], inp["C"][sample], inp["dt"][sample],
-                                      prob["A"], prob["D"], st64)
-        yg = y[sample].cpu().numpy().astype(np.float64)
-        assert np.abs(yg - yref).max() <= Y_TOL * np.abs(yref).max(), f"step {k}"
-    hg = st[sample].cpu().numpy().astype(np.float64)
-    assert np.abs(hg - st64).max() <= H_TOL * np.abs(st64).max()
+        yref = oracle.ref_decode_step(sc, inp["x"], inp["B"], inp["C"], inp["dt"], prob["A"], prob["D"], st64)
+        yg = y.cpu().numpy().astype(np.float64)
+        ey = np.abs(yg - yref).max() / np.abs(yref).max()
+        worst = max(worst, ey)
+        assert ey <= Y_TOL, f"step {k}: y error {ey:.3e}"
+    hmax = np.abs(st64).max()
+    eh = 0.0
+    for b0 in range(0, s.batch, 32):   # in slices: the fp64 copy of the whole GPU state would be another 2 GiB
+        eh = max(eh, np.abs(st[b0:b0 + 32].cpu().numpy().astype(np.float64) - st64[b0:b0 + 32]).max() / hmax)
+    print(f"decode batch 256, 32 steps, all sequences: y err {worst:.2e}, state err {eh:.2e}")
+    assert eh <= H_TOL
     assert torch.isfinite(st).all() and torch.isfinite(y).all()
 
 

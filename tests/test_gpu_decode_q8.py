@@ -89,9 +89,9 @@ def test_q8_decode_clamps_like_the_oracle(gpu_lib):
     assert (np.abs(ref.astype(int)) == 127).mean() > 0.3
 
 
-def test_q8_decode_full_batch_sampled(gpu_lib):
-    """configs[4] at full size (batch 256, 256 MiB of codes), 8 steps, checked on 5 sampled sequences every step:
-    sequences are independent, so the oracle runs the sampled ones alone."""
+def test_q8_decode_full_batch(gpu_lib):
+    """configs[4] at full size (batch 256, 256 MiB of codes), 3 steps: the codes of every sequence bit for bit and
+    every y at every step (the numpy oracle walks the batch in slices of 32 sequences)."""
     import torch
     q = gpu_lib
     s = W.CONFIGS["m2_8b_decode"]
@@ -103,19 +103,22 @@ def test_q8_decode_full_batch_sampled(gpu_lib):
     gen = torch.Generator(device="cuda"); gen.manual_seed(4321)
     qs = torch.randint(-127, 128, (s.batch, s.nheads, s.headdim, s.d_state), device="cuda", generator=gen,
                        dtype=torch.int8)
-    sample = [0, 1, 100, 254, 255]
-    ref = qs[sample].cpu().numpy()
+    ref = qs.cpu().numpy()
     ssd = torch.from_numpy(ss).cuda()
     y = torch.empty((s.batch, s.nheads, s.headdim), dtype=torch.float16, device="cuda")
-    for k in range(8):
+    for k in range(3):
         inp = make_decode_inputs(s, sc, r, 4, k)
         t = {n: torch.from_numpy(v).cuda() for n, v in inp.items()}
         q.quamba_ssd_decode_step_q8(shape, dsc, ssd, t["x"], t["B"], t["C"], t["dt"], A, D, qs, y)
-        yref = oracle.ref_decode_step_q8(sc, ss, inp["x"][sample], inp["B"][sample], inp["C"][sample],
-                                         inp["dt"][sample], prob["A"], prob["D"], ref)
-        assert np.array_equal(qs[sample].cpu().numpy(), ref), f"step {k}"
-        yg = y[sample].cpu().numpy().astype(np.float64)
-        assert np.abs(yg - yref).max() <= Y_TOL * np.abs(yref).max(), f"step {k}"
+        got = qs.cpu().numpy()
+        yg = y.cpu().numpy().astype(np.float64)
+        for b0 in range(0, s.batch, 32):
+            sl = slice(b0, b0 + 32)
+            part = ref[sl]                       # a view: the oracle updates the reference codes in place
+            yref = oracle.ref_decode_step_q8(sc, ss, inp["x"][sl], inp["B"][sl], inp["C"][sl], inp["dt"][sl],
+                                             prob["A"], prob["D"], part)
+            assert np.array_equal(got[sl], part), f"step {k}, sequences {b0}..{b0 + 31}"
+            assert np.abs(yg[sl] - yref).max() <= Y_TOL * np.abs(yref).max(), f"step {k}, sequences {b0}..{b0 + 31}"
     assert torch.isfinite(y).all()
 
 
@@ -178,3 +181,47 @@ def test_q8_decode_is_deterministic(gpu_lib):
                                     dev["A"], dev["D"], qs, y)
         outs.append((qs.cpu(), y.cpu()))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
+@pytest.mark.parametrize("batch,steps", [(3, 4), (32, 2)])
+def test_q8_codes_against_the_fp64_step(gpu_lib, batch, steps):
+    """The kernel's codes against Eq. 2 itself, with no fp32 operation order involved: the cached state is
+    de-quantized in fp64, the pinned fp64 decode oracle takes one step, and every new code must be the Eq. 1 code of
+    that exact state: within half a quantization step of it, saturated where it leaves +-127.  The only slack is the
+    width of the kernel's own fp32 rounding around a tie (2e-3 of a step: the decision value h'/s is below 128 and
+    carries a few fp32 roundings of 6e-8 each, plus the 3e-7 of the exponential)."""
+    import torch
+    q = gpu_lib
+    s = W.CONFIGS["m2_8b_decode"]
+    sb, sc, prob, r, ss, codes, _, dev = _setup(q, s, 21, batch)
+    cells = oracle.cell_index_table(sc, s.nheads, s.headdim, s.ngroups)
+    sv = ss.astype(np.float64)[cells]                                   # [H,P,N] scale of every state element
+    qs = torch.from_numpy(codes.copy()).cuda()
+    y = torch.full((batch, s.nheads, s.headdim), float("nan"), dtype=torch.float16, device="cuda")
+    cur = codes.copy()
+    tie = 2e-3
+    near_tie = 0
+    for k in range(steps):
+        inp = make_decode_inputs(sb, sc, r, 21, k)
+        t = {n: torch.from_numpy(v).cuda() for n, v in inp.items()}
+        q.quamba_ssd_decode_step_q8(dev["shape"], dev["dsc"], dev["ss"], t["x"], t["B"], t["C"], t["dt"], dev["A"],
+                                    dev["D"], qs, y)
+        h = np.ascontiguousarray(cur.astype(np.float64) * sv[None])     # inverse of Eq. 1, exact in fp64
+        yref = oracle.ref_decode_step(sc, inp["x"], inp["B"], inp["C"], inp["dt"], prob["A"], prob["D"], h)
+        rr = h / sv[None]                                                # exact decision value
+        lo = np.clip(np.rint(rr - tie), -127, 127)
+        hi = np.clip(np.rint(rr + tie), -127, 127)
+        got = qs.cpu().numpy()
+        bad = np.argwhere((got < lo) | (got > hi))
+        assert bad.size == 0, (f"step {k}: {len(bad)} codes are not the Eq. 1 code of the fp64 state, first at "
+                               f"{bad[0]}: code {got[tuple(bad[0])]}, exact value {rr[tuple(bad[0])]}")
+        near_tie += int((lo != hi).sum())
+        inside = np.abs(rr) < 126.5
+        assert np.abs(got[inside] - rr[inside]).max() <= 0.5 + tie     # half a step inside the range
+        assert (np.abs(rr) >= 127.5).sum() == 0 or np.all(np.abs(got[np.abs(rr) >= 127.5]) == 127)
+        yg = y.cpu().numpy().astype(np.float64)
+        assert np.isfinite(yg).all()
+        assert np.abs(yg - yref).max() <= Y_TOL * np.abs(yref).max(), f"step {k}: y"
+        cur = got.copy()
+    print(f"q8 codes vs fp64 step, batch {batch}: all {cur.size * steps} codes are Eq. 1 codes of the exact state "
+          f"({near_tie} within {tie} of a tie)")
