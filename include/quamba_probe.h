@@ -17,23 +17,28 @@
 extern "C" {
 #endif
 
-/* Register-resident matrix-core loop: every wave of the launch issues `iters` rounds of 4 independent
+/* Register-resident matrix-core loop: waves_per_simd (1..8) waves on every SIMD of the device each issue `iters` rounds of 4 independent
  * v_mfma_f32_32x32x16_f16 (kind 0) or v_mfma_i32_32x32x32_i8 (kind 1) on operands that never leave its registers
  * (no memory traffic inside the loop), so the elapsed time of the launch gives the matrix-core rate the machine
- * sustains.  *ops_out (host) receives the number of multiply-add operations x 2 the launch performs
+ * sustains.  uniform_operands != 0 gives every lane the same operand values (the matrix cores then draw less power and
+ * the board stays below its cap: the figure comes out near the published peak); 0 gives every lane its own values, as
+ * a real contraction has them.  *ops_out (host) receives the number of multiply-add operations x 2 the launch performs
  * (32*32*16*2 per fp16 instruction, 32*32*32*2 per int8 instruction).  sink (device, >= 4 bytes) receives one word so
- * that the loop cannot be removed.  Errors: QUAMBA_ENULL, QUAMBA_EINVAL (kind, iters <= 0), QUAMBA_EHIP. */
-int quamba_probe_mfma(int kind, int iters, double *ops_out, uint32_t *sink, void *stream);
+ * that the loop cannot be removed.  Errors: QUAMBA_ENULL, QUAMBA_EINVAL (kind, iters <= 0, waves_per_simd), QUAMBA_EHIP. */
+int quamba_probe_mfma(int kind, int iters, int waves_per_simd, int uniform_operands, double *ops_out, uint32_t *sink,
+                      void *stream);
 
 /* In-place streaming pass over buf (device, n_bytes a multiple of 16): every 16-byte piece is read, changed and
  * written back once (non-temporal), the access pattern of the decode state update without its arithmetic.  The launch
- * moves 2 * n_bytes.  Errors: QUAMBA_ENULL, QUAMBA_EINVAL (n_bytes == 0 or not a multiple of 16), QUAMBA_EHIP. */
+ * moves 2 * n_bytes.  Errors: QUAMBA_ENULL, QUAMBA_EINVAL (n_bytes == 0, not a multiple of 16, or beyond 2^31 workgroups of 32 KiB), QUAMBA_EHIP. */
 int quamba_probe_stream_rmw(void *buf, size_t n_bytes, void *stream);
 
 /* Shader clock: one wave reads the shader-clock counter and the constant 100 MHz counter, spins for about
  * spin_iters dependent vector operations, reads both again and writes the two differences to out[0] (shader clocks)
- * and out[1] (ticks of 10 ns) (device, 16 bytes).  Enqueued between launches of a kernel it shows the clock the
- * power management holds the chip at while that kernel runs back to back.  Errors: QUAMBA_ENULL, QUAMBA_EINVAL, QUAMBA_EHIP. */
+ * and out[1] (ticks of 10 ns) (device, 16 bytes).  Enqueued on a second stream while a kernel runs back to back on
+ * the first, it takes a free wave slot when one opens and shows the clock the power management holds the chip at under
+ * that load (a probe that runs alone behind the launches reads the idle clock again within microseconds).
+ * Errors: QUAMBA_ENULL, QUAMBA_EINVAL, QUAMBA_EHIP. */
 int quamba_probe_clock(int64_t *out, int spin_iters, void *stream);
 
 #ifdef __cplusplus

@@ -22,7 +22,9 @@ EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "
                     "quamba_mamba1_decode_step", "quamba_mamba1_scan_gated", "quamba_mamba1_decode_step_gated",
                     "quamba_ssd_prefill_gated", "quamba_ssd_decode_step_gated", "quamba_ssd_decode_step_q8_gated",
                     "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x",
-                    "quamba_quantize_groups", "quamba_strerror")
+                    "quamba_quantize_groups", "quamba_strerror",
+                    # measurement helpers of the benchmark harness (include/quamba_probe.h)
+                    "quamba_probe_mfma", "quamba_probe_stream_rmw", "quamba_probe_clock")
 
 
 class QuambaError(RuntimeError):
@@ -480,3 +482,39 @@ def quamba_quantize_groups(v: np.ndarray, group_scales: np.ndarray) -> np.ndarra
     if rc != 0:
         raise QuambaError(rc, "quamba_quantize_groups")
     return out
+
+
+def quamba_probe_mfma(kind: int, iters: int, sink, stream=None, waves_per_simd: int = 2,
+                      uniform_operands: bool = False) -> float:
+    """Enqueue the register-resident matrix-core loop (kind 0: fp16, 1: int8); returns the operations of the launch."""
+    import torch
+    ops = C.c_double(0.0)
+    lib = load_library()
+    lib.quamba_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.c_void_p, C.c_void_p]
+    rc = lib.quamba_probe_mfma(int(kind), int(iters), int(waves_per_simd), int(bool(uniform_operands)), C.byref(ops),
+                               _dp(sink, torch.int32, name="sink"),
+                               _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_probe_mfma")
+    return ops.value
+
+
+def quamba_probe_stream_rmw(buf, stream=None) -> int:
+    """Enqueue one in-place read-modify-write pass over the device tensor buf; returns the bytes the launch moves."""
+    lib = load_library()
+    lib.quamba_probe_stream_rmw.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+    nbytes = buf.numel() * buf.element_size()
+    rc = lib.quamba_probe_stream_rmw(_dp(buf, buf.dtype, name="buf"), nbytes, _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_probe_stream_rmw")
+    return 2 * nbytes
+
+
+def quamba_probe_clock(out, spin_iters: int = 20000, stream=None) -> None:
+    """Enqueue the shader-clock probe; out: int64 device tensor of 2 (shader clocks, ticks of 10 ns)."""
+    import torch
+    lib = load_library()
+    lib.quamba_probe_clock.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+    rc = lib.quamba_probe_clock(_dp(out, torch.int64, (2,), "out"), int(spin_iters), _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_probe_clock")

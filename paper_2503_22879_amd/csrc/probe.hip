@@ -14,13 +14,14 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kProbeThreads = 256;     // 4 waves per workgroup
-constexpr int kProbeBlocksPerCu = 4;   // 4 waves per SIMD
 constexpr int kChains = 4;             // independent accumulators per wave
 
 template <int KIND>
-__global__ __launch_bounds__(kProbeThreads) void mfma_probe_kernel(int iters, uint32_t *sink)
+__global__ __launch_bounds__(kProbeThreads) void mfma_probe_kernel(int iters, int uniform, uint32_t *sink)
 {
-    const int lane = threadIdx.x & 63;
+    // uniform: every lane holds the same operand values (few bits toggle between lanes: the matrix cores draw less
+    // power and the board stays below its cap); otherwise the operands differ from lane to lane
+    const int lane = uniform ? 3 : (int)(threadIdx.x & 63);
     uint32_t keep = 0;
     if (KIND == 0) {
         f16x8 a, b;
@@ -62,13 +63,27 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_probe_kernel(int iters, ui
     if (keep == 0x9e3779b9u) sink[0] = keep;  // practically never: keeps the loop alive
 }
 
+// Every workgroup owns a contiguous run of 256 x kRmwPieces 16-byte pieces: all its loads are issued before the first
+// store, so that a wave keeps kRmwPieces pieces per lane in flight (the shape that streams fastest on this machine).
+constexpr int kRmwPieces = 8;
 __global__ __launch_bounds__(256) void stream_rmw_kernel(u32x4 *buf, size_t n16)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
-        u32x4 v = __builtin_nontemporal_load(buf + i);
-        v[0] += 1u;
-        __builtin_nontemporal_store(v, buf + i);
+    const size_t base = (size_t)blockIdx.x * 256 * kRmwPieces + threadIdx.x;
+    if (base - threadIdx.x + 256 * kRmwPieces <= n16) {  // a whole run (all workgroups but possibly the last)
+        u32x4 v[kRmwPieces];
+#pragma unroll
+        for (int i = 0; i < kRmwPieces; ++i) v[i] = __builtin_nontemporal_load(buf + base + (size_t)i * 256);
+#pragma unroll
+        for (int i = 0; i < kRmwPieces; ++i) {
+            v[i] += (u32x4){1u, 2u, 3u, 4u};  // every dword changes: the whole piece is read and written
+            __builtin_nontemporal_store(v[i], buf + base + (size_t)i * 256);
+        }
+    } else {
+        for (size_t j = base; j < n16; j += 256) {
+            u32x4 v = __builtin_nontemporal_load(buf + j);
+            v += (u32x4){1u, 2u, 3u, 4u};
+            __builtin_nontemporal_store(v, buf + j);
+        }
     }
 }
 
@@ -98,17 +113,20 @@ int device_cus()
 
 }  // namespace
 
-extern "C" int quamba_probe_mfma(int kind, int iters, double *ops_out, uint32_t *sink, void *stream)
+extern "C" int quamba_probe_mfma(int kind, int iters, int waves_per_simd, int uniform_operands, double *ops_out,
+                                 uint32_t *sink, void *stream)
 {
     if (!ops_out || !sink) return QUAMBA_ENULL;
-    if ((kind != 0 && kind != 1) || iters <= 0) return QUAMBA_EINVAL;
-    const int blocks = device_cus() * kProbeBlocksPerCu;
+    if ((kind != 0 && kind != 1) || iters <= 0 || waves_per_simd < 1 || waves_per_simd > 8) return QUAMBA_EINVAL;
+    const int blocks = device_cus() * waves_per_simd;  // a workgroup is 4 waves, one per SIMD of its compute unit
     const double per_inst = kind == 0 ? 32.0 * 32.0 * 16.0 * 2.0 : 32.0 * 32.0 * 32.0 * 2.0;
     *ops_out = per_inst * kChains * (double)iters * (kProbeThreads / 64) * blocks;
     if (kind == 0)
-        hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(blocks), dim3(kProbeThreads), 0, (hipStream_t)stream, iters, sink);
+        hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(blocks), dim3(kProbeThreads), 0, (hipStream_t)stream, iters,
+                           uniform_operands, sink);
     else
-        hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(blocks), dim3(kProbeThreads), 0, (hipStream_t)stream, iters, sink);
+        hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(blocks), dim3(kProbeThreads), 0, (hipStream_t)stream, iters,
+                           uniform_operands, sink);
     return hipGetLastError() == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }
 
@@ -116,9 +134,11 @@ extern "C" int quamba_probe_stream_rmw(void *buf, size_t n_bytes, void *stream)
 {
     if (!buf) return QUAMBA_ENULL;
     if (n_bytes == 0 || n_bytes % 16) return QUAMBA_EINVAL;
-    const int blocks = device_cus() * 8;
-    hipLaunchKernelGGL(stream_rmw_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, static_cast<u32x4 *>(buf),
-                       n_bytes / 16);
+    const size_t n16 = n_bytes / 16;
+    const size_t blocks = (n16 + 256 * kRmwPieces - 1) / (256 * kRmwPieces);
+    if (blocks > 0x7fffffffull) return QUAMBA_EINVAL;
+    hipLaunchKernelGGL(stream_rmw_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       static_cast<u32x4 *>(buf), n16);
     return hipGetLastError() == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }
 

@@ -12,9 +12,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "quamba_ssd.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(quamba_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in ("quamba_ssd.h", "quamba_probe.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(quamba_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported():
@@ -216,3 +219,19 @@ def test_mamba1_rejects_bad_arguments_without_a_device():
         assert gated(fn, n, _GateStruct(None, 0.0, p, 0.0, None), None) == -5
         assert gated(fn, n, _GateStruct(p, float("inf"), None, 0.0, None), p) == -5
         assert gated(fn, n, _GateStruct(p, 0.0, p, 0.1, None), None) == -5
+
+
+def test_probe_entry_points_validate_before_they_launch():
+    """The measurement helpers of the benchmark (include/quamba_probe.h) reject bad arguments on a GPU-less host."""
+    lib = q.load_library()
+    ops = C.c_double(0.0)
+    dummy = C.create_string_buffer(64)
+    p = C.addressof(dummy)
+    assert lib.quamba_probe_mfma(0, 10, 2, 0, None, C.c_void_p(p), None) == -1
+    assert lib.quamba_probe_mfma(2, 10, 2, 0, C.byref(ops), C.c_void_p(p), None) == -5
+    assert lib.quamba_probe_mfma(0, 0, 2, 0, C.byref(ops), C.c_void_p(p), None) == -5
+    assert lib.quamba_probe_mfma(0, 10, 9, 1, C.byref(ops), C.c_void_p(p), None) == -5
+    assert lib.quamba_probe_stream_rmw(None, C.c_size_t(64), None) == -1
+    assert lib.quamba_probe_stream_rmw(C.c_void_p(p), C.c_size_t(24), None) == -5
+    assert lib.quamba_probe_clock(None, 100, None) == -1
+    assert lib.quamba_probe_clock(C.c_void_p(p), 0, None) == -5

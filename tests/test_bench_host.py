@@ -22,6 +22,22 @@ def test_algorithmic_work_of_the_8b_shape():
     assert tokens == 16384 and abs(2 * f16 * tokens - 103.2e9) < 0.1e9 and abs(nbytes * tokens - 444.6e6) < 0.1e6
 
 
+def test_pricing_at_the_kernel_chunk_and_executed_work():
+    """The same formula at the kernel's 128-token chunks prices fewer intra-chunk products; what the kernel executes
+    (whole diagonal tiles, score tiles per head) is the count the committed matrix-core counters show."""
+    s = W.CONFIGS["m2_8b_b4"]
+    f16, i8, _ = bench.prefill_algorithmic(s)
+    k16, k8, _ = bench.prefill_algorithmic(s, bench.KERNEL_CHUNK)
+    assert k16 == 128 * (129 / 2 * 64 + 2 * 128 * 64) < f16 and k8 == 8 * 129 / 2 * 128 < i8
+    x16, x8 = bench.prefill_executed(s)
+    tokens = s.batch * s.seqlen
+    assert abs(2 * x16 * tokens - 9.02e10) < 0.01e10 and abs(2 * x8 * tokens - 4.29e10) < 0.01e10
+    assert bench.MAMBA1_MIN_SLOTS < bench.MAMBA1_EXECUTED_PER_ELEMENT + 3 * 1.06   # executed slots: 1.06 quarter-rate
+    assert bench.CONV_MIN_SLOTS < bench.CONV_EXECUTED_PER_ELEMENT + 3 * 2
+    for key, path in bench.TRAFFIC_SOURCE.items():
+        assert key in bench.MEASURED_TRAFFIC_BYTES and os.path.exists(os.path.join(ROOT, path))
+
+
 def test_decode_bytes_of_the_8b_batch():
     s = W.CONFIGS["m2_8b_decode"] if "m2_8b_decode" in W.CONFIGS else W.CONFIGS["m2_8b_b4"].with_(batch=256, seqlen=1)
     b, H, P, N, G = s.batch, s.nheads, s.headdim, s.d_state, s.ngroups
