@@ -106,6 +106,14 @@ size_t quamba_ssd_prefill_workspace_size(const quamba_ssd_shape_t *shape);
  * Any seqlen >= 1 is accepted; a last partial chunk is processed as if padded with dt = 0, x = 0 steps (identity
  * steps of Eq. 2) whose outputs are not written.  Errors: ENULL, ESHAPE (nheads % ngroups, non-positive sizes,
  * headdim*d_state too large for the generic kernel), EWORKSPACE, EHIP.
+ * Operand ranges of the matrix-core kernel (headdim 64, d_state 128), which narrows its operands to fp16 after fixed
+ * power-of-two scalings and does not check them (they live on the device; outside them the result becomes inf or
+ * NaN without an error; QUAMBA_FLAG_GENERIC_KERNEL computes in fp32 and has none of the three limits):
+ *   - 0 <= dt <= 16 (a softplus output far above any trained step size; the decayed scores times dt/4 must stay
+ *     below 65504) and A <= 0 (every decay exponent is formed for a non-rising prefix sum);
+ *   - every scale of `scales` finite and > 0 (an initial state is divided by s_x s_B);
+ *   - |state| / (s_x s_B) < 8e6 at every chunk boundary (the fp16 copy of the carried state): holds for full-scale
+ *     codes whenever |A_h| dt stays above about 3e-4 per token on average, and for any init_state of that size.
  */
 int quamba_ssd_prefill(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales, const int8_t *x,
                        const int8_t *B, const int8_t *C, const float *dt, const float *A, const float *D,
@@ -340,7 +348,7 @@ int quamba_gather_rows(void *dst, const void *src, const int32_t *new_to_old, in
  *   quamba_quantize_x:      x [tokens, nheads, headdim] fp32, already in reordered order -> xq int8, same shape;
  *                           scales is a struct of HOST pointers.
  *   quamba_quantize_groups: v [tokens, ngroups, d_state] fp32 -> int8 with group_scales [ngroups] (B or C).
- * Errors: ENULL, ESHAPE.
+ * Errors: ENULL, ESHAPE, EINVAL (a scale that is not finite and > 0: Eq. 1 divides by it).
  */
 int quamba_quantize_x(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *host_scales, int64_t tokens,
                       const float *x, int8_t *xq);

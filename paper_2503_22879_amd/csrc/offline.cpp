@@ -261,6 +261,8 @@ extern "C" int quamba_quantize_x(const quamba_ssd_shape_t *shape, const quamba_s
         }
     }
     const size_t row = (size_t)H * P;
+    for (size_t k = 0; k < row; ++k)
+        if (!(table[k] > 0.0f) || !std::isfinite(table[k])) return QUAMBA_EINVAL;  // Eq. 1 divides by the scale
     for (int64_t t = 0; t < tokens; ++t)
         for (size_t k = 0; k < row; ++k) xq[t * row + k] = quantize_one(x[t * row + k], table[k]);
     return QUAMBA_OK;
@@ -271,6 +273,8 @@ extern "C" int quamba_quantize_groups(int64_t tokens, int32_t ngroups, int32_t d
 {
     if (!group_scales || !v || !vq) return QUAMBA_ENULL;
     if (tokens < 0 || ngroups <= 0 || d_state <= 0) return QUAMBA_ESHAPE;
+    for (int g = 0; g < ngroups; ++g)
+        if (!(group_scales[g] > 0.0f) || !std::isfinite(group_scales[g])) return QUAMBA_EINVAL;
     for (int64_t t = 0; t < tokens; ++t)
         for (int g = 0; g < ngroups; ++g) {
             const size_t o = ((size_t)t * ngroups + g) * d_state;

@@ -303,6 +303,27 @@ def test_extreme_decay_takes_the_per_element_diagonal(gpu_lib):
         check(yg, hg, yref, href if want_state else None, f"extreme decay, state={want_state}, flags={flags}")
 
 
+def test_step_sizes_up_to_the_documented_limit(gpu_lib):
+    """The matrix-core kernel documents 0 <= dt <= 16 (the narrowed scores times dt / 4 must stay in fp16).  Step sizes
+    scaled up and capped just below the limit on every other head, B scales lowered so that y stays inside fp16: the
+    result meets the oracle like any other, with and without the final state, on both launch shapes."""
+    s = W.CONFIGS["m2_130m"].with_(seqlen=400)
+    sc, prob, _ = make_problem(s, 16, calib_tokens=256)
+    p1 = dict(prob)
+    dt = prob["dt"].copy()
+    dt[:, :, 0::2] = np.minimum(dt[:, :, 0::2] * 300.0, 15.9)
+    p1["dt"] = dt.astype(np.float32)
+    assert dt.max() > 15.8 and (dt[:, :, 0::2] > 15.0).mean() > 0.2
+    sc.B_scales = (sc.B_scales / 200.0).astype(np.float32)
+    for want_state, flags in ((True, 0), (False, 0), (False, NO_SPLIT)):
+        yref, href, _ = oracle.ref_prefill(sc, p1["x"], p1["B"], p1["C"], p1["dt"], p1["A"], p1["D"],
+                                           want_state=want_state)
+        assert np.abs(yref).max() < 6e4
+        yg, hg = run_prefill(gpu_lib, s, sc, p1, flags=flags, want_state=want_state)
+        check(yg, hg, yref, href if want_state else None, f"dt up to 15.9, state={want_state}, flags={flags}",
+              cells=oracle.cell_index_table(sc, s.nheads, s.headdim, s.ngroups))
+
+
 NO_DECAY_SKIP = 0x8
 
 

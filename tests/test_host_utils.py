@@ -111,3 +111,21 @@ def test_state_scales_bit_exact_against_oracle_and_argument_checks():
         q.quamba_state_scales(H, P, G, m, n, N, he, np.array([4, 3] * 4, np.int32), mx)       # decreasing
     with pytest.raises(q.QuambaError):
         q.quamba_state_scales(5, P, G, m, n, N, he, ce, np.zeros((5, P, N), np.float32))      # H % G
+
+
+def test_the_host_quantizers_reject_scales_that_are_not_positive_and_finite():
+    """Eq. 1 divides by the scale: zero, negative, infinite and NaN scales are refused before anything is written."""
+    import paper_2503_22879_amd as q
+    v = np.ones((2, 3, 4), np.float32)
+    for bad in (0.0, -1.0, np.inf, np.nan):
+        gs = np.array([1.0, bad, 1.0], np.float32)
+        with pytest.raises(q.QuambaError):
+            q.quamba_quantize_groups(v, gs)
+    assert q.quamba_quantize_groups(v, np.ones(3, np.float32)).dtype == np.int8
+    shape = q.Shape(batch=1, seqlen=1, nheads=2, headdim=4, d_state=4, ngroups=1, chunk=1, n_head_clusters=1,
+                    n_chan_clusters=2, flags=0)
+    for bad in (0.0, -2.0, np.nan):
+        hs = q.HostScales(np.array([1.0, bad], np.float32), np.array([2], np.int32), np.array([2, 4], np.int32),
+                          np.ones(1, np.float32), np.ones(1, np.float32))
+        with pytest.raises(q.QuambaError):
+            q.quamba_quantize_x(shape, hs, np.ones((1, 2, 4), np.float32))
