@@ -161,7 +161,18 @@ def sample_board_power(torch, fn, key):
         if time.perf_counter() - t0 > 0.5 * POWER_SECONDS:
             vals.append(_hwmon("power1_input"))
     vals = [v for v in vals if v is not None]
-    BOARD_POWER_W[key] = {"mean": sum(vals) / len(vals), "max": max(vals)} if vals else None
+    # the same call timed at the end of these POWER_SECONDS of uninterrupted launches: the sustained figure
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(100):
+        fn()
+    ev1.record()
+    torch.cuda.synchronize()
+    BOARD_POWER_W[key] = {"mean": sum(vals) / len(vals), "max": max(vals),
+                          "sustained_ms_per_call": ev0.elapsed_time(ev1) / 100,
+                          "note": "sustained_ms_per_call: 100 calls timed after %.0f s of uninterrupted launches"
+                                  % POWER_SECONDS} if vals else None
 
 
 def time_region(torch, fn, steps, warmup, min_warm_ms=0.0, power_key=None, after=None):
@@ -447,6 +458,7 @@ def main() -> int:
                            "timed launches again (ms_per_step, value); HIP events on the launch stream; consecutive "
                            "launches rotate over the input/output sets" % SPIN_UP_MS,
         "shader_clock_mhz": pre["shader_clock_mhz"],
+        "sustained_ms_per_step": (BOARD_POWER_W.get("prefill") or {}).get("sustained_ms_per_call"),
         "prefill_decay_skip": pre.get("prefill_decay_skip"),
         "roofline": pre["roofline"], "roofline_hbm": pre["roofline_hbm"],
     }

@@ -50,10 +50,11 @@ __device__ __forceinline__ uint32_t pack4(uint32_t m0, uint32_t m1, uint32_t m2,
 // byte k of the result through the sub-dword destination select, so rounding and packing cost one instruction per code.
 __device__ __forceinline__ uint32_t codes4(float r0, float r1, float r2, float r3)
 {
-    const float c0 = __builtin_fminf(__builtin_fmaxf(r0, -127.0f), 127.0f);
-    const float c1 = __builtin_fminf(__builtin_fmaxf(r1, -127.0f), 127.0f);
-    const float c2 = __builtin_fminf(__builtin_fmaxf(r2, -127.0f), 127.0f);
-    const float c3 = __builtin_fminf(__builtin_fmaxf(r3, -127.0f), 127.0f);
+    // the median of (r, -127, 127) is r clamped to the code range, in one instruction
+    const float c0 = __builtin_amdgcn_fmed3f(r0, -127.0f, 127.0f);
+    const float c1 = __builtin_amdgcn_fmed3f(r1, -127.0f, 127.0f);
+    const float c2 = __builtin_amdgcn_fmed3f(r2, -127.0f, 127.0f);
+    const float c3 = __builtin_amdgcn_fmed3f(r3, -127.0f, 127.0f);
     const float magic = 12582912.0f;  // 1.5 * 2^23
     uint32_t out;
     asm("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD"
@@ -73,6 +74,13 @@ __device__ __forceinline__ float code_to_float(uint32_t w, int e) { return (floa
 // inv_tab[n][N] their reciprocals (correctly rounded divisions, done once per workgroup).
 // floats in front of the scale tables: xv and cl, rounded up so that the tables' rows can be read 16 bytes at a time
 __host__ __device__ inline size_t table_offset(int P) { return ((size_t)2 * P + 3) & ~(size_t)3; }
+
+// Rows of N floats that lanes read 16 bytes at a time, lane j of a row at floats 16 j ...: with 4-byte banks lanes j and
+// j + 4 would meet in the same banks, and rows of different cells start N floats apart, in the same bank again.  The
+// vector kernel therefore keeps such rows padded: 4 floats after every 64, element e at e + 4 (e / 64), rows
+// padded_row(N) apart (136 floats for N = 128: a shift of 8 banks from row to row).
+__host__ __device__ constexpr int padded_row(int N) { return N + 4 * ((N + 63) / 64); }
+__host__ __device__ constexpr int padded_pos(int e) { return e + 4 * (e >> 6); }
 
 struct Tables {
     float *xv;
@@ -122,6 +130,7 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
                                                                  int seqs_per_block)
 {
     constexpr int LPR = N / 16, RPI = 64 / LPR;
+    constexpr int NP = padded_row(N);
     extern __shared__ float lds[];
     const int P = a.s.headdim, H = a.s.nheads, G = a.s.ngroups;
     const int h = blockIdx.x, g = h / (H / G);
@@ -132,13 +141,19 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
     float *s_dt = lds + table_offset(P) + 2 * (size_t)a.s.n_chan_clusters * N;
     float *s_dA = s_dt + kMaxSeqs;
     float *s_xf = s_dA + kMaxSeqs;                     // [nb][P]  x codes as fp32
-    float *s_Bv = s_xf + (((size_t)seqs_per_block * P + 3) & ~(size_t)3);  // [nb][N]  s_B * B code (one rounding)
-    float *s_Cf = s_Bv + (size_t)seqs_per_block * N;   // [nb][N]  C codes as fp32 (s_C is applied to the sum)
-    float *s_sd = s_Cf + (size_t)seqs_per_block * N;   // [nb][n cells][N]  decay * scale: the decayed scale rows
+    // the arrays below hold padded rows (padded_row, padded_pos)
+    float *s_Bv = s_xf + (((size_t)seqs_per_block * P + 3) & ~(size_t)3);  // [nb][NP]  s_B * B code (one rounding)
+    float *s_Cf = s_Bv + (size_t)seqs_per_block * NP;  // [nb][NP]  C codes as fp32 (s_C is applied to the sum)
+    float *s_sd = s_Cf + (size_t)seqs_per_block * NP;  // [nb][n cells][NP]  decay * scale: the decayed scale rows
     const int nc = a.s.n_chan_clusters;
+    float *s_inv = s_sd + (size_t)seqs_per_block * nc * NP;  // [n cells][NP]  reciprocal scale rows
     const float sB = a.B_scales[g], sC = a.C_scales[g];
     const float Dh = a.D ? a.D[h] : 0.0f;
     const Tables t = stage_tables(a, state_scales, 0, h, lds, false);  // xv holds s_x of every row; ends in a barrier
+    for (int i = threadIdx.x; i < nc * N; i += kThreads) {
+        const int c = i / N, n = i - c * N;
+        s_inv[c * NP + padded_pos(n)] = t.inv_tab[i];
+    }
 
     // the workgroup's slices of the batch: slice s covers sequences [s seqs_per_block, (s + 1) seqs_per_block)
     const int nslices = (a.s.batch + seqs_per_block - 1) / seqs_per_block;
@@ -155,14 +170,17 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
         const size_t bh = (size_t)(b_begin + bb) * H + h, bg = (size_t)(b_begin + bb) * G + g;
         for (int p = lane; p < P; p += 64) s_xf[bb * P + p] = (float)a.x[bh * P + p];
         for (int n = lane; n < N; n += 64) {
-            s_Bv[bb * N + n] = sB * (float)a.B[bg * N + n];
-            s_Cf[bb * N + n] = (float)a.C[bg * N + n];
+            s_Bv[bb * NP + padded_pos(n)] = sB * (float)a.B[bg * N + n];
+            s_Cf[bb * NP + padded_pos(n)] = (float)a.C[bg * N + n];
         }
     }
     __syncthreads();
     for (int bb = 0; bb < nb; ++bb) {
         const float dA = s_dA[bb];
-        for (int i = threadIdx.x; i < nc * N; i += kThreads) s_sd[bb * nc * N + i] = dA * t.s_tab[i];
+        for (int i = threadIdx.x; i < nc * N; i += kThreads) {
+            const int c = i / N, n = i - c * N;
+            s_sd[(bb * nc + c) * NP + padded_pos(n)] = dA * t.s_tab[i];
+        }
     }
     __syncthreads();
 
@@ -174,8 +192,8 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
             prow[i] = FULL ? p0 + i * RPI + sub : min(p0 + i * RPI + sub, P - 1);
-            srow[i] = s_sd + t.cl[prow[i]] * N + 16 * j;  // of the slice's first sequence; the others nc * N apart
-            irow[i] = t.inv_tab + t.cl[prow[i]] * N + 16 * j;
+            srow[i] = s_sd + t.cl[prow[i]] * NP + padded_pos(16 * j);  // of the slice's first sequence; the others nc * NP apart
+            irow[i] = s_inv + t.cl[prow[i]] * NP + padded_pos(16 * j);
             sx[i] = t.xv[prow[i]];
         }
         auto load = [&](int b, u32x4(&w)[ROWS]) {
@@ -209,11 +227,11 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
             }
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4 B4 = *reinterpret_cast<const f32x4 *>(s_Bv + bb * N + 16 * j + 4 * q4);
-                const f32x4 C4 = *reinterpret_cast<const f32x4 *>(s_Cf + bb * N + 16 * j + 4 * q4);
+                const f32x4 B4 = *reinterpret_cast<const f32x4 *>(s_Bv + bb * NP + padded_pos(16 * j) + 4 * q4);
+                const f32x4 C4 = *reinterpret_cast<const f32x4 *>(s_Cf + bb * NP + padded_pos(16 * j) + 4 * q4);
 #pragma unroll
                 for (int i = 0; i < ROWS; ++i) {
-                    const f32x4 s4 = *reinterpret_cast<const f32x4 *>(srow[i] + (size_t)bb * nc * N + 4 * q4);
+                    const f32x4 s4 = *reinterpret_cast<const f32x4 *>(srow[i] + (size_t)bb * nc * NP + 4 * q4);
                     const f32x4 i4 = *reinterpret_cast<const f32x4 *>(irow[i] + 4 * q4);
                     float r[4];
 #pragma unroll
@@ -383,8 +401,9 @@ namespace {
 size_t vec_lds_bytes(const quamba_ssd_shape_t &s, int seqs)
 {
     const size_t xf = ((size_t)seqs * s.headdim + 3) & ~(size_t)3;
+    const size_t np = (size_t)padded_row(s.d_state);
     return decode_q8_lds_bytes(s) +
-           sizeof(float) * (2 * kMaxSeqs + xf + (2 + (size_t)s.n_chan_clusters) * seqs * s.d_state);
+           sizeof(float) * (2 * kMaxSeqs + xf + (2 + (size_t)s.n_chan_clusters) * seqs * np + s.n_chan_clusters * np);
 }
 
 }  // namespace
