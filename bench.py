@@ -313,15 +313,31 @@ def prefill_leg(q, torch, dev, s, seed, steps, warmup, args, headline):
     def prefill_skip():
         launch(shape)
 
+    side_legs = headline and not args.lean
     cold_ms = None
-    if headline:   # the timed region without the spin-up: W warm-up launches, then K timed ones, right after the host-side preparation
+    if side_legs:   # the timed region without the spin-up: W warm-up launches, then K timed ones, right after the host-side preparation
         cold_ms, _ = time_region(torch, prefill, steps, warmup)
     ms, wall_ms = time_region(torch, prefill, steps, warmup, min_warm_ms=SPIN_UP_MS,
                               power_key="prefill" if headline else None)
-    clock_mhz = shader_clock_under_load(q, torch, dev, prefill) if headline else None
+    clock_mhz = shader_clock_under_load(q, torch, dev, prefill) if side_legs else None
     ms_skip = None
-    if headline and not args.no_decay_skip_leg:
+    if side_legs and not args.no_decay_skip_leg:
         ms_skip, _ = time_region(torch, prefill_skip, steps, warmup, min_warm_ms=SPIN_UP_MS)
+    # The same launches with every x, B and C code zero: the instruction stream, the addresses and the bytes moved are
+    # the same (nothing in the kernel branches on a code), only the operand bits stop toggling.  A duration that follows
+    # the operand values shows a kernel held by the board's power limit, not by an execution unit.
+    zero_codes = None
+    if side_legs and gate is None:
+        kept = [{k: t[k] for k in ("x", "B", "C")} for t in sets]
+        for t in sets:
+            for k in ("x", "B", "C"):
+                t[k] = torch.zeros_like(t[k])
+        ms_zero, _ = time_region(torch, prefill, steps, warmup, min_warm_ms=SPIN_UP_MS)
+        zero_codes = {"ms_per_step": ms_zero, "shader_clock_mhz": shader_clock_under_load(q, torch, dev, prefill),
+                      "note": "same launches on all-zero x, B and C codes: identical instructions, addresses and "
+                              "traffic; the duration differs through the power the operands' bit changes draw"}
+        for t, k3 in zip(sets, kept):
+            t.update(k3)
     tokens = s.batch * s.seqlen
     f16_macs, i8_macs, bytes_tok = prefill_algorithmic(s)
     k16, k8, _ = prefill_algorithmic(s, KERNEL_CHUNK)
@@ -357,6 +373,8 @@ def prefill_leg(q, torch, dev, s, seed, steps, warmup, args, headline):
     }
     if cold_ms is not None:
         res["cold_ms_per_step"] = cold_ms
+    if zero_codes is not None:
+        res["zero_codes"] = zero_codes
     if headline:
         res["prefill_decay_skip"] = None if ms_skip is None else {
             "ms_per_step": ms_skip, "value": tokens / (ms_skip * 1e-3), "unit": "tokens/s",
@@ -383,6 +401,9 @@ def main() -> int:
                     help="report the board power (hwmon sensor, 2 more seconds of launches) of every leg, not only of "
                          "the prefill")
     ap.add_argument("--no-power", action="store_true", help="do not sample the board power at all")
+    ap.add_argument("--lean", action="store_true",
+                    help="time the headline prefill alone: no cold figure, no default-skip leg, no zero-code leg, no "
+                         "clock probe (for runs under a profiler, whose kernel statistics then cover these launches only)")
     ap.add_argument("--no-attainable", action="store_true", help="skip the probe kernels that measure attainable peaks")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the legs of the other prefill configurations (8B at batch 1, 2.7B, 130M)")
@@ -460,6 +481,7 @@ def main() -> int:
         "shader_clock_mhz": pre["shader_clock_mhz"],
         "sustained_ms_per_step": (BOARD_POWER_W.get("prefill") or {}).get("sustained_ms_per_call"),
         "prefill_decay_skip": pre.get("prefill_decay_skip"),
+        "prefill_zero_codes": pre.get("zero_codes"),
         "roofline": pre["roofline"], "roofline_hbm": pre["roofline_hbm"],
     }
     if attainable is not None:

@@ -123,11 +123,13 @@ __device__ __forceinline__ Tables stage_tables(const SsdArgs &a, const float *st
 // resident at once (no tail of partly filled rounds).  Everything but the codes goes through LDS: once per workgroup
 // the head's scale rows, their reciprocals and the cell of every row; once per slice dt, the decay, the decayed scale
 // rows, x as fp32 codes, s_B B and C as fp32 codes.  The loop over the sequences of a slice then issues nothing but
-// the 16-byte code loads (two sequences ahead) and stores, so that the dependent look-ups, divisions and conversions
-// are paid once per workgroup or slice instead of once per 8 KB of state.
+// the 16-byte code loads (one sequence ahead) and stores, so that the dependent look-ups, divisions and conversions
+// are paid once per workgroup or slice instead of once per 8 KB of state.  Four workgroups of four waves share a
+// compute unit (one wave of each per SIMD), which needs at most 128 vector registers per lane: hence the second
+// launch bound.
 template <int N, int ROWS, bool FULL>
-__global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, const float *state_scales, int8_t *state_q,
-                                                                 int seqs_per_block)
+__global__ __launch_bounds__(kThreads, 4) void decode_q8_vec_kernel(SsdArgs a, const float *state_scales,
+                                                                    int8_t *state_q, int seqs_per_block)
 {
     constexpr int LPR = N / 16, RPI = 64 / LPR;
     constexpr int NP = padded_row(N);
@@ -149,6 +151,92 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
     float *s_inv = s_sd + (size_t)seqs_per_block * nc * NP;  // [n cells][NP]  reciprocal scale rows
     const float sB = a.B_scales[g], sC = a.C_scales[g];
     const float Dh = a.D ? a.D[h] : 0.0f;
+    // The side inputs of a slice (step sizes, x, B and C codes) are requested one slice ahead and wait in registers
+    // while the slice in front of them is computed: under full streaming load a trip to memory takes about as long as
+    // two sequences' worth of the main loop, and a slice would otherwise start with such a trip.  Thread t holds 4
+    // states of B and C of the slice's sequence t / (N/4) (the host keeps seqs_per_block within kThreads / (N/4)), the
+    // step size of sequence t, and, when headdim is a multiple of 4, dword t of the slice's x codes.
+    constexpr int kQuads = N / 4;
+    static_assert(kThreads % kQuads == 0, "whole rows of B per round of threads");
+    struct Side {
+        float dt;
+        uint32_t bw, cw, xw[1];
+    };
+    const bool x_quads = (P & 3) == 0;
+    auto request_side = [&](int slice, Side &sd) {
+        // a thread index the compiler cannot carry across slices: what is derived from it is recomputed here instead
+        // of occupying registers throughout the main loop
+        int tix = (int)threadIdx.x;
+        asm volatile("" : "+v"(tix));
+        const int side_bb = tix / kQuads, side_q = tix % kQuads;
+        const int bb0 = slice * seqs_per_block, nbs = min(seqs_per_block, a.s.batch - bb0);
+        if (tix < nbs) sd.dt = a.dt[(size_t)(bb0 + tix) * H + h];
+        if (side_bb < nbs) {
+            const size_t bg = (size_t)(bb0 + side_bb) * G + g;
+            sd.bw = *reinterpret_cast<const uint32_t *>(a.B + bg * N + 4 * side_q);
+            sd.cw = *reinterpret_cast<const uint32_t *>(a.C + bg * N + 4 * side_q);
+        }
+        if (x_quads) {
+            const int xq = P >> 2;
+#pragma unroll
+            for (int k = 0; k < 1; ++k) {
+                const int e = tix + k * kThreads;
+                if (e < nbs * xq) {
+                    const int bb = e / xq, pq = e - bb * xq;
+                    sd.xw[k] = *reinterpret_cast<const uint32_t *>(a.x + ((size_t)(bb0 + bb) * H + h) * P + 4 * pq);
+                }
+            }
+        }
+    };
+    auto stage_side = [&](int b_begin, int nb, const Side &sd) {
+        // a thread index the compiler cannot carry across slices: what is derived from it is recomputed here instead
+        // of occupying registers throughout the main loop
+        int tix = (int)threadIdx.x;
+        asm volatile("" : "+v"(tix));
+        const int side_bb = tix / kQuads, side_q = tix % kQuads;
+        if (tix < nb) {  // one decay per thread: the exponential is a long dependent chain
+            s_dt[tix] = sd.dt;
+            s_dA[tix] = exp_steps(sd.dt * a.A[h]);
+        }
+        if (side_bb < nb) {
+            f32x4 bv, cv;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                bv[k] = sB * code_to_float(sd.bw, k);
+                cv[k] = code_to_float(sd.cw, k);
+            }
+            *reinterpret_cast<f32x4 *>(s_Bv + side_bb * NP + padded_pos(4 * side_q)) = bv;
+            *reinterpret_cast<f32x4 *>(s_Cf + side_bb * NP + padded_pos(4 * side_q)) = cv;
+        }
+        if (x_quads) {
+            const int xq = P >> 2;
+#pragma unroll
+            for (int k = 0; k < 1; ++k) {
+                const int e = tix + k * kThreads;
+                if (e < nb * xq) {
+                    f32x4 xv4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) xv4[i] = code_to_float(sd.xw[k], i);
+                    *reinterpret_cast<f32x4 *>(s_xf + 4 * e) = xv4;
+                }
+            }
+            // what one dword per thread does not cover (headdim * sequences above 4 * kThreads) is read here
+            for (int e = tix + kThreads; e < nb * xq; e += kThreads) {
+                const int bb = e / xq, pq = e - bb * xq;
+                const uint32_t w = *reinterpret_cast<const uint32_t *>(a.x + ((size_t)(b_begin + bb) * H + h) * P + 4 * pq);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s_xf[4 * e + i] = code_to_float(w, i);
+            }
+        } else {
+            for (int e = tix; e < nb * P; e += kThreads) {
+                const int bb = e / P, p = e - bb * P;
+                s_xf[e] = (float)a.x[((size_t)(b_begin + bb) * H + h) * P + p];
+            }
+        }
+    };
+    Side side = {};
+    request_side((int)blockIdx.y, side);  // the grid has at most one row of workgroups per slice
+
     const Tables t = stage_tables(a, state_scales, 0, h, lds, false);  // xv holds s_x of every row; ends in a barrier
     for (int i = threadIdx.x; i < nc * N; i += kThreads) {
         const int c = i / N, n = i - c * N;
@@ -160,20 +248,7 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
     for (int slice = blockIdx.y; slice < nslices; slice += gridDim.y) {
     const int b_begin = slice * seqs_per_block, b_end = min(b_begin + seqs_per_block, a.s.batch);
     const int nb = b_end - b_begin;
-    if ((int)threadIdx.x < nb) {  // one decay per thread: the exponential is a long dependent chain
-        const float dt = a.dt[(size_t)(b_begin + threadIdx.x) * H + h];
-        s_dt[threadIdx.x] = dt;
-        s_dA[threadIdx.x] = exp_steps(dt * a.A[h]);
-    }
-    // one wave per sequence at a time, lanes over the elements: no integer division in these loops
-    for (int bb = wave; bb < nb; bb += kWaves) {
-        const size_t bh = (size_t)(b_begin + bb) * H + h, bg = (size_t)(b_begin + bb) * G + g;
-        for (int p = lane; p < P; p += 64) s_xf[bb * P + p] = (float)a.x[bh * P + p];
-        for (int n = lane; n < N; n += 64) {
-            s_Bv[bb * NP + padded_pos(n)] = sB * (float)a.B[bg * N + n];
-            s_Cf[bb * NP + padded_pos(n)] = (float)a.C[bg * N + n];
-        }
-    }
+    stage_side(b_begin, nb, side);
     __syncthreads();
     for (int bb = 0; bb < nb; ++bb) {
         const float dA = s_dA[bb];
@@ -183,6 +258,7 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
         }
     }
     __syncthreads();
+    if (slice + (int)gridDim.y < nslices) request_side(slice + (int)gridDim.y, side);
 
     for (int p0 = wave * RPI * ROWS; p0 < P; p0 += kWaves * RPI * ROWS) {
         // per row of this trip: its scale rows and its x scale (the same for every sequence)
@@ -202,23 +278,37 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
                 w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
                     state_q + (((size_t)b * H + h) * P + prow[i]) * N + 16 * j));
         };
-        // the codes of the next two sequences are always in flight while one is computed
-        u32x4 nxt[ROWS], nxt2[ROWS];
+        // The codes of the next sequence are requested while one is computed, and the results of a sequence (codes
+        // and outputs) are stored at the start of the next step, right behind that request: the wait for the requested
+        // codes at the top of a step then meets only loads and stores that were issued a whole step earlier.  Stored
+        // at the end of their own step, the results would be a step's worth of fresh stores in front of that wait
+        // (loads and stores complete in the order they were issued).
+        u32x4 nxt[ROWS], out[ROWS];
+        uint16_t yout[ROWS];
+        auto store_results = [&](int bb) {
+            const size_t bh = (size_t)(b_begin + bb) * H + h;
+#pragma unroll
+            for (int i = 0; i < ROWS; ++i)
+                if (FULL || p0 + i * RPI + sub < P)
+                    __builtin_nontemporal_store(out[i],
+                                                reinterpret_cast<u32x4 *>(state_q + (bh * P + prow[i]) * N + 16 * j));
+#pragma unroll
+            for (int i = 0; i < ROWS; ++i) {
+                const int p = p0 + i * RPI + sub;
+                if (j == 0 && (FULL || p < P)) a.y[bh * P + p] = yout[i];
+            }
+        };
         load(b_begin, nxt);
-        if (nb > 1) load(b_begin + 1, nxt2);
         for (int bb = 0; bb < nb; ++bb) {
             const int b = b_begin + bb;
             u32x4 cur[ROWS];
 #pragma unroll
-            for (int i = 0; i < ROWS; ++i) {
-                cur[i] = nxt[i];
-                nxt[i] = nxt2[i];
-            }
-            if (bb + 2 < nb) load(b + 2, nxt2);
+            for (int i = 0; i < ROWS; ++i) cur[i] = nxt[i];
+            if (bb + 1 < nb) load(b + 1, nxt);
+            if (bb > 0) store_results(bb - 1);
             const float dt = s_dt[bb];
             const size_t bh = (size_t)b * H + h;
             float acc[ROWS], xv[ROWS], dtx[ROWS];
-            u32x4 out[ROWS];
 #pragma unroll
             for (int i = 0; i < ROWS; ++i) {
                 xv[i] = sx[i] * s_xf[bb * P + prow[i]];
@@ -246,11 +336,6 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
                 }
             }
 #pragma unroll
-            for (int i = 0; i < ROWS; ++i)
-                if (FULL || p0 + i * RPI + sub < P)
-                    __builtin_nontemporal_store(out[i],
-                                                reinterpret_cast<u32x4 *>(state_q + (bh * P + prow[i]) * N + 16 * j));
-#pragma unroll
             for (int i = 0; i < ROWS; ++i) acc[i] = group_sum<LPR>(acc[i]);
 #pragma unroll
             for (int i = 0; i < ROWS; ++i) {
@@ -258,10 +343,11 @@ __global__ __launch_bounds__(kThreads) void decode_q8_vec_kernel(SsdArgs a, cons
                 if (j == 0 && (FULL || p < P))
                 {
                     const float gate = a.z ? silu_of_code(a.z_scale, a.z[bh * P + p]) : 1.0f;  // y * SiLU(z)
-                    a.y[bh * P + p] = f32_to_f16_bits(__builtin_fmaf(Dh, xv[i], sC * acc[i]) * gate);
+                    yout[i] = f32_to_f16_bits(__builtin_fmaf(Dh, xv[i], sC * acc[i]) * gate);
                 }
             }
         }
+        store_results(nb - 1);
     }
     __syncthreads();  // every wave is done with the slice's arrays before the next slice overwrites them
     }
@@ -366,6 +452,7 @@ int seqs_per_block(const quamba_ssd_shape_t &s)
 {
     const int64_t pairs = (int64_t)s.batch * s.nheads;
     int n = (int)std::min<int64_t>(kMaxSeqs, std::max<int64_t>(1, pairs / 4096));
+    if (s.d_state >= 4) n = std::min(n, std::max(1, kThreads / (s.d_state / 4)));  // one round of threads covers the slice's B rows
     while (n > 1 && vec_lds_bytes(s, n) > 64 * 1024) --n;
     if (vec_lds_bytes(s, n) > kLdsLimit || (s.batch + n - 1) / n > 65535) return 0;
     return n;
@@ -410,7 +497,9 @@ size_t vec_lds_bytes(const quamba_ssd_shape_t &s, int seqs)
 
 hipError_t launch_decode_q8(const SsdArgs &a, const float *state_scales, int8_t *state_q, hipStream_t stream)
 {
-    const bool al = reinterpret_cast<uintptr_t>(state_q) % 16 == 0;
+    // the vector kernel reads the codes 16 bytes at a time and x, B and C 4 bytes at a time
+    const bool al = reinterpret_cast<uintptr_t>(state_q) % 16 == 0 && reinterpret_cast<uintptr_t>(a.x) % 4 == 0 &&
+                    reinterpret_cast<uintptr_t>(a.B) % 4 == 0 && reinterpret_cast<uintptr_t>(a.C) % 4 == 0;
     const int spb = seqs_per_block(a.s);
     if (al && spb > 0) {
         switch (a.s.d_state) {

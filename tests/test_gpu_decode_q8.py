@@ -122,6 +122,62 @@ def test_q8_decode_full_batch(gpu_lib):
     assert torch.isfinite(y).all()
 
 
+def _big_batch_steps(q, s, seed, steps, misalign=False):
+    """Random codes as the cached state of a whole batch, `steps` steps, every code and every y against the oracle
+    (in slices of 32 sequences).  misalign: x, B and C start one byte past a 4-byte boundary."""
+    import torch
+    sc, prob, r = make_problem(s.with_(batch=1, seqlen=4), seed, calib_tokens=512)
+    ss, _, _ = make_state_cache(s.with_(batch=1), sc, r, seed, batch=1)
+    dsc = q.DeviceScales(host_scales(q, sc))
+    shape = to_shape(q, s)
+    A = torch.from_numpy(prob["A"]).cuda(); D = torch.from_numpy(prob["D"]).cuda()
+    gen = torch.Generator(device="cuda"); gen.manual_seed(1000 + seed)
+    qs = torch.randint(-127, 128, (s.batch, s.nheads, s.headdim, s.d_state), device="cuda", generator=gen,
+                       dtype=torch.int8)
+    ref = qs.cpu().numpy()
+    ssd = torch.from_numpy(ss).cuda()
+    y = torch.empty((s.batch, s.nheads, s.headdim), dtype=torch.float16, device="cuda")
+
+    def dev(v):
+        t = torch.from_numpy(v).cuda()
+        if not misalign or t.dtype != torch.int8:
+            return t
+        buf = torch.empty(t.numel() + 5, dtype=torch.int8, device="cuda")
+        off = 1 + (-buf.data_ptr()) % 4          # data_ptr % 4 == 1
+        view = buf[off:off + t.numel()].view(t.shape)
+        view.copy_(t)
+        assert view.data_ptr() % 4 == 1
+        return view
+
+    for k in range(steps):
+        inp = make_decode_inputs(s, sc, r, seed, k)
+        t = {n: dev(v) for n, v in inp.items()}
+        q.quamba_ssd_decode_step_q8(shape, dsc, ssd, t["x"], t["B"], t["C"], t["dt"], A, D, qs, y)
+        got = qs.cpu().numpy()
+        yg = y.cpu().numpy().astype(np.float64)
+        for b0 in range(0, s.batch, 32):
+            sl = slice(b0, b0 + 32)
+            part = ref[sl]                       # a view: the oracle updates the reference codes in place
+            yref = oracle.ref_decode_step_q8(sc, ss, inp["x"][sl], inp["B"][sl], inp["C"][sl], inp["dt"][sl],
+                                             prob["A"], prob["D"], part)
+            assert np.array_equal(got[sl], part), f"step {k}, sequences {b0}..{b0 + 31}"
+            assert np.abs(yg[sl] - yref).max() <= Y_TOL * np.abs(yref).max(), f"step {k}, sequences {b0}..{b0 + 31}"
+
+
+@pytest.mark.parametrize("batch,H,P,N,G,misalign", [
+    (250, 128, 32, 32, 4, False),    # 7 sequences per workgroup, a last slice of 5
+    (512, 128, 128, 16, 8, False),   # 16 sequences per workgroup: more x codes per slice than one dword per thread
+    (64, 128, 6, 16, 1, False),      # headdim not a multiple of 4: x byte by byte
+    (130, 64, 64, 64, 2, False),     # 2 sequences per workgroup
+    (96, 128, 64, 128, 8, True),     # x, B and C off the 4-byte grid: the any-shape kernel takes the step
+])
+def test_q8_decode_several_sequences_per_workgroup(gpu_lib, batch, H, P, N, G, misalign):
+    """Batches large enough that a workgroup of the vector kernel owns slices of several sequences (the slice's side
+    inputs are then requested one slice ahead), with ragged last slices and the x paths of the staging."""
+    s = W.LayerShape("t", batch, 1, H, P, N, G, 64, 2, 3)
+    _big_batch_steps(gpu_lib, s, seed=9, steps=2, misalign=misalign)
+
+
 @pytest.mark.parametrize("P,N,H,G", [(64, 128, 8, 2), (20, 24, 4, 2), (7, 5, 3, 1), (33, 16, 4, 1)])
 def test_quantize_state_bit_exact(gpu_lib, P, N, H, G):
     """fp32 state -> codes of the cache: the 4-wide path, the scalar path (d_state not a multiple of 4), clamping."""
