@@ -186,6 +186,10 @@ int quamba_ssd_decode_step_q8_gated(const quamba_ssd_shape_t *shape, const quamb
  * where dA = exp(dt*A) is evaluated as t = (dt*A)*log2(e) (fp32 constant 0x3FB8AA3B), k = rint(t), f = t - k,
  * 2^f by Horner's rule on the fp32-rounded coefficients (ln 2)^i / i!, i = 7..0 (multiply and add rounded
  * separately), times 2^k; 0 when t < -125.  y = sum_n (s_C[g]*C[n])*hn + D*xv in fp32, rounded to fp16.
+ * The codes of the cached state stay within [-127, 127]: narrower on the negative side than Eq. 1's 8-bit range
+ * [-128, 127], on purpose.  The scales are (calibrated maximum) / 127, so the grid is symmetric, and an element is
+ * re-quantized at every step: a code of -128 would let a saturated negative state sit one step beyond the
+ * calibrated maximum where a positive one cannot.
  * Errors: ENULL, ESHAPE, EHIP.
  */
 int quamba_ssd_decode_step_q8(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
