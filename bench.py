@@ -420,7 +420,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by sequence or by "
-              "state group with no exchange, see DESIGN.md)" % args.gpus, file=sys.stderr)
+              "state group with no exchange between devices)" % args.gpus, file=sys.stderr)
         return 2
 
     global POWER_SECONDS, POWER_ALL_LEGS
