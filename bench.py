@@ -229,6 +229,13 @@ def measure_attainable(q, torch, dev, big):
     ms, _ = time_region(torch, rmw, 10, 2, min_warm_ms=40.0)
     res["hbm_stream_rmw"] = {"value": moved[0] / (ms * 1e-3) / 1e9, "unit": "GB/s", "bytes_per_launch": moved[0],
                              "ms_per_launch": ms}
+    def rd():
+        moved[0] = q.quamba_probe_stream_read(big, sink)
+    ms, _ = time_region(torch, rd, 10, 2, min_warm_ms=40.0)
+    res["hbm_stream_read"] = {"value": moved[0] / (ms * 1e-3) / 1e9, "unit": "GB/s", "bytes_per_launch": moved[0],
+                              "ms_per_launch": ms,
+                              "note": "reads alone: the ceiling of a kernel that reads more than it writes (the Hadamard "
+                                      "transform reads 2 bytes per byte it writes)"}
     res["note"] = ("measured in this run by small kernels of the same library: 4 independent 32x32 MFMA chains per wave, "
                    "2 waves per SIMD, operands in registers -- with operands that differ from lane to lane (mfma_f16, "
                    "mfma_i8: what a real contraction can sustain; the board reaches its power cap and lowers the clock) "
@@ -592,6 +599,7 @@ def main() -> int:
         if attainable is not None:
             out["hadamard"]["roofline"]["attainable"] = attainable["hbm_stream_rmw"]["value"]
             out["hadamard"]["roofline"]["frac_of_attainable"] = hgbs / attainable["hbm_stream_rmw"]["value"]
+            out["hadamard"]["roofline"]["frac_of_read_stream"] = hgbs / attainable["hbm_stream_read"]["value"]
         if not args.no_cpu:   # spot check against the oracle: 16 rows spread over the launch, codes bit for bit
             import oracle
             pick = torch.arange(0, rows, rows // 16, device=dev)

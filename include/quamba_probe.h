@@ -33,6 +33,13 @@ int quamba_probe_mfma(int kind, int iters, int waves_per_simd, int uniform_opera
  * moves 2 * n_bytes.  Errors: QUAMBA_ENULL, QUAMBA_EINVAL (n_bytes == 0, not a multiple of 16, or beyond 2^31 workgroups of 32 KiB), QUAMBA_EHIP. */
 int quamba_probe_stream_rmw(void *buf, size_t n_bytes, void *stream);
 
+/* Read-only streaming pass over buf (device, n_bytes a multiple of 16): 16 workgroups per compute unit stride over
+ * the buffer with 16-byte loads; nothing is written (sink, device, >= 4 bytes, receives one word in a case that
+ * practically never occurs, so that the loads cannot be removed).  The launch moves n_bytes: the rate HBM reads
+ * alone reach, the ceiling of a kernel that reads more than it writes.
+ * Errors: QUAMBA_ENULL, QUAMBA_EINVAL (n_bytes == 0 or not a multiple of 16), QUAMBA_EHIP. */
+int quamba_probe_stream_read(const void *buf, size_t n_bytes, uint32_t *sink, void *stream);
+
 /* Shader clock: one wave reads the shader-clock counter and the constant 100 MHz counter, spins for about
  * spin_iters dependent vector operations, reads both again and writes the two differences to out[0] (shader clocks)
  * and out[1] (ticks of 10 ns) (device, 16 bytes).  Enqueued on a second stream while a kernel runs back to back on

@@ -10,7 +10,8 @@ from .binding import (QuambaError, Shape, HostScales, DeviceScales, Gate, load_l
                       quamba_hadamard_quantize, quamba_conv1d_q8, quamba_mamba1_scan, quamba_mamba1_decode_step,
                       quamba_reorder_params, quamba_gather_rows, quamba_quantize_x, quamba_quantize_groups,
                       quamba_strerror, FLAG_GENERIC_KERNEL, FLAG_PRECISE_STATE, FLAG_NO_CHANNEL_SPLIT, FLAG_NO_DECAY_SKIP,
-                      EXPORTED_SYMBOLS, quamba_probe_mfma, quamba_probe_stream_rmw, quamba_probe_clock)
+                      EXPORTED_SYMBOLS, quamba_probe_mfma, quamba_probe_stream_rmw, quamba_probe_stream_read,
+                      quamba_probe_clock)
 
 __all__ = ["QuambaError", "Shape", "HostScales", "DeviceScales", "Gate", "load_library", "library_path",
            "quamba_ssd_prefill", "quamba_ssd_prefill_workspace_size", "quamba_ssd_decode_step",
@@ -18,4 +19,5 @@ __all__ = ["QuambaError", "Shape", "HostScales", "DeviceScales", "Gate", "load_l
            "quamba_hadamard_quantize", "quamba_conv1d_q8", "quamba_mamba1_scan", "quamba_mamba1_decode_step",
            "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x", "quamba_quantize_groups",
            "quamba_strerror", "FLAG_GENERIC_KERNEL", "FLAG_PRECISE_STATE", "FLAG_NO_CHANNEL_SPLIT", "FLAG_NO_DECAY_SKIP",
-           "EXPORTED_SYMBOLS", "quamba_probe_mfma", "quamba_probe_stream_rmw", "quamba_probe_clock"]
+           "EXPORTED_SYMBOLS", "quamba_probe_mfma", "quamba_probe_stream_rmw", "quamba_probe_stream_read",
+           "quamba_probe_clock"]

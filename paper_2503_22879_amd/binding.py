@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "
                     "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x",
                     "quamba_quantize_groups", "quamba_strerror",
                     # measurement helpers of the benchmark harness (include/quamba_probe.h)
-                    "quamba_probe_mfma", "quamba_probe_stream_rmw", "quamba_probe_clock")
+                    "quamba_probe_mfma", "quamba_probe_stream_rmw", "quamba_probe_stream_read", "quamba_probe_clock")
 
 
 class QuambaError(RuntimeError):
@@ -508,6 +508,20 @@ def quamba_probe_stream_rmw(buf, stream=None) -> int:
     if rc != 0:
         raise QuambaError(rc, "quamba_probe_stream_rmw")
     return 2 * nbytes
+
+
+def quamba_probe_stream_read(buf, sink, stream=None) -> int:
+    """Enqueue one read-only pass over the device tensor buf; sink: int32 device tensor (>= 1 element); returns the
+    bytes the launch moves."""
+    import torch
+    lib = load_library()
+    lib.quamba_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    nbytes = buf.numel() * buf.element_size()
+    rc = lib.quamba_probe_stream_read(_dp(buf, buf.dtype, name="buf"), nbytes, _dp(sink, torch.int32, name="sink"),
+                                      _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_probe_stream_read")
+    return nbytes
 
 
 def quamba_probe_clock(out, spin_iters: int = 20000, stream=None) -> None:

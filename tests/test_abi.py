@@ -233,5 +233,8 @@ def test_probe_entry_points_validate_before_they_launch():
     assert lib.quamba_probe_mfma(0, 10, 9, 1, C.byref(ops), C.c_void_p(p), None) == -5
     assert lib.quamba_probe_stream_rmw(None, C.c_size_t(64), None) == -1
     assert lib.quamba_probe_stream_rmw(C.c_void_p(p), C.c_size_t(24), None) == -5
+    assert lib.quamba_probe_stream_read(None, C.c_size_t(64), C.c_void_p(p), None) == -1
+    assert lib.quamba_probe_stream_read(C.c_void_p(p), C.c_size_t(64), None, None) == -1
+    assert lib.quamba_probe_stream_read(C.c_void_p(p), C.c_size_t(0), C.c_void_p(p), None) == -5
     assert lib.quamba_probe_clock(None, 100, None) == -1
     assert lib.quamba_probe_clock(C.c_void_p(p), 0, None) == -5
