@@ -62,6 +62,12 @@ typedef enum quamba_status {
                                            the chunk state; what is left out is below 2.4e-10 of the term's own
                                            undecayed size, five orders under the tightest tolerance)          */
 
+#define QUAMBA_FLAG_NO_SEQ_SPLIT 0x10u  /* prefill: walk every sequence with one workgroup (or pair of workgroups) from
+                                           its first to its last token even when the batch is too short to fill the
+                                           chip (by default such batches are cut into up to 8 segments: a first
+                                           launch computes the state at the end of every segment, a second one gives
+                                           every segment its own workgroups; the results agree to rounding)       */
+
 typedef struct quamba_ssd_shape_t {
     int32_t batch;           /* sequences                                                             */
     int32_t seqlen;          /* tokens per sequence (ignored by decode)                               */
@@ -88,8 +94,11 @@ typedef struct quamba_ssd_scales_t {
 } quamba_ssd_scales_t;
 
 /*
- * Bytes of device workspace quamba_ssd_prefill needs for this shape (may be 0).  Returns 0 for an invalid shape;
- * quamba_ssd_prefill reports the error.
+ * Bytes of device workspace quamba_ssd_prefill needs for this shape on the current device (may be 0).  Non-zero
+ * only for batches short enough for the sequence split of the matrix-core kernel (QUAMBA_FLAG_NO_SEQ_SPLIT): the
+ * states at the segment boundaries, (segments - 1) * batch * nheads * (headdim * d_state + 1) floats.  The workspace
+ * is scratch: written and read by the call's own launches, contents undefined afterwards; calls that share one
+ * workspace must not overlap.  Returns 0 for an invalid shape; quamba_ssd_prefill reports the error.
  */
 size_t quamba_ssd_prefill_workspace_size(const quamba_ssd_shape_t *shape);
 

@@ -10,6 +10,7 @@ from .binding import (QuambaError, Shape, HostScales, DeviceScales, Gate, load_l
                       quamba_hadamard_quantize, quamba_conv1d_q8, quamba_mamba1_scan, quamba_mamba1_decode_step,
                       quamba_reorder_params, quamba_gather_rows, quamba_quantize_x, quamba_quantize_groups,
                       quamba_strerror, FLAG_GENERIC_KERNEL, FLAG_PRECISE_STATE, FLAG_NO_CHANNEL_SPLIT, FLAG_NO_DECAY_SKIP,
+                      FLAG_NO_SEQ_SPLIT,
                       EXPORTED_SYMBOLS, quamba_probe_mfma, quamba_probe_stream_rmw, quamba_probe_stream_read,
                       quamba_probe_clock)
 
@@ -19,5 +20,6 @@ __all__ = ["QuambaError", "Shape", "HostScales", "DeviceScales", "Gate", "load_l
            "quamba_hadamard_quantize", "quamba_conv1d_q8", "quamba_mamba1_scan", "quamba_mamba1_decode_step",
            "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x", "quamba_quantize_groups",
            "quamba_strerror", "FLAG_GENERIC_KERNEL", "FLAG_PRECISE_STATE", "FLAG_NO_CHANNEL_SPLIT", "FLAG_NO_DECAY_SKIP",
+           "FLAG_NO_SEQ_SPLIT",
            "EXPORTED_SYMBOLS", "quamba_probe_mfma", "quamba_probe_stream_rmw", "quamba_probe_stream_read",
            "quamba_probe_clock"]

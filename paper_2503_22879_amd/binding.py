@@ -15,6 +15,7 @@ FLAG_GENERIC_KERNEL = 0x1
 FLAG_PRECISE_STATE = 0x2
 FLAG_NO_CHANNEL_SPLIT = 0x4
 FLAG_NO_DECAY_SKIP = 0x8
+FLAG_NO_SEQ_SPLIT = 0x10
 
 EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "quamba_ssd_decode_step",
                     "quamba_ssd_decode_step_q8", "quamba_ssd_quantize_state", "quamba_state_scales",

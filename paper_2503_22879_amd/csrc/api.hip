@@ -14,7 +14,7 @@ int check_shape(const quamba_ssd_shape_t *s, bool prefill)
         return QUAMBA_ESHAPE;
     if (s->nheads % s->ngroups) return QUAMBA_ESHAPE;
     if (s->flags & ~(QUAMBA_FLAG_GENERIC_KERNEL | QUAMBA_FLAG_PRECISE_STATE | QUAMBA_FLAG_NO_CHANNEL_SPLIT |
-                     QUAMBA_FLAG_NO_DECAY_SKIP))
+                     QUAMBA_FLAG_NO_DECAY_SKIP | QUAMBA_FLAG_NO_SEQ_SPLIT))
         return QUAMBA_EINVAL;
     if ((int64_t)s->batch * s->nheads > 0x7fffffffLL) return QUAMBA_ESHAPE;
     if (prefill) {
@@ -48,6 +48,7 @@ quamba::SsdArgs pack(const quamba_ssd_shape_t *s, const quamba_ssd_scales_t *sc,
     a.state = state;
     a.y = y;
     a.z = nullptr; a.z_scale = 0.0f; a.dt_q = nullptr; a.dt_scale = 0.0f; a.dt_bias = nullptr;
+    a.nseg = 1; a.seg_chunks = 0; a.seg_pass = 0; a.seg_state = nullptr; a.seg_decay = nullptr;
     return a;
 }
 
@@ -83,7 +84,10 @@ bool use_mfma(const quamba_ssd_shape_t *s, const void *x, const void *B, const v
 extern "C" size_t quamba_ssd_prefill_workspace_size(const quamba_ssd_shape_t *shape)
 {
     if (!shape || check_shape(shape, true) != QUAMBA_OK) return 0;
-    return 0;  // both prefill kernels keep every intermediate on chip
+    // the generic kernel keeps every intermediate on chip; the matrix-core kernel needs the segment states of a
+    // sequence split (short batches only)
+    if ((shape->flags & QUAMBA_FLAG_GENERIC_KERNEL) || !quamba::prefill_mfma_supports(*shape)) return 0;
+    return quamba::prefill_mfma_workspace_bytes(*shape);
 }
 
 extern "C" int quamba_ssd_prefill(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
@@ -116,7 +120,8 @@ extern "C" int quamba_ssd_prefill_gated(const quamba_ssd_shape_t *shape, const q
     rc = apply_gate(gate, dt, &a);
     if (rc != QUAMBA_OK) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const hipError_t e = mfma ? quamba::launch_prefill_mfma(a, stream) : quamba::launch_prefill_generic(a, stream);
+    const hipError_t e = mfma ? quamba::launch_prefill_mfma(a, workspace, stream)
+                              : quamba::launch_prefill_generic(a, stream);
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }
 

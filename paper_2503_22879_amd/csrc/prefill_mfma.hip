@@ -40,6 +40,7 @@
 // operands that need the token index as k (x^T, B^T) are fetched with the transposing LDS loads
 // (ds_read_b64_tr_b8 / _tr_b16), whose source lanes address whole token rows; the rows are stored with bits 2 and 3
 // of the token index swapped so that the 8 tokens of one k group are 8 consecutive rows.
+#include <algorithm>
 #include <atomic>
 
 #include "quamba_internal.h"
@@ -224,7 +225,8 @@ __device__ __forceinline__ int block_to_bh(const SsdArgs &a, int i)
 // half of the channels, its own half of the state and its own copy of the G^T work; chosen when there are fewer
 // heads in the batch than compute units, so that the whole chip works on short batches.
 // GATED: the output is multiplied by SiLU(z) of the caller's int8 gate codes (Section 3.2) in the epilogue.
-template <bool PRECISE, int PT, bool GATED>
+// SEG: the launch belongs to a sequence split (see SsdArgs); the instantiations without it carry none of its code.
+template <bool PRECISE, int PT, bool GATED, bool SEG>
 __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
 {
     typedef Lds<PT> LY;
@@ -246,9 +248,18 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
     constexpr int kZsStride = LY::kZsStride;
 
     const int L = a.s.seqlen, H = a.s.nheads, G = a.s.ngroups;
+    // Sequence split: the workgroups of segment `seg` walk the chunks [c_begin, c_end) of their sequence; without a
+    // split that is the whole sequence.  Everything below is uniform over the workgroup.
+    const int wgs_per_seg = a.s.batch * H * (2 / PT);
+    const int seg = SEG ? (int)blockIdx.x / wgs_per_seg : 0;
+    const int nchunks = (L + kQ - 1) / kQ;
+    const int c_begin = SEG ? seg * a.seg_chunks : 0;
+    const int c_end = (SEG && seg + 1 < a.nseg) ? c_begin + a.seg_chunks : nchunks;
+    const bool state_pass = SEG && a.seg_pass != 0;  // this launch only carries the state to the end of its segments
+    const bool convert_init = a.init_state && (!SEG || seg == 0);  // the caller's initial state belongs to segment 0
     // with two workgroups per head, ids i and i + 8 (same XCD, and the same compute unit when two workgroups fit one)
     // take the two halves of a head
-    const int bid = blockIdx.x;
+    const int bid = SEG ? (int)blockIdx.x - seg * wgs_per_seg : (int)blockIdx.x;
     int pair = bid, half = 0;  // index of the (sequence, head) pair before the XCD mapping; channel half
     if (PT == 1) {
         // complete groups of 8 pairs take 16 consecutive ids (8 first halves, 8 second halves); the last, incomplete
@@ -298,14 +309,21 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
         // a gate code has 256 values: their SiLU is tabulated once (exp and reciprocal are quarter-rate instructions)
         if (GATED && tid < 256) s_silu[tid] = silu_of_code(a.z_scale, (int8_t)tid);
     };
-    const int nchunks = (L + kQ - 1) / kQ;
     // decay below which a 32-token block's product is left out; +inf keeps everything
     const float dead = (a.s.flags & QUAMBA_FLAG_NO_DECAY_SKIP) ? __builtin_inff() : kDead;
     constexpr float kStScale = kNarrow;
     const uint32_t x_row = (uint32_t)H * kP, b_row = (uint32_t)G * kN, dt_row = (uint32_t)H * 4u;
     typedef uint32_t xvec __attribute__((ext_vector_type(PT)));
 
-    if (out_role) {
+    if (out_role && state_pass) {
+        // a launch without outputs: these waves only fill the tables and keep the barriers of every chunk
+        fill_tables();
+        if (convert_init) __syncthreads();
+        for (int c = c_begin; c < c_end; ++c) {
+            __syncthreads();
+            __syncthreads();
+        }
+    } else if (out_role) {
         // ================= output waves: wave w produces the outputs of one 32-token block per chunk =================
         // C rows of the wave's block of chunk c (operand of G^T, and, as fp16, of the carried-state product), loaded a
         // chunk ahead.  k-step kk of the G^T product covers states 32 kk + 16 hb + [0,16): the two half-waves read
@@ -322,10 +340,10 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
             for (int kk = 0; kk < 4; ++kk)
                 ct[kk] = *reinterpret_cast<const i32x4 *>(cbase + (row * b_row + 16u * (ln >> 5)) + 32 * kk);
         };
-        issue_c_rows(0);
+        issue_c_rows(c_begin);
         fill_tables();
-        if (a.init_state) __syncthreads();  // the state waves wait for the scales
-        for (int c = 0; c < nchunks; ++c) {
+        if (convert_init) __syncthreads();  // the state waves wait for the scales
+        for (int c = c_begin; c < c_end; ++c) {
             const int t0 = c * kQ;
             const int nv = min(kQ, L - t0);
             const size_t tokbase = (size_t)b * L + t0;
@@ -454,7 +472,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                     gi = gn;
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (c + 1 < nchunks) issue_c_rows(c + 1);
+                if (c + 1 < c_end) issue_c_rows(c + 1);
                 __builtin_amdgcn_sched_barrier(0);
                 {  // diagonal block pair: per-element decay, causal mask, plain x codes
                     f16x8 xd[2][PT];
@@ -601,7 +619,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                     __syncthreads();  // this epilogue reads the staged x: the chunk's LDS arrays are free only now
                 }
             } else {
-                if (c + 1 < nchunks) issue_c_rows(c + 1);
+                if (c + 1 < c_end) issue_c_rows(c + 1);
                 __syncthreads();  // both roles are done with the chunk's LDS arrays
             }
         }
@@ -660,8 +678,33 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 br[k] = *reinterpret_cast<const u32x4 *>(bbase + (row * b_row + 16u * bn16));
             }
         };
-        issue_loads(0);
-        if (a.init_state) {
+        issue_loads(c_begin);
+        float seg_cum = 0.0f;  // sum of the chunks' dt*A*log2(e) totals (state pass, first state wave)
+        if (SEG && seg > 0 && !state_pass) {
+            // Start state of segment seg from the state pass: with local_j the state segment j ends with when started
+            // from zero (segment 0: from the caller's initial state) and d_j the sum of dt*A*log2(e) over its tokens,
+            //   H = local_{seg-1} + 2^{d_{seg-1}} local_{seg-2} + 2^{d_{seg-1} + d_{seg-2}} local_{seg-3} + ...
+            // (accumulator units: no scales involved)
+            const size_t pairs = (size_t)a.s.batch * H;
+            float dsum = 0.0f;
+            for (int j = seg - 1; j >= 0; --j) {
+                const float w = exp2_fast(dsum);
+                const float *src = a.seg_state + ((size_t)j * pairs + bh) * kP * kN;
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt) {
+                    const int p = pt * 32 + l32;
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const int n0 = 32 * wave + 8 * rg + 4 * hb;
+                        const f32x4 v = *reinterpret_cast<const f32x4 *>(src + (size_t)(p_base + p) * kN + n0);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) st[pt][4 * rg + i] = fmaf(w, v[i], st[pt][4 * rg + i]);
+                    }
+                }
+                dsum += a.seg_decay[(size_t)j * pairs + bh];
+            }
+        }
+        if (convert_init) {
             __syncthreads();  // the scales are in LDS
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt) {
@@ -677,7 +720,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 }
             }
         }
-        for (int c = 0; c < nchunks; ++c) {
+        for (int c = c_begin; c < c_end; ++c) {
             const int t0 = c * kQ;
             const int nv = min(kQ, L - t0);
             // ---- the first wave turns dt into everything the chunk needs of it: the inclusive prefix sum of dt*A
@@ -709,6 +752,8 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 float loc1;
                 const float cum1 = wave_inclusive_scan(a0 + a1, loc1), cum0 = cum1 - a1;
                 const float loc0 = loc1 - a1;
+                if (state_pass)  // the segment's total: the chunk's prefix sum at its last token
+                    seg_cum += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cum1), 63));
                 const float m_loc = __shfl(loc1, lane | 15, 64);
                 // weights towards the output accumulators
                 const float d0 = dt0 * (kAcc / kXs), d1 = dt1 * (kAcc / kXs);
@@ -779,7 +824,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                     *reinterpret_cast<u32x4 *>(s_bq + (row0 + k) * kBqStride + 16 * bn16) = br[k];
             }
             __syncthreads();  // the chunk is staged: the output waves start on it
-            if (c + 1 < nchunks) issue_loads(c + 1);  // the next chunk's global loads fly while this chunk is computed
+            if (c + 1 < c_end) issue_loads(c + 1);  // the next chunk's global loads fly while this chunk is computed
             // ---- state update: wave w owns states n in [32w, 32w+32) ----
             // source-lane roles of the transposing loads, rebuilt per chunk like the addresses of the output phase
             int lane_s = fresh_lane();
@@ -863,7 +908,24 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
             __syncthreads();  // the output waves are done with x, B, the weights and the fp16 state of this chunk
         }
 
-        if (a.state) {
+        if (state_pass) {
+            // the state at the end of the segment, as it stands in the accumulators, and the segment's decay total
+            const size_t pairs = (size_t)a.s.batch * H;
+            float *dst = a.seg_state + ((size_t)seg * pairs + bh) * kP * kN;
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) {
+                const int p = pt * 32 + l32;
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int n0 = 32 * wave + 8 * rg + 4 * hb;
+                    f32x4 v;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = st[pt][4 * rg + i];
+                    *reinterpret_cast<f32x4 *>(dst + (size_t)(p_base + p) * kN + n0) = v;
+                }
+            }
+            if (wave == 0 && lane == 0 && half == 0) a.seg_decay[(size_t)seg * pairs + bh] = seg_cum;
+        } else if (a.state && (!SEG || seg + 1 == a.nseg)) {
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt) {
                 const int p = pt * 32 + l32;
@@ -887,16 +949,25 @@ bool prefill_mfma_supports(const quamba_ssd_shape_t &s) { return s.headdim == kP
 
 namespace {
 
+template <bool PRECISE, int PT, bool GATED, bool SEG>
+hipError_t launch_scan_seg(const SsdArgs &a, hipStream_t stream)
+{
+    constexpr int lds = GATED ? Lds<PT>::kBytesGated : Lds<PT>::kBytes;
+    // one set of workgroups per segment; the state pass leaves the last segment out
+    const int segs = a.nseg > 1 ? (a.seg_pass ? a.nseg - 1 : a.nseg) : 1;
+    const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT) * segs));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT, GATED, SEG>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((prefill_mfma_kernel<PRECISE, PT, GATED, SEG>), grid, dim3(kThreads), lds, stream, a);
+    return hipGetLastError();
+}
+
 template <bool PRECISE, int PT, bool GATED>
 hipError_t launch_scan_gated(const SsdArgs &a, hipStream_t stream)
 {
-    constexpr int lds = GATED ? Lds<PT>::kBytesGated : Lds<PT>::kBytes;
-    const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT)));
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT, GATED>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_mfma_kernel<PRECISE, PT, GATED>), grid, dim3(kThreads), lds, stream, a);
-    return hipGetLastError();
+    return a.nseg > 1 ? launch_scan_seg<PRECISE, PT, GATED, true>(a, stream)
+                      : launch_scan_seg<PRECISE, PT, GATED, false>(a, stream);
 }
 
 template <bool PRECISE, int PT>
@@ -921,14 +992,94 @@ int compute_units()
 
 }  // namespace
 
-hipError_t launch_prefill_mfma(const SsdArgs &a, hipStream_t stream)
+// Few (sequence, head) pairs leave compute units idle, and a workgroup walks its sequence chunk by chunk.  Such
+// batches are cut along the sequence: with `pairs` workgroups per segment (twice that with the channel split) the
+// plan aims at two workgroups per compute unit, at least two chunks per segment and at most kMaxSegments segments.
+constexpr int kMaxSegments = 8;
+PrefillPlan prefill_mfma_plan(const quamba_ssd_shape_t &s)
 {
-    const bool precise = a.state != nullptr || (a.s.flags & QUAMBA_FLAG_PRECISE_STATE);
+    const int64_t pairs = (int64_t)s.batch * s.nheads;
+    const int cus = compute_units();
+    PrefillPlan plan;
     // fewer (sequence, head) pairs than compute units: give every head two workgroups (half of the channels each)
-    const bool split = !(a.s.flags & QUAMBA_FLAG_NO_CHANNEL_SPLIT) &&
-                       (int64_t)a.s.batch * a.s.nheads <= (int64_t)compute_units();
-    if (precise) return split ? launch_scan<true, 1>(a, stream) : launch_scan<true, 2>(a, stream);
-    return split ? launch_scan<false, 1>(a, stream) : launch_scan<false, 2>(a, stream);
+    plan.channel_split = !(s.flags & QUAMBA_FLAG_NO_CHANNEL_SPLIT) && pairs <= (int64_t)cus;
+    plan.nseg = 1;
+    plan.seg_chunks = 0;
+    const int nchunks = (s.seqlen + kQ - 1) / kQ;
+    // The split costs a second launch and a pass over all but the last segment that only carries the state (about a
+    // third of the work of those tokens).  Measured on MI355X it pays from 8 chunks on where the unsplit launch leaves
+    // compute units empty, and from 16 chunks on where it already has a workgroup on every compute unit (the split
+    // then only buys the second workgroup per unit).
+    const int64_t unsplit_wgs = pairs * (plan.channel_split ? 2 : 1);
+    const int min_chunks = unsplit_wgs >= (int64_t)cus ? 16 : 8;
+    if ((s.flags & QUAMBA_FLAG_NO_SEQ_SPLIT) || !prefill_mfma_supports(s) || nchunks < min_chunks ||
+        pairs > (int64_t)cus)
+        return plan;
+    // Whole heads (one workgroup per pair and segment) compute the score tiles once instead of twice, so the channel
+    // split is kept only where even kMaxSegments segments of whole heads would not fill the compute units.
+    const int seg_cap = (int)std::min<int64_t>(kMaxSegments, nchunks / 2);
+    int nseg;
+    if (!plan.channel_split || pairs * seg_cap >= (int64_t)cus) {
+        plan.channel_split = false;
+        nseg = (int)std::min<int64_t>(seg_cap, (2 * (int64_t)cus) / pairs);
+    } else {
+        nseg = (int)std::min<int64_t>(seg_cap, (int64_t)cus / pairs);
+    }
+    if (nseg < 2) return plan;
+    plan.seg_chunks = (nchunks + nseg - 1) / nseg;
+    plan.nseg = (nchunks + plan.seg_chunks - 1) / plan.seg_chunks;  // every segment holds at least one chunk
+    if (plan.nseg < 2) {
+        plan.nseg = 1;
+        plan.seg_chunks = 0;
+    }
+    return plan;
+}
+
+size_t prefill_mfma_workspace_bytes(const quamba_ssd_shape_t &s)
+{
+    const PrefillPlan plan = prefill_mfma_plan(s);
+    if (plan.nseg < 2) return 0;
+    const size_t pairs = (size_t)s.batch * s.nheads;
+    return sizeof(float) * (size_t)(plan.nseg - 1) * pairs * ((size_t)kP * kN + 1);
+}
+
+hipError_t launch_prefill_mfma(const SsdArgs &a_in, void *workspace, hipStream_t stream)
+{
+    SsdArgs a = a_in;
+    const bool precise = a.state != nullptr || (a.s.flags & QUAMBA_FLAG_PRECISE_STATE);
+    PrefillPlan plan = prefill_mfma_plan(a.s);
+    if (plan.nseg > 1 && (!workspace || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)) {
+        // no usable workspace: the unsplit launch (the entry point has already checked the size)
+        const int64_t pairs = (int64_t)a.s.batch * a.s.nheads;
+        plan.nseg = 1;
+        plan.channel_split = !(a.s.flags & QUAMBA_FLAG_NO_CHANNEL_SPLIT) && pairs <= (int64_t)compute_units();
+    }
+    auto launch = [&](const SsdArgs &args) {
+        if (precise) return plan.channel_split ? launch_scan<true, 1>(args, stream) : launch_scan<true, 2>(args, stream);
+        return plan.channel_split ? launch_scan<false, 1>(args, stream) : launch_scan<false, 2>(args, stream);
+    };
+    a.nseg = 1;
+    a.seg_chunks = 0;
+    a.seg_pass = 0;
+    a.seg_state = nullptr;
+    a.seg_decay = nullptr;
+    if (plan.nseg < 2) return launch(a);
+
+    const size_t pairs = (size_t)a.s.batch * a.s.nheads;
+    a.nseg = plan.nseg;
+    a.seg_chunks = plan.seg_chunks;
+    a.seg_state = static_cast<float *>(workspace);
+    a.seg_decay = a.seg_state + (size_t)(plan.nseg - 1) * pairs * kP * kN;
+    // first launch: the states at the ends of segments 0 .. nseg-2 (no outputs, no gate, no final state)
+    SsdArgs pass = a;
+    pass.seg_pass = 1;
+    pass.z = nullptr;
+    pass.y = nullptr;
+    pass.state = nullptr;
+    hipError_t e = launch(pass);
+    if (e != hipSuccess) return e;
+    // second launch: every segment with its own workgroups
+    return launch(a);
 }
 
 }  // namespace quamba

@@ -29,7 +29,27 @@ struct SsdArgs {
     const int8_t *dt_q;        // codes of the step size's pre-activation, laid out like dt (dt is then unused)
     float dt_scale;
     const float *dt_bias;      // [nheads] or null
+    // Sequence split of the chunked prefill (matrix-core kernel only; nseg == 1: none).  The sequence is cut into nseg
+    // segments of seg_chunks 128-token chunks (the last takes the rest).  A first launch (seg_pass == 1) walks
+    // segments 0 .. nseg-2 without producing outputs and leaves, per segment, the state it ends with when started
+    // from zero (segment 0: from init_state) and the sum of dt*A*log2(e) over its tokens; the second launch
+    // (seg_pass == 0) gives every segment its own workgroups, which start from the combination of those.
+    int32_t nseg;
+    int32_t seg_chunks;
+    int32_t seg_pass;
+    float *seg_state;          // [nseg-1][batch*nheads][headdim][d_state], in the kernel's accumulator units
+    float *seg_decay;          // [nseg-1][batch*nheads]
 };
+
+// Plan of the sequence split for a shape on the current device: segments (1 = no split), chunks per segment, and
+// whether every head is cut into two workgroups of 32 channels each.
+struct PrefillPlan {
+    int nseg;
+    int seg_chunks;
+    bool channel_split;
+};
+PrefillPlan prefill_mfma_plan(const quamba_ssd_shape_t &s);
+size_t prefill_mfma_workspace_bytes(const quamba_ssd_shape_t &s);
 
 // Step size of (token or sequence) index idx of head h: the caller's fp32 dt, or softplus(s_dt * code + bias[h])
 // (Section 3.2: Delta = softplus(F(x)) with the bias) when the pre-activation comes as int8 codes.
@@ -156,7 +176,7 @@ hipError_t launch_mamba1_decode(const SsdArgs &a, const float *A, hipStream_t st
 bool mamba1_scan_supports_any(const quamba_ssd_shape_t &s);
 hipError_t launch_prefill_generic(const SsdArgs &a, hipStream_t stream);
 bool prefill_mfma_supports(const quamba_ssd_shape_t &s);
-hipError_t launch_prefill_mfma(const SsdArgs &a, hipStream_t stream);
+hipError_t launch_prefill_mfma(const SsdArgs &a, void *workspace, hipStream_t stream);
 size_t prefill_generic_lds_bytes(const quamba_ssd_shape_t &s);
 
 }  // namespace quamba
