@@ -39,7 +39,7 @@ typedef enum quamba_status {
     QUAMBA_OK = 0,
     QUAMBA_ENULL = -1,      /* a required pointer is NULL                                   */
     QUAMBA_ESHAPE = -2,     /* a dimension is non-positive, inconsistent or unsupported      */
-    QUAMBA_EWORKSPACE = -3, /* workspace_bytes smaller than quamba_ssd_prefill_workspace_size */
+    QUAMBA_EWORKSPACE = -3, /* a shape needs more scratch memory than an entry point with a fixed scratch area has */
     QUAMBA_EHIP = -4,       /* the HIP runtime refused the launch (no device, bad stream ...) */
     QUAMBA_EINVAL = -5      /* an argument value is invalid (unknown flag, bad permutation ...) */
 } quamba_status;
@@ -94,11 +94,13 @@ typedef struct quamba_ssd_scales_t {
 } quamba_ssd_scales_t;
 
 /*
- * Bytes of device workspace quamba_ssd_prefill needs for this shape on the current device (may be 0).  Non-zero
- * only for batches short enough for the sequence split of the matrix-core kernel (QUAMBA_FLAG_NO_SEQ_SPLIT): the
- * states at the segment boundaries, (segments - 1) * batch * nheads * (headdim * d_state + 1) floats.  The workspace
- * is scratch: written and read by the call's own launches, contents undefined afterwards; calls that share one
- * workspace must not overlap.  Returns 0 for an invalid shape; quamba_ssd_prefill reports the error.
+ * Bytes of device workspace with which quamba_ssd_prefill runs this shape fastest on the current device (may be 0).
+ * Non-zero only for batches short enough for the sequence split of the matrix-core kernel
+ * (QUAMBA_FLAG_NO_SEQ_SPLIT): the states at the segment boundaries, (segments - 1) * batch * nheads *
+ * (headdim * d_state + 1) floats.  A call with a NULL, smaller or not 16-byte aligned workspace is not an error: it
+ * takes the unsplit launch (same results to rounding, slower on such batches).  The workspace is scratch: written
+ * and read by the call's own launches, contents undefined afterwards; calls that share one workspace must not
+ * overlap.  Returns 0 for an invalid shape; quamba_ssd_prefill reports the error.
  */
 size_t quamba_ssd_prefill_workspace_size(const quamba_ssd_shape_t *shape);
 
@@ -111,10 +113,11 @@ size_t quamba_ssd_prefill_workspace_size(const quamba_ssd_shape_t *shape);
  *   init_state  device fp32 [batch, nheads, headdim, d_state] or NULL (zero state)
  *   y           device fp16 [batch, seqlen, nheads, headdim]   (written, round-to-nearest-even)
  *   final_state device fp32 [batch, nheads, headdim, d_state] or NULL (not returned); may alias init_state
- *   workspace   device, workspace_bytes >= quamba_ssd_prefill_workspace_size(shape); may be NULL when that is 0
+ *   workspace   device scratch of workspace_bytes, 16-byte aligned; NULL or fewer bytes than
+ *               quamba_ssd_prefill_workspace_size(shape) select the launch that needs none
  * Any seqlen >= 1 is accepted; a last partial chunk is processed as if padded with dt = 0, x = 0 steps (identity
  * steps of Eq. 2) whose outputs are not written.  Errors: ENULL, ESHAPE (nheads % ngroups, non-positive sizes,
- * headdim*d_state too large for the generic kernel), EWORKSPACE, EHIP.
+ * headdim*d_state too large for the generic kernel), EHIP.
  * Operand ranges of the matrix-core kernel (headdim 64, d_state 128), which narrows its operands to fp16 after fixed
  * power-of-two scalings and does not check them (they live on the device; outside them the result becomes inf or
  * NaN without an error; QUAMBA_FLAG_GENERIC_KERNEL computes in fp32 and has none of the three limits):

@@ -111,8 +111,9 @@ extern "C" int quamba_ssd_prefill_gated(const quamba_ssd_shape_t *shape, const q
     if (!x || !B || !C || !A || !y) return QUAMBA_ENULL;
     rc = check_shape(shape, true);
     if (rc != QUAMBA_OK) return rc;
+    // a workspace that is missing or too small selects the launch that needs none
     const size_t need = quamba_ssd_prefill_workspace_size(shape);
-    if (workspace_bytes < need || (need && !workspace)) return QUAMBA_EWORKSPACE;
+    if (!workspace || workspace_bytes < need) workspace = nullptr;
     const bool mfma = use_mfma(shape, x, B, C, y, init_state, final_state) && (!gate || aligned16(gate->z));
     if (!mfma && quamba::prefill_generic_lds_bytes(*shape) > kMaxLdsBytes) return QUAMBA_ESHAPE;
 

@@ -1049,7 +1049,7 @@ hipError_t launch_prefill_mfma(const SsdArgs &a_in, void *workspace, hipStream_t
     const bool precise = a.state != nullptr || (a.s.flags & QUAMBA_FLAG_PRECISE_STATE);
     PrefillPlan plan = prefill_mfma_plan(a.s);
     if (plan.nseg > 1 && (!workspace || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)) {
-        // no usable workspace: the unsplit launch (the entry point has already checked the size)
+        // no usable workspace (the entry point passes NULL when the caller's is missing or too small): the unsplit launch
         const int64_t pairs = (int64_t)a.s.batch * a.s.nheads;
         plan.nseg = 1;
         plan.channel_split = !(a.s.flags & QUAMBA_FLAG_NO_CHANNEL_SPLIT) && pairs <= (int64_t)compute_units();

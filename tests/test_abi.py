@@ -85,8 +85,7 @@ def test_prefill_rejects_nulls_and_flags():
 def test_workspace_of_the_sequence_split():
     """Short batches of the matrix-core shape are cut along the sequence and need the segment states as workspace:
     (segments - 1) * batch * heads * (headdim * d_state + 1) floats; the flag, the generic kernel, long batches and short
-    sequences need none; a call with too little workspace is refused before anything is enqueued.  (Without a GPU the
-    library plans for 256 compute units.)"""
+    sequences need none.  (Without a GPU the library plans for 256 compute units.)"""
     mm = dict(headdim=64, d_state=128, chunk=256, n_head_clusters=1, n_chan_clusters=1)
     unit = 64 * 128 + 1
     # 24 heads, 2048 tokens = 16 chunks: 8 segments of 2 chunks
@@ -102,10 +101,6 @@ def test_workspace_of_the_sequence_split():
         d.update(kw)
         assert q.quamba_ssd_prefill_workspace_size(_shape(**d)) == 0, kw
     assert q.quamba_ssd_prefill_workspace_size(_shape(batch=1, seqlen=512, nheads=24, ngroups=1, **mm)) == 0
-    need = q.quamba_ssd_prefill_workspace_size(s8)
-    assert _call_prefill(s8, ws_bytes=need - 1) == -3
-    assert _call_prefill(s8, ws_bytes=0) == -3
-    assert _call_prefill(s8, null_arg=9, ws_bytes=need) == -3     # a NULL workspace where one is needed
 
 
 def test_decode_rejects_bad_arguments_without_a_device():

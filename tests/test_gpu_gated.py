@@ -53,6 +53,38 @@ def test_prefill_gated(gpu_lib, flags, use_z, use_dt):
     assert ey <= Y_TOL and eh <= H_TOL
 
 
+@pytest.mark.parametrize("flags", [0, NO_SPLIT])
+def test_prefill_gated_with_the_sequence_split(gpu_lib, flags):
+    """130M-shaped layer at full length with both side inputs and a workspace: the launch is cut along the sequence
+    (the state pass reads the step-size codes, the output pass applies the gate), with initial and final state."""
+    import torch
+    q = gpu_lib
+    s = W.CONFIGS["m2_130m"]
+    shape = to_shape(q, s, flags=flags)
+    need = q.quamba_ssd_prefill_workspace_size(shape)
+    assert need > 0
+    sc, prob, r = make_problem(s, 23)
+    g = make_gate_inputs(s, r, 23)
+    dt_ref = oracle.dt_from_codes(g["dt_q"], g["dt_scale"], g["dt_bias"]).astype(np.float32)
+    init = (0.05 * np.random.default_rng(4).standard_normal((1, s.nheads, s.headdim, s.d_state))).astype(np.float32)
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], dt_ref, prob["A"], prob["D"],
+                                       init_state=init.astype(np.float64))
+    yref = oracle.silu_gate(yref, g["z"], g["z_scale"])
+    t = {k: (torch.from_numpy(v).cuda() if v is not None else None) for k, v in prob.items()}
+    y = torch.full((1, s.seqlen, s.nheads, s.headdim), float("nan"), dtype=torch.float16, device="cuda")
+    fin = torch.full((1, s.nheads, s.headdim, s.d_state), float("nan"), device="cuda")
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    q.quamba_ssd_prefill(shape, q.DeviceScales(host_scales(q, sc)), t["x"], t["B"], t["C"], None, t["A"], t["D"],
+                         torch.from_numpy(init).cuda(), y, fin, ws, gate=_gate(q, g, True, True))
+    yg = y.cpu().numpy().astype(np.float64)
+    hg = fin.cpu().numpy().astype(np.float64)
+    assert np.isfinite(yg).all() and np.isfinite(hg).all()
+    ey = np.abs(yg - yref).max() / np.abs(yref).max()
+    eh = np.abs(hg - href).max() / np.abs(href).max()
+    print(f"gated prefill with the sequence split, flags={flags}: y err {ey:.3e}, state err {eh:.3e}")
+    assert ey <= Y_TOL and eh <= H_TOL
+
+
 def test_prefill_gated_8b_shape_sampled(gpu_lib):
     """The bench shape (batch 4 x 4096, one workgroup per head) with both side inputs, checked on sampled heads."""
     import torch

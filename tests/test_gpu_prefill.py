@@ -119,6 +119,69 @@ def test_ragged_lengths_and_init_state(gpu_lib, flags, L):
         check(yg, None, yref, None, f"L={L} flags={flags}, no final state")
 
 
+NO_SEQ_SPLIT = 0x10
+
+
+@pytest.mark.parametrize("H,G,L,flags", [
+    (24, 1, 2048, 0),          # 130M shape: 8 segments of 2 chunks, two workgroups per head and segment
+    (24, 1, 2333, 0),          # 19 chunks: 7 segments of 3 chunks, the last one a single ragged chunk
+    (24, 1, 1100, NO_SPLIT),   # 9 chunks, whole heads: 3 segments of 3 chunks, the last chunk ragged
+    (128, 8, 4096, 0),         # 8B shape at batch 1: whole heads, 4 segments
+    (80, 1, 1500, 0),          # 12 chunks, 80 heads: 6 segments of whole heads, ragged last chunk
+])
+def test_sequence_split_against_the_oracle_and_the_unsplit_launch(gpu_lib, H, G, L, flags):
+    """Short batches are cut along the sequence (a state pass, then one set of workgroups per segment).  With an
+    initial state and the final state: against the oracle, and against the unsplit launch of the same library, whose
+    outputs differ only where an fp16 rounding flips (the start states of the segments are combined in another
+    order than the chunk-by-chunk walk forms them)."""
+    q = gpu_lib
+    s = W.CONFIGS["m2_8b_b1"].with_(batch=1, seqlen=L, nheads=H, ngroups=G)
+    assert q.quamba_ssd_prefill_workspace_size(to_shape(q, s, flags=flags)) > 0
+    assert q.quamba_ssd_prefill_workspace_size(to_shape(q, s, flags=flags | NO_SEQ_SPLIT)) == 0
+    sc, prob, _ = make_problem(s, 31, calib_tokens=512)
+    h0 = W.draw_state(s, 31).astype(np.float32)
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"],
+                                       init_state=h0.astype(np.float64))
+    cells = oracle.cell_index_table(sc, s.nheads, s.headdim, s.ngroups)
+    for want_state in (True, False):
+        yg, hg = run_prefill(q, s, sc, prob, flags, init_state=h0, want_state=want_state)
+        check(yg, hg, yref, href if want_state else None, f"split H={H} L={L} flags={flags} state={want_state}", cells=cells)
+        yu, hu = run_prefill(q, s, sc, prob, flags | NO_SEQ_SPLIT, init_state=h0, want_state=want_state)
+        flipped = np.count_nonzero(yg != yu)
+        assert flipped <= 1e-2 * yg.size, f"{flipped} of {yg.size} outputs differ from the unsplit launch"
+        assert np.abs(yg - yu).max() <= 2.0 ** -9 * np.abs(yu).max()
+        if want_state:
+            assert np.abs(hg - hu).max() <= 2e-5 * np.abs(hu).max()
+
+
+def test_sequence_split_without_a_usable_workspace_takes_the_unsplit_launch(gpu_lib):
+    """A missing, short or misaligned workspace is not an error: the call runs unsplit, bit for bit like the flag."""
+    import torch
+    q = gpu_lib
+    s = W.CONFIGS["m2_130m"]
+    sc, prob, _ = make_problem(s, 32, calib_tokens=512)
+    dsc = q.DeviceScales(host_scales(q, sc))
+    t = {k: (torch.from_numpy(v).cuda() if v is not None else None) for k, v in prob.items()}
+    need = q.quamba_ssd_prefill_workspace_size(to_shape(q, s))
+    assert need > 0
+
+    def run(flags, ws):
+        y = torch.full((s.batch, s.seqlen, s.nheads, s.headdim), float("nan"), dtype=torch.float16, device="cuda")
+        q.quamba_ssd_prefill(to_shape(q, s, flags=flags), dsc, t["x"], t["B"], t["C"], t["dt"], t["A"], t["D"], None, y,
+                             None, ws)
+        torch.cuda.synchronize()
+        return y.cpu().numpy()
+
+    ref = run(NO_SEQ_SPLIT, None)
+    assert np.isfinite(ref.astype(np.float64)).all()
+    buf = torch.empty(need + 64, dtype=torch.uint8, device="cuda")
+    assert buf.data_ptr() % 16 == 0
+    for ws in (None, buf[:need - 16], buf[4:4 + need]):
+        assert np.array_equal(run(0, ws).view(np.uint16), ref.view(np.uint16))
+    split = run(0, buf[:need])
+    assert np.count_nonzero(split.view(np.uint16) != ref.view(np.uint16)) <= 1e-2 * ref.size
+
+
 @pytest.mark.parametrize("P,N,H,G,Q", [(64, 64, 4, 2, 128), (32, 128, 4, 1, 64), (64, 32, 6, 3, 256), (48, 24, 4, 2, 32),
                                        (16, 8, 2, 1, 16)])
 def test_other_shapes(gpu_lib, P, N, H, G, Q):
