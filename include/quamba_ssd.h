@@ -133,6 +133,20 @@ int quamba_ssd_prefill(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_
                        size_t workspace_bytes, void *hip_stream);
 
 /*
+ * quamba_ssd_prefill for callers that cannot provide a workspace and must not allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as quamba_ssd_prefill
+ * without the workspace; the scratch memory of the sequence split is a fixed area of 16 MiB inside the library's
+ * device image (one per GPU, held until the process ends), enough for every shape the matrix-core kernel takes.
+ * The call allocates nothing and synchronises nothing.  All calls on one GPU share that area: calls that overlap in
+ * time on the same GPU (different streams) race on it and must be ordered by the caller; nothing in it has to be
+ * cleared between calls (a call writes what it reads).
+ * Errors: as quamba_ssd_prefill, and EWORKSPACE for a shape whose split would need more than the fixed area.
+ */
+int quamba_ssd_prefill_noalloc(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales, const int8_t *x,
+                               const int8_t *B, const int8_t *C, const float *dt, const float *A, const float *D,
+                               const float *init_state, uint16_t *y, float *final_state, void *hip_stream);
+
+/*
  * Single-token decode: one application of Eq. 2 on a persistent state, the step the paper identifies as the
  * generation bottleneck at large batch (Appendix E, "The cached state sizes").
  *   x device int8 [batch, nheads, headdim]    B, C device int8 [batch, ngroups, d_state]

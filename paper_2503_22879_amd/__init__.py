@@ -5,7 +5,8 @@ library's HIP kernels; this package only marshals arguments.  There is no CPU fa
 library has not been built.
 """
 from .binding import (QuambaError, Shape, HostScales, DeviceScales, Gate, load_library, library_path,
-                      quamba_ssd_prefill, quamba_ssd_prefill_workspace_size, quamba_ssd_decode_step,
+                      quamba_ssd_prefill, quamba_ssd_prefill_noalloc, quamba_ssd_prefill_workspace_size,
+                      quamba_ssd_decode_step,
                       quamba_ssd_decode_step_q8, quamba_ssd_quantize_state, quamba_state_scales,
                       quamba_hadamard_quantize, quamba_conv1d_q8, quamba_mamba1_scan, quamba_mamba1_decode_step,
                       quamba_reorder_params, quamba_gather_rows, quamba_quantize_x, quamba_quantize_groups,
@@ -15,7 +16,8 @@ from .binding import (QuambaError, Shape, HostScales, DeviceScales, Gate, load_l
                       quamba_probe_clock)
 
 __all__ = ["QuambaError", "Shape", "HostScales", "DeviceScales", "Gate", "load_library", "library_path",
-           "quamba_ssd_prefill", "quamba_ssd_prefill_workspace_size", "quamba_ssd_decode_step",
+           "quamba_ssd_prefill", "quamba_ssd_prefill_noalloc", "quamba_ssd_prefill_workspace_size",
+           "quamba_ssd_decode_step",
            "quamba_ssd_decode_step_q8", "quamba_ssd_quantize_state", "quamba_state_scales",
            "quamba_hadamard_quantize", "quamba_conv1d_q8", "quamba_mamba1_scan", "quamba_mamba1_decode_step",
            "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x", "quamba_quantize_groups",

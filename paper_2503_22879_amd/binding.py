@@ -17,7 +17,7 @@ FLAG_NO_CHANNEL_SPLIT = 0x4
 FLAG_NO_DECAY_SKIP = 0x8
 FLAG_NO_SEQ_SPLIT = 0x10
 
-EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "quamba_ssd_decode_step",
+EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "quamba_ssd_prefill_noalloc", "quamba_ssd_decode_step",
                     "quamba_ssd_decode_step_q8", "quamba_ssd_quantize_state", "quamba_state_scales",
                     "quamba_hadamard_quantize", "quamba_conv1d_q8", "quamba_mamba1_scan",
                     "quamba_mamba1_decode_step", "quamba_mamba1_scan_gated", "quamba_mamba1_decode_step_gated",
@@ -95,6 +95,8 @@ def load_library():
         lib.quamba_ssd_prefill.restype = C.c_int
         lib.quamba_ssd_prefill.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 10 + \
             [C.c_size_t, C.c_void_p]
+        lib.quamba_ssd_prefill_noalloc.restype = C.c_int
+        lib.quamba_ssd_prefill_noalloc.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 10
         lib.quamba_ssd_decode_step.restype = C.c_int
         lib.quamba_ssd_decode_step.argtypes = [C.POINTER(Shape), C.POINTER(_ScalesStruct)] + [C.c_void_p] * 9
         lib.quamba_mamba1_scan.restype = C.c_int
@@ -223,6 +225,27 @@ def quamba_ssd_prefill(shape: Shape, scales, x, B, Cm, dt, A, D, init_state, y, 
         ws_ptr, ws_bytes, _stream_ptr(stream))
     if rc != 0:
         raise QuambaError(rc, "quamba_ssd_prefill")
+
+
+def quamba_ssd_prefill_noalloc(shape: Shape, scales, x, B, Cm, dt, A, D, init_state, y, final_state=None,
+                               stream=None) -> None:
+    """Enqueue the chunked prefill with the library's own fixed scratch area instead of a caller's workspace."""
+    import torch
+    s = shape
+    sc = scales.struct()
+    st_shape = (s.batch, s.nheads, s.headdim, s.d_state)
+    rc = load_library().quamba_ssd_prefill_noalloc(
+        C.byref(s), C.byref(sc),
+        _dp(x, torch.int8, (s.batch, s.seqlen, s.nheads, s.headdim), "x"),
+        _dp(B, torch.int8, (s.batch, s.seqlen, s.ngroups, s.d_state), "B"),
+        _dp(Cm, torch.int8, (s.batch, s.seqlen, s.ngroups, s.d_state), "C"),
+        _dp(dt, torch.float32, (s.batch, s.seqlen, s.nheads), "dt"),
+        _dp(A, torch.float32, (s.nheads,), "A"), _dp(D, torch.float32, (s.nheads,), "D"),
+        _dp(init_state, torch.float32, st_shape, "init_state"),
+        _dp(y, torch.float16, (s.batch, s.seqlen, s.nheads, s.headdim), "y"),
+        _dp(final_state, torch.float32, st_shape, "final_state"), _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_ssd_prefill_noalloc")
 
 
 def _prefill_gated(s, sc, gate, x, B, Cm, dt, A, D, init_state, y, final_state, workspace, stream) -> None:

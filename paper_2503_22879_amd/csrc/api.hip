@@ -1,4 +1,5 @@
 // The C-ABI layer: argument validation (before anything is enqueued) and kernel dispatch.
+#include <atomic>
 #include <cmath>
 
 #include "quamba_internal.h"
@@ -124,6 +125,56 @@ extern "C" int quamba_ssd_prefill_gated(const quamba_ssd_shape_t *shape, const q
     const hipError_t e = mfma ? quamba::launch_prefill_mfma(a, workspace, stream)
                               : quamba::launch_prefill_generic(a, stream);
     return e == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
+namespace {
+
+// Scratch area of quamba_ssd_prefill_noalloc: device memory that belongs to the library's code object, one copy per
+// GPU, held until the process ends.  16 MiB covers the sequence split of every shape the matrix-core kernel takes
+// (at most 7 * 64 (sequence, head) pairs * (64 * 128 + 1) floats).  In host code the array's name is only a handle:
+// the address kernels can use comes from hipGetSymbolAddress, once per device.
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char *> scratch_address[kMaxDevices];  // zero-initialised; concurrent first calls store the same value
+
+int scratch_of_current_device(unsigned char **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return QUAMBA_EHIP;
+    unsigned char *p = scratch_address[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return QUAMBA_EHIP;
+        p = static_cast<unsigned char *>(sym);
+        scratch_address[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return QUAMBA_OK;
+}
+
+}  // namespace
+
+extern "C" int quamba_ssd_prefill_noalloc(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,
+                                          const int8_t *x, const int8_t *B, const int8_t *C, const float *dt,
+                                          const float *A, const float *D, const float *init_state, uint16_t *y,
+                                          float *final_state, void *hip_stream)
+{
+    if (!shape) return QUAMBA_ENULL;
+    int rc = check_scales(scales);
+    if (rc != QUAMBA_OK) return rc;
+    if (!x || !B || !C || !dt || !A || !y) return QUAMBA_ENULL;
+    rc = check_shape(shape, true);
+    if (rc != QUAMBA_OK) return rc;
+    const size_t need = quamba_ssd_prefill_workspace_size(shape);
+    if (need > kScratchBytes) return QUAMBA_EWORKSPACE;
+    unsigned char *ws = nullptr;
+    if (need) {
+        rc = scratch_of_current_device(&ws);
+        if (rc != QUAMBA_OK) return rc;
+    }
+    return quamba_ssd_prefill_gated(shape, scales, nullptr, x, B, C, dt, A, D, init_state, y, final_state, ws,
+                                    need ? kScratchBytes : 0, hip_stream);
 }
 
 extern "C" int quamba_ssd_decode_step(const quamba_ssd_shape_t *shape, const quamba_ssd_scales_t *scales,

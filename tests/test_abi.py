@@ -103,6 +103,22 @@ def test_workspace_of_the_sequence_split():
     assert q.quamba_ssd_prefill_workspace_size(_shape(batch=1, seqlen=512, nheads=24, ngroups=1, **mm)) == 0
 
 
+def test_noalloc_prefill_validates_like_the_prefill():
+    lib = q.load_library()
+    dummy = C.create_string_buffer(64)
+    p = C.addressof(dummy)
+    from paper_2503_22879_amd.binding import _ScalesStruct
+    sc = _ScalesStruct(p, p, p, p, p)
+    ok = [p] * 9                               # x B C dt A D init y final
+    assert lib.quamba_ssd_prefill_noalloc(None, C.byref(sc), *ok, None) == -1
+    for i in (0, 1, 2, 3, 4, 7):               # x B C dt A y are required
+        args = list(ok)
+        args[i] = None
+        assert lib.quamba_ssd_prefill_noalloc(C.byref(_shape()), C.byref(sc), *args, None) == -1
+    assert lib.quamba_ssd_prefill_noalloc(C.byref(_shape(seqlen=0)), C.byref(sc), *ok, None) == -2
+    assert lib.quamba_ssd_prefill_noalloc(C.byref(_shape(flags=0x80)), C.byref(sc), *ok, None) == -5
+
+
 def test_decode_rejects_bad_arguments_without_a_device():
     assert _call_decode(_shape(nheads=5)) == -2
     assert _call_decode(_shape(batch=0)) == -2
