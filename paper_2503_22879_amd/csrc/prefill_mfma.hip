@@ -30,6 +30,11 @@
 // whose decay factor is below 2^-32 is left out unless QUAMBA_FLAG_NO_DECAY_SKIP is set.  The chunk's closing barrier
 // sits in front of the output epilogue, which reads registers and constant tables only.
 //
+// Batches with fewer (sequence, head) pairs than compute units are also cut along the sequence (SEG instantiations):
+// one launch walks all but the last segment with the state waves alone and leaves every segment's end state (from a
+// zero start) and decay total in the workspace, a second launch gives every segment its own workgroups, which start
+// from the combination of the earlier segments' states (Eq. 2 is linear in the state).
+//
 // All of this is Eq. 2 with A-dot = exp(dt A), B-dot = dt B (Section 3.2) regrouped; the quantization scales of
 // Section 4.1 enter only in the epilogue because x enters linearly and channel-wise and B, C have one scale per
 // state group.  The result does not depend on the chunk length, so the caller's `chunk` is not used here.
