@@ -112,7 +112,8 @@ size_t quamba_ssd_prefill_workspace_size(const quamba_ssd_shape_t *shape);
  *   A  device fp32  [nheads], <= 0           D  device fp32 [nheads] or NULL (no skip term)
  *   init_state  device fp32 [batch, nheads, headdim, d_state] or NULL (zero state)
  *   y           device fp16 [batch, seqlen, nheads, headdim]   (written, round-to-nearest-even)
- *   final_state device fp32 [batch, nheads, headdim, d_state] or NULL (not returned); may alias init_state
+ *   final_state device fp32 [batch, nheads, headdim, d_state] or NULL (not returned); may alias init_state (an update
+ *               in place; such a call is never cut along the sequence)
  *   workspace   device scratch of workspace_bytes, 16-byte aligned; NULL or fewer bytes than
  *               quamba_ssd_prefill_workspace_size(shape) select the launch that needs none
  * Any seqlen >= 1 is accepted; a last partial chunk is processed as if padded with dt = 0, x = 0 steps (identity

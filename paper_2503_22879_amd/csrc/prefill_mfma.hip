@@ -1053,8 +1053,13 @@ hipError_t launch_prefill_mfma(const SsdArgs &a_in, void *workspace, hipStream_t
     SsdArgs a = a_in;
     const bool precise = a.state != nullptr || (a.s.flags & QUAMBA_FLAG_PRECISE_STATE);
     PrefillPlan plan = prefill_mfma_plan(a.s);
-    if (plan.nseg > 1 && (!workspace || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)) {
-        // no usable workspace (the entry point passes NULL when the caller's is missing or too small): the unsplit launch
+    // A final state that overlaps the initial state (allowed: an update in place) rules the split out: the last
+    // segment's workgroups write the final state while those of the first segment may still have to read the initial one.
+    const size_t state_bytes = sizeof(float) * (size_t)a.s.batch * a.s.nheads * kP * kN;
+    const uintptr_t i0 = reinterpret_cast<uintptr_t>(a.init_state), f0 = reinterpret_cast<uintptr_t>(a.state);
+    const bool in_place = a.init_state && a.state && i0 < f0 + state_bytes && f0 < i0 + state_bytes;
+    if (plan.nseg > 1 && (in_place || !workspace || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)) {
+        // also without a usable workspace (the entry point passes NULL when the caller's is missing or too small)
         const int64_t pairs = (int64_t)a.s.batch * a.s.nheads;
         plan.nseg = 1;
         plan.channel_split = !(a.s.flags & QUAMBA_FLAG_NO_CHANNEL_SPLIT) && pairs <= (int64_t)compute_units();

@@ -154,6 +154,31 @@ def test_sequence_split_against_the_oracle_and_the_unsplit_launch(gpu_lib, H, G,
             assert np.abs(hg - hu).max() <= 2e-5 * np.abs(hu).max()
 
 
+def test_state_updated_in_place_on_a_shape_that_would_be_split(gpu_lib):
+    """final_state may be the init_state buffer.  With a sequence split the last segment would write it while the
+    first still reads it, so such a call takes the unsplit launch: bit for bit the flagged launch with two buffers."""
+    import torch
+    q = gpu_lib
+    s = W.CONFIGS["m2_130m"]
+    sc, prob, _ = make_problem(s, 33, calib_tokens=512)
+    dsc = q.DeviceScales(host_scales(q, sc))
+    t = {k: (torch.from_numpy(v).cuda() if v is not None else None) for k, v in prob.items()}
+    h0 = torch.from_numpy(W.draw_state(s, 33)).cuda()
+    ws = torch.empty(q.quamba_ssd_prefill_workspace_size(to_shape(q, s)), dtype=torch.uint8, device="cuda")
+
+    def run(flags, init, fin):
+        y = torch.full((s.batch, s.seqlen, s.nheads, s.headdim), float("nan"), dtype=torch.float16, device="cuda")
+        q.quamba_ssd_prefill(to_shape(q, s, flags=flags), dsc, t["x"], t["B"], t["C"], t["dt"], t["A"], t["D"], init, y,
+                             fin, ws)
+        torch.cuda.synchronize()
+        return y.cpu().numpy().view(np.uint16), fin.cpu().numpy()
+
+    y_ref, h_ref = run(NO_SEQ_SPLIT, h0.clone(), torch.empty_like(h0))
+    state = h0.clone()
+    y_inp, h_inp = run(0, state, state)
+    assert np.array_equal(y_inp, y_ref) and np.array_equal(h_inp, h_ref)
+
+
 def test_sequence_split_without_a_usable_workspace_takes_the_unsplit_launch(gpu_lib):
     """A missing, short or misaligned workspace is not an error: the call runs unsplit, bit for bit like the flag."""
     import torch
