@@ -46,6 +46,7 @@
 // (ds_read_b64_tr_b8 / _tr_b16), whose source lanes address whole token rows; the rows are stored with bits 2 and 3
 // of the token index swapped so that the 8 tokens of one k group are 8 consecutive rows.
 #include <algorithm>
+#include <climits>
 #include <atomic>
 
 #include "quamba_internal.h"
@@ -293,6 +294,17 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
     // every other group of 8 workgroup ids (one id per XCD) walks the blocks in the opposite order, so that the long
     // and the short blocks of different workgroups are spread over the SIMDs.
     const int rot_flip = ((bid >> 3) & 1) ? (kNBlk - 1) : 0;
+    // Two workgroups share a compute unit, and its SIMDs favour the waves of the one dispatched first: that one would
+    // finish well before the other, which then runs alone at less than the unit's paired throughput.  Workgroups are
+    // dispatched in id order, one per compute unit and round; when the host asks for it (a launch of at most two
+    // rounds, all resident at once), those of the second round (ids from pace_first on) raise their priority in every
+    // other chunk, which lets the pair advance at about the same pace.
+    auto set_chunk_priority = [&](int c) {
+        if ((int)blockIdx.x >= a.pace_first) {  // never without pacing: pace_first is then INT_MAX
+            if (c & 1) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
+    };
 
     const float Ah = a.A[h] * 1.44269504088896340736f;  // log2(e): prefix sums are kept in log2 units (exp2 below)
     const float Dh = a.D ? a.D[h] : 0.0f;
@@ -349,6 +361,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
         fill_tables();
         if (convert_init) __syncthreads();  // the state waves wait for the scales
         for (int c = c_begin; c < c_end; ++c) {
+            set_chunk_priority(c);
             const int t0 = c * kQ;
             const int nv = min(kQ, L - t0);
             const size_t tokbase = (size_t)b * L + t0;
@@ -726,6 +739,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
             }
         }
         for (int c = c_begin; c < c_end; ++c) {
+            set_chunk_priority(c);
             const int t0 = c * kQ;
             const int nv = min(kQ, L - t0);
             // ---- the first wave turns dt into everything the chunk needs of it: the inclusive prefix sum of dt*A
@@ -1073,6 +1087,16 @@ hipError_t launch_prefill_mfma(const SsdArgs &a_in, void *workspace, hipStream_t
     a.seg_pass = 0;
     a.seg_state = nullptr;
     a.seg_decay = nullptr;
+    // Pacing of the two workgroups of a compute unit (see the kernel) pays when the whole launch is resident at once and
+    // most compute units hold two workgroups that each walk many chunks; with more workgroups than that, the early finish
+    // of the first arrivals is what lets the rest start, and pacing costs time (measured on 640 pairs).
+    const int cus = compute_units();
+    auto pace = [&](int segs, int chunks_per_wg) {
+        const int64_t wgs = (int64_t)a.s.batch * a.s.nheads * (plan.channel_split ? 2 : 1) * segs;
+        return (wgs > cus + cus / 2 && wgs <= 2 * (int64_t)cus && chunks_per_wg >= 8) ? cus : INT_MAX;
+    };
+    const int nchunks = (a.s.seqlen + kQ - 1) / kQ;
+    a.pace_first = pace(1, nchunks);
     if (plan.nseg < 2) return launch(a);
 
     const size_t pairs = (size_t)a.s.batch * a.s.nheads;
@@ -1082,6 +1106,8 @@ hipError_t launch_prefill_mfma(const SsdArgs &a_in, void *workspace, hipStream_t
     a.seg_decay = a.seg_state + (size_t)(plan.nseg - 1) * pairs * kP * kN;
     // first launch: the states at the ends of segments 0 .. nseg-2 (no outputs, no gate, no final state)
     SsdArgs pass = a;
+    pass.pace_first = pace(plan.nseg - 1, plan.seg_chunks);
+    a.pace_first = pace(plan.nseg, plan.seg_chunks);
     pass.seg_pass = 1;
     pass.z = nullptr;
     pass.y = nullptr;

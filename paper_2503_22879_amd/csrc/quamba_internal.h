@@ -39,6 +39,9 @@ struct SsdArgs {
     int32_t seg_pass;
     float *seg_state;          // [nseg-1][batch*nheads][headdim][d_state], in the kernel's accumulator units
     float *seg_decay;          // [nseg-1][batch*nheads]
+    int32_t pace_first;        // matrix-core prefill: first workgroup id of the second dispatch round when the two
+                               // workgroups of a compute unit are to be kept at the same pace (see the kernel), else
+                               // INT_MAX
 };
 
 // Plan of the sequence split for a shape on the current device: segments (1 = no split), chunks per segment, and
