@@ -49,7 +49,7 @@ quamba::SsdArgs pack(const quamba_ssd_shape_t *s, const quamba_ssd_scales_t *sc,
     a.state = state;
     a.y = y;
     a.z = nullptr; a.z_scale = 0.0f; a.dt_q = nullptr; a.dt_scale = 0.0f; a.dt_bias = nullptr;
-    a.nseg = 1; a.seg_chunks = 0; a.seg_pass = 0; a.seg_state = nullptr; a.seg_decay = nullptr; a.pace_first = 0x7fffffff;
+    a.nseg = 1; a.seg_chunks = 0; a.seg_state = nullptr; a.seg_decay = nullptr; a.pace_first = 0x7fffffff;
     return a;
 }
 

@@ -30,10 +30,10 @@
 // whose decay factor is below 2^-32 is left out unless QUAMBA_FLAG_NO_DECAY_SKIP is set.  The chunk's closing barrier
 // sits in front of the output epilogue, which reads registers and constant tables only.
 //
-// Batches with fewer (sequence, head) pairs than compute units are also cut along the sequence (SEG instantiations):
-// one launch walks all but the last segment with the state waves alone and leaves every segment's end state (from a
-// zero start) and decay total in the workspace, a second launch gives every segment its own workgroups, which start
-// from the combination of the earlier segments' states (Eq. 2 is linear in the state).
+// Batches with fewer (sequence, head) pairs than compute units are also cut along the sequence: a first kernel
+// (segment_state_kernel) walks all but the last segment without outputs and leaves every segment's end state (from a
+// zero start) and decay total in the workspace, then this kernel (SEG instantiations) gives every segment its own
+// workgroups, which start from the combination of the earlier segments' states (Eq. 2 is linear in the state).
 //
 // All of this is Eq. 2 with A-dot = exp(dt A), B-dot = dt B (Section 3.2) regrouped; the quantization scales of
 // Section 4.1 enter only in the epilogue because x enters linearly and channel-wise and B, C have one scale per
@@ -261,7 +261,6 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
     const int nchunks = (L + kQ - 1) / kQ;
     const int c_begin = SEG ? seg * a.seg_chunks : 0;
     const int c_end = (SEG && seg + 1 < a.nseg) ? c_begin + a.seg_chunks : nchunks;
-    const bool state_pass = SEG && a.seg_pass != 0;  // this launch only carries the state to the end of its segments
     const bool convert_init = a.init_state && (!SEG || seg == 0);  // the caller's initial state belongs to segment 0
     // with two workgroups per head, ids i and i + 8 (same XCD, and the same compute unit when two workgroups fit one)
     // take the two halves of a head
@@ -332,15 +331,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
     const uint32_t x_row = (uint32_t)H * kP, b_row = (uint32_t)G * kN, dt_row = (uint32_t)H * 4u;
     typedef uint32_t xvec __attribute__((ext_vector_type(PT)));
 
-    if (out_role && state_pass) {
-        // a launch without outputs: these waves only fill the tables and keep the barriers of every chunk
-        fill_tables();
-        if (convert_init) __syncthreads();
-        for (int c = c_begin; c < c_end; ++c) {
-            __syncthreads();
-            __syncthreads();
-        }
-    } else if (out_role) {
+    if (out_role) {
         // ================= output waves: wave w produces the outputs of one 32-token block per chunk =================
         // C rows of the wave's block of chunk c (operand of G^T, and, as fp16, of the carried-state product), loaded a
         // chunk ahead.  k-step kk of the G^T product covers states 32 kk + 16 hb + [0,16): the two half-waves read
@@ -697,8 +688,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
             }
         };
         issue_loads(c_begin);
-        float seg_cum = 0.0f;  // sum of the chunks' dt*A*log2(e) totals (state pass, first state wave)
-        if (SEG && seg > 0 && !state_pass) {
+        if (SEG && seg > 0) {
             // Start state of segment seg from the state pass: with local_j the state segment j ends with when started
             // from zero (segment 0: from the caller's initial state) and d_j the sum of dt*A*log2(e) over its tokens,
             //   H = local_{seg-1} + 2^{d_{seg-1}} local_{seg-2} + 2^{d_{seg-1} + d_{seg-2}} local_{seg-3} + ...
@@ -771,8 +761,6 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 float loc1;
                 const float cum1 = wave_inclusive_scan(a0 + a1, loc1), cum0 = cum1 - a1;
                 const float loc0 = loc1 - a1;
-                if (state_pass)  // the segment's total: the chunk's prefix sum at its last token
-                    seg_cum += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cum1), 63));
                 const float m_loc = __shfl(loc1, lane | 15, 64);
                 // weights towards the output accumulators
                 const float d0 = dt0 * (kAcc / kXs), d1 = dt1 * (kAcc / kXs);
@@ -927,24 +915,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
             __syncthreads();  // the output waves are done with x, B, the weights and the fp16 state of this chunk
         }
 
-        if (state_pass) {
-            // the state at the end of the segment, as it stands in the accumulators, and the segment's decay total
-            const size_t pairs = (size_t)a.s.batch * H;
-            float *dst = a.seg_state + ((size_t)seg * pairs + bh) * kP * kN;
-#pragma unroll
-            for (int pt = 0; pt < PT; ++pt) {
-                const int p = pt * 32 + l32;
-#pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    const int n0 = 32 * wave + 8 * rg + 4 * hb;
-                    f32x4 v;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[i] = st[pt][4 * rg + i];
-                    *reinterpret_cast<f32x4 *>(dst + (size_t)(p_base + p) * kN + n0) = v;
-                }
-            }
-            if (wave == 0 && lane == 0 && half == 0) a.seg_decay[(size_t)seg * pairs + bh] = seg_cum;
-        } else if (a.state && (!SEG || seg + 1 == a.nseg)) {
+        if (a.state && (!SEG || seg + 1 == a.nseg)) {
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt) {
                 const int p = pt * 32 + l32;
@@ -962,6 +933,310 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
     }
 }
 
+
+// ---- State pass of the sequence split ----
+// One workgroup of four waves carries the state of one (sequence, head) (or channel half) through the chunks of one
+// segment, from zero (segment 0: from the caller's initial state), and leaves it in the workspace as it stands in the
+// accumulators, with the segment's decay total.  Staging, token weights and the state update are those of the state
+// waves of prefill_mfma_kernel (same operations in the same order on the same values).  There are no outputs and a
+// launch has one or two workgroups per compute unit, so nothing hides latency but the wave itself: the global loads
+// of kStateDepth chunks are in flight, each chunk's in a register set of its own, and the LDS operands of a group of
+// 16 tokens are requested one group ahead of their use.  Measured per chunk and workgroup (cycles): staging 640,
+// barrier 260, issuing the next loads 640, state update 2090, barrier 160; a lone wave issues a vector instruction
+// every 8 cycles and an LDS instruction every 12, which is what these phases add up to.  Eight waves that split a
+// chunk's tokens between two copies of the state were not faster (the phases are serial between the barriers and
+// the two waves of a SIMD share its LDS and memory paths).
+constexpr int kStateThreads = 256;
+constexpr int kStateDepth = 2;
+
+template <int PT>
+struct StateLds {
+    static constexpr int kXsStride = Lds<PT>::kXsStride;
+    static constexpr int kOffCum = 0;                       // float[128]
+    static constexpr int kOffWs = kOffCum + 4 * kQ;         // fp16[128]
+    static constexpr int kOffWd = kOffWs + 2 * kQ;          // fp16[128]
+    static constexpr int kOffBq = kOffWd + 2 * kQ;          // int8 [128][144]
+    static constexpr int kOffXs = kOffBq + kQ * kBqStride;  // fp16 [128][kXsStride]
+    static constexpr int kBytes = kOffXs + 2 * kQ * kXsStride;
+    static_assert(kOffBq % 16 == 0 && kOffXs % 16 == 0, "LDS arrays must be 16-byte aligned");
+};
+
+template <bool PRECISE, int PT>
+__global__ __launch_bounds__(kStateThreads, 2) void segment_state_kernel(SsdArgs a)
+{
+    typedef StateLds<PT> LY;
+    constexpr int kXsStride = LY::kXsStride;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float *s_cum = reinterpret_cast<float *>(smem + LY::kOffCum);
+    _Float16 *s_ws = reinterpret_cast<_Float16 *>(smem + LY::kOffWs);
+    _Float16 *s_wd = reinterpret_cast<_Float16 *>(smem + LY::kOffWd);
+    unsigned char *s_bq = smem + LY::kOffBq;
+    unsigned char *s_xs = smem + LY::kOffXs;
+
+    const int L = a.s.seqlen, H = a.s.nheads, G = a.s.ngroups;
+    const int wgs_per_seg = a.s.batch * H * (2 / PT);
+    const int seg = (int)blockIdx.x / wgs_per_seg;  // 0 .. nseg-2
+    const int c_begin = seg * a.seg_chunks, c_end = c_begin + a.seg_chunks;
+    const int bid = (int)blockIdx.x - seg * wgs_per_seg;
+    int pair = bid, half = 0;  // as in prefill_mfma_kernel
+    if (PT == 1) {
+        const int npairs = a.s.batch * H, full = npairs >> 3;
+        if (bid < 16 * full) {
+            pair = (bid & 7) | ((bid >> 4) << 3);
+            half = (bid >> 3) & 1;
+        } else {
+            const int t = bid - 16 * full, r = npairs - 8 * full;
+            pair = 8 * full + t % r;
+            half = t / r;
+        }
+    }
+    const int p_base = 32 * half;
+    const int bh = block_to_bh(a, pair);
+    const int b = bh / H, h = bh - b * H, g = h / (H / G);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, hb = lane >> 5;
+    const float Ah = a.A[h] * 1.44269504088896340736f;
+    const float dead = (a.s.flags & QUAMBA_FLAG_NO_DECAY_SKIP) ? __builtin_inff() : kDead;
+    const uint32_t x_row = (uint32_t)H * kP, b_row = (uint32_t)G * kN, dt_row = (uint32_t)H * 4u;
+    typedef uint32_t xvec __attribute__((ext_vector_type(PT)));
+
+    f32x16 st[PT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[pt][r] = 0.0f;
+
+    struct LoadSet {
+        xvec xr[4];
+        u32x4 br[4];
+        float dt0, dt1;
+    };
+    LoadSet sets[kStateDepth];
+    const int xs4 = tid >> 3, xp8 = tid & 7;
+    const int bs4 = tid >> 3, bn16 = tid & 7;
+    // Every chunk of the state pass is complete (only the last segment, which this kernel does not walk, can end in a
+    // partial chunk), so a thread's rows sit at fixed offsets from the chunk's first token.
+    uint32_t x_off[4], b_off[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        x_off[k] = (uint32_t)(4 * xs4 + k) * x_row + (uint32_t)(4 * PT) * xp8;
+        b_off[k] = (uint32_t)(4 * bs4 + k) * b_row + 16u * bn16;
+    }
+    const uint32_t dt_off = (uint32_t)(2 * lane) * dt_row, dq_off = (uint32_t)(2 * lane) * (uint32_t)H;
+    auto issue_loads = [&](int c, LoadSet &ls) {
+        const size_t tokbase = (size_t)b * L + (size_t)c * kQ;
+        const int8_t *xbase = a.x + (tokbase * H + h) * kP + p_base;
+        const int8_t *bbase = a.B + (tokbase * G + g) * kN;
+        // every wave issues the same loads (only the first uses dt): a wait for one set's registers is then an exact
+        // count of the younger loads, and leaves those of the other sets in flight
+        ls.dt0 = ls.dt1 = 0.0f;
+        if (wave == 0) {
+            if (a.dt_q) {
+                const int8_t *qbase = a.dt_q + tokbase * H + h;
+                ls.dt0 = __builtin_bit_cast(float, (int)qbase[dq_off]);
+                ls.dt1 = __builtin_bit_cast(float, (int)qbase[dq_off + (uint32_t)H]);
+            } else {
+                const char *dbase = reinterpret_cast<const char *>(a.dt + tokbase * H + h);
+                ls.dt0 = *reinterpret_cast<const float *>(dbase + dt_off);
+                ls.dt1 = *reinterpret_cast<const float *>(dbase + dt_off + dt_row);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) ls.xr[k] = *reinterpret_cast<const xvec *>(xbase + x_off[k]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) ls.br[k] = *reinterpret_cast<const u32x4 *>(bbase + b_off[k]);
+    };
+    // Loads are issued unconditionally (past the segment's end: its last chunk once more, unused), for the same reason.
+#pragma unroll
+    for (int k = 0; k < kStateDepth; ++k) issue_loads(min(c_begin + k, c_end - 1), sets[k]);
+
+    if (a.init_state && seg == 0) {
+        // the caller's initial state in accumulator units: the same arithmetic as in prefill_mfma_kernel
+        const float sB = a.B_scales[g], sC = a.C_scales[g];
+        const float y_scale = sB * sC * (1.0f / (kNarrow * kAcc));
+        const float Dh = a.D ? a.D[h] : 0.0f;
+        const float d_acc = Dh / (y_scale * kXs);
+        const bool d_by_mfma = fabsf(d_acc) < 3.0e4f;
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) {
+            const int p = pt * 32 + l32;
+            const float sx = x_scale_lookup(a, h, p_base + p) * (d_by_mfma ? y_scale : 1.0f);
+            const float inv = kNarrow * (d_by_mfma ? y_scale : 1.0f) / (sx * sB);
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int n0 = 32 * wave + 8 * rg + 4 * hb;
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(a.init_state + ((size_t)bh * kP + p_base + p) * kN + n0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) st[pt][4 * rg + i] = v[i] * inv;
+            }
+        }
+    }
+
+    float seg_cum = 0.0f;  // sum of the chunks' dt*A*log2(e) totals (first wave)
+    auto stage = [&](LoadSet &ls) {
+        if (wave == 0) {
+            float dt0 = ls.dt0, dt1 = ls.dt1;
+            if (a.dt_q) {  // step size = softplus(s_dt * code + bias) (Section 3.2)
+                const float bias = a.dt_bias ? a.dt_bias[h] : 0.0f;
+                const float v0 = a.dt_scale * (float)__builtin_bit_cast(int, dt0) + bias;
+                const float v1 = a.dt_scale * (float)__builtin_bit_cast(int, dt1) + bias;
+                dt0 = fmaxf(v0, 0.0f) + log1pf(expf(-fabsf(v0)));
+                dt1 = fmaxf(v1, 0.0f) + log1pf(expf(-fabsf(v1)));
+            }
+            const float a0 = dt0 * Ah, a1 = dt1 * Ah;
+            float loc1;
+            const float cum1 = wave_inclusive_scan(a0 + a1, loc1), cum0 = cum1 - a1;
+            const float loc0 = loc1 - a1;
+            const float cum_last = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cum1), 63));
+            seg_cum += cum_last;
+            const float q0 = dt0 * (kNarrow / kXs), q1 = dt1 * (kNarrow / kXs);
+            *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
+            if (!PRECISE) {
+                *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) =
+                    (f16x2){(_Float16)(exp2_fast(cum_last - cum0) * q0), (_Float16)(exp2_fast(cum_last - cum1) * q1)};
+            } else {
+                const float m_loc = __shfl(loc1, lane | 15, 64);
+                const float e0 = exp2_fast(m_loc - loc0), e1 = exp2_fast(m_loc - loc1);
+                const float w[2] = {e0 * q0, e1 * q1};
+                f16x2 wq, wd;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const float q =
+                        __builtin_bit_cast(float, (__builtin_bit_cast(uint32_t, w[i]) + 0x00080000u) & 0xfff00000u);
+                    wq[i] = (_Float16)q;
+                    wd[i] = (_Float16)(q > 0.0f ? (w[i] - q) / q : 0.0f);
+                }
+                *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) = wq;
+                *reinterpret_cast<f16x2 *>(s_wd + 2 * lane) = wd;
+            }
+        }
+        {
+            const int s0 = 4 * xs4, row0 = tok_pos(s0);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const xvec w = ls.xr[k];
+                unsigned char *xs_row = s_xs + ((row0 + k) * kXsStride + 4 * PT * xp8) * 2;
+#pragma unroll
+                for (int q = 0; q < PT; ++q) *reinterpret_cast<f16x4 *>(xs_row + 8 * q) = i8x4_to_f16_xs(w[q]);
+            }
+        }
+        {
+            const int row0 = tok_pos(4 * bs4);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                *reinterpret_cast<u32x4 *>(s_bq + (row0 + k) * kBqStride + 16 * bn16) = ls.br[k];
+        }
+    };
+    // The LDS operands of the next group of 16 tokens are requested before the current group is converted and
+    // multiplied: the workgroup has one wave per SIMD, so nothing else hides the LDS latency.
+    struct StepOps {
+        u32x2 bw;
+        f16x8 wv, wd, xb[PT];
+    };
+    const int i16s = lane & 15, c16s = (lane >> 4) & 1;
+    const unsigned char *bq_src = s_bq + (8 * hb + (i16s >> 1)) * kBqStride + 32 * wave + 16 * c16s + 8 * (i16s & 1);
+    const int xs_off = ((8 * hb + (i16s >> 2)) * kXsStride + 16 * c16s + 4 * (i16s & 3)) * 2;
+    auto update = [&]() {
+        auto fetch = [&](int step, StepOps &o) {  // step = 2 sb + ks: tokens 16 step .. 16 step + 15
+            const int row = 16 * step;
+            o.bw = lds_read_tr8(bq_src + row * kBqStride);
+            // weights of the 8 tokens of this k group: tokens row + 4 hb + [0,4) and row + 8 + 4 hb + [0,4)
+            o.wv = __builtin_shufflevector(*reinterpret_cast<const f16x4 *>(s_ws + row + 4 * hb),
+                                           *reinterpret_cast<const f16x4 *>(s_ws + row + 8 + 4 * hb), 0, 1, 2, 3, 4, 5, 6,
+                                           7);
+            if (PRECISE)
+                o.wd = __builtin_shufflevector(*reinterpret_cast<const f16x4 *>(s_wd + row + 4 * hb),
+                                               *reinterpret_cast<const f16x4 *>(s_wd + row + 8 + 4 * hb), 0, 1, 2, 3, 4,
+                                               5, 6, 7);
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt)
+                o.xb[pt] = lds_read_tr16x8<kXsStride>(s_xs + xs_off + (row * kXsStride + 32 * pt) * 2);
+        };
+        StepOps ops[2];
+        fetch(0, ops[0]);
+        const float cum_last = s_cum[kQ - 1];
+        if (!PRECISE) {
+            const float gdec = exp2_fast(cum_last);
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
+        }
+        float m_prev = 0.0f;
+#pragma unroll
+        for (int step = 0; step < 2 * kNBlk; ++step) {
+            const int sb = step >> 1;
+            if (step + 1 < 2 * kNBlk) fetch(step + 1, ops[(step + 1) & 1]);
+            const StepOps &o = ops[step & 1];
+            const float m = s_cum[sb * kBlk + kBlk - 1];
+            if (PRECISE && (step & 1) == 0) {
+                const float gdec = exp2_fast(m - m_prev);
+                m_prev = m;
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
+            }
+            // what this block adds decays by exp2(cum_last - m) before the chunk ends: dead blocks only decay
+            const bool skip = __builtin_amdgcn_readfirstlane(cum_last - m < -dead);
+            if (!skip) {
+                const f16x8 bf = i8x8_to_f16(o.bw[0], o.bw[1]) * o.wv;  // two-term path: exact (7 bits times 4 bits)
+                if (PRECISE) {
+                    const f16x8 bfd = bf * o.wd;  // the small term, rounded
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt) {
+                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, o.xb[pt], st[pt], 0, 0, 0);
+                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bfd, o.xb[pt], st[pt], 0, 0, 0);
+                    }
+                } else {
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt)
+                        st[pt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf, o.xb[pt], st[pt], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    int c = c_begin;
+    for (; c + kStateDepth <= c_end; c += kStateDepth) {
+#pragma unroll
+        for (int k = 0; k < kStateDepth; ++k) {
+            stage(sets[k]);
+            __syncthreads();  // the chunk is staged
+            issue_loads(min(c + k + kStateDepth, c_end - 1), sets[k]);
+            update();
+            __syncthreads();  // every wave is done with the staged chunk
+        }
+    }
+    // the remaining chunks (fewer than kStateDepth) are in flight already
+#pragma unroll
+    for (int k = 0; k + 1 < kStateDepth; ++k) {
+        if (c + k < c_end) {  // uniform over the workgroup
+            stage(sets[k]);
+            __syncthreads();
+            update();
+            __syncthreads();
+        }
+    }
+
+    const size_t pairs = (size_t)a.s.batch * H;
+    float *dst = a.seg_state + ((size_t)seg * pairs + bh) * kP * kN;
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+        const int p = pt * 32 + l32;
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const int n0 = 32 * wave + 8 * rg + 4 * hb;
+            f32x4 v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = st[pt][4 * rg + i];
+            *reinterpret_cast<f32x4 *>(dst + (size_t)(p_base + p) * kN + n0) = v;
+        }
+    }
+    if (wave == 0 && lane == 0 && half == 0) a.seg_decay[(size_t)seg * pairs + bh] = seg_cum;
+}
+
 }  // namespace
 
 bool prefill_mfma_supports(const quamba_ssd_shape_t &s) { return s.headdim == kP && s.d_state == kN; }
@@ -972,8 +1247,7 @@ template <bool PRECISE, int PT, bool GATED, bool SEG>
 hipError_t launch_scan_seg(const SsdArgs &a, hipStream_t stream)
 {
     constexpr int lds = GATED ? Lds<PT>::kBytesGated : Lds<PT>::kBytes;
-    // one set of workgroups per segment; the state pass leaves the last segment out
-    const int segs = a.nseg > 1 ? (a.seg_pass ? a.nseg - 1 : a.nseg) : 1;
+    const int segs = a.nseg > 1 ? a.nseg : 1;  // one set of workgroups per segment
     const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT) * segs));
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_mfma_kernel<PRECISE, PT, GATED, SEG>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -993,6 +1267,16 @@ template <bool PRECISE, int PT>
 hipError_t launch_scan(const SsdArgs &a, hipStream_t stream)
 {
     return a.z ? launch_scan_gated<PRECISE, PT, true>(a, stream) : launch_scan_gated<PRECISE, PT, false>(a, stream);
+}
+
+// The state pass of a sequence split: segments 0 .. nseg-2, one workgroup per (segment, sequence, head or channel half).
+template <bool PRECISE, int PT>
+hipError_t launch_segment_state(const SsdArgs &a, hipStream_t stream)
+{
+    constexpr int lds = StateLds<PT>::kBytes;
+    const dim3 grid((unsigned)(a.s.batch * a.s.nheads * (2 / PT) * (a.nseg - 1)));
+    hipLaunchKernelGGL((segment_state_kernel<PRECISE, PT>), grid, dim3(kStateThreads), lds, stream, a);
+    return hipGetLastError();
 }
 
 // Compute units of the current device (cached per device id).
@@ -1084,7 +1368,6 @@ hipError_t launch_prefill_mfma(const SsdArgs &a_in, void *workspace, hipStream_t
     };
     a.nseg = 1;
     a.seg_chunks = 0;
-    a.seg_pass = 0;
     a.seg_state = nullptr;
     a.seg_decay = nullptr;
     // Pacing of the two workgroups of a compute unit (see the kernel) pays when the whole launch is resident at once and
@@ -1104,17 +1387,15 @@ hipError_t launch_prefill_mfma(const SsdArgs &a_in, void *workspace, hipStream_t
     a.seg_chunks = plan.seg_chunks;
     a.seg_state = static_cast<float *>(workspace);
     a.seg_decay = a.seg_state + (size_t)(plan.nseg - 1) * pairs * kP * kN;
-    // first launch: the states at the ends of segments 0 .. nseg-2 (no outputs, no gate, no final state)
-    SsdArgs pass = a;
-    pass.pace_first = pace(plan.nseg - 1, plan.seg_chunks);
     a.pace_first = pace(plan.nseg, plan.seg_chunks);
-    pass.seg_pass = 1;
-    pass.z = nullptr;
-    pass.y = nullptr;
-    pass.state = nullptr;
-    hipError_t e = launch(pass);
+    // first kernel: the states at the ends of segments 0 .. nseg-2 (it reads x, B, dt, A and the initial state only)
+    hipError_t e;
+    if (precise)
+        e = plan.channel_split ? launch_segment_state<true, 1>(a, stream) : launch_segment_state<true, 2>(a, stream);
+    else
+        e = plan.channel_split ? launch_segment_state<false, 1>(a, stream) : launch_segment_state<false, 2>(a, stream);
     if (e != hipSuccess) return e;
-    // second launch: every segment with its own workgroups
+    // then every segment with its own workgroups
     return launch(a);
 }
 

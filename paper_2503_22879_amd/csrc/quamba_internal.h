@@ -29,14 +29,13 @@ struct SsdArgs {
     const int8_t *dt_q;        // codes of the step size's pre-activation, laid out like dt (dt is then unused)
     float dt_scale;
     const float *dt_bias;      // [nheads] or null
-    // Sequence split of the chunked prefill (matrix-core kernel only; nseg == 1: none).  The sequence is cut into nseg
-    // segments of seg_chunks 128-token chunks (the last takes the rest).  A first launch (seg_pass == 1) walks
-    // segments 0 .. nseg-2 without producing outputs and leaves, per segment, the state it ends with when started
-    // from zero (segment 0: from init_state) and the sum of dt*A*log2(e) over its tokens; the second launch
-    // (seg_pass == 0) gives every segment its own workgroups, which start from the combination of those.
+    // Sequence split of the chunked prefill (matrix-core kernels only; nseg == 1: none).  The sequence is cut into nseg
+    // segments of seg_chunks 128-token chunks (the last takes the rest).  A first kernel walks segments 0 .. nseg-2
+    // without producing outputs and leaves, per segment, the state it ends with when started from zero (segment 0:
+    // from init_state) and the sum of dt*A*log2(e) over its tokens; the prefill kernel then gives every segment its
+    // own workgroups, which start from the combination of those.
     int32_t nseg;
     int32_t seg_chunks;
-    int32_t seg_pass;
     float *seg_state;          // [nseg-1][batch*nheads][headdim][d_state], in the kernel's accumulator units
     float *seg_decay;          // [nseg-1][batch*nheads]
     int32_t pace_first;        // matrix-core prefill: first workgroup id of the second dispatch round when the two
