@@ -154,6 +154,39 @@ def test_sequence_split_against_the_oracle_and_the_unsplit_launch(gpu_lib, H, G,
             assert np.abs(hg - hu).max() <= 2e-5 * np.abs(hu).max()
 
 
+def _random_split_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        G = int(rng.choice([1, 2, 4]))
+        H = G * int(rng.choice([1, 2, 3, 5]))
+        cases.append((int(rng.choice([1, 1, 2, 3])), H, G, int(rng.integers(1024, 3000)),
+                      int(rng.choice([0, 0, 0x2, NO_SPLIT, NO_SPLIT | 0x8, 0x8, 0x2 | 0x8])), int(rng.integers(1, 10 ** 6)),
+                      bool(rng.integers(0, 2)), bool(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("b,H,G,L,flags,seed,want_state,use_init", _random_split_cases(24, 2503))
+def test_sequence_split_on_drawn_shapes(gpu_lib, b, H, G, L, flags, seed, want_state, use_init):
+    """Drawn small batches of 1024..3000 tokens, all of which the plan cuts along the sequence (state-pass kernel with
+    whole heads or channel halves, single- or two-term state update, odd and even chunk counts per segment, ragged
+    last chunks), with step sizes spread over e^-3 .. e^3 per head: against the oracle."""
+    q = gpu_lib
+    s = W.CONFIGS["m2_130m"].with_(batch=b, seqlen=L, nheads=H, ngroups=G)
+    assert q.quamba_ssd_prefill_workspace_size(to_shape(q, s, flags=flags)) > 0
+    sc, prob, _ = make_problem(s, seed, calib_tokens=128)
+    rng = np.random.default_rng(seed)
+    prob = dict(prob)
+    prob["dt"] = np.minimum(prob["dt"] * np.exp(rng.uniform(-3, 3.0, size=H)).astype(np.float32)[None, None, :],
+                            20.0).astype(np.float32)
+    h0 = (0.05 * rng.standard_normal((b, H, s.headdim, s.d_state))).astype(np.float32) if use_init else None
+    yref, href, _ = oracle.ref_prefill(sc, prob["x"], prob["B"], prob["C"], prob["dt"], prob["A"], prob["D"],
+                                       init_state=None if h0 is None else h0.astype(np.float64), want_state=want_state)
+    yg, hg = run_prefill(q, s, sc, prob, flags, init_state=h0, want_state=want_state)
+    check(yg, hg, yref, href if want_state else None,
+          f"drawn split b={b} H={H} G={G} L={L} flags={flags} state={want_state} init={use_init}")
+
+
 def test_state_updated_in_place_on_a_shape_that_would_be_split(gpu_lib):
     """final_state may be the init_state buffer.  With a sequence split the last segment would write it while the
     first still reads it, so such a call takes the unsplit launch: bit for bit the flagged launch with two buffers."""
