@@ -265,6 +265,28 @@ def shader_clock_under_load(q, torch, dev, fn, launches=60):
     return float(v[0]) / float(v[1]) * 100.0 if v[1] > 0 else None
 
 
+def xcd_clocks_under_load(q, torch, dev, fn, launches=60):
+    """Shader clock per XCD in MHz while fn runs back to back (see shader_clock_under_load): eight one-wave workgroups,
+    which the hardware deals out to the eight XCDs in turn.  Returns a list indexed by the XCD id each wave read back,
+    or None where a wave did not report."""
+    out = torch.full((8, 3), -1, dtype=torch.int64, device=dev)
+    side = torch.cuda.Stream(device=dev)
+    torch.cuda.synchronize()
+    for _ in range(launches // 3):
+        fn()
+    with torch.cuda.stream(side):
+        q.quamba_probe_clock_xcd(out, 100000, stream=side)
+    for _ in range(launches - launches // 3):
+        fn()
+    torch.cuda.synchronize()
+    v = out.cpu().numpy()
+    res = [None] * 8
+    for cyc, ticks, xcd in v:
+        if ticks > 0 and 0 <= xcd < 8:
+            res[int(xcd)] = round(float(cyc) / float(ticks) * 100.0, 1)
+    return res
+
+
 def prefill_leg(q, torch, dev, s, seed, steps, warmup, args, headline):
     """One prefill workload: inputs made with the library's offline entry points, K timed launches on rotating input
     and output sets (the second set is the first rolled by one sequence, or by 1024 tokens for a single sequence, so
@@ -328,6 +350,7 @@ def prefill_leg(q, torch, dev, s, seed, steps, warmup, args, headline):
     ms, wall_ms = time_region(torch, prefill, steps, warmup, min_warm_ms=SPIN_UP_MS,
                               power_key="prefill" if headline else None)
     clock_mhz = shader_clock_under_load(q, torch, dev, prefill) if side_legs else None
+    xcd_mhz = xcd_clocks_under_load(q, torch, dev, prefill) if side_legs else None
     ms_skip = None
     if side_legs and not args.no_decay_skip_leg:
         ms_skip, _ = time_region(torch, prefill_skip, steps, warmup, min_warm_ms=SPIN_UP_MS)
@@ -363,6 +386,7 @@ def prefill_leg(q, torch, dev, s, seed, steps, warmup, args, headline):
         "bytes_per_input_and_output_set": int(sum(v.numel() * v.element_size() for v in t0.values()) +
                                               ys[0].numel() * 2),
         "shader_clock_mhz": clock_mhz,
+        "shader_clock_mhz_per_xcd": xcd_mhz,
         # batches too short to fill the chip are cut along the sequence (two launches: a state pass over all but the last
         # segment, then one set of workgroups per segment); the workspace holds the segment states
         "sequence_split": {"workspace_bytes": int(ws_need),
@@ -491,6 +515,7 @@ def main() -> int:
                            "timed launches again (ms_per_step, value); HIP events on the launch stream; consecutive "
                            "launches rotate over the input/output sets" % SPIN_UP_MS,
         "shader_clock_mhz": pre["shader_clock_mhz"],
+        "shader_clock_mhz_per_xcd": pre.get("shader_clock_mhz_per_xcd"),
         "sustained_ms_per_step": (BOARD_POWER_W.get("prefill") or {}).get("sustained_ms_per_call"),
         "prefill_decay_skip": pre.get("prefill_decay_skip"),
         "prefill_zero_codes": pre.get("zero_codes"),

@@ -48,6 +48,13 @@ int quamba_probe_stream_read(const void *buf, size_t n_bytes, uint32_t *sink, vo
  * Errors: QUAMBA_ENULL, QUAMBA_EINVAL, QUAMBA_EHIP. */
 int quamba_probe_clock(int64_t *out, int spin_iters, void *stream);
 
+/* The same probe on n workgroups of one wave each, which the hardware hands to the XCDs in turn: out (device,
+ * n x 3 x 8 bytes) receives per workgroup the shader clocks, the ticks of 10 ns and the id of the XCD the wave ran on
+ * (hardware register XCC_ID).  The XCDs of one chip run at different clocks under a power-limited load, and a launch
+ * that gives every XCD the same work ends with the slowest one; n = 8 covers the 8 XCDs of an MI355X.
+ * Errors: QUAMBA_ENULL, QUAMBA_EINVAL (n outside 1..64, spin_iters <= 0), QUAMBA_EHIP. */
+int quamba_probe_clock_xcd(int64_t *out, int n, int spin_iters, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

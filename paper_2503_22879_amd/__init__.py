@@ -13,7 +13,7 @@ from .binding import (QuambaError, Shape, HostScales, DeviceScales, Gate, load_l
                       quamba_strerror, FLAG_GENERIC_KERNEL, FLAG_PRECISE_STATE, FLAG_NO_CHANNEL_SPLIT, FLAG_NO_DECAY_SKIP,
                       FLAG_NO_SEQ_SPLIT,
                       EXPORTED_SYMBOLS, quamba_probe_mfma, quamba_probe_stream_rmw, quamba_probe_stream_read,
-                      quamba_probe_clock)
+                      quamba_probe_clock, quamba_probe_clock_xcd)
 
 __all__ = ["QuambaError", "Shape", "HostScales", "DeviceScales", "Gate", "load_library", "library_path",
            "quamba_ssd_prefill", "quamba_ssd_prefill_noalloc", "quamba_ssd_prefill_workspace_size",
@@ -24,4 +24,4 @@ __all__ = ["QuambaError", "Shape", "HostScales", "DeviceScales", "Gate", "load_l
            "quamba_strerror", "FLAG_GENERIC_KERNEL", "FLAG_PRECISE_STATE", "FLAG_NO_CHANNEL_SPLIT", "FLAG_NO_DECAY_SKIP",
            "FLAG_NO_SEQ_SPLIT",
            "EXPORTED_SYMBOLS", "quamba_probe_mfma", "quamba_probe_stream_rmw", "quamba_probe_stream_read",
-           "quamba_probe_clock"]
+           "quamba_probe_clock", "quamba_probe_clock_xcd"]

@@ -25,7 +25,8 @@ EXPORTED_SYMBOLS = ("quamba_ssd_prefill_workspace_size", "quamba_ssd_prefill", "
                     "quamba_reorder_params", "quamba_gather_rows", "quamba_quantize_x",
                     "quamba_quantize_groups", "quamba_strerror",
                     # measurement helpers of the benchmark harness (include/quamba_probe.h)
-                    "quamba_probe_mfma", "quamba_probe_stream_rmw", "quamba_probe_stream_read", "quamba_probe_clock")
+                    "quamba_probe_mfma", "quamba_probe_stream_rmw", "quamba_probe_stream_read", "quamba_probe_clock",
+                    "quamba_probe_clock_xcd")
 
 
 class QuambaError(RuntimeError):
@@ -546,6 +547,17 @@ def quamba_probe_stream_read(buf, sink, stream=None) -> int:
     if rc != 0:
         raise QuambaError(rc, "quamba_probe_stream_read")
     return nbytes
+
+
+def quamba_probe_clock_xcd(out, spin_iters: int = 20000, stream=None) -> None:
+    """Enqueue the per-XCD shader-clock probe; out: int64 device tensor [n, 3] (shader clocks, ticks of 10 ns, XCD id)."""
+    import torch
+    lib = load_library()
+    lib.quamba_probe_clock_xcd.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+    n = int(out.shape[0])
+    rc = lib.quamba_probe_clock_xcd(_dp(out, torch.int64, (n, 3), "out"), n, int(spin_iters), _stream_ptr(stream))
+    if rc != 0:
+        raise QuambaError(rc, "quamba_probe_clock_xcd")
 
 
 def quamba_probe_clock(out, spin_iters: int = 20000, stream=None) -> None:

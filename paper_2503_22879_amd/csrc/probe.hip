@@ -114,6 +114,26 @@ __global__ __launch_bounds__(64) void clock_probe_kernel(int64_t *out, int spin_
     if (v == 12345.678f) out[0] = 0;
 }
 
+// One wave per workgroup; the hardware hands consecutive workgroup ids to the XCDs in turn, so n workgroups sample n
+// XCDs (the id register read back says which).
+__global__ __launch_bounds__(64) void clock_probe_xcd_kernel(int64_t *out, int spin_iters)
+{
+    const long long c0 = __builtin_amdgcn_s_memtime();
+    const long long r0 = __builtin_amdgcn_s_memrealtime();
+    float v = (float)threadIdx.x;
+    for (int i = 0; i < spin_iters; ++i) v = __builtin_fmaf(v, 1.0000001f, 1.0e-7f);
+    asm volatile("" : "+v"(v));
+    const long long c1 = __builtin_amdgcn_s_memtime();
+    const long long r1 = __builtin_amdgcn_s_memrealtime();
+    if (threadIdx.x == 0) {
+        int64_t *o = out + 3 * (size_t)blockIdx.x;
+        o[0] = c1 - c0;
+        o[1] = r1 - r0;
+        o[2] = (int64_t)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 0xf);  // XCC_ID, bits 3:0
+    }
+    if (v == 12345.678f) out[0] = 0;
+}
+
 int device_cus()
 {
     int dev = 0, n = 0;
@@ -162,6 +182,14 @@ extern "C" int quamba_probe_stream_read(const void *buf, size_t n_bytes, uint32_
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)(cus * 16)), dim3(256), 0, (hipStream_t)stream,
                        static_cast<const u32x4 *>(buf), n_bytes / 16, sink);
+    return hipGetLastError() == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
+}
+
+extern "C" int quamba_probe_clock_xcd(int64_t *out, int n, int spin_iters, void *stream)
+{
+    if (!out) return QUAMBA_ENULL;
+    if (n <= 0 || n > 64 || spin_iters <= 0) return QUAMBA_EINVAL;
+    hipLaunchKernelGGL(clock_probe_xcd_kernel, dim3((unsigned)n), dim3(64), 0, (hipStream_t)stream, out, spin_iters);
     return hipGetLastError() == hipSuccess ? QUAMBA_OK : QUAMBA_EHIP;
 }
 

@@ -275,3 +275,7 @@ def test_probe_entry_points_validate_before_they_launch():
     assert lib.quamba_probe_stream_read(C.c_void_p(p), C.c_size_t(0), C.c_void_p(p), None) == -5
     assert lib.quamba_probe_clock(None, 100, None) == -1
     assert lib.quamba_probe_clock(C.c_void_p(p), 0, None) == -5
+    assert lib.quamba_probe_clock_xcd(None, 8, 100, None) == -1
+    assert lib.quamba_probe_clock_xcd(C.c_void_p(p), 0, 100, None) == -5
+    assert lib.quamba_probe_clock_xcd(C.c_void_p(p), 65, 100, None) == -5
+    assert lib.quamba_probe_clock_xcd(C.c_void_p(p), 8, 0, None) == -5

@@ -56,3 +56,18 @@ def test_clock_probe_reads_a_shader_clock(gpu_lib):
     assert ticks > 0 and cycles > 0
     mhz = cycles / ticks * 100.0
     assert 500.0 < mhz < 3000.0, mhz
+
+
+def test_clock_probe_per_xcd(gpu_lib):
+    """Eight one-wave workgroups land on eight different XCDs (the hardware deals the ids out in turn) and each
+    reads a plausible clock."""
+    import torch
+    q = gpu_lib
+    out = torch.full((8, 3), -1, dtype=torch.int64, device="cuda")
+    q.quamba_probe_clock_xcd(out, 20000)
+    torch.cuda.synchronize()
+    v = out.cpu().numpy()
+    assert (v[:, 0] > 0).all() and (v[:, 1] > 0).all()
+    mhz = v[:, 0] / v[:, 1] * 100.0
+    assert ((mhz > 500.0) & (mhz < 3000.0)).all(), mhz
+    assert sorted(int(x) for x in v[:, 2]) == list(range(8)), v[:, 2]
