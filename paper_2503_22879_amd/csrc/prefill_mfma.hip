@@ -205,6 +205,19 @@ __device__ __forceinline__ float wave_inclusive_scan(float v, float &row)
     return v;
 }
 
+// Sum of the values of the lanes behind this one inside its row of 16 lanes (0 for the row's last lane): row shifts
+// towards lower lanes with zero fill.  Unlike the difference of two prefix sums it carries no rounding error of the
+// size of the sums in front of the lane.
+__device__ __forceinline__ float row_suffix_sum_exclusive(float v)
+{
+    float s = dpp_f32<0x101, 0xf, true>(v);  // row_shl:1
+    s += dpp_f32<0x101, 0xf, true>(s);
+    s += dpp_f32<0x102, 0xf, true>(s);       // row_shl:2
+    s += dpp_f32<0x104, 0xf, true>(s);       // row_shl:4
+    s += dpp_f32<0x108, 0xf, true>(s);       // row_shl:8
+    return s;
+}
+
 __device__ __forceinline__ f16x8 pack_f16x8(const float v[8])
 {
     f16x8 r;
@@ -755,18 +768,20 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 if (2 * lane + 1 >= nv) dt1 = 0.0f;
                 const float a0 = dt0 * Ah, a1 = dt1 * Ah;
                 // A row of 16 lanes is one 32-token block: the weights inside a block are formed from the block's own
-                // prefix sums (loc), not from differences of the chunk's, which lose ulp(|prefix sum|) when the decay
+                // sums, not from differences of the chunk's prefix sums, which lose ulp(|prefix sum|) when the decay
                 // is extreme.  With m and R the chunk's prefix sums at the block's end and in front of it:
-                // m - cum_s = m_loc - loc_s and R - cum_s = -loc_s.
+                // m - cum_s is the sum of dt*A over the block's tokens behind s, taken as that sum (a difference of
+                // two prefix sums would be off by their rounding, 1e-4 of the weight of the last token of a block that
+                // decays by 2^-2000), and R - cum_s = -loc_s with loc the block's own prefix sum.
                 float loc1;
                 const float cum1 = wave_inclusive_scan(a0 + a1, loc1), cum0 = cum1 - a1;
                 const float loc0 = loc1 - a1;
-                const float m_loc = __shfl(loc1, lane | 15, 64);
+                const float suf1 = row_suffix_sum_exclusive(a0 + a1), suf0 = suf1 + a1;  // behind tokens 2l+1, 2l
                 // weights towards the output accumulators
                 const float d0 = dt0 * (kAcc / kXs), d1 = dt1 * (kAcc / kXs);
                 // weights towards the state accumulators
                 const float q0 = dt0 * (kNarrow / kXs), q1 = dt1 * (kNarrow / kXs);
-                const float e0 = exp2_fast(m_loc - loc0), e1 = exp2_fast(m_loc - loc1);
+                const float e0 = exp2_fast(suf0), e1 = exp2_fast(suf1);
                 const float we0 = e0 * d0, we1 = e1 * d1;
                 *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
                 *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(d0 * kNarrow, d1 * kNarrow);
@@ -1087,7 +1102,6 @@ __global__ __launch_bounds__(kStateThreads, 2) void segment_state_kernel(SsdArgs
             const float a0 = dt0 * Ah, a1 = dt1 * Ah;
             float loc1;
             const float cum1 = wave_inclusive_scan(a0 + a1, loc1), cum0 = cum1 - a1;
-            const float loc0 = loc1 - a1;
             const float cum_last = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cum1), 63));
             seg_cum += cum_last;
             const float q0 = dt0 * (kNarrow / kXs), q1 = dt1 * (kNarrow / kXs);
@@ -1096,8 +1110,8 @@ __global__ __launch_bounds__(kStateThreads, 2) void segment_state_kernel(SsdArgs
                 *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) =
                     (f16x2){(_Float16)(exp2_fast(cum_last - cum0) * q0), (_Float16)(exp2_fast(cum_last - cum1) * q1)};
             } else {
-                const float m_loc = __shfl(loc1, lane | 15, 64);
-                const float e0 = exp2_fast(m_loc - loc0), e1 = exp2_fast(m_loc - loc1);
+                const float suf1 = row_suffix_sum_exclusive(a0 + a1), suf0 = suf1 + a1;  // as in prefill_mfma_kernel
+                const float e0 = exp2_fast(suf0), e1 = exp2_fast(suf1);
                 const float w[2] = {e0 * q0, e1 * q1};
                 f16x2 wq, wd;
 #pragma unroll

@@ -424,6 +424,33 @@ def test_extreme_decay_takes_the_per_element_diagonal(gpu_lib):
         check(yg, hg, yref, href if want_state else None, f"extreme decay, state={want_state}, flags={flags}")
 
 
+@pytest.mark.parametrize("L", [700, 668, 2333])
+def test_final_state_when_only_the_last_tokens_count(gpu_lib, L):
+    """Decay of 2^-50 and more per token on every other head: the final state of such a head is the last token's
+    term alone, sitting at the end of a ragged chunk behind a block prefix sum of thousands (log2 units).  Its weight
+    is exp2 of the sum of dt*A over the tokens behind it, here exactly 1; formed as a difference of two prefix sums it
+    would be off by their rounding (1e-4 of the state, the whole spec allowance).  The bar here is half of the
+    allowance; what remains is the rounding of the two-term product (at most 2^-14).  L = 2333 takes the sequence
+    split, whose state-pass kernel forms the same weights."""
+    s = W.CONFIGS["m2_130m"].with_(seqlen=L, nheads=8)
+    sc, prob, _ = make_problem(s, 45, calib_tokens=256)
+    p1 = dict(prob)
+    dt = prob["dt"].copy()
+    dt[:, :, 1::2] = np.clip(dt[:, :, 1::2] * 60.0, 2.5, 15.0)
+    p1["dt"] = dt.astype(np.float32)
+    p1["A"] = prob["A"].copy()
+    p1["A"][1::2] = -13.0
+    h0 = W.draw_state(s, 45).astype(np.float32)
+    yref, href, _ = oracle.ref_prefill(sc, p1["x"], p1["B"], p1["C"], p1["dt"], p1["A"], p1["D"],
+                                       init_state=h0.astype(np.float64))
+    for flags in (0, NO_SPLIT):
+        yg, hg = run_prefill(gpu_lib, s, sc, p1, flags=flags, init_state=h0)
+        check(yg, hg, yref, href, f"last tokens only, L={L}, flags={flags}")
+        for h in range(1, s.nheads, 2):
+            e = np.abs(hg[:, h] - href[:, h]).max() / np.abs(href[:, h]).max()
+            assert e <= 5e-5, f"head {h}: state err {e:.2e}"
+
+
 def test_step_sizes_up_to_the_documented_limit(gpu_lib):
     """The matrix-core kernel documents 0 <= dt <= 16 (the narrowed scores times dt / 4 must stay in fp16).  Step sizes
     scaled up and capped just below the limit on every other head, B scales lowered so that y stays inside fp16: the
