@@ -96,7 +96,10 @@ struct Lds {
     static constexpr int kOffWs = kOffWe + 2 * kQ;           // fp16[128]   token weights of the state update
     static constexpr int kOffWd = kOffWs + 2 * kQ;           // fp16[128]   their residuals (two-term path)
     static constexpr int kOffSx = kOffWd + 2 * kQ;           // float[64]
-    static constexpr int kOffBq = kOffSx + 4 * kP + 64;      // int8 [128][144]
+    static constexpr int kOffLoc = kOffSx + 4 * kP;          // float[128]  prefix sums inside each 32-token block
+    static constexpr int kOffTot = kOffLoc + 4 * kQ;         // float[4]    the blocks' totals
+    static constexpr int kOffGap = kOffTot + 4 * kNBlk;      // float[4][4] [tb][sb]: sum of the totals of blocks sb+1..tb-1
+    static constexpr int kOffBq = kOffGap + 4 * kNBlk * kNBlk + 48;  // int8 [128][144]
     static constexpr int kOffHs = kOffBq + kQ * kBqStride;   // fp16 [kPw][136]
     static constexpr int kOffXs = kOffHs + 2 * kPw * kHsStride;  // fp16 [128][kXsStride]
     static constexpr int kBytes = kOffXs + 2 * kQ * kXsStride;
@@ -259,6 +262,9 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
     _Float16 *s_ws = reinterpret_cast<_Float16 *>(smem + LY::kOffWs);
     _Float16 *s_wd = reinterpret_cast<_Float16 *>(smem + LY::kOffWd);  // PRECISE only
     float *s_sx = reinterpret_cast<float *>(smem + LY::kOffSx);
+    float *s_loc = reinterpret_cast<float *>(smem + LY::kOffLoc);
+    float *s_tot = reinterpret_cast<float *>(smem + LY::kOffTot);
+    float *s_gap = reinterpret_cast<float *>(smem + LY::kOffGap);
     unsigned char *s_bq = smem + LY::kOffBq;
     _Float16 *s_hs = reinterpret_cast<_Float16 *>(smem + LY::kOffHs);
     unsigned char *s_xs = smem + LY::kOffXs;  // fp16 rows, addressed in bytes
@@ -395,6 +401,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 const unsigned char *xs_src =
                     s_xs + ((8 * hba + (i16 >> 2)) * kXsStride + 16 * c16 + 4 * (i16 & 3)) * 2;
                 const float cum_t = s_cum[tb * kBlk + l32a];
+                const float loc_t = s_loc[tb * kBlk + l32a];  // the same sum from the start of the token's own block
 
                 // B rows of block sb as the A operand of G^T
                 auto load_bq = [&](int sb, i32x4(&bq)[4]) {
@@ -465,7 +472,9 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                         for (int pt = 0; pt < PT; ++pt)
                             xa[ks][pt] = lds_read_tr16x8<kXsStride>(
                                 xs_src + ((sb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
-                    const float m_sb = s_cum[sb * kBlk + kBlk - 1];
+                    // cum_t - m_sb, formed from the block's own prefix sum and the totals of the blocks in between
+                    // (the difference of two chunk-wide sums would carry their rounding)
+                    const float gap_sb = s_gap[tb * kNBlk + sb];
                     f16x4 wq4[4];  // weights of tokens 8 rg + 4 hb + [0,4) of block sb
 #pragma unroll
                     for (int rg = 0; rg < 4; ++rg)
@@ -473,7 +482,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                     __builtin_amdgcn_sched_barrier(0);
                     // the current tile is narrowed before the next one is issued, so that both can share registers (the
                     // other wave of the SIMD fills the matrix core meanwhile)
-                    const float rowf = exp2_fast(cum_t - m_sb) * kNarrow;
+                    const float rowf = exp2_fast(loc_t + gap_sb) * kNarrow;
                     float lv[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) lv[r] = (float)gi[r] * rowf;
@@ -504,12 +513,10 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                         for (int pt = 0; pt < PT; ++pt)
                             xd[ks][pt] = lds_read_tr16x8<kXsStride>(
                                 xs_src + ((tb * kBlk + 16 * ks) * kXsStride + 32 * pt) * 2);
-                    // R: prefix sum in front of the block, m: at its last token.  When the decay across the block stays
+                    // When the decay across the block (its total of dt*A) stays
                     // below 2^64 the weight exp2(cum_t - cum_s) dt_s is the product of a row factor and the staged
                     // column weights (both inside the fp32 range); otherwise every element takes its own exponential.
-                    const float R = tb > 0 ? s_cum[tb * kBlk - 1] : 0.0f;
-                    const float m_tb = s_cum[tb * kBlk + kBlk - 1];
-                    const bool factored = __builtin_amdgcn_readfirstlane((R - m_tb) < 64.0f);
+                    const bool factored = __builtin_amdgcn_readfirstlane(-s_tot[tb] < 64.0f);
                     // the skip coefficient is made new per chunk for the compiler: the 16 selects below then stay here
                     // (lane masks in scalar registers) instead of 16 loop-invariant vector registers
                     float d_sel_c = d_sel;
@@ -518,7 +525,7 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                     // so that at most one group's temporaries are live
                     f16x4 lq[4];
                     if (factored) {
-                        const float e_row = exp2_fast(cum_t - R);
+                        const float e_row = exp2_fast(loc_t);
 #pragma unroll
                         for (int rg = 0; rg < 4; ++rg) {
                             const int s0 = 8 * rg + 4 * hb;
@@ -535,14 +542,14 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
 #pragma unroll
                         for (int rg = 0; rg < 4; ++rg) {  // four consecutive tokens of the block per register group
                             const int s0 = 8 * rg + 4 * hb;
-                            const f32x4 cs4 = *reinterpret_cast<const f32x4 *>(s_cum + tb * kBlk + 8 * rg + 4 * hba);
+                            const f32x4 cs4 = *reinterpret_cast<const f32x4 *>(s_loc + tb * kBlk + 8 * rg + 4 * hba);
                             const f32x4 ds4 = *reinterpret_cast<const f32x4 *>(s_dt + tb * kBlk + 8 * rg + 4 * hba);
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
                                 // exponent forced to a huge negative value above the diagonal: weight exactly 0, no
                                 // branch cum is non-increasing (dt >= 0, A <= 0): the exponent is <= 0 on and below the
                                 // diagonal
-                                const float arg = (s0 + i <= l32) ? cum_t - cs4[i] : -1.0e30f;
+                                const float arg = (s0 + i <= l32) ? loc_t - cs4[i] : -1.0e30f;
                                 const float dd = (s0 + i == l32) ? d_sel_c : 0.0f;  // skip term on the diagonal
                                 lq[rg][i] = (_Float16)fmaf((float)gi[4 * rg + i], exp2_fast(arg) * ds4[i], dd);
                             }
@@ -784,15 +791,27 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 const float e0 = exp2_fast(suf0), e1 = exp2_fast(suf1);
                 const float we0 = e0 * d0, we1 = e1 * d1;
                 *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
+                // Every exponent that spans a stretch of tokens is formed from sums over that stretch: the block's own
+                // prefix sums, the blocks' totals (the row scan's value in the last lane of a row) and the sums of the
+                // totals in between, never from differences of the chunk's prefix sums, which carry rounding of the
+                // size of what lies in front of the stretch.
+                *reinterpret_cast<float2 *>(s_loc + 2 * lane) = make_float2(loc0, loc1);
+                const float T1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, loc1), 31));
+                const float T2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, loc1), 47));
+                const float T3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, loc1), 63));
+                if ((lane & 15) == 15) s_tot[lane >> 4] = loc1;
+                if (lane < kNBlk * kNBlk)  // [tb][sb]: lane 8 = (2,0): T1, lane 12 = (3,0): T1 + T2, lane 13 = (3,1): T2
+                    s_gap[lane] = lane == 8 ? T1 : lane == 12 ? T1 + T2 : lane == 13 ? T2 : 0.0f;
                 *reinterpret_cast<float2 *>(s_dt + 2 * lane) = make_float2(d0 * kNarrow, d1 * kNarrow);
                 *reinterpret_cast<float2 *>(s_w2 + 2 * lane) =
                     make_float2(exp2_fast(-loc0) * d0 * kNarrow, exp2_fast(-loc1) * d1 * kNarrow);
                 *reinterpret_cast<f16x2 *>(s_we + 2 * lane) = (f16x2){(_Float16)we0, (_Float16)we1};
                 if (!PRECISE) {
-                    const float cum_last =
-                        __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cum1), 63));
-                    *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) = (f16x2){(_Float16)(exp2_fast(cum_last - cum0) * q0),
-                                                                          (_Float16)(exp2_fast(cum_last - cum1) * q1)};
+                    // cum_last - cum_s: what lies behind s in its block plus the totals of the later blocks
+                    const int row = lane >> 4;
+                    const float later = row == 0 ? T1 + (T2 + T3) : row == 1 ? T2 + T3 : row == 2 ? T3 : 0.0f;
+                    *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) = (f16x2){(_Float16)(exp2_fast(suf0 + later) * q0),
+                                                                          (_Float16)(exp2_fast(suf1 + later) * q1)};
                 } else {
                     f16x2 wq, wd;
                     const float w[2] = {e0 * q0, e1 * q1};
@@ -856,12 +875,10 @@ __global__ __launch_bounds__(kThreads, 4) void prefill_mfma_kernel(SsdArgs a)
                 s_bq + (8 * hbs + (i16s >> 1)) * kBqStride + 32 * wave + 16 * c16s + 8 * (i16s & 1);
             const int xs_off = ((8 * hbs + (i16s >> 2)) * kXsStride + 16 * c16s + 4 * (i16s & 3)) * 2;
             if (PRECISE) {
-                float m_prev = 0.0f;
                 for (int sb = 0; sb < kNBlk; ++sb) {
                     if (sb * kBlk >= nv) break;  // the padded steps are identity steps
                     const float m = s_cum[sb * kBlk + kBlk - 1];
-                    const float gdec = exp2_fast(m - m_prev);
-                    m_prev = m;
+                    const float gdec = exp2_fast(s_tot[sb]);  // the block's own total, not m - m_prev
 #pragma unroll
                     for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
@@ -970,7 +987,8 @@ struct StateLds {
     static constexpr int kOffCum = 0;                       // float[128]
     static constexpr int kOffWs = kOffCum + 4 * kQ;         // fp16[128]
     static constexpr int kOffWd = kOffWs + 2 * kQ;          // fp16[128]
-    static constexpr int kOffBq = kOffWd + 2 * kQ;          // int8 [128][144]
+    static constexpr int kOffTot = kOffWd + 2 * kQ;         // float[4]  the blocks' totals
+    static constexpr int kOffBq = kOffTot + 4 * kNBlk + 48; // int8 [128][144]
     static constexpr int kOffXs = kOffBq + kQ * kBqStride;  // fp16 [128][kXsStride]
     static constexpr int kBytes = kOffXs + 2 * kQ * kXsStride;
     static_assert(kOffBq % 16 == 0 && kOffXs % 16 == 0, "LDS arrays must be 16-byte aligned");
@@ -985,6 +1003,7 @@ __global__ __launch_bounds__(kStateThreads, 2) void segment_state_kernel(SsdArgs
     float *s_cum = reinterpret_cast<float *>(smem + LY::kOffCum);
     _Float16 *s_ws = reinterpret_cast<_Float16 *>(smem + LY::kOffWs);
     _Float16 *s_wd = reinterpret_cast<_Float16 *>(smem + LY::kOffWd);
+    float *s_tot = reinterpret_cast<float *>(smem + LY::kOffTot);
     unsigned char *s_bq = smem + LY::kOffBq;
     unsigned char *s_xs = smem + LY::kOffXs;
 
@@ -1106,11 +1125,18 @@ __global__ __launch_bounds__(kStateThreads, 2) void segment_state_kernel(SsdArgs
             seg_cum += cum_last;
             const float q0 = dt0 * (kNarrow / kXs), q1 = dt1 * (kNarrow / kXs);
             *reinterpret_cast<float2 *>(s_cum + 2 * lane) = make_float2(cum0, cum1);
+            // exponents from sums over their own stretch of tokens, as in prefill_mfma_kernel
+            const float suf1 = row_suffix_sum_exclusive(a0 + a1), suf0 = suf1 + a1;
+            if ((lane & 15) == 15) s_tot[lane >> 4] = loc1;
             if (!PRECISE) {
+                const float T1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, loc1), 31));
+                const float T2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, loc1), 47));
+                const float T3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, loc1), 63));
+                const int row = lane >> 4;
+                const float later = row == 0 ? T1 + (T2 + T3) : row == 1 ? T2 + T3 : row == 2 ? T3 : 0.0f;
                 *reinterpret_cast<f16x2 *>(s_ws + 2 * lane) =
-                    (f16x2){(_Float16)(exp2_fast(cum_last - cum0) * q0), (_Float16)(exp2_fast(cum_last - cum1) * q1)};
+                    (f16x2){(_Float16)(exp2_fast(suf0 + later) * q0), (_Float16)(exp2_fast(suf1 + later) * q1)};
             } else {
-                const float suf1 = row_suffix_sum_exclusive(a0 + a1), suf0 = suf1 + a1;  // as in prefill_mfma_kernel
                 const float e0 = exp2_fast(suf0), e1 = exp2_fast(suf1);
                 const float w[2] = {e0 * q0, e1 * q1};
                 f16x2 wq, wd;
@@ -1177,7 +1203,6 @@ __global__ __launch_bounds__(kStateThreads, 2) void segment_state_kernel(SsdArgs
 #pragma unroll
                 for (int r = 0; r < 16; ++r) st[pt][r] *= gdec;
         }
-        float m_prev = 0.0f;
 #pragma unroll
         for (int step = 0; step < 2 * kNBlk; ++step) {
             const int sb = step >> 1;
@@ -1185,8 +1210,7 @@ __global__ __launch_bounds__(kStateThreads, 2) void segment_state_kernel(SsdArgs
             const StepOps &o = ops[step & 1];
             const float m = s_cum[sb * kBlk + kBlk - 1];
             if (PRECISE && (step & 1) == 0) {
-                const float gdec = exp2_fast(m - m_prev);
-                m_prev = m;
+                const float gdec = exp2_fast(s_tot[sb]);  // the block's own total
 #pragma unroll
                 for (int pt = 0; pt < PT; ++pt)
 #pragma unroll

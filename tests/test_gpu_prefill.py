@@ -451,6 +451,32 @@ def test_final_state_when_only_the_last_tokens_count(gpu_lib, L):
             assert e <= 5e-5, f"head {h}: state err {e:.2e}"
 
 
+@pytest.mark.parametrize("seed", [26, 626, 654, 727])
+def test_step_sizes_that_jump_inside_a_chunk(gpu_lib, seed):
+    """Step sizes of 4..16 on the first tokens of every chunk and one small step size (0.01..0.3) from a drawn
+    position on, A drawn from -0.5 .. -16 per head: the chunk's prefix sums reach thousands to tens of thousands (log2
+    units) in front of a stretch whose own decay is mild, so what that stretch carries and adds is what the final
+    state consists of.  Every exponent over such a stretch has to come from sums over the stretch itself (the block's
+    own prefix sums, the blocks' totals); taken as a difference of the chunk's prefix sums it is off by their rounding.
+    The four seeds are the worst of 1500 draws for a build that took those differences (final state off by 1.8e-4 ..
+    2.8e-4 of its maximum; the bar is 1e-4)."""
+    rng = np.random.default_rng(seed)
+    L = int(rng.choice([256, 300, 640]))
+    s = W.CONFIGS["m2_130m"].with_(seqlen=L, nheads=4)
+    sc, prob, _ = make_problem(s, 7, calib_tokens=128)
+    p1 = dict(prob)
+    dt = rng.uniform(4.0, 15.9, (1, L, s.nheads))
+    dt[:, (np.arange(L) % 128) >= int(rng.integers(40, 127)), :] = rng.uniform(0.01, 0.3)
+    p1["dt"] = dt.astype(np.float32)
+    p1["A"] = (-rng.uniform(0.5, 16.0, s.nheads)).astype(np.float32)
+    yref, href, _ = oracle.ref_prefill(sc, p1["x"], p1["B"], p1["C"], p1["dt"], p1["A"], p1["D"])
+    for want_state, flags in ((True, 0), (True, NO_SPLIT), (False, 0)):
+        yg, hg = run_prefill(gpu_lib, s, sc, p1, flags=flags, want_state=want_state)
+        check(yg, hg, yref, href if want_state else None, f"jumping step sizes, seed={seed}, state={want_state}, flags={flags}")
+        if want_state:
+            assert np.abs(hg - href).max() <= 5e-5 * np.abs(href).max()
+
+
 def test_step_sizes_up_to_the_documented_limit(gpu_lib):
     """The matrix-core kernel documents 0 <= dt <= 16 (the narrowed scores times dt / 4 must stay in fp16).  Step sizes
     scaled up and capped just below the limit on every other head, B scales lowered so that y stays inside fp16: the
