@@ -25,8 +25,9 @@
 // so that Bq wq_s is exact in fp16 (7 + 4 bits); the update takes two products, xq^T (wq_s Bq) and xq^T (d_s wq_s Bq),
 // the first exact, the second (|d_s| <= 1/16) rounded at 2^-16 of the total.
 //
-// The token weights inside a 32-token block come from the block's own prefix sums (no cancellation against the
-// chunk's when the decay is extreme); a block pair, a carried-state product or a block's share of the chunk state
+// Every exponent that spans a stretch of tokens is formed from sums of dt A over that stretch (the block's own prefix
+// and suffix sums, the blocks' totals), not from differences of the chunk's prefix sums, which carry rounding of the
+// size of whatever decay lies in front of the stretch; a block pair, a carried-state product or a block's share of the chunk state
 // whose decay factor is below 2^-32 is left out unless QUAMBA_FLAG_NO_DECAY_SKIP is set.  The chunk's closing barrier
 // sits in front of the output epilogue, which reads registers and constant tables only.
 //
