@@ -36,7 +36,7 @@ KERNEL_CHUNK = 128             # tokens per chunk of prefill_mfma_kernel (the ca
 # 256 MiB device copy in the same run: factors 1.9998 and 1.0000).  These are constants taken from the committed
 # profile summaries, not measurements of this run: `traffic_source` in every roofline object names the file.
 # None for workloads that were not profiled.
-MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 488.1e6, "m2_8b_decode": 2162.3e6, "m2_8b_decode_q8": 550.9e6,
+MEASURED_TRAFFIC_BYTES = {"m2_8b_b4": 496.4e6, "m2_8b_decode": 2162.3e6, "m2_8b_decode_q8": 550.9e6,
                           "m2_8b_b4_hadamard": 402.7e6, "m2_8b_b4_conv1d": 352.1e6,
                           "mamba1_2p8b_scan": 599.1e6, "mamba1_2p8b_decode": 178.8e6}
 TRAFFIC_SOURCE = {
