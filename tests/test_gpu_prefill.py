@@ -477,6 +477,46 @@ def test_step_sizes_that_jump_inside_a_chunk(gpu_lib, seed):
             assert np.abs(hg - href).max() <= 5e-5 * np.abs(href).max()
 
 
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_drawn_step_size_patterns(gpu_lib, mode, seed):
+    """Step-size patterns far from the workloads' (which draw every token alike), on drawn lengths, head counts and A:
+    0: every token tiny (1e-4..0.1) or huge (2..16) at a drawn rate; 1: the same per 32-token block; 2: huge, then one
+    small value from a drawn position of every chunk on; 3: ordinary step sizes scaled by 0.2..30 with stretches of 16
+    tokens set to zero, and A = 0 on some heads; 4: 1e-5..2e-3 everywhere (almost no decay over the whole sequence),
+    A = 0 on some heads.  Outputs and the final state against the oracle, lengths up to the sequence split."""
+    rng = np.random.default_rng(1000 * mode + seed)
+    L = int(rng.choice([256, 300, 511, 640, 1100, 1500])); H = int(rng.choice([2, 4, 8]))
+    s = W.CONFIGS["m2_130m"].with_(seqlen=L, nheads=H)
+    sc, prob, _ = make_problem(s, int(rng.integers(1, 10 ** 6)), calib_tokens=128)
+    p1 = dict(prob)
+    tiny = lambda: rng.uniform(1e-4, 0.1, (1, L, H))
+    huge = lambda: rng.uniform(2.0, 15.9, (1, L, H))
+    if mode == 0:
+        dt = np.where(rng.random((1, L, H)) < rng.uniform(0.05, 0.95), huge(), tiny())
+    elif mode == 1:
+        pick = np.repeat(rng.random((1, (L + 31) // 32, H)) < 0.5, 32, axis=1)[:, :L]
+        dt = np.where(pick, huge(), tiny())
+    elif mode == 2:
+        dt = rng.uniform(4.0, 15.9, (1, L, H))
+        dt[:, (np.arange(L) % 128) >= int(rng.integers(40, 127)), :] = rng.uniform(0.01, 0.3)
+    elif mode == 3:
+        dt = prob["dt"].astype(np.float64) * rng.uniform(0.2, 30.0)
+        dt = dt * np.repeat(rng.random((1, (L + 15) // 16, H)) < 0.6, 16, axis=1)[:, :L]
+    else:
+        dt = rng.uniform(1e-5, 2e-3, (1, L, H))
+    p1["dt"] = np.minimum(dt, 15.9).astype(np.float32)
+    p1["A"] = (-rng.uniform(0.5, 16.0, H)).astype(np.float32)
+    if mode >= 3:
+        p1["A"][rng.random(H) < 0.3] = 0.0
+    yref, href, _ = oracle.ref_prefill(sc, p1["x"], p1["B"], p1["C"], p1["dt"], p1["A"], p1["D"])
+    assert np.isfinite(yref).all() and 0 < np.abs(yref).max() < 6e4
+    for want_state, flags in ((True, 0), (False, NO_SPLIT)):
+        yg, hg = run_prefill(gpu_lib, s, sc, p1, flags=flags, want_state=want_state)
+        check(yg, hg, yref, href if want_state else None,
+              f"step-size pattern {mode}, seed {seed}, L={L}, H={H}, state={want_state}, flags={flags}")
+
+
 def test_step_sizes_up_to_the_documented_limit(gpu_lib):
     """The matrix-core kernel documents 0 <= dt <= 16 (the narrowed scores times dt / 4 must stay in fp16).  Step sizes
     scaled up and capped just below the limit on every other head, B scales lowered so that y stays inside fp16: the
